@@ -1,0 +1,203 @@
+/*
+ * mpo_ref — CPU oracle (see mpo_ref.h).  TEST INFRASTRUCTURE ONLY.
+ *
+ * Build: gcc -O2 -std=c11 -ffp-contract=off -fno-fast-math -fPIC -shared
+ * One element at a time, one rounded fp32 operation per line.
+ */
+#include "mpo_ref.h"
+
+#include <math.h>
+#include <string.h>
+
+/* ---- bit views ---------------------------------------------------------- */
+
+static uint32_t bits_of(float x) { uint32_t b; memcpy(&b, &x, 4); return b; }
+static float float_of(uint32_t b) { float x; memcpy(&x, &b, 4); return x; }
+
+/* ---- bf16: 1 + 8 + 7 bits (Table 1); 16 significand bits dropped (Sec. 3.1) */
+
+static void split_bf16(float x, uint16_t *hi, uint16_t *res)
+{
+    uint32_t b = bits_of(x);
+    *hi = (uint16_t)(b >> 16);      /* sign, exponent, leading 7 fraction bits */
+    *res = (uint16_t)(b & 0xFFFFu); /* the 16 fraction bits bf16 cannot hold   */
+}
+
+static float merge_bf16(uint16_t hi, uint16_t res)
+{
+    return float_of(((uint32_t)hi << 16) | (uint32_t)res);
+}
+
+/* ---- fp16: 1 + 5 + 10 bits (Table 1); 13 significand bits dropped (Sec. 3.1)
+ *
+ * The 13 extra bits sit right-aligned in the 16-bit residual; its top three
+ * bits are written as zero and ignored on merge.
+ * fp16 keeps its subnormals (Sec. 1.1): below 2^-14 the pair (hi, res) is a
+ * 23-bit fixed-point number in units of 2^-37.  Values the pair cannot hold are
+ * truncated toward zero, in line with the round-toward-zero reading of Sec. 3.1:
+ * finite magnitudes of 65536 or more saturate at the largest finite pair.
+ */
+
+static void split_fp16(float x, uint16_t *hi, uint16_t *res)
+{
+    uint32_t b = bits_of(x);
+    uint16_t s = (uint16_t)((b >> 31) << 15);
+    uint32_t E = (b >> 23) & 0xFFu;
+    uint32_t M = b & 0x7FFFFFu;
+
+    if (E == 255u) {                       /* infinity or NaN */
+        *hi = (uint16_t)(s | (M == 0 ? 0x7C00u : 0x7E00u));
+        *res = 0;
+        return;
+    }
+    if (E == 0u) {                         /* fp32 zero or subnormal: below 2^-37 */
+        *hi = s;
+        *res = 0;
+        return;
+    }
+    int e = (int)E - 127;
+    if (e > 15) {                          /* too large: largest finite pair */
+        *hi = (uint16_t)(s | 0x7BFFu);
+        *res = 0x1FFFu;
+        return;
+    }
+    if (e >= -14) {                        /* fp16 normal range: re-bias the exponent */
+        *hi = (uint16_t)(s | ((uint32_t)(e + 15) << 10) | (M >> 13));
+        *res = (uint16_t)(M & 0x1FFFu);
+        return;
+    }
+    /* fp16 subnormal range: shift the 24-bit significand down to the 2^-37 grid */
+    int shift = -14 - e;
+    uint32_t F = shift >= 24 ? 0u : ((1u << 23) | M) >> shift;
+    *hi = (uint16_t)(s | (F >> 13));
+    *res = (uint16_t)(F & 0x1FFFu);
+}
+
+static float merge_fp16(uint16_t hi, uint16_t res)
+{
+    uint32_t s = (uint32_t)(hi >> 15) << 31;
+    uint32_t E = (hi >> 10) & 0x1Fu;
+    uint32_t k = hi & 0x3FFu;
+    uint32_t r = res & 0x1FFFu;
+
+    if (E == 31u)                          /* infinity, or a quiet NaN */
+        return float_of(s | 0x7F800000u | (k == 0 ? 0u : (0x00400000u | (k << 13))));
+    if (E == 0u) {                         /* subnormal: (k, r) counts units of 2^-37 */
+        float mag = ldexpf((float)((k << 13) | r), -37);   /* exact: integer < 2^23 */
+        return s ? -mag : mag;
+    }
+    return float_of(s | ((E + 112u) << 23) | (k << 13) | r);
+}
+
+static void split_one(float x, uint16_t *hi, uint16_t *res, int fmt)
+{
+    if (fmt == MPO_REF_FP16) split_fp16(x, hi, res); else split_bf16(x, hi, res);
+}
+
+static float merge_one(uint16_t hi, uint16_t res, int fmt)
+{
+    return fmt == MPO_REF_FP16 ? merge_fp16(hi, res) : merge_bf16(hi, res);
+}
+
+/* A 16-bit float read as fp32: every bf16 and fp16 value is an fp32 value. */
+float mpo_ref_cvt16(uint16_t x, int fmt)
+{
+    return fmt == MPO_REF_FP16 ? merge_fp16(x, 0) : merge_bf16(x, 0);
+}
+
+void mpo_ref_split(const float *w32, uint16_t *hi, uint16_t *res, uint64_t n, int fmt)
+{
+    for (uint64_t i = 0; i < n; ++i) split_one(w32[i], &hi[i], &res[i], fmt);
+}
+
+void mpo_ref_merge(const uint16_t *hi, const uint16_t *res, float *w32, uint64_t n, int fmt)
+{
+    for (uint64_t i = 0; i < n; ++i) w32[i] = merge_one(hi[i], res[i], fmt);
+}
+
+/* ---- Adam (Sec. 3.1: the classic optimizer, hyper-parameters unchanged) ----
+ *
+ * Kingma & Ba's Adam with bias correction; epsilon is added to the
+ * bias-corrected root of v; decoupled decay (AdamW) scales the weight by
+ * 1 - lr*wd before the update, L2 decay adds wd*w to the gradient.
+ * Scalars are formed in double and rounded to fp32 once.  Per element every
+ * line below is one rounded fp32 operation.
+ */
+void mpo_ref_adam_step(uint16_t *hi, uint16_t *res, const uint16_t *grad, float *m, float *v,
+                       uint64_t n, const mpo_ref_adam_cfg *cfg, uint64_t step)
+{
+    const double t = (double)step;
+    const float B1 = (float)cfg->beta1;
+    const float B2 = (float)cfg->beta2;
+    const float O1 = (float)(1.0 - cfg->beta1);
+    const float O2 = (float)(1.0 - cfg->beta2);
+    const float SS = (float)(cfg->lr / (1.0 - pow(cfg->beta1, t)));  /* lr / bias_correction1   */
+    const float SQ = (float)sqrt(1.0 - pow(cfg->beta2, t));          /* sqrt(bias_correction2)  */
+    const float EPS = (float)cfg->eps;
+    const float DEC = (float)(1.0 - cfg->lr * cfg->weight_decay);
+    const float WD = (float)cfg->weight_decay;
+    const float IS = (float)(1.0 / cfg->loss_scale);
+    const int has_wd = cfg->weight_decay != 0.0;
+
+    for (uint64_t i = 0; i < n; ++i) {
+        float w = merge_one(hi[i], res[i], cfg->weight_fmt);
+        float g = mpo_ref_cvt16(grad[i], cfg->grad_fmt);
+        g = g * IS;
+        if (has_wd) {
+            if (cfg->decoupled_wd) {
+                w = w * DEC;
+            } else {
+                float wdw = WD * w;
+                g = g + wdw;
+            }
+        }
+        float b1m = B1 * m[i];
+        float o1g = O1 * g;
+        float m1 = b1m + o1g;
+        float b2v = B2 * v[i];
+        float o2g = O2 * g;
+        float o2gg = o2g * g;
+        float v1 = b2v + o2gg;
+        float root = sqrtf(v1);
+        float rootc = root / SQ;
+        float d = rootc + EPS;
+        float q = m1 / d;
+        float upd = SS * q;
+        float w1 = w - upd;
+        m[i] = m1;
+        v[i] = v1;
+        split_one(w1, &hi[i], &res[i], cfg->weight_fmt);
+    }
+}
+
+/* ---- SGD with momentum (Sec. 3.1; appendix: SGD with momentum, weight decay) */
+void mpo_ref_sgd_step(uint16_t *hi, uint16_t *res, const uint16_t *grad, float *buf,
+                      uint64_t n, const mpo_ref_sgd_cfg *cfg, uint64_t step)
+{
+    (void)step; /* momentum buffers start at zero, so step 1 needs no special case */
+    const float LR = (float)cfg->lr;
+    const float MU = (float)cfg->momentum;
+    const float WD = (float)cfg->weight_decay;
+    const float IS = (float)(1.0 / cfg->loss_scale);
+    const int has_wd = cfg->weight_decay != 0.0;
+    const int has_mu = cfg->momentum != 0.0;
+
+    for (uint64_t i = 0; i < n; ++i) {
+        float w = merge_one(hi[i], res[i], cfg->weight_fmt);
+        float g = mpo_ref_cvt16(grad[i], cfg->grad_fmt);
+        g = g * IS;
+        if (has_wd) {
+            float wdw = WD * w;
+            g = g + wdw;
+        }
+        float b = g;
+        if (has_mu) {
+            float mub = MU * buf[i];
+            b = mub + g;
+            buf[i] = b;
+        }
+        float upd = LR * b;
+        float w1 = w - upd;
+        split_one(w1, &hi[i], &res[i], cfg->weight_fmt);
+    }
+}

@@ -1,0 +1,69 @@
+/*
+ * mpo_ref — CPU oracle for the split-precision optimizer step.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is the slow, plain definition of what the
+ * GPU library must compute.  Only tests, the smoke check and the benchmark's
+ * cpu_baseline leg may use it; the product path never does.  It shares no
+ * code with the GPU library.
+ *
+ * What it follows (arXiv 2309.12381):
+ *   - Table 1           : field widths of fp32 / bf16 / fp16.
+ *   - Section 3.1       : a weight is kept as a 16-bit float plus the
+ *                         significand bits that an fp32 copy would have kept
+ *                         (16 for bf16, 13 for fp16); keeping only the leading
+ *                         part of the significand is a round-toward-zero; the
+ *                         update is carried out in full (fp32) precision and
+ *                         both parts are written back; Adam and SGD are the
+ *                         classic ones.
+ *   - Section 3.2, 4.1  : the step runs per parameter as soon as its gradient
+ *                         exists; gradient scaling is applied inside the step.
+ *
+ * All arithmetic is fp32, one IEEE round-to-nearest-even operation at a time
+ * (no fused multiply-add, denormals kept).  Every pointer is a host pointer.
+ * Parity status: every function here is pinned by tests/test_oracle_*.py.
+ */
+#ifndef MPO_REF_H
+#define MPO_REF_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { MPO_REF_BF16 = 0, MPO_REF_FP16 = 1 };
+
+typedef struct {
+    double lr, beta1, beta2, eps, weight_decay;
+    int32_t decoupled_wd; /* 1: AdamW (w *= 1-lr*wd), 0: L2 (g += wd*w)      */
+    double loss_scale;    /* gradients arrive multiplied by this              */
+    int32_t weight_fmt;   /* format of hi                                     */
+    int32_t grad_fmt;     /* format of grad                                   */
+} mpo_ref_adam_cfg;
+
+typedef struct {
+    double lr, momentum, weight_decay; /* weight decay is L2 (added to g)     */
+    double loss_scale;
+    int32_t weight_fmt, grad_fmt;
+} mpo_ref_sgd_cfg;
+
+/* Section 3.1, Table 1: fp32 -> (16-bit float, extra bits), truncation. */
+void mpo_ref_split(const float *w32, uint16_t *hi, uint16_t *res, uint64_t n, int fmt);
+/* Section 3.1: (16-bit float, extra bits) -> fp32. */
+void mpo_ref_merge(const uint16_t *hi, const uint16_t *res, float *w32, uint64_t n, int fmt);
+
+/* Section 3.1 "classic optimizers": bias-corrected Adam / AdamW on one tensor. */
+void mpo_ref_adam_step(uint16_t *hi, uint16_t *res, const uint16_t *grad, float *m, float *v,
+                       uint64_t n, const mpo_ref_adam_cfg *cfg, uint64_t step);
+/* Section 3.1 "classic optimizers": SGD with momentum (dampening 0, no Nesterov).
+ * momentum == 0 leaves buf untouched (it may then be NULL). */
+void mpo_ref_sgd_step(uint16_t *hi, uint16_t *res, const uint16_t *grad, float *buf,
+                      uint64_t n, const mpo_ref_sgd_cfg *cfg, uint64_t step);
+
+/* Exact conversion of one 16-bit float to fp32 (used for gradients). */
+float mpo_ref_cvt16(uint16_t x, int fmt);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,162 @@
+"""ctypes access to the CPU oracle (oracle/mpo_ref.c) on numpy arrays.
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's cpu_baseline leg.  The product package never imports it.
+
+Each function forwards to the C routine of the same name; there is no
+arithmetic here.  Arrays are updated in place, as the C routines do.
+
+`Oracle(path)` wraps one compiled library; the module-level functions use the
+one built from oracle/mpo_ref.c.  (Tests of the pins load deliberately broken
+builds through the same class to show that the pins notice.)
+"""
+import ctypes
+from dataclasses import dataclass
+
+import numpy as np
+
+from . import build as _build
+
+BF16 = 0
+FP16 = 1
+
+_u16p = ctypes.POINTER(ctypes.c_uint16)
+_f32p = ctypes.POINTER(ctypes.c_float)
+
+
+class _AdamCfg(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
+                ("eps", ctypes.c_double), ("weight_decay", ctypes.c_double),
+                ("decoupled_wd", ctypes.c_int32), ("loss_scale", ctypes.c_double),
+                ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32)]
+
+
+class _SgdCfg(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_double), ("momentum", ctypes.c_double),
+                ("weight_decay", ctypes.c_double), ("loss_scale", ctypes.c_double),
+                ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32)]
+
+
+@dataclass
+class AdamCfg:
+    lr: float = 1e-3
+    beta1: float = 0.9
+    beta2: float = 0.999
+    eps: float = 1e-8
+    weight_decay: float = 0.0
+    decoupled_wd: bool = True
+    loss_scale: float = 1.0
+    weight_fmt: int = BF16
+    grad_fmt: int = BF16
+
+    def _c(self):
+        return _AdamCfg(self.lr, self.beta1, self.beta2, self.eps, self.weight_decay,
+                        int(self.decoupled_wd), self.loss_scale, self.weight_fmt, self.grad_fmt)
+
+
+@dataclass
+class SgdCfg:
+    lr: float = 1e-2
+    momentum: float = 0.9
+    weight_decay: float = 0.0
+    loss_scale: float = 1.0
+    weight_fmt: int = BF16
+    grad_fmt: int = BF16
+
+    def _c(self):
+        return _SgdCfg(self.lr, self.momentum, self.weight_decay, self.loss_scale,
+                       self.weight_fmt, self.grad_fmt)
+
+
+def _chk(a, dtype, n=None):
+    if not isinstance(a, np.ndarray) or a.dtype != dtype or a.ndim != 1 or not a.flags.c_contiguous:
+        raise TypeError("expected a contiguous 1-d %s array" % np.dtype(dtype).name)
+    if n is not None and a.shape[0] != n:
+        raise ValueError("length mismatch")
+    return a
+
+
+def _p16(a):
+    return a.ctypes.data_as(_u16p)
+
+
+def _p32(a):
+    return a.ctypes.data_as(_f32p)
+
+
+class Oracle:
+    BF16 = BF16
+    FP16 = FP16
+    AdamCfg = AdamCfg
+    SgdCfg = SgdCfg
+
+    def __init__(self, path):
+        lib = ctypes.CDLL(path)
+        lib.mpo_ref_split.argtypes = [_f32p, _u16p, _u16p, ctypes.c_uint64, ctypes.c_int]
+        lib.mpo_ref_split.restype = None
+        lib.mpo_ref_merge.argtypes = [_u16p, _u16p, _f32p, ctypes.c_uint64, ctypes.c_int]
+        lib.mpo_ref_merge.restype = None
+        lib.mpo_ref_adam_step.argtypes = [_u16p, _u16p, _u16p, _f32p, _f32p, ctypes.c_uint64,
+                                          ctypes.POINTER(_AdamCfg), ctypes.c_uint64]
+        lib.mpo_ref_adam_step.restype = None
+        lib.mpo_ref_sgd_step.argtypes = [_u16p, _u16p, _u16p, _f32p, ctypes.c_uint64,
+                                         ctypes.POINTER(_SgdCfg), ctypes.c_uint64]
+        lib.mpo_ref_sgd_step.restype = None
+        lib.mpo_ref_cvt16.argtypes = [ctypes.c_uint16, ctypes.c_int]
+        lib.mpo_ref_cvt16.restype = ctypes.c_float
+        self._lib = lib
+
+    def split(self, w32, fmt=BF16):
+        """fp32 array -> (hi, res) uint16 arrays."""
+        _chk(w32, np.float32)
+        n = w32.shape[0]
+        hi = np.empty(n, np.uint16)
+        res = np.empty(n, np.uint16)
+        self._lib.mpo_ref_split(_p32(w32), _p16(hi), _p16(res), n, fmt)
+        return hi, res
+
+    def merge(self, hi, res, fmt=BF16):
+        """(hi, res) uint16 arrays -> fp32 array."""
+        n = _chk(hi, np.uint16).shape[0]
+        _chk(res, np.uint16, n)
+        w32 = np.empty(n, np.float32)
+        self._lib.mpo_ref_merge(_p16(hi), _p16(res), _p32(w32), n, fmt)
+        return w32
+
+    def adam_step(self, hi, res, grad, m, v, cfg: AdamCfg, step: int):
+        """One Adam step on one tensor, in place on hi, res, m, v."""
+        n = _chk(hi, np.uint16).shape[0]
+        _chk(res, np.uint16, n)
+        _chk(grad, np.uint16, n)
+        _chk(m, np.float32, n)
+        _chk(v, np.float32, n)
+        if step < 1:
+            raise ValueError("step counts from 1")
+        c = cfg._c()
+        self._lib.mpo_ref_adam_step(_p16(hi), _p16(res), _p16(grad), _p32(m), _p32(v), n,
+                                    ctypes.byref(c), step)
+
+    def sgd_step(self, hi, res, grad, buf, cfg: SgdCfg, step: int):
+        """One SGD(-momentum) step on one tensor, in place on hi, res, buf."""
+        n = _chk(hi, np.uint16).shape[0]
+        _chk(res, np.uint16, n)
+        _chk(grad, np.uint16, n)
+        if cfg.momentum != 0.0:
+            _chk(buf, np.float32, n)
+        if step < 1:
+            raise ValueError("step counts from 1")
+        c = cfg._c()
+        bp = _p32(buf) if buf is not None else ctypes.cast(None, _f32p)
+        self._lib.mpo_ref_sgd_step(_p16(hi), _p16(res), _p16(grad), bp, n, ctypes.byref(c), step)
+
+    def cvt16(self, x: int, fmt=BF16) -> float:
+        """One 16-bit float pattern read as fp32."""
+        return float(self._lib.mpo_ref_cvt16(int(x) & 0xFFFF, fmt))
+
+
+_default = Oracle(_build.build())
+split = _default.split
+merge = _default.merge
+adam_step = _default.adam_step
+sgd_step = _default.sgd_step
+cvt16 = _default.cvt16

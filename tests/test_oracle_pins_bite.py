@@ -1,0 +1,104 @@
+"""The pins must notice a plausible mistake anywhere in the oracle.
+
+Each case below plants one mistake in a copy of oracle/mpo_ref.c (a dropped
+term, a wrong sign or index, swapped operands, a rounding shortcut), builds it
+into a scratch library on the CPU, and checks that at least one pin from
+test_oracle_split.py / test_oracle_steps.py fails on it, while all of them
+pass on the untouched source built the same way.
+"""
+import os
+import subprocess
+
+import pytest
+
+from oracle import build as obuild
+from oracle import ref as oref
+
+import test_oracle_split as ts
+import test_oracle_steps as tp
+
+SRC = open(obuild.SRC).read()
+
+PINS = [
+    ts.pins_golden_patterns,
+    lambda r: ts.pins_split_value_definition(r, "bf16"),
+    lambda r: ts.pins_split_value_definition(r, "fp16"),
+    tp.pins_torch_optim,
+    tp.pins_fp32_master_equivalence,
+    tp.pins_fp32_master_sgd,
+    tp.pins_exact_rational_adam,
+    tp.pins_exact_rational_sgd,
+    tp.pins_adam_first_step_closed_form,
+    tp.pins_adam_constant_gradient,
+    tp.pins_sgd_geometric_series,
+    tp.pins_decay_only_steps,
+    tp.pins_loss_scale_power_of_two,
+    tp.pins_residual_carries_small_updates,
+    tp.pins_mixed_formats,
+]
+
+# (name, text in mpo_ref.c, what it is replaced with, occurrences expected)
+MUTANTS = [
+    ("update sign", "float w1 = w - upd;", "float w1 = w + upd;", 2),
+    ("second moment not squared", "float o2gg = o2g * g;", "float o2gg = o2g;", 1),
+    ("epsilon dropped", "float d = rootc + EPS;", "float d = rootc;", 1),
+    ("epsilon inside the root", "float root = sqrtf(v1);", "float root = sqrtf(v1 + EPS);", 1),
+    ("no first bias correction", "cfg->lr / (1.0 - pow(cfg->beta1, t))", "cfg->lr", 1),
+    ("no second bias correction", "(float)sqrt(1.0 - pow(cfg->beta2, t))", "1.0f", 1),
+    ("step count off by one", "pow(cfg->beta2, t)", "pow(cfg->beta2, t + 1.0)", 1),
+    ("beta1 correction uses beta2", "pow(cfg->beta1, t)", "pow(cfg->beta2, t)", 1),
+    ("decay kinds swapped", "if (cfg->decoupled_wd) {", "if (!cfg->decoupled_wd) {", 1),
+    ("decoupled decay ignores lr", "1.0 - cfg->lr * cfg->weight_decay", "1.0 - cfg->weight_decay", 1),
+    ("loss scale ignored", "g = g * IS;", "g = g * 1.0f;", 2),
+    ("loss scale multiplied", "(float)(1.0 / cfg->loss_scale)", "(float)(cfg->loss_scale)", 2),
+    ("moment coefficients swapped", "float b1m = B1 * m[i];", "float b1m = O1 * m[i];", 1),
+    ("first moment not stored", "m[i] = m1;", "m[i] = m[i];", 1),
+    ("m and v swapped on store", "v[i] = v1;", "v[i] = m1;", 1),
+    ("momentum with dampening", "b = mub + g;", "b = mub + (1.0f - MU) * g;", 1),
+    ("momentum buffer not stored", "buf[i] = b;", "", 1),
+    ("sgd decay dropped", "float wdw = WD * w;\n            g = g + wdw;\n        }\n        float b = g;",
+     "float wdw = WD * w;\n            g = g + 0.0f * wdw;\n        }\n        float b = g;", 1),
+    ("fused multiply-add in m", "float m1 = b1m + o1g;", "float m1 = fmaf(O1, g, b1m);", 1),
+    ("double-precision quotient", "float upd = SS * q;",
+     "float upd = (float)((double)SS * ((double)m1 / (double)d));", 1),
+    ("bf16 hi rounded to nearest", "*hi = (uint16_t)(b >> 16);", "*hi = (uint16_t)((b + 0x8000u) >> 16);", 1),
+    ("bf16 merge halves swapped", "((uint32_t)hi << 16) | (uint32_t)res", "((uint32_t)res << 16) | (uint32_t)hi", 1),
+    ("bf16 residual one bit short", "*res = (uint16_t)(b & 0xFFFFu);", "*res = (uint16_t)(b & 0x7FFFu);", 1),
+    ("fp16 split bias", "(uint32_t)(e + 15) << 10", "(uint32_t)(e + 16) << 10", 1),
+    ("fp16 merge bias", "((E + 112u) << 23)", "((E + 111u) << 23)", 1),
+    ("fp16 residual mask", "*res = (uint16_t)(M & 0x1FFFu);", "*res = (uint16_t)(M & 0x0FFFu);", 1),
+    ("fp16 subnormal shift", "int shift = -14 - e;", "int shift = -15 - e;", 1),
+    ("fp16 subnormal scale", "ldexpf((float)((k << 13) | r), -37)", "ldexpf((float)((k << 13) | r), -36)", 1),
+    ("fp16 no saturation", "if (e > 15) {", "if (e > 16) {", 1),
+    ("fp16 sign lost in subnormal merge", "return s ? -mag : mag;", "return mag;", 1),
+]
+
+
+def _build(tmp_path, name, text):
+    c = tmp_path / (name + ".c")
+    c.write_text(text)
+    so = tmp_path / (name + ".so")
+    flags = [f for f in obuild.CFLAGS if f != "-Werror"] + ["-w"]
+    subprocess.check_call(["gcc", *flags, "-I", obuild.HERE, "-o", str(so), str(c), "-lm"])
+    return oref.Oracle(str(so))
+
+
+def _failing_pins(lib):
+    failed = []
+    for i, pin in enumerate(PINS):
+        try:
+            pin(lib)
+        except (AssertionError, ValueError, OverflowError, ZeroDivisionError):   # NaN/inf reaching exact arithmetic counts
+            failed.append(i)
+    return failed
+
+
+def test_untouched_source_passes_every_pin(tmp_path):
+    assert _failing_pins(_build(tmp_path, "clean", SRC)) == []
+
+
+@pytest.mark.parametrize("name,old,new,count", MUTANTS, ids=[m[0].replace(" ", "_") for m in MUTANTS])
+def test_planted_mistake_is_caught(tmp_path, name, old, new, count):
+    assert SRC.count(old) == count, "mutation site moved: %r" % old
+    lib = _build(tmp_path, "mutant", SRC.replace(old, new))
+    assert _failing_pins(lib), "no pin noticed: " + name

@@ -1,0 +1,240 @@
+"""Pins for the oracle's split / merge (arXiv 2309.12381, Table 1 and Section 3.1).
+
+None of these re-type the oracle's bit formulas.  They pin it to
+  * hand-worked patterns (tests/golden/split_patterns.txt),
+  * the value definition: hi is the 16-bit float obtained by rounding x toward
+    zero, and res counts how many units of the fp32 grid lie between hi and x
+    (checked in exact rational arithmetic with a decoder that knows only the
+    field widths of Table 1),
+  * library casts (torch bfloat16, numpy float16) turned into round-toward-zero,
+  * the lossless round trip over every fp32 bit pattern, and over every pair.
+"""
+import os
+from concurrent.futures import ThreadPoolExecutor
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from exact_fp32 import decode, float_of
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "split_patterns.txt")
+WORKERS = min(8, os.cpu_count() or 1)
+CHUNK = 1 << 21
+
+
+def _golden_rows():
+    rows = []
+    with open(GOLDEN) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if not line:
+                continue
+            fmt, b, hi, res, mb = line.split()[:5]
+            rows.append((fmt, int(b, 16), int(hi, 16), int(res, 16), int(mb, 16)))
+    return rows
+
+
+def test_golden_patterns(ref):
+    pins_golden_patterns(ref)
+
+
+def pins_golden_patterns(ref):
+    rows = _golden_rows()
+    assert len(rows) >= 18
+    for fmt, b, hi, res, mb in rows:
+        f = ref.FP16 if fmt == "fp16" else ref.BF16
+        x = np.array([b], np.uint32).view(np.float32)
+        h, r = ref.split(x, f)
+        assert (int(h[0]), int(r[0])) == (hi, res), (fmt, hex(b), hex(int(h[0])), hex(int(r[0])))
+        w = ref.merge(h, r, f)
+        assert int(w.view(np.uint32)[0]) == mb, (fmt, hex(b))
+
+
+# ---- value definition, exact rational arithmetic -------------------------
+
+FIELDS = {"bf16": (8, 7), "fp16": (5, 10)}   # exponent, stored significand bits (Table 1)
+
+
+def _expected_split_value(x: Fraction, fmt: str):
+    """(|hi| as a rational, res as an integer) from the value definition alone."""
+    ebits, mbits = FIELDS[fmt]
+    bias = (1 << (ebits - 1)) - 1
+    emin = 1 - bias
+    a = abs(x)
+    if a == 0:
+        return Fraction(0), 0
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fraction(2) ** e > a:
+        e -= 1
+    max16 = (2 - Fraction(1, 1 << mbits)) * Fraction(2) ** bias
+    if a >= Fraction(2) ** (bias + 1):
+        # beyond the 16-bit format's range: largest finite pair (only fp16 can get here)
+        return max16, (1 << (23 - mbits)) - 1
+    e16 = max(e, emin)                        # exponent of the 16-bit float's grid
+    ulp16 = Fraction(2) ** (e16 - mbits)
+    hi = (a / ulp16).__floor__() * ulp16      # round toward zero
+    # the residual counts units of 2^(23-mbits) per ulp16; in the 16-bit
+    # subnormal range x may lie below that grid and is cut
+    unit = ulp16 / (1 << (23 - mbits))
+    if fmt == "bf16":
+        # bf16 shares fp32's exponent range: fp32 subnormals sit on 2^-149 = unit
+        assert unit == Fraction(2) ** (max(e, -126) - 23)
+    res = ((a - hi) / unit).__floor__()
+    return hi, res
+
+
+def _sample_patterns(rng, n):
+    pats = list(rng.integers(0, 1 << 32, size=n, dtype=np.uint64))
+    # edges: every exponent with all-zero, all-one and single-bit fractions
+    for E in range(0, 255):
+        for M in (0, 1, 0x7FFFFF, 0x400000, 0x1FFF, 0x2000, 0xFFFF, 0x10000, 0x7FE000):
+            pats.append((E << 23) | M)
+            pats.append((1 << 31) | (E << 23) | M)
+    return [int(p) for p in pats]
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "fp16"])
+def test_split_is_round_toward_zero_plus_grid_count(ref, fmt):
+    pins_split_value_definition(ref, fmt)
+
+
+def pins_split_value_definition(ref, fmt):
+    f = ref.FP16 if fmt == "fp16" else ref.BF16
+    ebits, mbits = FIELDS[fmt]
+    rng = np.random.default_rng(12381)
+    pats = [p for p in _sample_patterns(rng, 6000) if ((p >> 23) & 0xFF) != 255]
+    x = np.array(pats, np.uint32).view(np.float32)
+    hi, res = ref.split(x, f)
+    w = ref.merge(hi, res, f)
+    for i, p in enumerate(pats):
+        xv = Fraction(float_of(p))
+        exp_hi, exp_res = _expected_split_value(xv, fmt)
+        got_hi = decode(int(hi[i]), ebits, mbits)
+        assert not isinstance(got_hi, str), hex(p)
+        assert abs(got_hi) == exp_hi, (fmt, hex(p))
+        assert (int(hi[i]) >> 15) == (p >> 31), (fmt, hex(p))        # sign kept, also on zero
+        assert int(res[i]) == exp_res, (fmt, hex(p), int(res[i]), exp_res)
+        # merge puts back exactly what the pair holds
+        e16 = max((int(hi[i]) >> mbits) & ((1 << ebits) - 1), 1) - ((1 << (ebits - 1)) - 1)
+        unit = Fraction(2) ** (e16 - 23)
+        sign = -1 if p >> 31 else 1
+        assert Fraction(float(w[i])) == sign * (exp_hi + exp_res * unit), (fmt, hex(p))
+
+
+# ---- exhaustive sweeps ---------------------------------------------------
+
+def _rtz_bf16(x):
+    """Library cast (round-to-nearest) stepped back toward zero where it overshot."""
+    t = torch.from_numpy(x)
+    h = t.to(torch.bfloat16)
+    over = (h.float().abs() > t.abs()).numpy()
+    hb = h.view(torch.int16).numpy().view(np.uint16)
+    return hb - over.astype(np.uint16)
+
+
+def _rtz_fp16(x):
+    with np.errstate(over="ignore"):
+        h = x.astype(np.float16)
+    over = np.abs(h.astype(np.float32)) > np.abs(x)
+    return h.view(np.uint16) - over.astype(np.uint16)
+
+
+def _check_bf16_chunk(ref, c):
+    b = np.arange(c * CHUNK, (c + 1) * CHUNK, dtype=np.uint64).astype(np.uint32)
+    x = b.view(np.float32)
+    hi, res = ref.split(x, ref.BF16)
+    w = ref.merge(hi, res, ref.BF16)
+    assert np.array_equal(w.view(np.uint32), b), "round trip, chunk %d" % c
+    fin = np.isfinite(x)
+    assert np.array_equal(hi[fin], _rtz_bf16(x)[fin]), "hi is not the RTZ cast, chunk %d" % c
+    # every (hi, res) pair, enumerated directly, survives merge then split
+    ph = (b >> 16).astype(np.uint16)
+    pr = (b & 0xFFFF).astype(np.uint16)
+    h2, r2 = ref.split(ref.merge(ph, pr, ref.BF16), ref.BF16)
+    assert np.array_equal(h2, ph) and np.array_equal(r2, pr), "pair round trip, chunk %d" % c
+    return True
+
+
+def test_bf16_exhaustive_all_fp32_patterns(ref):
+    with ThreadPoolExecutor(WORKERS) as ex:
+        assert all(ex.map(lambda c: _check_bf16_chunk(ref, c), range((1 << 32) // CHUNK)))
+
+
+def _check_fp16_chunk(ref, c):
+    b = np.arange(c * CHUNK, (c + 1) * CHUNK, dtype=np.uint64).astype(np.uint32)
+    x = b.view(np.float32)
+    sign = b & np.uint32(0x80000000)
+    hi, res = ref.split(x, ref.FP16)
+    w = ref.merge(hi, res, ref.FP16)
+    wb = w.view(np.uint32)
+    a = np.abs(x)
+    fin = np.isfinite(x)
+    nan = np.isnan(x)
+    assert np.all(res < 0x2000)
+    # hi is the round-toward-zero cast of x (library cast, corrected)
+    assert np.array_equal(hi[fin], _rtz_fp16(x)[fin]), "hi is not the RTZ cast, chunk %d" % c
+    # exact where the pair can hold x
+    normal = fin & (a >= np.float32(2.0 ** -14)) & (a < np.float32(65536.0))
+    assert np.array_equal(wb[normal], b[normal]), "normal range round trip, chunk %d" % c
+    # too large: largest finite pair
+    big = fin & (a >= np.float32(65536.0))
+    assert np.all(wb[big] == (sign[big] | np.uint32(0x477FFFFF)))
+    # below 2^-14: cut to a multiple of 2^-37 (exact in binary64)
+    small = a < np.float32(2.0 ** -14)
+    cut = (np.trunc(x[small].astype(np.float64) * 2.0 ** 37) / 2.0 ** 37).astype(np.float32)
+    assert np.array_equal(wb[small], cut.view(np.uint32)), "subnormal range, chunk %d" % c
+    # infinities and NaN
+    inf = np.isinf(x)
+    assert np.array_equal(wb[inf], b[inf])
+    assert np.all(np.isnan(w[nan])) and np.all((wb[nan] & np.uint32(0x80000000)) == sign[nan])
+    # what split keeps is stable: split(merge(split(x))) == split(x)
+    h2, r2 = ref.split(w, ref.FP16)
+    assert np.array_equal(h2, hi) and np.array_equal(r2, res), "idempotence, chunk %d" % c
+    return True
+
+
+def test_fp16_exhaustive_all_fp32_patterns(ref):
+    with ThreadPoolExecutor(WORKERS) as ex:
+        assert all(ex.map(lambda c: _check_fp16_chunk(ref, c), range((1 << 32) // CHUNK)))
+
+
+def _check_fp16_pairs_chunk(ref, c):
+    idx = np.arange(c * CHUNK, (c + 1) * CHUNK, dtype=np.uint64)
+    ph = (idx >> 13).astype(np.uint16)            # all 2^16 hi patterns
+    pr = (idx & 0x1FFF).astype(np.uint16)         # all 2^13 residuals
+    w = ref.merge(ph, pr, ref.FP16)
+    h2, r2 = ref.split(w, ref.FP16)
+    nonfin = (ph & 0x7C00) == 0x7C00
+    isnan = nonfin & ((ph & 0x3FF) != 0)
+    ok = ~nonfin | (~isnan & (pr == 0))           # finite pairs, and the two infinities
+    assert np.array_equal(h2[ok], ph[ok]) and np.array_equal(r2[ok], pr[ok]), "chunk %d" % c
+    assert np.all(np.isnan(w[isnan])) and np.all(np.isinf(w[nonfin & ~isnan]))
+    # the three spare residual bits are ignored by merge
+    w_spare = ref.merge(ph, pr | np.uint16(0xE000), ref.FP16)
+    assert np.array_equal(w_spare.view(np.uint32)[ok], w.view(np.uint32)[ok])
+    return True
+
+
+def test_fp16_every_pair_round_trips(ref):
+    with ThreadPoolExecutor(WORKERS) as ex:
+        assert all(ex.map(lambda c: _check_fp16_pairs_chunk(ref, c), range((1 << 29) // CHUNK)))
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "fp16"])
+def test_cvt16_matches_library_cast(ref, fmt):
+    """The gradient conversion reads every 16-bit pattern as the library does."""
+    pats = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16)
+    if fmt == "bf16":
+        lib = torch.from_numpy(pats.view(np.int16)).view(torch.bfloat16).float().numpy()
+        f = ref.BF16
+    else:
+        lib = pats.view(np.float16).astype(np.float32)
+        f = ref.FP16
+    got = ref.merge(pats, np.zeros(1 << 16, np.uint16), f)
+    nan = np.isnan(lib)
+    assert np.array_equal(got.view(np.uint32)[~nan], lib.view(np.uint32)[~nan])
+    assert np.all(np.isnan(got[nan]))
+    for p in (0x0001, 0x03FF, 0x0400, 0x3C00, 0x7BFF, 0x8001, 0xBA83, 0x3A80):
+        assert ref.cvt16(p, f) == float(lib[p])
