@@ -1,0 +1,145 @@
+#!/usr/bin/env python3
+"""Throughput of the split-precision Adam step on one MI355X.
+
+A "step" is one optimizer step over the whole synthetic model: for the default
+workload (c3, Llama-7B-shaped, 6.74 B parameters) that is one mpo_step_layer call
+per layer, last layer first, every layer reading its gradient from the one reused
+gradient buffer.  All state and the gradients are resident in HBM before the
+timed region; the timed region contains nothing but the library's launches.
+
+Prints ONE JSON line: parameters updated per second, with a `roofline` object
+(algorithmic bytes = 26 B per parameter for Adam, against 8 TB/s) and a
+`cpu_baseline` object (the CPU oracle timed on this host on a bounded sample).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBPS = 8000.0            # MI355X HBM3E, published peak
+ADAM_BYTES_PER_PARAM = 26         # read hi, res, grad (2 B each), m, v (4 B each); write hi, res, m, v
+
+
+def cpu_baseline(wl, sample_params: int, steps: int):
+    """The oracle as it stands, on host cores, on a slice of the same workload: elementwise work,
+    so a slice of one tensor is a fair sample.  Threads split the slice; each calls the C routine."""
+    import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import ref
+    from paper_2309_12381_amd import synth
+    rfmt = ref.BF16 if wl.fmt == "bf16" else ref.FP16
+    n = sample_params
+    w = synth.gen_weights(n, 99, "cpu", wl.weight_std).numpy()
+    g = synth.bits16(synth.gen_grads(n, 98, "cpu", wl.grad_std, wl.fmt, wl.loss_scale))
+    cfg = ref.AdamCfg(lr=1e-3, weight_decay=wl.weight_decay, decoupled_wd=(wl.optimizer == "adamw"),
+                      loss_scale=wl.loss_scale, weight_fmt=rfmt, grad_fmt=rfmt)
+    cores = max(1, min(16, os.cpu_count() or 1))
+    out = {}
+    for label, k in (("1", 1), ("all", cores)):
+        hi, res = ref.split(w, rfmt)
+        m = np.zeros(n, np.float32)
+        v = np.zeros(n, np.float32)
+        bounds = np.linspace(0, n, k + 1).astype(np.int64)
+
+        def run(i, t):
+            lo, up = int(bounds[i]), int(bounds[i + 1])
+            ref.adam_step(hi[lo:up], res[lo:up], g[lo:up], m[lo:up], v[lo:up], cfg, t)
+        with ThreadPoolExecutor(k) as ex:
+            list(ex.map(lambda i: run(i, 1), range(k)))          # warm the pages
+            t0 = time.perf_counter()
+            for t in range(2, 2 + steps):
+                list(ex.map(lambda i: run(i, t), range(k)))
+            dt = time.perf_counter() - t0
+        out[label] = n * steps / dt
+    return {"value": out["all"], "unit": "params/s", "cores": cores, "kind": "oracle",
+            "value_1core": out["1"],
+            "sample": "%d params of the same value distributions, %d Adam steps, oracle/mpo_ref.c as built for "
+                      "the tests, slice-parallel over %d host threads" % (n, steps, cores)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c3", choices=["c0", "c1", "c2", "c3", "c4"])
+    ap.add_argument("--fresh-grads", action="store_true",
+                    help="regenerate each layer's gradients inside the loop (adds generator kernels to the timing)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 26)
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus %d is not supported"
+              % a.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2309_12381_amd import harness, synth
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    wl = synth.workload(a.workload)
+    steps = a.steps if a.steps is not None else wl.steps
+    t_setup = time.perf_counter()
+    st = harness.ModelState(wl, dev)
+    if wl.per_layer:
+        # the reused buffer holds one (largest) layer's worth of gradient values, read by every layer
+        st.grad.normal_(0.0, wl.grad_std * wl.loss_scale, generator=synth.generator(7, dev))
+    else:
+        st.fill_grads(range(len(st.views)), 0)
+    torch.cuda.synchronize()
+    setup_s = time.perf_counter() - t_setup
+
+    stream = torch.cuda.current_stream()
+    cfg = st.adam_cfg()
+    step_no = 0
+    for _ in range(a.warmup):
+        step_no += 1
+        st.step(step_no, cfg, stream, fresh_grads=a.fresh_grads)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    launches = 0
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(steps):
+        step_no += 1
+        launches += st.step(step_no, cfg, stream, fresh_grads=a.fresh_grads)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ev_ms = ev0.elapsed_time(ev1)
+
+    P = wl.num_params
+    value = P * steps / wall
+    bytes_per_launch = ADAM_BYTES_PER_PARAM * P * steps / launches
+    achieved = ADAM_BYTES_PER_PARAM * P * steps / (ev_ms * 1e-3) / 1e9
+    res = {
+        "metric": "params updated/sec, split-precision Adam (achieved HBM GB/s and % of peak in roofline)",
+        "value": value, "unit": "params/s", "n_gpus": 1, "steps": steps, "warmup": a.warmup,
+        "ms_per_step": wall * 1e3 / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: %s" % (wl.key, wl.description), "params": P, "tensors": len(wl.tensors),
+                   "format": wl.fmt + "+16-bit residual", "optimizer": wl.optimizer, "loss_scale": wl.loss_scale,
+                   "launches_per_step": launches // steps, "per_layer": wl.per_layer,
+                   "fresh_grads_in_loop": bool(a.fresh_grads), "resident_GB": st.resident_bytes / 1e9},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                     "frac": achieved / PEAK_HBM_GBPS, "traffic": None,
+                     "kernel": "step_kernel<adam,%s>" % wl.fmt, "bytes_per_param": ADAM_BYTES_PER_PARAM,
+                     "bytes_per_launch": bytes_per_launch, "avg_launch_ms": ev_ms / launches,
+                     "event_ms": ev_ms, "launches": launches},
+        "setup_s": setup_s,
+    }
+    st.close()
+    if not a.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(wl, a.cpu_sample, 5)
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,171 @@
+/*
+ * mpo — split-precision optimizer step for AMD MI355X (gfx950).
+ *
+ * Method: arXiv 2309.12381, "Memory Efficient Mixed Precision Optimizers".
+ * A weight is stored as a 16-bit float `hi` (bf16 or fp16: what forward and
+ * backward use) plus a 16-bit residual `res` holding the significand bits an
+ * fp32 master copy would have kept (Section 3.1; field widths in Table 1).
+ * The optimizer step rebuilds the fp32 weight from (hi, res), applies Adam or
+ * SGD in fp32 with fp32 moments, and splits the result again; no fp32 copy of
+ * the weights exists.  The step can be run per layer as soon as that layer's
+ * gradient exists, so a gradient is consumed and never kept (Section 3.2).
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers on the current HIP device, owned by
+ *     the caller.  Arrays are dense, element i of every array of a tensor
+ *     belongs to parameter i.  `hi`, `res`, `grad` are uint16_t bit patterns.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = default stream).
+ *     Calls only enqueue work on that stream and return; they never wait for
+ *     the device.  The step entry points allocate nothing.
+ *   - Pointers need no particular alignment: 16-byte aligned tensors take the
+ *     128-bit path, others a slower element-wise path with identical results.
+ *   - Errors are reported by return code only and nothing is enqueued when a
+ *     call fails validation.  n == 0 and empty lists are legal no-ops.
+ *   - All arithmetic is IEEE binary32, one rounding per operation (no fused
+ *     multiply-add, correctly rounded division and square root, denormals
+ *     kept), so results are reproducible bit for bit.
+ */
+#ifndef MPO_H
+#define MPO_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MPO_OK = 0,
+    MPO_ERR_INVALID_ARG = 1, /* null pointer with n > 0, step == 0, unknown enum, bad size   */
+    MPO_ERR_UNSUPPORTED = 2, /* a mode that is declared but not built yet                    */
+    MPO_ERR_ALIAS = 3,       /* buffers that are written overlap each other or an input      */
+    MPO_ERR_HIP = 4,         /* a HIP runtime call failed (see mpo_last_hip_error)           */
+    MPO_ERR_NOMEM = 5        /* host or device allocation for a plan failed                  */
+} mpo_status;
+
+/* Format of a 16-bit float array (Table 1): bf16 = 1+8+7 bits, 16 extra bits;
+ * fp16 = 1+5+10 bits, 13 extra bits right-aligned in the 16-bit residual (its
+ * top three bits are written as zero and ignored when read). */
+typedef enum { MPO_BF16 = 0, MPO_FP16 = 1 } mpo_fmt;
+
+/* How `hi` is derived from the fp32 value.  Section 3.1: keeping the leading
+ * bits is a round-toward-zero (MPO_ROUND_TRUNC, the method's base mode).
+ * NEAREST and STOCHASTIC (Section 3.1, last paragraph) are declared for later
+ * and return MPO_ERR_UNSUPPORTED. */
+typedef enum { MPO_ROUND_TRUNC = 0, MPO_ROUND_NEAREST = 1, MPO_ROUND_STOCHASTIC = 2 } mpo_round;
+
+typedef enum { MPO_OPT_ADAM = 0, MPO_OPT_SGD = 1 } mpo_opt;
+
+/* ---- split / merge (Section 3.1, Table 1) --------------------------------
+ *
+ * mpo_split: w32[i] -> (hi[i], res[i]).  bf16: hi = upper, res = lower half of
+ * the fp32 pattern (a bijection on all 2^32 patterns).  fp16: exact for
+ * 2^-14 <= |x| < 65536 and for multiples of 2^-37 below that; other values are
+ * cut toward zero to the 2^-37 grid, finite values of 65536 or more saturate
+ * at the largest finite pair, +-inf and NaN map to fp16 +-inf / NaN.
+ * mpo_merge: the inverse, (hi[i], res[i]) -> w32[i].
+ * w32 must not overlap hi or res (MPO_ERR_ALIAS); n is a number of elements.
+ */
+mpo_status mpo_split(const float *w32, uint16_t *hi, uint16_t *res, uint64_t n,
+                     mpo_fmt fmt, mpo_round round, void *hip_stream);
+mpo_status mpo_merge(const uint16_t *hi, const uint16_t *res, float *w32, uint64_t n,
+                     mpo_fmt fmt, void *hip_stream);
+
+/* ---- parameter list -------------------------------------------------------
+ *
+ * One entry per parameter tensor.  `grad` may be NULL if gradients are only
+ * ever supplied per call (mpo_step_layer).  `v` may be NULL for a list that is
+ * only stepped with SGD, `m` (the momentum buffer) too if momentum is 0.
+ * `layer` (>= 0) groups tensors whose gradients become available together.
+ * Gradient buffers may overlap each other (one reused buffer for all layers);
+ * nothing may overlap hi, res, m or v.
+ */
+typedef struct {
+    uint16_t *hi;
+    uint16_t *res;
+    const uint16_t *grad;
+    float *m;
+    float *v;
+    uint64_t n;
+    int32_t layer;
+} mpo_tensor;
+
+/* Adam / AdamW (Section 3.1: the classic optimizer, hyper-parameters
+ * unchanged): bias-corrected moments, eps added to sqrt(v_hat); step size,
+ * corrections and decay factor are formed in double on the host and rounded to
+ * fp32 once.  decoupled_wd != 0: w *= 1 - lr*wd before the update (AdamW);
+ * else g += wd*w (L2).  Gradients arrive multiplied by loss_scale and are
+ * divided by it inside the step (Section 4.1); loss_scale must be finite, > 0.
+ */
+typedef struct {
+    double lr, beta1, beta2, eps, weight_decay;
+    int32_t decoupled_wd;
+    double loss_scale;
+    int32_t weight_fmt; /* mpo_fmt of hi   */
+    int32_t grad_fmt;   /* mpo_fmt of grad */
+    int32_t round;      /* mpo_round       */
+} mpo_adam_cfg;
+
+/* SGD with momentum (dampening 0, no Nesterov), L2 weight decay.
+ * momentum == 0 leaves m untouched. */
+typedef struct {
+    double lr, momentum, weight_decay;
+    double loss_scale;
+    int32_t weight_fmt, grad_fmt, round;
+} mpo_sgd_cfg;
+
+typedef struct mpo_plan mpo_plan;
+
+/* Section 3.1 ("Fused" optimizer: all parameters handled as one stream so one
+ * launch covers many tensors).  Validates the list, rejects overlaps, orders
+ * tensors by layer (stable), cuts them into fixed-size chunks and uploads the
+ * chunk table and tensor descriptors to the current device once.  The plan
+ * owns only that table (a few MB); free it with mpo_plan_destroy.  The list is
+ * copied: `tensors` may be freed after the call.  nt == 0 gives a valid empty
+ * plan.  mpo_plan_destroy(NULL) is a no-op. */
+mpo_status mpo_plan_create(const mpo_tensor *tensors, uint64_t nt, mpo_plan **out);
+mpo_status mpo_plan_destroy(mpo_plan *plan);
+
+/* Same validation and layout, kept on the host only (no HIP call at all): for
+ * inspecting the layout and for tests on machines without a GPU.  Step calls
+ * on such a plan return MPO_ERR_INVALID_ARG. */
+mpo_status mpo_plan_create_host(const mpo_tensor *tensors, uint64_t nt, mpo_plan **out);
+
+/* Layout queries (host side, no HIP call).  Chunks are numbered in launch
+ * order; chunk i covers elements [index*chunk_elems, min(n, (index+1)*chunk_elems))
+ * of tensor `tensor` (an index into the list given at creation). */
+uint64_t mpo_plan_chunk_elems(const mpo_plan *plan);
+uint64_t mpo_plan_num_chunks(const mpo_plan *plan);
+uint64_t mpo_plan_num_params(const mpo_plan *plan);
+mpo_status mpo_plan_get_chunk(const mpo_plan *plan, uint64_t i, uint64_t *tensor, uint64_t *index);
+/* Chunk range and parameter count of one layer; an unknown layer is MPO_ERR_INVALID_ARG. */
+mpo_status mpo_plan_layer_info(const mpo_plan *plan, int32_t layer, uint64_t *first_chunk,
+                               uint64_t *num_chunks, uint64_t *num_tensors, uint64_t *num_params);
+
+/* One optimizer step over every tensor of the plan in ONE kernel launch
+ * (Section 3.1).  `step` counts from 1 and is shared by all tensors.  Every
+ * tensor needs grad and m (and v for Adam) from plan creation. */
+mpo_status mpo_adam_step(mpo_plan *plan, const mpo_adam_cfg *cfg, uint64_t step, void *hip_stream);
+mpo_status mpo_sgd_step(mpo_plan *plan, const mpo_sgd_cfg *cfg, uint64_t step, void *hip_stream);
+
+/* Section 3.2: the step of ONE layer, to be called as soon as that layer's
+ * gradients exist, in one launch; the caller may reuse the gradient memory as
+ * soon as later work on the same stream is enqueued.  `cfg` points to an
+ * mpo_adam_cfg (opt == MPO_OPT_ADAM) or an mpo_sgd_cfg (MPO_OPT_SGD).
+ * `grads` is NULL to use the gradient pointers given at plan creation, else
+ * `ngrads` device pointers, one per tensor of that layer in the order the
+ * tensors were listed at creation (ngrads must equal the layer's tensor count
+ * and be at most MPO_MAX_LAYER_GRADS).  Stepping every layer once with the
+ * same `step` is bit-identical to one mpo_adam_step / mpo_sgd_step. */
+#define MPO_MAX_LAYER_GRADS 64
+mpo_status mpo_step_layer(mpo_plan *plan, int32_t layer, const void *const *grads, uint64_t ngrads,
+                          mpo_opt opt, const void *cfg, uint64_t step, void *hip_stream);
+
+const char *mpo_status_string(mpo_status s);
+/* hipError_t (as int) of the most recent failing HIP call on this thread, 0 if none. */
+int mpo_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MPO_H */

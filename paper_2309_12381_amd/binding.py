@@ -1,0 +1,247 @@
+"""Thin ctypes binding of libmpo.so (include/mpo.h): argument marshalling only.
+
+Function names match the C entry points.  Tensors may be given as torch
+tensors (their device pointer is taken) or as plain integer addresses.  Every
+step of the method runs inside the library's HIP kernels; there is no Python
+or CPU fallback: if the library is missing, importing this module fails.
+"""
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+from . import build as _build
+
+MPO_OK = 0
+MPO_ERR_INVALID_ARG = 1
+MPO_ERR_UNSUPPORTED = 2
+MPO_ERR_ALIAS = 3
+MPO_ERR_HIP = 4
+MPO_ERR_NOMEM = 5
+
+MPO_BF16 = 0
+MPO_FP16 = 1
+
+MPO_ROUND_TRUNC = 0
+MPO_ROUND_NEAREST = 1
+MPO_ROUND_STOCHASTIC = 2
+
+MPO_OPT_ADAM = 0
+MPO_OPT_SGD = 1
+
+MPO_MAX_LAYER_GRADS = 64
+
+
+class mpo_tensor(ctypes.Structure):
+    _fields_ = [("hi", ctypes.c_void_p), ("res", ctypes.c_void_p), ("grad", ctypes.c_void_p),
+                ("m", ctypes.c_void_p), ("v", ctypes.c_void_p), ("n", ctypes.c_uint64),
+                ("layer", ctypes.c_int32)]
+
+
+class mpo_adam_cfg(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
+                ("eps", ctypes.c_double), ("weight_decay", ctypes.c_double),
+                ("decoupled_wd", ctypes.c_int32), ("loss_scale", ctypes.c_double),
+                ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32), ("round", ctypes.c_int32)]
+
+
+class mpo_sgd_cfg(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_double), ("momentum", ctypes.c_double), ("weight_decay", ctypes.c_double),
+                ("loss_scale", ctypes.c_double),
+                ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32), ("round", ctypes.c_int32)]
+
+
+EXPORTS = {
+    "mpo_split": ([ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int,
+                   ctypes.c_int, ctypes.c_void_p], ctypes.c_int),
+    "mpo_merge": ([ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int,
+                   ctypes.c_void_p], ctypes.c_int),
+    "mpo_plan_create": ([ctypes.POINTER(mpo_tensor), ctypes.c_uint64, ctypes.POINTER(ctypes.c_void_p)], ctypes.c_int),
+    "mpo_plan_create_host": ([ctypes.POINTER(mpo_tensor), ctypes.c_uint64, ctypes.POINTER(ctypes.c_void_p)],
+                             ctypes.c_int),
+    "mpo_plan_destroy": ([ctypes.c_void_p], ctypes.c_int),
+    "mpo_plan_chunk_elems": ([ctypes.c_void_p], ctypes.c_uint64),
+    "mpo_plan_num_chunks": ([ctypes.c_void_p], ctypes.c_uint64),
+    "mpo_plan_num_params": ([ctypes.c_void_p], ctypes.c_uint64),
+    "mpo_plan_get_chunk": ([ctypes.c_void_p, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint64),
+                            ctypes.POINTER(ctypes.c_uint64)], ctypes.c_int),
+    "mpo_plan_layer_info": ([ctypes.c_void_p, ctypes.c_int32] + [ctypes.POINTER(ctypes.c_uint64)] * 4, ctypes.c_int),
+    "mpo_adam_step": ([ctypes.c_void_p, ctypes.POINTER(mpo_adam_cfg), ctypes.c_uint64, ctypes.c_void_p], ctypes.c_int),
+    "mpo_sgd_step": ([ctypes.c_void_p, ctypes.POINTER(mpo_sgd_cfg), ctypes.c_uint64, ctypes.c_void_p], ctypes.c_int),
+    "mpo_step_layer": ([ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint64,
+                        ctypes.c_int, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p], ctypes.c_int),
+    "mpo_status_string": ([ctypes.c_int], ctypes.c_char_p),
+    "mpo_last_hip_error": ([], ctypes.c_int),
+}
+
+
+def _load():
+    path = _build.LIB
+    if not os.path.exists(path):
+        # nothing built yet: build once (needs hipcc); never fall back to another implementation
+        path = _build.build()
+    lib = ctypes.CDLL(path)
+    for name, (argtypes, restype) in EXPORTS.items():
+        fn = getattr(lib, name)
+        fn.argtypes = argtypes
+        fn.restype = restype
+    return lib
+
+
+lib = _load()
+
+
+class MpoError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib.mpo_status_string(status).decode()
+        if status in (MPO_ERR_HIP, MPO_ERR_NOMEM):
+            msg += " (hipError_t %d)" % lib.mpo_last_hip_error()
+        super().__init__("%s: %s" % (where, msg))
+
+
+def _check(status: int, where: str):
+    if status != MPO_OK:
+        raise MpoError(status, where)
+
+
+def _ptr(x) -> Optional[int]:
+    """Device address of a torch tensor, or an int / None passed through."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x or None
+    return x.data_ptr() or None
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None        # torch.cuda.Stream
+
+
+@dataclass
+class AdamCfg:
+    lr: float = 1e-3
+    beta1: float = 0.9
+    beta2: float = 0.999
+    eps: float = 1e-8
+    weight_decay: float = 0.0
+    decoupled_wd: bool = True
+    loss_scale: float = 1.0
+    weight_fmt: int = MPO_BF16
+    grad_fmt: int = MPO_BF16
+    round: int = MPO_ROUND_TRUNC
+
+    def c(self) -> mpo_adam_cfg:
+        return mpo_adam_cfg(self.lr, self.beta1, self.beta2, self.eps, self.weight_decay, int(self.decoupled_wd),
+                            self.loss_scale, self.weight_fmt, self.grad_fmt, self.round)
+
+
+@dataclass
+class SgdCfg:
+    lr: float = 1e-2
+    momentum: float = 0.9
+    weight_decay: float = 0.0
+    loss_scale: float = 1.0
+    weight_fmt: int = MPO_BF16
+    grad_fmt: int = MPO_BF16
+    round: int = MPO_ROUND_TRUNC
+
+    def c(self) -> mpo_sgd_cfg:
+        return mpo_sgd_cfg(self.lr, self.momentum, self.weight_decay, self.loss_scale, self.weight_fmt,
+                           self.grad_fmt, self.round)
+
+
+def mpo_split(w32, hi, res, n: int, fmt: int = MPO_BF16, round: int = MPO_ROUND_TRUNC, stream=None):
+    _check(lib.mpo_split(_ptr(w32), _ptr(hi), _ptr(res), n, fmt, round, _stream(stream)), "mpo_split")
+
+
+def mpo_merge(hi, res, w32, n: int, fmt: int = MPO_BF16, stream=None):
+    _check(lib.mpo_merge(_ptr(hi), _ptr(res), _ptr(w32), n, fmt, _stream(stream)), "mpo_merge")
+
+
+@dataclass
+class Tensor:
+    """One parameter tensor of a plan; fields as in mpo_tensor."""
+    hi: object
+    res: object
+    grad: object
+    m: object
+    v: object
+    n: int
+    layer: int = 0
+
+
+class Plan:
+    """Owns an mpo_plan*.  Keeps references to torch tensors so their memory outlives the plan."""
+
+    def __init__(self, tensors: Sequence[Tensor], host_only: bool = False):
+        self._keep = list(tensors)
+        arr = (mpo_tensor * max(len(tensors), 1))()
+        for i, t in enumerate(tensors):
+            arr[i] = mpo_tensor(_ptr(t.hi), _ptr(t.res), _ptr(t.grad), _ptr(t.m), _ptr(t.v), t.n, t.layer)
+        handle = ctypes.c_void_p()
+        create = lib.mpo_plan_create_host if host_only else lib.mpo_plan_create
+        _check(create(arr, len(tensors), ctypes.byref(handle)), "mpo_plan_create")
+        self._h = handle
+
+    def destroy(self):
+        if self._h is not None:
+            h, self._h = self._h, None
+            _check(lib.mpo_plan_destroy(h), "mpo_plan_destroy")
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    # layout queries
+    @property
+    def chunk_elems(self) -> int:
+        return lib.mpo_plan_chunk_elems(self._h)
+
+    @property
+    def num_chunks(self) -> int:
+        return lib.mpo_plan_num_chunks(self._h)
+
+    @property
+    def num_params(self) -> int:
+        return lib.mpo_plan_num_params(self._h)
+
+    def chunk(self, i: int):
+        t, k = ctypes.c_uint64(), ctypes.c_uint64()
+        _check(lib.mpo_plan_get_chunk(self._h, i, ctypes.byref(t), ctypes.byref(k)), "mpo_plan_get_chunk")
+        return t.value, k.value
+
+    def layer_info(self, layer: int):
+        a, b, c, d = (ctypes.c_uint64() for _ in range(4))
+        _check(lib.mpo_plan_layer_info(self._h, layer, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c),
+                                       ctypes.byref(d)), "mpo_plan_layer_info")
+        return {"first_chunk": a.value, "num_chunks": b.value, "num_tensors": c.value, "num_params": d.value}
+
+
+def mpo_adam_step(plan: Plan, cfg: AdamCfg, step: int, stream=None):
+    c = cfg.c()
+    _check(lib.mpo_adam_step(plan._h, ctypes.byref(c), step, _stream(stream)), "mpo_adam_step")
+
+
+def mpo_sgd_step(plan: Plan, cfg: SgdCfg, step: int, stream=None):
+    c = cfg.c()
+    _check(lib.mpo_sgd_step(plan._h, ctypes.byref(c), step, _stream(stream)), "mpo_sgd_step")
+
+
+def mpo_step_layer(plan: Plan, layer: int, cfg, step: int, grads: Optional[Sequence] = None, stream=None):
+    """cfg is an AdamCfg or an SgdCfg; grads is None (plan's own) or one tensor/address per tensor of the layer."""
+    opt = MPO_OPT_ADAM if isinstance(cfg, AdamCfg) else MPO_OPT_SGD
+    c = cfg.c()
+    if grads is None:
+        gp, ng = None, 0
+    else:
+        ng = len(grads)
+        gp = (ctypes.c_void_p * max(ng, 1))(*[_ptr(g) for g in grads])
+    _check(lib.mpo_step_layer(plan._h, layer, gp, ng, opt, ctypes.cast(ctypes.byref(c), ctypes.c_void_p), step,
+                              _stream(stream)), "mpo_step_layer")

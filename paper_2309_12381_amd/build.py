@@ -1,0 +1,47 @@
+"""Build libmpo.so (hand-written HIP for gfx950 + the C entry points) in-tree with hipcc."""
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libmpo.so")
+SOURCES = [os.path.join(CSRC, "mpo_host.cpp"), os.path.join(CSRC, "mpo_kernels.hip")]
+HEADERS = [os.path.join(CSRC, "mpo_internal.h"), os.path.join(ROOT, "include", "mpo.h")]
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+
+# One IEEE operation per source-level operation: no contraction into FMA, correctly rounded
+# division and square root, denormals kept; no fast-math anywhere.  Packed fp32 VALU forms are
+# switched off (the compiler would otherwise pair independent fp32 operations).
+FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt", "-fno-fast-math",
+    "-fno-gpu-flush-denormals-to-zero",
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wextra", "-Wno-unused-command-line-argument",
+    "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+]
+
+
+def needs_build() -> bool:
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS)
+
+
+def build(force: bool = False, extra=(), out: str = LIB) -> str:
+    """Compile the library.  `extra` adds compiler flags (tuning macros) for experiments."""
+    if not force and out == LIB and not needs_build():
+        return out
+    tmp = out + ".tmp.%d" % os.getpid()
+    cmd = [HIPCC, *FLAGS, *extra, "-x", "hip", *SOURCES, "-o", tmp]
+    subprocess.check_call(cmd)
+    os.replace(tmp, out)
+    return out
+
+
+if __name__ == "__main__":
+    print(build(force=True, extra=sys.argv[1:]))

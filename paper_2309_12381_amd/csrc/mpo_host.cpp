@@ -1,0 +1,441 @@
+/*
+ * Host side of libmpo: the C entry points declared in include/mpo.h.
+ * Argument validation, overlap detection, the multi-tensor plan (layer order,
+ * chunk table, descriptors) and the per-step scalars.  No arithmetic on
+ * parameters happens here; every step of the method runs in mpo_kernels.hip.
+ */
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include <hip/hip_runtime_api.h>
+
+#include "mpo_internal.h"
+
+using namespace mpo;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+mpo_status hip_fail(hipError_t e)
+{
+    g_last_hip_error = (int)e;
+    return e == hipErrorOutOfMemory ? MPO_ERR_NOMEM : MPO_ERR_HIP;
+}
+
+bool valid_fmt(int f) { return f == MPO_BF16 || f == MPO_FP16; }
+
+/* MPO_OK for the mode that is built, UNSUPPORTED for the declared ones. */
+mpo_status check_round(int r)
+{
+    if (r == MPO_ROUND_TRUNC) return MPO_OK;
+    if (r == MPO_ROUND_NEAREST || r == MPO_ROUND_STOCHASTIC) return MPO_ERR_UNSUPPORTED;
+    return MPO_ERR_INVALID_ARG;
+}
+
+constexpr uint64_t kMaxElems = 1ull << 48; /* keeps every byte count far from overflow */
+
+struct Range {
+    uintptr_t lo, hi; /* [lo, hi) in bytes */
+    bool written;
+};
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+/* True if some written range overlaps any other range.  Read-only ranges
+ * (gradients) may overlap each other: one buffer reused for every layer. */
+bool has_conflict(std::vector<Range> &r)
+{
+    std::sort(r.begin(), r.end(), [](const Range &a, const Range &b) { return a.lo < b.lo; });
+    /* sweep: furthest end seen so far among all ranges and among written ranges */
+    uintptr_t end_any = 0, end_written = 0;
+    bool first = true;
+    for (const Range &x : r) {
+        if (x.lo == x.hi) continue;
+        if (!first) {
+            if (x.written && x.lo < end_any) return true;
+            if (!x.written && x.lo < end_written) return true;
+        }
+        first = false;
+        end_any = std::max(end_any, x.hi);
+        if (x.written) end_written = std::max(end_written, x.hi);
+    }
+    return false;
+}
+
+struct LayerInfo {
+    int32_t id;
+    uint64_t first_tensor, num_tensors; /* in layer order */
+    uint64_t first_chunk, num_chunks;
+    uint64_t num_params;
+};
+
+} // namespace
+
+struct mpo_plan {
+    std::vector<TensorDesc> descs;      /* layer order */
+    std::vector<uint64_t> caller_index; /* layer order -> index in the caller's list */
+    std::vector<Chunk> chunks;
+    std::vector<LayerInfo> layers;      /* sorted by id */
+    uint64_t num_params = 0;
+    bool all_have_grad = true, all_have_m = true, all_have_v = true;
+    bool on_device = false;
+    int device = -1;
+    TensorDesc *d_descs = nullptr;
+    Chunk *d_chunks = nullptr;
+};
+
+namespace {
+
+mpo_status build_plan(const mpo_tensor *tensors, uint64_t nt, mpo_plan **out)
+{
+    if (!out) return MPO_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (nt > 0 && !tensors) return MPO_ERR_INVALID_ARG;
+    if (nt > 0xFFFFFFFFull) return MPO_ERR_INVALID_ARG;
+
+    std::vector<Range> ranges;
+    try {
+        ranges.reserve(nt * 5);
+    } catch (const std::bad_alloc &) {
+        return MPO_ERR_NOMEM;
+    }
+    for (uint64_t i = 0; i < nt; ++i) {
+        const mpo_tensor &t = tensors[i];
+        if (t.layer < 0) return MPO_ERR_INVALID_ARG;
+        if (t.n > kMaxElems) return MPO_ERR_INVALID_ARG;
+        if (t.n == 0) continue;
+        if (!t.hi || !t.res) return MPO_ERR_INVALID_ARG;
+        auto add = [&](const void *p, uint64_t bytes, bool written) {
+            const uintptr_t lo = reinterpret_cast<uintptr_t>(p);
+            ranges.push_back(Range{lo, lo + bytes, written});
+        };
+        add(t.hi, t.n * 2, true);
+        add(t.res, t.n * 2, true);
+        if (t.grad) add(t.grad, t.n * 2, false);
+        if (t.m) add(t.m, t.n * 4, true);
+        if (t.v) add(t.v, t.n * 4, true);
+    }
+    if (has_conflict(ranges)) return MPO_ERR_ALIAS;
+
+    mpo_plan *p = new (std::nothrow) mpo_plan;
+    if (!p) return MPO_ERR_NOMEM;
+    try {
+        /* stable order by layer: a layer's tensors and chunks are contiguous */
+        std::vector<uint64_t> order(nt);
+        for (uint64_t i = 0; i < nt; ++i) order[i] = i;
+        std::stable_sort(order.begin(), order.end(),
+                         [&](uint64_t a, uint64_t b) { return tensors[a].layer < tensors[b].layer; });
+        p->descs.reserve(nt);
+        p->caller_index = order;
+        for (uint64_t k = 0; k < nt; ++k) {
+            const mpo_tensor &t = tensors[order[k]];
+            TensorDesc d;
+            std::memset(&d, 0, sizeof d);
+            d.hi = t.hi; d.res = t.res; d.grad = t.grad; d.m = t.m; d.v = t.v; d.n = t.n;
+            if (aligned16(t.hi) && aligned16(t.res) && aligned16(t.m) && aligned16(t.v)) d.flags |= kStateAligned;
+            if (t.grad && aligned16(t.grad)) d.flags |= kGradAligned;
+            p->descs.push_back(d);
+            if (t.n) {
+                p->all_have_grad &= t.grad != nullptr;
+                p->all_have_m &= t.m != nullptr;
+                p->all_have_v &= t.v != nullptr;
+            }
+            if (p->layers.empty() || p->layers.back().id != t.layer)
+                p->layers.push_back(LayerInfo{t.layer, k, 0, (uint64_t)p->chunks.size(), 0, 0});
+            LayerInfo &L = p->layers.back();
+            const uint64_t nc = (t.n + kChunkElems - 1) / kChunkElems;
+            if (nc > 0xFFFFFFFFull) { delete p; return MPO_ERR_INVALID_ARG; }
+            for (uint64_t c = 0; c < nc; ++c) p->chunks.push_back(Chunk{(uint32_t)k, (uint32_t)c});
+            L.num_tensors += 1;
+            L.num_chunks += nc;
+            L.num_params += t.n;
+            p->num_params += t.n;
+        }
+    } catch (const std::bad_alloc &) {
+        delete p;
+        return MPO_ERR_NOMEM;
+    }
+    *out = p;
+    return MPO_OK;
+}
+
+const LayerInfo *find_layer(const mpo_plan *p, int32_t layer)
+{
+    auto it = std::lower_bound(p->layers.begin(), p->layers.end(), layer,
+                               [](const LayerInfo &L, int32_t id) { return L.id < id; });
+    return (it != p->layers.end() && it->id == layer) ? &*it : nullptr;
+}
+
+bool finite_pos(double x) { return std::isfinite(x) && x > 0.0; }
+
+/* Adam scalars: formed in double, rounded to fp32 once (Section 3.1: classic Adam). */
+mpo_status adam_scalars(const mpo_adam_cfg *c, uint64_t step, StepLaunch &L)
+{
+    if (!c || step == 0) return MPO_ERR_INVALID_ARG;
+    if (!valid_fmt(c->weight_fmt) || !valid_fmt(c->grad_fmt)) return MPO_ERR_INVALID_ARG;
+    const mpo_status rs = check_round(c->round);
+    if (rs != MPO_OK) return rs;
+    if (!std::isfinite(c->lr) || !std::isfinite(c->eps) || !std::isfinite(c->weight_decay)) return MPO_ERR_INVALID_ARG;
+    if (!(c->beta1 >= 0.0 && c->beta1 < 1.0) || !(c->beta2 >= 0.0 && c->beta2 < 1.0)) return MPO_ERR_INVALID_ARG;
+    if (!finite_pos(c->loss_scale)) return MPO_ERR_INVALID_ARG;
+    const double t = (double)step;
+    const double bc1 = 1.0 - std::pow(c->beta1, t);
+    const double bc2 = 1.0 - std::pow(c->beta2, t);
+    StepScalars &s = L.s;
+    std::memset(&s, 0, sizeof s);
+    s.B1 = (float)c->beta1;
+    s.B2 = (float)c->beta2;
+    s.O1 = (float)(1.0 - c->beta1);
+    s.O2 = (float)(1.0 - c->beta2);
+    s.SS = (float)(c->lr / bc1);
+    s.SQ = (float)std::sqrt(bc2);
+    s.EPS = (float)c->eps;
+    s.DEC = (float)(1.0 - c->lr * c->weight_decay);
+    s.WD = (float)c->weight_decay;
+    s.IS = (float)(1.0 / c->loss_scale);
+    L.opt = MPO_OPT_ADAM;
+    L.wfmt = c->weight_fmt;
+    L.gfmt = c->grad_fmt;
+    L.decay = c->weight_decay == 0.0 ? kNoDecay : (c->decoupled_wd ? kDecoupled : kL2);
+    L.momentum = 1;
+    return MPO_OK;
+}
+
+mpo_status sgd_scalars(const mpo_sgd_cfg *c, uint64_t step, StepLaunch &L)
+{
+    if (!c || step == 0) return MPO_ERR_INVALID_ARG;
+    if (!valid_fmt(c->weight_fmt) || !valid_fmt(c->grad_fmt)) return MPO_ERR_INVALID_ARG;
+    const mpo_status rs = check_round(c->round);
+    if (rs != MPO_OK) return rs;
+    if (!std::isfinite(c->lr) || !std::isfinite(c->momentum) || !std::isfinite(c->weight_decay)) return MPO_ERR_INVALID_ARG;
+    if (!finite_pos(c->loss_scale)) return MPO_ERR_INVALID_ARG;
+    StepScalars &s = L.s;
+    std::memset(&s, 0, sizeof s);
+    s.LR = (float)c->lr;
+    s.MU = (float)c->momentum;
+    s.WD = (float)c->weight_decay;
+    s.IS = (float)(1.0 / c->loss_scale);
+    L.opt = MPO_OPT_SGD;
+    L.wfmt = c->weight_fmt;
+    L.gfmt = c->grad_fmt;
+    L.decay = c->weight_decay == 0.0 ? kNoDecay : kL2;
+    L.momentum = c->momentum != 0.0;
+    return MPO_OK;
+}
+
+/* Buffers the chosen optimizer needs, over tensors [k0, k0+nk) in layer order. */
+bool state_present(const mpo_plan *p, uint64_t k0, uint64_t nk, const StepLaunch &L, bool need_plan_grad)
+{
+    const bool need_m = L.opt == MPO_OPT_ADAM || L.momentum;
+    const bool need_v = L.opt == MPO_OPT_ADAM;
+    for (uint64_t k = k0; k < k0 + nk; ++k) {
+        const TensorDesc &d = p->descs[k];
+        if (d.n == 0) continue;
+        if (need_m && !d.m) return false;
+        if (need_v && !d.v) return false;
+        if (need_plan_grad && !d.grad) return false;
+    }
+    return true;
+}
+
+mpo_status run(mpo_plan *p, StepLaunch &L, void *stream)
+{
+    L.descs = p->d_descs;
+    L.chunks = p->d_chunks;
+    L.stream = static_cast<hipStream_t>(stream);
+    const hipError_t e = launch_step(L);
+    return e == hipSuccess ? MPO_OK : hip_fail(e);
+}
+
+mpo_status step_all(mpo_plan *p, StepLaunch &L, void *stream)
+{
+    if (!p || !p->on_device) return MPO_ERR_INVALID_ARG;
+    if (!state_present(p, 0, p->descs.size(), L, true)) return MPO_ERR_INVALID_ARG;
+    L.first_chunk = 0;
+    L.num_chunks = p->chunks.size();
+    std::memset(&L.ov, 0, sizeof L.ov);
+    return run(p, L, stream);
+}
+
+} // namespace
+
+extern "C" {
+
+mpo_status mpo_split(const float *w32, uint16_t *hi, uint16_t *res, uint64_t n, mpo_fmt fmt, mpo_round round,
+                     void *hip_stream)
+{
+    if (!valid_fmt(fmt)) return MPO_ERR_INVALID_ARG;
+    const mpo_status rs = check_round(round);
+    if (rs != MPO_OK) return rs;
+    if (n > kMaxElems) return MPO_ERR_INVALID_ARG;
+    if (n == 0) return MPO_OK;
+    if (!w32 || !hi || !res) return MPO_ERR_INVALID_ARG;
+    std::vector<Range> r;
+    const uintptr_t a = (uintptr_t)w32, b = (uintptr_t)hi, c = (uintptr_t)res;
+    r.push_back(Range{a, a + n * 4, false});
+    r.push_back(Range{b, b + n * 2, true});
+    r.push_back(Range{c, c + n * 2, true});
+    if (has_conflict(r)) return MPO_ERR_ALIAS;
+    const hipError_t e = launch_split(w32, hi, res, n, fmt, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MPO_OK : hip_fail(e);
+}
+
+mpo_status mpo_merge(const uint16_t *hi, const uint16_t *res, float *w32, uint64_t n, mpo_fmt fmt, void *hip_stream)
+{
+    if (!valid_fmt(fmt)) return MPO_ERR_INVALID_ARG;
+    if (n > kMaxElems) return MPO_ERR_INVALID_ARG;
+    if (n == 0) return MPO_OK;
+    if (!w32 || !hi || !res) return MPO_ERR_INVALID_ARG;
+    std::vector<Range> r;
+    const uintptr_t a = (uintptr_t)w32, b = (uintptr_t)hi, c = (uintptr_t)res;
+    r.push_back(Range{a, a + n * 4, true});
+    r.push_back(Range{b, b + n * 2, false});
+    r.push_back(Range{c, c + n * 2, false});
+    if (has_conflict(r)) return MPO_ERR_ALIAS;
+    const hipError_t e = launch_merge(hi, res, w32, n, fmt, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MPO_OK : hip_fail(e);
+}
+
+mpo_status mpo_plan_create_host(const mpo_tensor *tensors, uint64_t nt, mpo_plan **out)
+{
+    return build_plan(tensors, nt, out);
+}
+
+mpo_status mpo_plan_create(const mpo_tensor *tensors, uint64_t nt, mpo_plan **out)
+{
+    mpo_plan *p = nullptr;
+    const mpo_status s = build_plan(tensors, nt, &p);
+    if (s != MPO_OK) return s;
+    hipError_t e = hipGetDevice(&p->device);
+    if (e == hipSuccess && !p->descs.empty())
+        e = hipMalloc(reinterpret_cast<void **>(&p->d_descs), p->descs.size() * sizeof(TensorDesc));
+    if (e == hipSuccess && !p->chunks.empty())
+        e = hipMalloc(reinterpret_cast<void **>(&p->d_chunks), p->chunks.size() * sizeof(Chunk));
+    if (e == hipSuccess && !p->descs.empty())
+        e = hipMemcpy(p->d_descs, p->descs.data(), p->descs.size() * sizeof(TensorDesc), hipMemcpyHostToDevice);
+    if (e == hipSuccess && !p->chunks.empty())
+        e = hipMemcpy(p->d_chunks, p->chunks.data(), p->chunks.size() * sizeof(Chunk), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        if (p->d_descs) (void)hipFree(p->d_descs);
+        if (p->d_chunks) (void)hipFree(p->d_chunks);
+        delete p;
+        *out = nullptr;
+        return hip_fail(e);
+    }
+    p->on_device = true;
+    *out = p;
+    return MPO_OK;
+}
+
+mpo_status mpo_plan_destroy(mpo_plan *p)
+{
+    if (!p) return MPO_OK;
+    mpo_status s = MPO_OK;
+    if (p->d_descs) { const hipError_t e = hipFree(p->d_descs); if (e != hipSuccess) s = hip_fail(e); }
+    if (p->d_chunks) { const hipError_t e = hipFree(p->d_chunks); if (e != hipSuccess) s = hip_fail(e); }
+    delete p;
+    return s;
+}
+
+uint64_t mpo_plan_chunk_elems(const mpo_plan *) { return kChunkElems; }
+uint64_t mpo_plan_num_chunks(const mpo_plan *p) { return p ? p->chunks.size() : 0; }
+uint64_t mpo_plan_num_params(const mpo_plan *p) { return p ? p->num_params : 0; }
+
+mpo_status mpo_plan_get_chunk(const mpo_plan *p, uint64_t i, uint64_t *tensor, uint64_t *index)
+{
+    if (!p || !tensor || !index || i >= p->chunks.size()) return MPO_ERR_INVALID_ARG;
+    *tensor = p->caller_index[p->chunks[i].tensor];
+    *index = p->chunks[i].index;
+    return MPO_OK;
+}
+
+mpo_status mpo_plan_layer_info(const mpo_plan *p, int32_t layer, uint64_t *first_chunk, uint64_t *num_chunks,
+                               uint64_t *num_tensors, uint64_t *num_params)
+{
+    if (!p) return MPO_ERR_INVALID_ARG;
+    const LayerInfo *L = find_layer(p, layer);
+    if (!L) return MPO_ERR_INVALID_ARG;
+    if (first_chunk) *first_chunk = L->first_chunk;
+    if (num_chunks) *num_chunks = L->num_chunks;
+    if (num_tensors) *num_tensors = L->num_tensors;
+    if (num_params) *num_params = L->num_params;
+    return MPO_OK;
+}
+
+mpo_status mpo_adam_step(mpo_plan *p, const mpo_adam_cfg *cfg, uint64_t step, void *hip_stream)
+{
+    StepLaunch L;
+    const mpo_status s = adam_scalars(cfg, step, L);
+    if (s != MPO_OK) return s;
+    return step_all(p, L, hip_stream);
+}
+
+mpo_status mpo_sgd_step(mpo_plan *p, const mpo_sgd_cfg *cfg, uint64_t step, void *hip_stream)
+{
+    StepLaunch L;
+    const mpo_status s = sgd_scalars(cfg, step, L);
+    if (s != MPO_OK) return s;
+    return step_all(p, L, hip_stream);
+}
+
+mpo_status mpo_step_layer(mpo_plan *p, int32_t layer, const void *const *grads, uint64_t ngrads, mpo_opt opt,
+                          const void *cfg, uint64_t step, void *hip_stream)
+{
+    StepLaunch L;
+    mpo_status s;
+    if (opt == MPO_OPT_ADAM) s = adam_scalars(static_cast<const mpo_adam_cfg *>(cfg), step, L);
+    else if (opt == MPO_OPT_SGD) s = sgd_scalars(static_cast<const mpo_sgd_cfg *>(cfg), step, L);
+    else return MPO_ERR_INVALID_ARG;
+    if (s != MPO_OK) return s;
+    if (!p || !p->on_device) return MPO_ERR_INVALID_ARG;
+    const LayerInfo *info = find_layer(p, layer);
+    if (!info) return MPO_ERR_INVALID_ARG;
+    std::memset(&L.ov, 0, sizeof L.ov);
+    if (grads) {
+        if (ngrads != info->num_tensors) return MPO_ERR_INVALID_ARG;
+        if (ngrads > MPO_MAX_LAYER_GRADS) return MPO_ERR_UNSUPPORTED;
+        /* per-call gradients must not overlap anything this layer writes */
+        std::vector<Range> r;
+        for (uint64_t k = 0; k < ngrads; ++k) {
+            const TensorDesc &d = p->descs[info->first_tensor + k];
+            if (d.n == 0) continue;
+            if (!grads[k]) return MPO_ERR_INVALID_ARG;
+            const uintptr_t g = (uintptr_t)grads[k];
+            r.push_back(Range{g, g + d.n * 2, false});
+            r.push_back(Range{(uintptr_t)d.hi, (uintptr_t)d.hi + d.n * 2, true});
+            r.push_back(Range{(uintptr_t)d.res, (uintptr_t)d.res + d.n * 2, true});
+            if (d.m) r.push_back(Range{(uintptr_t)d.m, (uintptr_t)d.m + d.n * 4, true});
+            if (d.v) r.push_back(Range{(uintptr_t)d.v, (uintptr_t)d.v + d.n * 4, true});
+            L.ov.ptr[k] = static_cast<const uint16_t *>(grads[k]);
+            if (!aligned16(grads[k])) L.ov.misaligned |= 1ull << k;
+        }
+        if (has_conflict(r)) return MPO_ERR_ALIAS;
+        L.ov.first = (uint32_t)info->first_tensor;
+        L.ov.enabled = 1;
+    }
+    if (!state_present(p, info->first_tensor, info->num_tensors, L, grads == nullptr)) return MPO_ERR_INVALID_ARG;
+    L.first_chunk = info->first_chunk;
+    L.num_chunks = info->num_chunks;
+    return run(p, L, hip_stream);
+}
+
+const char *mpo_status_string(mpo_status s)
+{
+    switch (s) {
+    case MPO_OK: return "ok";
+    case MPO_ERR_INVALID_ARG: return "invalid argument";
+    case MPO_ERR_UNSUPPORTED: return "mode declared but not built";
+    case MPO_ERR_ALIAS: return "buffers overlap";
+    case MPO_ERR_HIP: return "HIP runtime error";
+    case MPO_ERR_NOMEM: return "out of memory";
+    }
+    return "unknown status";
+}
+
+int mpo_last_hip_error(void) { return g_last_hip_error; }
+
+} // extern "C"

@@ -1,0 +1,80 @@
+/* Shared between the host side (mpo_host.cpp) and the kernels (mpo_kernels.hip)
+ * of libmpo.  Not part of the public interface (see include/mpo.h). */
+#ifndef MPO_INTERNAL_H
+#define MPO_INTERNAL_H
+
+#include <hip/hip_runtime_api.h>
+#include <stdint.h>
+
+#include "mpo.h"
+
+namespace mpo {
+
+/* One workgroup (256 lanes = 4 wavefronts of 64) owns one chunk. */
+constexpr uint32_t kBlock = 256;
+constexpr uint32_t kChunkElems = 8192;
+
+/* Bits of TensorDesc::flags. */
+constexpr uint32_t kStateAligned = 1u; /* hi, res, m, v all 16-byte aligned          */
+constexpr uint32_t kGradAligned = 2u;  /* the plan's own grad pointer 16-byte aligned */
+
+struct TensorDesc {
+    uint16_t *hi;
+    uint16_t *res;
+    const uint16_t *grad;
+    float *m;
+    float *v;
+    uint64_t n;
+    uint32_t flags;
+    uint32_t pad;
+};
+static_assert(sizeof(TensorDesc) == 56, "descriptor layout is read by the kernels");
+
+/* Chunk table entry: which tensor (index into the plan's layer-ordered
+ * descriptor array) and which chunk of it. */
+struct Chunk {
+    uint32_t tensor;
+    uint32_t index;
+};
+
+/* Scalars of one step, already rounded to fp32 on the host (Section 3.1:
+ * the classic optimizers).  Adam uses all but LR/MU; SGD uses LR, MU, WD, IS. */
+struct StepScalars {
+    float B1, B2, O1, O2; /* beta1, beta2, 1-beta1, 1-beta2                      */
+    float SS, SQ, EPS;    /* lr/(1-beta1^t), sqrt(1-beta2^t), eps                */
+    float DEC, WD, IS;    /* 1-lr*wd, wd, 1/loss_scale                           */
+    float LR, MU;         /* SGD learning rate and momentum                      */
+};
+
+/* Per-call gradient pointers for one layer (Section 3.2), passed by value. */
+struct GradOverride {
+    const uint16_t *ptr[MPO_MAX_LAYER_GRADS];
+    uint64_t misaligned; /* bit i set: ptr[i] is not 16-byte aligned            */
+    uint32_t first;      /* descriptor index of the layer's first tensor        */
+    uint32_t enabled;
+};
+
+enum Decay { kNoDecay = 0, kDecoupled = 1, kL2 = 2 };
+
+struct StepLaunch {
+    const TensorDesc *descs; /* device */
+    const Chunk *chunks;     /* device */
+    uint64_t first_chunk, num_chunks;
+    int opt;      /* mpo_opt */
+    int wfmt;     /* mpo_fmt of hi   */
+    int gfmt;     /* mpo_fmt of grad */
+    int decay;    /* Decay           */
+    int momentum; /* SGD: momentum != 0 */
+    StepScalars s;
+    GradOverride ov;
+    hipStream_t stream;
+};
+
+hipError_t launch_step(const StepLaunch &L);
+hipError_t launch_split(const float *w32, uint16_t *hi, uint16_t *res, uint64_t n, int fmt,
+                        hipStream_t stream);
+hipError_t launch_merge(const uint16_t *hi, const uint16_t *res, float *w32, uint64_t n, int fmt,
+                        hipStream_t stream);
+
+} // namespace mpo
+#endif

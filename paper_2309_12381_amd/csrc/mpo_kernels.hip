@@ -1,0 +1,513 @@
+/*
+ * mpo kernels for gfx950 (MI355X): split, merge and the fused optimizer step.
+ *
+ * arXiv 2309.12381, Section 3.1: each weight is a 16-bit float plus the
+ * significand bits an fp32 copy would have kept; the update runs in fp32 and
+ * both parts are written back.  Here the whole step (merge, un-scale, decay,
+ * moments, update, split) is ONE pass over memory: per parameter it reads
+ * hi, res, grad (2 B each) and m, v (4 B each) and writes hi, res, m, v:
+ * 26 B for Adam, 18 B for SGD with momentum.  Nothing is a contraction, so
+ * there is no MFMA; the work is bounded by HBM bandwidth and by plain VALU
+ * issue (two IEEE divisions and a square root per parameter).
+ *
+ * Mapping: one workgroup of 256 lanes (4 wavefronts of 64) per chunk of 8192
+ * consecutive parameters of one tensor; the chunk table lets one launch cover
+ * every tensor of a list (Section 3.1, "Fused" optimizer).  A lane owns
+ * MPO_EPL consecutive parameters per row, so every load and store is 64 or 128
+ * bits per lane and dense across the wavefront.  MPO_BATCH rows are loaded
+ * before any arithmetic to keep several requests per lane in flight.
+ *
+ * Built with -ffp-contract=off and correctly rounded division / square root:
+ * every line of arithmetic below is one IEEE binary32 operation.
+ */
+#include <hip/hip_runtime.h>
+
+#include "mpo_internal.h"
+
+#ifndef MPO_EPL
+#define MPO_EPL 8 /* parameters per lane per row: 8 (128-bit 16-bit-array accesses) or 4 */
+#endif
+#ifndef MPO_BATCH
+#define MPO_BATCH 2 /* rows loaded together */
+#endif
+#ifndef MPO_NT_LOAD
+#define MPO_NT_LOAD 0
+#endif
+#ifndef MPO_NT_STORE
+#define MPO_NT_STORE 0
+#endif
+
+namespace mpo {
+namespace {
+
+constexpr int EPL = MPO_EPL;
+constexpr int ROWS = kChunkElems / (kBlock * EPL);
+constexpr int BATCH = MPO_BATCH;
+static_assert(EPL == 4 || EPL == 8, "a lane owns 4 or 8 parameters per row");
+static_assert(ROWS % BATCH == 0, "rows per chunk must be a multiple of the batch");
+
+/* Every parameter array lives in device (global) memory.  Saying so lets the
+ * compiler emit global_load/global_store instead of flat accesses for pointers
+ * that were read from a descriptor. */
+#define MPO_GLOBAL __attribute__((address_space(1)))
+typedef MPO_GLOBAL uint16_t *gu16p;
+typedef const MPO_GLOBAL uint16_t *gcu16p;
+typedef MPO_GLOBAL float *gf32p;
+typedef const MPO_GLOBAL float *gcf32p;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <int NDW> struct DwVec;
+template <> struct DwVec<4> { typedef u32x4 T; };
+template <> struct DwVec<2> { typedef u32x2 T; };
+
+/* EPL 16-bit values = EPL/2 dwords in one access. */
+__device__ __forceinline__ void load16(gcu16p p, uint32_t (&out)[EPL / 2])
+{
+    typedef DwVec<EPL / 2>::T T;
+    const MPO_GLOBAL T *q = reinterpret_cast<const MPO_GLOBAL T *>(p);
+    T x = MPO_NT_LOAD ? __builtin_nontemporal_load(q) : *q;
+#pragma unroll
+    for (int i = 0; i < EPL / 2; ++i) out[i] = x[i];
+}
+
+__device__ __forceinline__ void store16(gu16p p, const uint32_t (&in)[EPL / 2])
+{
+    typedef DwVec<EPL / 2>::T T;
+    T x;
+#pragma unroll
+    for (int i = 0; i < EPL / 2; ++i) x[i] = in[i];
+    MPO_GLOBAL T *q = reinterpret_cast<MPO_GLOBAL T *>(p);
+    if (MPO_NT_STORE) __builtin_nontemporal_store(x, q); else *q = x;
+}
+
+__device__ __forceinline__ void load32(gcf32p p, float (&out)[EPL])
+{
+    const MPO_GLOBAL f32x4 *q = reinterpret_cast<const MPO_GLOBAL f32x4 *>(p);
+#pragma unroll
+    for (int k = 0; k < EPL / 4; ++k) {
+        f32x4 x = MPO_NT_LOAD ? __builtin_nontemporal_load(q + k) : q[k];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) out[4 * k + i] = x[i];
+    }
+}
+
+__device__ __forceinline__ void store32(gf32p p, const float (&in)[EPL])
+{
+    MPO_GLOBAL f32x4 *q = reinterpret_cast<MPO_GLOBAL f32x4 *>(p);
+#pragma unroll
+    for (int k = 0; k < EPL / 4; ++k) {
+        f32x4 x;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] = in[4 * k + i];
+        if (MPO_NT_STORE) __builtin_nontemporal_store(x, q + k); else q[k] = x;
+    }
+}
+
+/* ---- formats (Table 1; Section 3.1) --------------------------------------
+ * Both 16-bit values travel in the low half of a dword. */
+
+template <int FMT> __device__ __forceinline__ float merge16(uint32_t hi, uint32_t res);
+template <int FMT> __device__ __forceinline__ void split32(float w, uint32_t &hi, uint32_t &res);
+template <int FMT> __device__ __forceinline__ float cvt16(uint32_t x);
+
+/* bf16 is the upper half of an fp32 pattern, the residual the lower half. */
+template <> __device__ __forceinline__ float merge16<MPO_BF16>(uint32_t hi, uint32_t res)
+{
+    return __uint_as_float((hi << 16) | res);
+}
+template <> __device__ __forceinline__ void split32<MPO_BF16>(float w, uint32_t &hi, uint32_t &res)
+{
+    const uint32_t b = __float_as_uint(w);
+    hi = b >> 16;
+    res = b & 0xFFFFu;
+}
+template <> __device__ __forceinline__ float cvt16<MPO_BF16>(uint32_t x)
+{
+    return __uint_as_float(x << 16);
+}
+
+/* fp16 + 13 extra bits.  P = (hi without sign) << 13 | res is a 28-bit payload:
+ * 5 exponent bits above a 23-bit fraction, i.e. an fp32 magnitude with the
+ * exponent re-biased by 112.  Exponent 0 holds fp16 subnormals: P then counts
+ * units of 2^-37.  Exponent 31 is infinity / NaN. */
+template <> __device__ __forceinline__ float merge16<MPO_FP16>(uint32_t hi, uint32_t res)
+{
+    const uint32_t sign = (hi & 0x8000u) << 16;
+    const uint32_t P = ((hi & 0x7FFFu) << 13) | (res & 0x1FFFu);
+    const uint32_t E = (hi >> 10) & 31u;
+    const uint32_t k = hi & 0x3FFu;
+    const uint32_t normal = P + 0x38000000u;                  /* exponent + 112 */
+    const float sub = (float)P * 0x1p-37f;                    /* exact: P < 2^23 when E == 0 */
+    const uint32_t nonfinite = 0x7F800000u | (k ? (0x00400000u | (k << 13)) : 0u);
+    uint32_t mag = normal;
+    mag = (E == 0u) ? __float_as_uint(sub) : mag;
+    mag = (E == 31u) ? nonfinite : mag;
+    return __uint_as_float(sign | mag);
+}
+template <> __device__ __forceinline__ void split32<MPO_FP16>(float w, uint32_t &hi, uint32_t &res)
+{
+    const uint32_t b = __float_as_uint(w);
+    const uint32_t sign = (b >> 16) & 0x8000u;
+    const uint32_t a = b & 0x7FFFFFFFu;
+    const uint32_t E = a >> 23;
+    /* below 2^-14: shift the 24-bit significand down to the 2^-37 grid, toward zero */
+    const uint32_t sh = 113u - E;
+    const uint32_t sig = (a & 0x7FFFFFu) | 0x800000u;
+    const uint32_t F = (E == 0u || sh >= 24u) ? 0u : (sig >> (sh & 31u));
+    uint32_t P = (a >= 0x38800000u) ? (a - 0x38000000u) : F;  /* 2^-14 and up: re-bias */
+    P = (a >= 0x47800000u) ? 0x0F7FFFFFu : P;                 /* 65536 and up: largest finite pair */
+    P = (a == 0x7F800000u) ? 0x0F800000u : P;                 /* infinity */
+    P = (a > 0x7F800000u) ? 0x0FC00000u : P;                  /* NaN */
+    hi = sign | (P >> 13);
+    res = P & 0x1FFFu;
+}
+template <> __device__ __forceinline__ float cvt16<MPO_FP16>(uint32_t x)
+{
+    return merge16<MPO_FP16>(x, 0u);
+}
+
+/* ---- the update of one parameter (Section 3.1) ---------------------------
+ * One IEEE operation per line; the order is part of the definition. */
+
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM>
+__device__ __forceinline__ void step_one(uint32_t &hi, uint32_t &res, uint32_t g16, float &m, float &v,
+                                         const StepScalars &s)
+{
+    float w = merge16<WFMT>(hi, res);
+    float g = cvt16<GFMT>(g16);
+    g = g * s.IS;
+    if (OPT == MPO_OPT_ADAM) {
+        if (DECAY == kDecoupled) {
+            w = w * s.DEC;
+        } else if (DECAY == kL2) {
+            const float wdw = s.WD * w;
+            g = g + wdw;
+        }
+        const float b1m = s.B1 * m;
+        const float o1g = s.O1 * g;
+        m = b1m + o1g;
+        const float b2v = s.B2 * v;
+        const float o2g = s.O2 * g;
+        const float o2gg = o2g * g;
+        v = b2v + o2gg;
+        const float root = __builtin_sqrtf(v);
+        const float rootc = root / s.SQ;
+        const float d = rootc + s.EPS;
+        const float q = m / d;
+        const float upd = s.SS * q;
+        w = w - upd;
+    } else {
+        if (DECAY == kL2) {
+            const float wdw = s.WD * w;
+            g = g + wdw;
+        }
+        float b = g;
+        if (MOM) {
+            const float mub = s.MU * m;
+            b = mub + g;
+            m = b;
+        }
+        const float upd = s.LR * b;
+        w = w - upd;
+    }
+    split32<WFMT>(w, hi, res);
+}
+
+template <int OPT, bool MOM> struct Uses {
+    static constexpr bool m = (OPT == MPO_OPT_ADAM) || MOM;
+    static constexpr bool v = (OPT == MPO_OPT_ADAM);
+};
+
+struct Row {
+    uint32_t h[EPL / 2], r[EPL / 2], g[EPL / 2];
+    float m[EPL], v[EPL];
+};
+
+template <int OPT, bool MOM>
+__device__ __forceinline__ void load_row(Row &x, gcu16p hi, gcu16p res, gcu16p grad, gcf32p m, gcf32p v, uint32_t e)
+{
+    load16(hi + e, x.h);
+    load16(res + e, x.r);
+    load16(grad + e, x.g);
+    if (Uses<OPT, MOM>::m) load32(m + e, x.m);
+    if (Uses<OPT, MOM>::v) load32(v + e, x.v);
+}
+
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM>
+__device__ __forceinline__ void compute_row(Row &x, const StepScalars &s)
+{
+#pragma unroll
+    for (int j = 0; j < EPL / 2; ++j) {
+        uint32_t h0 = x.h[j] & 0xFFFFu, h1 = x.h[j] >> 16;
+        uint32_t r0 = x.r[j] & 0xFFFFu, r1 = x.r[j] >> 16;
+        step_one<OPT, WFMT, GFMT, DECAY, MOM>(h0, r0, x.g[j] & 0xFFFFu, x.m[2 * j], x.v[2 * j], s);
+        step_one<OPT, WFMT, GFMT, DECAY, MOM>(h1, r1, x.g[j] >> 16, x.m[2 * j + 1], x.v[2 * j + 1], s);
+        x.h[j] = h0 | (h1 << 16);
+        x.r[j] = r0 | (r1 << 16);
+    }
+}
+
+template <int OPT, bool MOM>
+__device__ __forceinline__ void store_row(const Row &x, gu16p hi, gu16p res, gf32p m, gf32p v, uint32_t e)
+{
+    store16(hi + e, x.h);
+    store16(res + e, x.r);
+    if (Uses<OPT, MOM>::m) store32(m + e, x.m);
+    if (Uses<OPT, MOM>::v) store32(v + e, x.v);
+}
+
+/* Parameters [e0, e1) one at a time: ragged tails and tensors that are not
+ * 16-byte aligned.  Same arithmetic, 16- and 32-bit accesses. */
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM>
+__device__ __forceinline__ void step_scalar(gu16p hi, gu16p res, gcu16p grad, gf32p m, gf32p v, uint32_t e,
+                                            const StepScalars &s)
+{
+    uint32_t h = hi[e], r = res[e];
+    float mm = Uses<OPT, MOM>::m ? m[e] : 0.0f;
+    float vv = Uses<OPT, MOM>::v ? v[e] : 0.0f;
+    step_one<OPT, WFMT, GFMT, DECAY, MOM>(h, r, grad[e], mm, vv, s);
+    hi[e] = (uint16_t)h;
+    res[e] = (uint16_t)r;
+    if (Uses<OPT, MOM>::m) m[e] = mm;
+    if (Uses<OPT, MOM>::v) v[e] = vv;
+}
+
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM>
+__global__ void __launch_bounds__(kBlock)
+step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chunks, uint64_t first_chunk,
+            StepScalars s, GradOverride ov)
+{
+    /* Uniform per workgroup: scalar loads. */
+    const Chunk c = chunks[first_chunk + blockIdx.x];
+    const TensorDesc d = descs[c.tensor];
+    const uint16_t *gbase = d.grad;
+    bool aligned = (d.flags & (kStateAligned | kGradAligned)) == (kStateAligned | kGradAligned);
+    if (ov.enabled) {
+        const uint32_t k = c.tensor - ov.first;
+        gbase = ov.ptr[k];
+        aligned = (d.flags & kStateAligned) && !((ov.misaligned >> k) & 1ull);
+    }
+    const uint64_t off = (uint64_t)c.index * kChunkElems;
+    const uint64_t left = d.n - off;
+    const uint32_t len = left < kChunkElems ? (uint32_t)left : kChunkElems;
+
+    gu16p hi = (gu16p)(d.hi + off);
+    gu16p res = (gu16p)(d.res + off);
+    gcu16p grad = (gcu16p)(gbase + off);
+    gf32p m = Uses<OPT, MOM>::m ? (gf32p)(d.m + off) : (gf32p) nullptr;
+    gf32p v = Uses<OPT, MOM>::v ? (gf32p)(d.v + off) : (gf32p) nullptr;
+    const uint32_t t = threadIdx.x;
+
+    if (aligned && len == kChunkElems) {
+        /* whole chunk: no bounds checks */
+#pragma unroll 1
+        for (int r0 = 0; r0 < ROWS; r0 += BATCH) {
+            Row x[BATCH];
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b)
+                load_row<OPT, MOM>(x[b], hi, res, grad, m, v, ((r0 + b) * kBlock + t) * EPL);
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) {
+                compute_row<OPT, WFMT, GFMT, DECAY, MOM>(x[b], s);
+                store_row<OPT, MOM>(x[b], hi, res, m, v, ((r0 + b) * kBlock + t) * EPL);
+            }
+        }
+    } else if (aligned) {
+        /* last chunk of a tensor: full vectors, then one lane finishes the ragged end */
+#pragma unroll 1
+        for (int r = 0; r < ROWS; ++r) {
+            const uint32_t e = (r * kBlock + t) * EPL;
+            if (e + EPL <= len) {
+                Row x;
+                load_row<OPT, MOM>(x, hi, res, grad, m, v, e);
+                compute_row<OPT, WFMT, GFMT, DECAY, MOM>(x, s);
+                store_row<OPT, MOM>(x, hi, res, m, v, e);
+            } else if (e < len) {
+                for (uint32_t i = e; i < len; ++i)
+                    step_scalar<OPT, WFMT, GFMT, DECAY, MOM>(hi, res, grad, m, v, i, s);
+            }
+        }
+    } else {
+        for (uint32_t i = t; i < len; i += kBlock)
+            step_scalar<OPT, WFMT, GFMT, DECAY, MOM>(hi, res, grad, m, v, i, s);
+    }
+}
+
+/* ---- split / merge: 8 B per parameter ------------------------------------ */
+
+template <int FMT>
+__global__ void __launch_bounds__(kBlock)
+split_kernel(const float *__restrict__ w32_, uint16_t *__restrict__ hi_, uint16_t *__restrict__ res_, uint64_t n,
+             int aligned)
+{
+    const uint64_t off = (uint64_t)blockIdx.x * kChunkElems;
+    const uint64_t left = n - off;
+    const uint32_t len = left < kChunkElems ? (uint32_t)left : kChunkElems;
+    gcf32p w32 = (gcf32p)(w32_ + off);
+    gu16p hi = (gu16p)(hi_ + off);
+    gu16p res = (gu16p)(res_ + off);
+    const uint32_t t = threadIdx.x;
+    if (!aligned) {
+        for (uint32_t i = t; i < len; i += kBlock) {
+            uint32_t h, r;
+            split32<FMT>(w32[i], h, r);
+            hi[i] = (uint16_t)h;
+            res[i] = (uint16_t)r;
+        }
+        return;
+    }
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const uint32_t e = (r * kBlock + t) * EPL;
+        if (e + EPL <= len) {
+            float w[EPL];
+            uint32_t h[EPL / 2], q[EPL / 2];
+            load32(w32 + e, w);
+#pragma unroll
+            for (int j = 0; j < EPL / 2; ++j) {
+                uint32_t h0, r0, h1, r1;
+                split32<FMT>(w[2 * j], h0, r0);
+                split32<FMT>(w[2 * j + 1], h1, r1);
+                h[j] = h0 | (h1 << 16);
+                q[j] = r0 | (r1 << 16);
+            }
+            store16(hi + e, h);
+            store16(res + e, q);
+        } else if (e < len) {
+            for (uint32_t i = e; i < len; ++i) {
+                uint32_t h, q;
+                split32<FMT>(w32[i], h, q);
+                hi[i] = (uint16_t)h;
+                res[i] = (uint16_t)q;
+            }
+        }
+    }
+}
+
+template <int FMT>
+__global__ void __launch_bounds__(kBlock)
+merge_kernel(const uint16_t *__restrict__ hi_, const uint16_t *__restrict__ res_, float *__restrict__ w32_, uint64_t n,
+             int aligned)
+{
+    const uint64_t off = (uint64_t)blockIdx.x * kChunkElems;
+    const uint64_t left = n - off;
+    const uint32_t len = left < kChunkElems ? (uint32_t)left : kChunkElems;
+    gf32p w32 = (gf32p)(w32_ + off);
+    gcu16p hi = (gcu16p)(hi_ + off);
+    gcu16p res = (gcu16p)(res_ + off);
+    const uint32_t t = threadIdx.x;
+    if (!aligned) {
+        for (uint32_t i = t; i < len; i += kBlock) w32[i] = merge16<FMT>(hi[i], res[i]);
+        return;
+    }
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const uint32_t e = (r * kBlock + t) * EPL;
+        if (e + EPL <= len) {
+            float w[EPL];
+            uint32_t h[EPL / 2], q[EPL / 2];
+            load16(hi + e, h);
+            load16(res + e, q);
+#pragma unroll
+            for (int j = 0; j < EPL / 2; ++j) {
+                w[2 * j] = merge16<FMT>(h[j] & 0xFFFFu, q[j] & 0xFFFFu);
+                w[2 * j + 1] = merge16<FMT>(h[j] >> 16, q[j] >> 16);
+            }
+            store32(w32 + e, w);
+        } else if (e < len) {
+            for (uint32_t i = e; i < len; ++i) w32[i] = merge16<FMT>(hi[i], res[i]);
+        }
+    }
+}
+
+/* Grids are limited to 2^31-1 workgroups: longer lists go out in slices. */
+constexpr uint64_t kMaxGrid = 0x7FFFFFFFull;
+
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM>
+hipError_t launch_step_t(const StepLaunch &L)
+{
+    uint64_t done = 0;
+    while (done < L.num_chunks) {
+        const uint64_t now = (L.num_chunks - done < kMaxGrid) ? (L.num_chunks - done) : kMaxGrid;
+        step_kernel<OPT, WFMT, GFMT, DECAY, MOM><<<dim3((uint32_t)now), dim3(kBlock), 0, L.stream>>>(
+            L.descs, L.chunks, L.first_chunk + done, L.s, L.ov);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        done += now;
+    }
+    return hipSuccess;
+}
+
+template <int OPT, int DECAY, bool MOM>
+hipError_t launch_step_fmt(const StepLaunch &L)
+{
+    if (L.wfmt == MPO_BF16)
+        return L.gfmt == MPO_BF16 ? launch_step_t<OPT, MPO_BF16, MPO_BF16, DECAY, MOM>(L)
+                                  : launch_step_t<OPT, MPO_BF16, MPO_FP16, DECAY, MOM>(L);
+    return L.gfmt == MPO_BF16 ? launch_step_t<OPT, MPO_FP16, MPO_BF16, DECAY, MOM>(L)
+                              : launch_step_t<OPT, MPO_FP16, MPO_FP16, DECAY, MOM>(L);
+}
+
+} // namespace
+
+hipError_t launch_step(const StepLaunch &L)
+{
+    if (L.num_chunks == 0) return hipSuccess;
+    if (L.opt == MPO_OPT_ADAM) {
+        switch (L.decay) {
+        case kNoDecay: return launch_step_fmt<MPO_OPT_ADAM, kNoDecay, true>(L);
+        case kDecoupled: return launch_step_fmt<MPO_OPT_ADAM, kDecoupled, true>(L);
+        default: return launch_step_fmt<MPO_OPT_ADAM, kL2, true>(L);
+        }
+    }
+    if (L.momentum)
+        return L.decay == kL2 ? launch_step_fmt<MPO_OPT_SGD, kL2, true>(L)
+                              : launch_step_fmt<MPO_OPT_SGD, kNoDecay, true>(L);
+    return L.decay == kL2 ? launch_step_fmt<MPO_OPT_SGD, kL2, false>(L)
+                          : launch_step_fmt<MPO_OPT_SGD, kNoDecay, false>(L);
+}
+
+static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+hipError_t launch_split(const float *w32, uint16_t *hi, uint16_t *res, uint64_t n, int fmt, hipStream_t stream)
+{
+    const int al = aligned16(w32) && aligned16(hi) && aligned16(res);
+    uint64_t done = 0;
+    const uint64_t blocks = (n + kChunkElems - 1) / kChunkElems;
+    while (done < blocks) {
+        const uint64_t now = (blocks - done < kMaxGrid) ? (blocks - done) : kMaxGrid;
+        const uint64_t e0 = done * kChunkElems;
+        if (fmt == MPO_BF16)
+            split_kernel<MPO_BF16><<<dim3((uint32_t)now), dim3(kBlock), 0, stream>>>(w32 + e0, hi + e0, res + e0, n - e0, al);
+        else
+            split_kernel<MPO_FP16><<<dim3((uint32_t)now), dim3(kBlock), 0, stream>>>(w32 + e0, hi + e0, res + e0, n - e0, al);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        done += now;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_merge(const uint16_t *hi, const uint16_t *res, float *w32, uint64_t n, int fmt, hipStream_t stream)
+{
+    const int al = aligned16(w32) && aligned16(hi) && aligned16(res);
+    uint64_t done = 0;
+    const uint64_t blocks = (n + kChunkElems - 1) / kChunkElems;
+    while (done < blocks) {
+        const uint64_t now = (blocks - done < kMaxGrid) ? (blocks - done) : kMaxGrid;
+        const uint64_t e0 = done * kChunkElems;
+        if (fmt == MPO_BF16)
+            merge_kernel<MPO_BF16><<<dim3((uint32_t)now), dim3(kBlock), 0, stream>>>(hi + e0, res + e0, w32 + e0, n - e0, al);
+        else
+            merge_kernel<MPO_FP16><<<dim3((uint32_t)now), dim3(kBlock), 0, stream>>>(hi + e0, res + e0, w32 + e0, n - e0, al);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        done += now;
+    }
+    return hipSuccess;
+}
+
+} // namespace mpo

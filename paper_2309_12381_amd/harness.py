@@ -1,0 +1,119 @@
+"""Device-side state of a synthetic workload and the stepping loops around libmpo.
+
+PyTorch is used for device memory, streams and seeded random numbers only; every
+step of the method is a call into the library.  Shared by bench.py, the smoke
+check and the full-size GPU tests.
+"""
+from dataclasses import dataclass
+from typing import Dict, List, Optional
+
+import torch
+
+from . import binding as mpo
+from . import synth
+
+FMT = {"bf16": mpo.MPO_BF16, "fp16": mpo.MPO_FP16}
+
+
+def _round_up(x: int, k: int) -> int:
+    return (x + k - 1) // k * k
+
+
+@dataclass
+class TensorView:
+    spec: synth.Spec
+    off: int            # element offset into the flat state arrays (multiple of 8: 16-byte aligned)
+    goff: int           # element offset into the reused gradient buffer, local to the tensor's layer
+
+
+class ModelState:
+    """hi, res, m, v for every tensor of a workload, each kind in ONE flat allocation (large
+    blocks keep the driver on large page fragments), plus ONE gradient buffer sized for the
+    largest layer and reused by every layer (Section 3.2: a gradient is consumed as soon as it
+    exists and never kept).  For workloads stepped in one launch the buffer holds all gradients."""
+
+    def __init__(self, wl: synth.Workload, device="cuda:0", seed: int = 2309, keep_w32_samples=None):
+        self.wl = wl
+        self.device = device
+        self.fmt = FMT[wl.fmt]
+        self.views: List[TensorView] = []
+        off = 0
+        layer_fill: Dict[int, int] = {}
+        for s in wl.tensors:
+            if wl.per_layer:
+                g = layer_fill.get(s.layer, 0)
+                layer_fill[s.layer] = g + _round_up(s.n, 8)
+            else:
+                g = off
+            self.views.append(TensorView(s, off, g))
+            off += _round_up(s.n, 8)
+        self.total = off
+        self.grad_len = max(layer_fill.values()) if wl.per_layer else off
+        self.hi = torch.empty(self.total, dtype=torch.int16, device=device)
+        self.res = torch.empty(self.total, dtype=torch.int16, device=device)
+        self.m = torch.zeros(self.total, dtype=torch.float32, device=device)
+        self.v = torch.zeros(self.total, dtype=torch.float32, device=device)
+        self.gdtype = torch.bfloat16 if wl.fmt == "bf16" else torch.float16
+        self.grad = torch.zeros(self.grad_len, dtype=self.gdtype, device=device)
+        self.seed = seed
+        self.w32_samples = {}
+        # weights: fp32 ~ N(0, std^2), drawn per tensor on the device, then split by the library
+        for i, tv in enumerate(self.views):
+            n = tv.spec.n
+            w = synth.gen_weights(n, synth.seed_for(seed, 1, i), device, wl.weight_std)
+            if keep_w32_samples is not None:
+                idx = keep_w32_samples(i, n)
+                if idx is not None:
+                    self.w32_samples[i] = (idx, w[idx].cpu())
+            mpo.mpo_split(w, self.hi[tv.off:], self.res[tv.off:], n, fmt=self.fmt)
+            del w
+        torch.cuda.synchronize(device)
+        self.plan = mpo.Plan([mpo.Tensor(self.hi[tv.off:], self.res[tv.off:], self.grad[tv.goff:],
+                                         self.m[tv.off:], self.v[tv.off:], tv.spec.n, tv.spec.layer)
+                              for tv in self.views])
+        self.layers_backward = wl.layers_backward
+        self.by_layer: Dict[int, List[int]] = {}
+        for i, tv in enumerate(self.views):
+            self.by_layer.setdefault(tv.spec.layer, []).append(i)
+
+    @property
+    def resident_bytes(self) -> int:
+        return self.total * 12 + self.grad_len * 2
+
+    def adam_cfg(self) -> mpo.AdamCfg:
+        wl = self.wl
+        return mpo.AdamCfg(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=wl.weight_decay,
+                           decoupled_wd=(wl.optimizer == "adamw"), loss_scale=wl.loss_scale,
+                           weight_fmt=self.fmt, grad_fmt=self.fmt)
+
+    def fill_grads(self, tensor_ids, step: int):
+        """Stand-in for backward: fresh seeded gradients for these tensors, written into the buffer."""
+        wl = self.wl
+        for i in tensor_ids:
+            tv = self.views[i]
+            synth.gen_grads(tv.spec.n, synth.seed_for(self.seed, 2, i, step), self.device, wl.grad_std, wl.fmt,
+                            wl.loss_scale, out=self.grad[tv.goff:])
+
+    def step(self, step: int, cfg=None, stream=None, fresh_grads: bool = False, before_layer=None) -> int:
+        """One optimizer step over the whole model.  Per-layer workloads: one mpo_step_layer per
+        layer in backward order; otherwise one mpo_adam_step.  Returns the number of launches.
+        `before_layer(layer, tensor_ids)` runs after that layer's gradients are in the buffer."""
+        cfg = cfg or self.adam_cfg()
+        if not self.wl.per_layer:
+            if fresh_grads:
+                self.fill_grads(range(len(self.views)), step)
+            if before_layer:
+                before_layer(None, list(range(len(self.views))))
+            mpo.mpo_adam_step(self.plan, cfg, step, stream=stream)
+            return 1
+        for layer in self.layers_backward:
+            ids = self.by_layer[layer]
+            if fresh_grads:
+                self.fill_grads(ids, step)
+            if before_layer:
+                before_layer(layer, ids)
+            mpo.mpo_step_layer(self.plan, layer, cfg, step, stream=stream)
+        return len(self.layers_backward)
+
+    def close(self):
+        self.plan.destroy()

@@ -1,0 +1,123 @@
+"""Helpers shared by the GPU parity tests: device state mirrored on the host for the oracle."""
+import os
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import torch
+
+import paper_2309_12381_amd as mpo
+from oracle import ref
+
+DEV = "cuda:0"
+WORKERS = min(16, os.cpu_count() or 1)
+FMT = {"bf16": (mpo.MPO_BF16, ref.BF16), "fp16": (mpo.MPO_FP16, ref.FP16)}
+
+
+def say(msg):
+    """Name the case before every GPU step, flushed, so that a fault can be attributed."""
+    print("[gpu-case] " + msg, flush=True)
+
+
+def dev_u16(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(a.view(np.int16).copy()).to(DEV)
+
+
+def host_u16(t: torch.Tensor) -> np.ndarray:
+    return t.detach().cpu().numpy().view(np.uint16).copy()
+
+
+def dev_f32(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(a.copy()).to(DEV)
+
+
+def host_f32(t: torch.Tensor) -> np.ndarray:
+    return t.detach().cpu().numpy().copy()
+
+
+def parallel_slices(n, fn, min_chunk=1 << 18):
+    """Run fn(lo, hi) over slices of [0, n) on host threads (the oracle is elementwise)."""
+    if n <= min_chunk:
+        fn(0, n)
+        return
+    k = min(WORKERS, (n + min_chunk - 1) // min_chunk)
+    bounds = np.linspace(0, n, k + 1).astype(np.int64)
+    with ThreadPoolExecutor(k) as ex:
+        list(ex.map(lambda i: fn(int(bounds[i]), int(bounds[i + 1])), range(k)))
+
+
+def ref_split(w32, rfmt):
+    hi = np.empty(w32.shape[0], np.uint16)
+    res = np.empty(w32.shape[0], np.uint16)
+
+    def f(lo, up):
+        h, r = ref.split(w32[lo:up], rfmt)
+        hi[lo:up] = h
+        res[lo:up] = r
+    parallel_slices(w32.shape[0], f)
+    return hi, res
+
+
+def ref_adam(hi, res, g, m, v, cfg, step):
+    parallel_slices(hi.shape[0], lambda lo, up: ref.adam_step(hi[lo:up], res[lo:up], g[lo:up], m[lo:up], v[lo:up],
+                                                              cfg, step))
+
+
+def ref_sgd(hi, res, g, buf, cfg, step):
+    parallel_slices(hi.shape[0], lambda lo, up: ref.sgd_step(hi[lo:up], res[lo:up], g[lo:up],
+                                                             None if buf is None else buf[lo:up], cfg, step))
+
+
+def cfg_pair(kind, fmt="bf16", gfmt=None, **kw):
+    """The same hyper-parameters for the library and for the oracle."""
+    gfmt = gfmt or fmt
+    if kind == "adam":
+        return (mpo.AdamCfg(weight_fmt=FMT[fmt][0], grad_fmt=FMT[gfmt][0], **kw),
+                ref.AdamCfg(weight_fmt=FMT[fmt][1], grad_fmt=FMT[gfmt][1], **kw))
+    return (mpo.SgdCfg(weight_fmt=FMT[fmt][0], grad_fmt=FMT[gfmt][0], **kw),
+            ref.SgdCfg(weight_fmt=FMT[fmt][1], grad_fmt=FMT[gfmt][1], **kw))
+
+
+class HostTensor:
+    """Oracle-side state of one tensor."""
+
+    def __init__(self, w32: np.ndarray, rfmt, with_v=True):
+        self.n = w32.shape[0]
+        self.hi, self.res = ref_split(w32, rfmt)
+        self.m = np.zeros(self.n, np.float32)
+        self.v = np.zeros(self.n, np.float32) if with_v else None
+
+
+class DevTensor:
+    """GPU-side state of one tensor, split by the library itself."""
+
+    def __init__(self, w32: np.ndarray, fmt, with_v=True, layer=0, grad=None, misalign=0, stream=None):
+        n = w32.shape[0]
+        self.n, self.layer = n, layer
+        # optional misalignment: carve each array out of a larger one at an odd element offset
+        def alloc(dtype):
+            full = torch.zeros(n + misalign + 8, dtype=dtype, device=DEV)
+            return full[misalign:misalign + n]
+        self.hi, self.res = alloc(torch.int16), alloc(torch.int16)
+        self.m = alloc(torch.float32)
+        self.v = alloc(torch.float32) if with_v else None
+        self.grad = grad if grad is not None else alloc(torch.int16)
+        w = torch.zeros(n + misalign + 8, dtype=torch.float32, device=DEV)[misalign:misalign + n]
+        w.copy_(torch.from_numpy(w32))
+        mpo.mpo_split(w, self.hi, self.res, n, fmt=fmt, stream=stream)
+
+    def spec(self):
+        return mpo.Tensor(self.hi, self.res, self.grad, self.m, self.v, self.n, self.layer)
+
+
+def assert_state_equal(d: DevTensor, h: HostTensor, what=""):
+    torch.cuda.synchronize()
+    ghi, gres = host_u16(d.hi), host_u16(d.res)
+    bad = np.flatnonzero((ghi != h.hi) | (gres != h.res))
+    assert bad.size == 0, "%s: %d of %d stored weights differ, first at %d: gpu %04x/%04x oracle %04x/%04x" % (
+        what, bad.size, h.n, bad[0] if bad.size else -1, *((ghi[bad[0]], gres[bad[0]], h.hi[bad[0]], h.res[bad[0]])
+                                                          if bad.size else (0, 0, 0, 0)))
+    gm = host_f32(d.m)
+    assert np.array_equal(gm.view(np.uint32), h.m.view(np.uint32)), what + ": m differs"
+    if h.v is not None and d.v is not None:
+        gv = host_f32(d.v)
+        assert np.array_equal(gv.view(np.uint32), h.v.view(np.uint32)), what + ": v differs"

@@ -1,0 +1,174 @@
+"""CPU-only checks of libmpo.so: it loads, exports everything include/mpo.h declares,
+validates arguments before touching the GPU, and lays plans out as documented.
+No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2309_12381_amd as mpo
+from paper_2309_12381_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "mpo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mpo_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared()
+    for required in ("mpo_split", "mpo_merge", "mpo_adam_step", "mpo_sgd_step", "mpo_step_layer",
+                     "mpo_plan_create", "mpo_plan_destroy"):
+        assert required in names
+    for n in names:
+        assert hasattr(mpo.lib, n), n
+        assert n in binding.EXPORTS, "binding does not cover " + n
+
+
+def test_status_strings():
+    seen = set()
+    for s in range(6):
+        msg = mpo.lib.mpo_status_string(s).decode()
+        assert msg and msg not in seen
+        seen.add(msg)
+    assert mpo.lib.mpo_status_string(99).decode() == "unknown status"
+
+
+A = 0x10000000  # fake, well separated, 16-byte aligned device addresses: never dereferenced on the host
+
+
+def T(i=0, n=1000, layer=0, **kw):
+    base = A + i * 0x1000000
+    d = dict(hi=base, res=base + 0x100000, grad=base + 0x200000, m=base + 0x300000, v=base + 0x400000, n=n, layer=layer)
+    d.update(kw)
+    return mpo.Tensor(**d)
+
+
+def _status(fn, *a, **k):
+    try:
+        fn(*a, **k)
+    except mpo.MpoError as e:
+        return e.status
+    return mpo.MPO_OK
+
+
+def test_split_merge_argument_validation():
+    # nothing is enqueued when validation fails, so fake addresses are fine
+    assert _status(mpo.mpo_split, 0, A, A + 0x1000, 10) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_split, A, 0, A + 0x1000, 10) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, fmt=7) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, round=mpo.MPO_ROUND_NEAREST) == mpo.MPO_ERR_UNSUPPORTED
+    assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, round=mpo.MPO_ROUND_STOCHASTIC) == mpo.MPO_ERR_UNSUPPORTED
+    assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, round=5) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 1 << 60) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_split, A, A + 16, A + 0x2000, 10) == mpo.MPO_ERR_ALIAS       # hi inside w32
+    assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x1000 + 10, 10) == mpo.MPO_ERR_ALIAS  # res inside hi
+    assert _status(mpo.mpo_merge, A, A + 0x1000, A + 0x1000 + 8, 10) == mpo.MPO_ERR_ALIAS
+    assert _status(mpo.mpo_merge, A, A + 0x1000, 0, 10) == mpo.MPO_ERR_INVALID_ARG
+    # zero elements: a legal no-op even with null pointers
+    assert _status(mpo.mpo_split, 0, 0, 0, 0) == mpo.MPO_OK
+    assert _status(mpo.mpo_merge, 0, 0, 0, 0, fmt=mpo.MPO_FP16) == mpo.MPO_OK
+
+
+def _host_plan(ts):
+    return mpo.Plan(ts, host_only=True)
+
+
+def test_plan_validation():
+    assert _status(_host_plan, [T(hi=0)]) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(_host_plan, [T(res=0)]) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(_host_plan, [T(layer=-1)]) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(_host_plan, [T(n=1 << 50)]) == mpo.MPO_ERR_INVALID_ARG
+    # optional buffers may be absent at creation
+    assert _status(_host_plan, [T(grad=0, v=0)]) == mpo.MPO_OK
+    assert _status(_host_plan, [T(m=0, v=0)]) == mpo.MPO_OK
+    # a zero-length tensor needs no pointers
+    assert _status(_host_plan, [T(n=0, hi=0, res=0, grad=0, m=0, v=0)]) == mpo.MPO_OK
+    assert _status(_host_plan, []) == mpo.MPO_OK
+
+
+def test_plan_alias_detection():
+    a, b = T(0), T(1)
+    assert _status(_host_plan, [a, b]) == mpo.MPO_OK
+    assert _status(_host_plan, [a, a]) == mpo.MPO_ERR_ALIAS                       # tied weights listed twice
+    assert _status(_host_plan, [a, T(1, hi=a.hi + 1998)]) == mpo.MPO_ERR_ALIAS    # last element of a.hi
+    assert _status(_host_plan, [a, T(1, hi=a.hi + 2000)]) == mpo.MPO_OK           # just past it
+    assert _status(_host_plan, [a, T(1, m=a.v + 3996)]) == mpo.MPO_ERR_ALIAS
+    assert _status(_host_plan, [a, T(1, grad=a.m)]) == mpo.MPO_ERR_ALIAS          # gradient over written state
+    assert _status(_host_plan, [T(0, grad=a.hi)]) == mpo.MPO_ERR_ALIAS
+    # gradients may share one buffer (one layer's gradient alive at a time)
+    assert _status(_host_plan, [a, T(1, grad=a.grad), T(2, grad=a.grad + 10)]) == mpo.MPO_OK
+    # a written range nested inside a long read-only range that starts earlier
+    assert _status(_host_plan, [T(0, grad=A - 0x100, n=1000), T(1, hi=A - 0x80, n=8)]) == mpo.MPO_ERR_ALIAS
+
+
+def test_plan_layout_covers_every_element_once_in_layer_order():
+    sizes = [1, 8191, 8192, 8193, 3 * 8192 + 5, 0, 100000, 64]
+    layers = [3, 0, 2, 0, 1, 1, 2, 0]
+    ts = [T(i, n=n, layer=l) for i, (n, l) in enumerate(zip(sizes, layers))]
+    p = _host_plan(ts)
+    ce = p.chunk_elems
+    assert ce == 8192
+    assert p.num_params == sum(sizes)
+    assert p.num_chunks == sum((n + ce - 1) // ce for n in sizes)
+    seen = {}
+    order = []
+    for i in range(p.num_chunks):
+        t, k = p.chunk(i)
+        assert (t, k) not in seen
+        seen[(t, k)] = i
+        order.append(t)
+    for t, n in enumerate(sizes):
+        for k in range((n + ce - 1) // ce):
+            assert (t, k) in seen
+    # launch order: by layer, then by position in the caller's list, chunks ascending
+    keys = [(layers[t], t) for t in order]
+    assert keys == sorted(keys)
+    for layer in set(layers):
+        info = p.layer_info(layer)
+        members = [t for t in range(len(sizes)) if layers[t] == layer]
+        assert info["num_tensors"] == len(members)
+        assert info["num_params"] == sum(sizes[t] for t in members)
+        rng = order[info["first_chunk"]: info["first_chunk"] + info["num_chunks"]]
+        assert set(rng) <= set(members) and info["num_chunks"] == sum((sizes[t] + ce - 1) // ce for t in members)
+    assert _status(p.layer_info, 7) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(p.chunk, p.num_chunks) == mpo.MPO_ERR_INVALID_ARG
+    p.destroy()
+    p.destroy()   # idempotent
+
+
+def test_step_calls_validate_before_touching_the_gpu():
+    p = _host_plan([T(0)])
+    # a host-only plan cannot be stepped
+    assert _status(mpo.mpo_adam_step, p, mpo.AdamCfg(), 1) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_sgd_step, p, mpo.SgdCfg(), 1) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_step_layer, p, 0, mpo.AdamCfg(), 1) == mpo.MPO_ERR_INVALID_ARG
+    # config errors are reported first
+    assert _status(mpo.mpo_adam_step, p, mpo.AdamCfg(), 0) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_adam_step, p, mpo.AdamCfg(round=mpo.MPO_ROUND_STOCHASTIC), 1) == mpo.MPO_ERR_UNSUPPORTED
+    assert _status(mpo.mpo_adam_step, p, mpo.AdamCfg(weight_fmt=3), 1) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_adam_step, p, mpo.AdamCfg(beta1=1.0), 1) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_adam_step, p, mpo.AdamCfg(loss_scale=0.0), 1) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_adam_step, p, mpo.AdamCfg(lr=float("nan")), 1) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_sgd_step, p, mpo.SgdCfg(round=mpo.MPO_ROUND_NEAREST), 1) == mpo.MPO_ERR_UNSUPPORTED
+    assert _status(mpo.mpo_sgd_step, p, mpo.SgdCfg(loss_scale=float("inf")), 1) == mpo.MPO_ERR_INVALID_ARG
+    # null plan / null cfg through the raw entry points
+    cfg = mpo.AdamCfg().c()
+    assert mpo.lib.mpo_adam_step(None, ctypes.byref(cfg), 1, None) == mpo.MPO_ERR_INVALID_ARG
+    assert mpo.lib.mpo_adam_step(p._h, None, 1, None) == mpo.MPO_ERR_INVALID_ARG
+    assert mpo.lib.mpo_step_layer(p._h, 0, None, 0, 9, ctypes.cast(ctypes.byref(cfg), ctypes.c_void_p), 1, None) \
+        == mpo.MPO_ERR_INVALID_ARG
+    assert mpo.lib.mpo_plan_destroy(None) == mpo.MPO_OK
+
+
+def test_plan_create_without_a_gpu_fails_loudly():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(mpo.MpoError) as e:
+        mpo.Plan([T(0)])
+    assert e.value.status == mpo.MPO_ERR_HIP and mpo.lib.mpo_last_hip_error() != 0

@@ -1,0 +1,496 @@
+"""GPU parity: libmpo (through its C interface) against the CPU oracle, element by element.
+
+Bar (arXiv 2309.12381, Section 3.1: the stored value is as precise as fp32 training):
+split, merge and SGD bit-exact; Adam: stored weights within 1 fp32 ulp of the oracle's,
+m and v within 1e-6 relative.  Both sides do one IEEE binary32 operation at a time in the
+same order, so these tests hold the stronger bar: every output bit-identical.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2309_12381_amd as mpo
+from paper_2309_12381_amd import synth
+from oracle import ref
+
+from gpu_util import (DEV, FMT, DevTensor, HostTensor, assert_state_equal, cfg_pair, dev_f32, dev_u16, host_f32,
+                      host_u16, parallel_slices, ref_adam, ref_sgd, ref_split, say)
+
+pytestmark = pytest.mark.gpu
+
+CHUNK = 8192
+SIZES = [1, 7, 8, 9, 2047, 2048, CHUNK - 1, CHUNK, CHUNK + 1, 3 * CHUNK + 5, (1 << 20) + 3]
+
+
+def interesting_f32(rng, n):
+    """Random fp32 bit patterns across all exponents, plus model-like weights and edge values."""
+    x = rng.integers(0, 1 << 32, size=n, dtype=np.uint64).astype(np.uint32).view(np.float32).copy()
+    k = n // 2
+    x[:k] = (rng.standard_normal(k) * 0.02).astype(np.float32)
+    edge = np.array([0.0, -0.0, 1.0, -1.0, 65504.0, 65535.99, 65536.0, 70000.0, -1e9, 6.1035156e-05, 6.1e-5, 3e-5,
+                     2.0 ** -37, 2.0 ** -38, 1e-45, -1e-40, 3.4028235e38, np.inf, -np.inf, np.nan], np.float32)
+    m = min(n, edge.size)
+    x[-m:] = edge[:m]
+    return x
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "fp16"])
+@pytest.mark.parametrize("misalign", [0, 1, 3])
+def test_split_merge_match_oracle(fmt, misalign):
+    gfmt, rfmt = FMT[fmt]
+    rng = np.random.default_rng(1)
+    for n in SIZES:
+        say("split/merge fmt=%s n=%d misalign=%d" % (fmt, n, misalign))
+        x = interesting_f32(rng, n)
+        w = torch.zeros(n + misalign + 8, dtype=torch.float32, device=DEV)[misalign:misalign + n]
+        w.copy_(torch.from_numpy(x))
+        hi = torch.full((n + misalign + 8,), 0x5555, dtype=torch.int16, device=DEV)
+        res = torch.full((n + misalign + 8,), 0x5555, dtype=torch.int16, device=DEV)
+        mpo.mpo_split(w, hi[misalign:], res[misalign:], n, fmt=gfmt)
+        want_hi, want_res = ref.split(x, rfmt)
+        assert np.array_equal(host_u16(hi[misalign:misalign + n]), want_hi)
+        assert np.array_equal(host_u16(res[misalign:misalign + n]), want_res)
+        # nothing outside [0, n) was written
+        for buf in (hi, res):
+            full = host_u16(buf)
+            assert np.all(full[:misalign] == 0x5555) and np.all(full[misalign + n:] == 0x5555)
+        out = torch.full((n + misalign + 8,), -7.0, dtype=torch.float32, device=DEV)
+        mpo.mpo_merge(hi[misalign:], res[misalign:], out[misalign:], n, fmt=gfmt)
+        want = ref.merge(want_hi, want_res, rfmt)
+        got = host_f32(out)
+        assert np.array_equal(got[misalign:misalign + n].view(np.uint32), want.view(np.uint32))
+        assert np.all(got[:misalign] == -7.0) and np.all(got[misalign + n:] == -7.0)
+
+
+def _structured_patterns():
+    """Every sign and exponent, every value of the 11 leading fraction bits, with the 12 trailing
+    bits drawn from a set that hits each boundary of the fp16 and bf16 cuts: 2^25 patterns."""
+    se = np.arange(512, dtype=np.uint32) << 23                        # sign + exponent
+    top = np.arange(2048, dtype=np.uint32) << 12
+    low = np.array([0, 1, 2, 0x3FF, 0x400, 0x7FF, 0x800, 0x801, 0xFFF, 0xFFE, 0x555, 0xAAA, 0x100, 0x0FF, 0x00F, 0xF00,
+                    0x123, 0x876, 0x3C3, 0xC3C, 0x00A, 0xA00, 0x080, 0x7F0, 0x111, 0x222, 0x444, 0x888, 0xEEE, 0xDDD,
+                    0xBBB, 0x777], np.uint32)
+    return (se[:, None, None] | top[None, :, None] | low[None, None, :]).reshape(-1)
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "fp16"])
+def test_split_merge_structured_and_random_patterns(fmt):
+    """2^25 structured plus 2^25 random fp32 patterns through mpo_split and back through
+    mpo_merge, against the oracle (which is itself checked on all 2^32 patterns on the CPU).
+    MPO_EXHAUSTIVE=1 runs all 2^32 patterns on the GPU as well."""
+    gfmt, rfmt = FMT[fmt]
+    rng = np.random.default_rng(2)
+    pats = np.concatenate([_structured_patterns(),
+                           rng.integers(0, 1 << 32, size=1 << 25, dtype=np.uint64).astype(np.uint32)])
+    n = pats.size
+    say("structured split/merge fmt=%s n=%d" % (fmt, n))
+    w = torch.from_numpy(pats.view(np.int32).copy()).to(DEV)
+    hi = torch.empty(n, dtype=torch.int16, device=DEV)
+    res = torch.empty(n, dtype=torch.int16, device=DEV)
+    back = torch.empty(n, dtype=torch.float32, device=DEV)
+    mpo.mpo_split(w.view(torch.float32), hi, res, n, fmt=gfmt)
+    mpo.mpo_merge(hi, res, back, n, fmt=gfmt)
+    want_hi, want_res = ref_split(pats.view(np.float32), rfmt)
+    assert np.array_equal(host_u16(hi), want_hi)
+    assert np.array_equal(host_u16(res), want_res)
+    want = np.empty(n, np.float32)
+    parallel_slices(n, lambda lo, up: want.__setitem__(slice(lo, up), ref.merge(want_hi[lo:up], want_res[lo:up], rfmt)))
+    assert np.array_equal(host_f32(back).view(np.uint32), want.view(np.uint32))
+
+
+@pytest.mark.skipif(os.environ.get("MPO_EXHAUSTIVE") != "1", reason="set MPO_EXHAUSTIVE=1 (several minutes)")
+@pytest.mark.parametrize("fmt", ["bf16", "fp16"])
+def test_split_merge_every_fp32_pattern(fmt):
+    """All 2^32 fp32 patterns through mpo_split and back through mpo_merge, against the oracle."""
+    gfmt, rfmt = FMT[fmt]
+    n = 1 << 26
+    w = torch.empty(n, dtype=torch.int32, device=DEV)
+    hi = torch.empty(n, dtype=torch.int16, device=DEV)
+    res = torch.empty(n, dtype=torch.int16, device=DEV)
+    back = torch.empty(n, dtype=torch.float32, device=DEV)
+    base = torch.arange(n, dtype=torch.int64, device=DEV)
+    for s in range((1 << 32) // n):
+        say("exhaustive split/merge fmt=%s slice %d/64" % (fmt, s))
+        pat = base + s * n
+        w.copy_(torch.where(pat >= (1 << 31), pat - (1 << 32), pat).to(torch.int32))
+        mpo.mpo_split(w.view(torch.float32), hi, res, n, fmt=gfmt)
+        mpo.mpo_merge(hi, res, back, n, fmt=gfmt)
+        x = np.arange(s * n, (s + 1) * n, dtype=np.uint64).astype(np.uint32).view(np.float32)
+        want_hi, want_res = ref_split(x, rfmt)
+        assert np.array_equal(host_u16(hi), want_hi), "hi, slice %d" % s
+        assert np.array_equal(host_u16(res), want_res), "res, slice %d" % s
+        want = np.empty(n, np.float32)
+        parallel_slices(n, lambda lo, up: want.__setitem__(slice(lo, up), ref.merge(want_hi[lo:up], want_res[lo:up], rfmt)))
+        assert np.array_equal(host_f32(back).view(np.uint32), want.view(np.uint32)), "merge, slice %d" % s
+
+
+def test_merge_every_fp16_pair():
+    """All 2^16 x 2^13 (hi, res) pairs, and the ignored spare bits, through mpo_merge."""
+    n = 1 << 29
+    idx = torch.arange(n, dtype=torch.int64, device=DEV)
+    hi = (idx >> 13).to(torch.int32)
+    hi = torch.where(hi >= 32768, hi - 65536, hi).to(torch.int16)
+    res = ((idx & 0x1FFF) | ((idx & 7) << 13)).to(torch.int32)        # spare bits set to junk
+    res = torch.where(res >= 32768, res - 65536, res).to(torch.int16)
+    out = torch.empty(n, dtype=torch.float32, device=DEV)
+    say("merge all fp16 pairs")
+    mpo.mpo_merge(hi, res, out, n, fmt=mpo.MPO_FP16)
+    got = host_f32(out).view(np.uint32)
+    hh, rr = host_u16(hi), host_u16(res)
+    want = np.empty(n, np.float32)
+    parallel_slices(n, lambda lo, up: want.__setitem__(slice(lo, up), ref.merge(hh[lo:up], rr[lo:up], ref.FP16)))
+    assert np.array_equal(got, want.view(np.uint32))
+
+
+# ---- single tensor: configuration 0 ------------------------------------------
+
+def _edge_grads(fmt, n, rng, std, scale):
+    g = synth.bits16(synth.gen_grads(n, int(rng.integers(1 << 30)), "cpu", std, fmt, scale))
+    if fmt == "bf16":
+        # zero, tiny (squares underflow to denormals or zero), huge, denormal bf16
+        edge = np.array([0x0000, 0x8000, 0x0001, 0x8001, 0x007F, 0x0080, 0x1000, 0x9000, 0x2000, 0x3F80, 0xBF80,
+                         0x4780, 0x5F00, 0xDF00, 0x0F80, 0x1F80], np.uint16)
+    else:
+        edge = np.array([0x0000, 0x8000, 0x0001, 0x8001, 0x03FF, 0x0400, 0x3C00, 0xBC00, 0x7BFF, 0xFBFF, 0x0200,
+                         0x1400], np.uint16)
+    g[:edge.size] = edge[:min(n, edge.size)]
+    return g
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "fp16"])
+def test_adam_single_tensor_config0(fmt):
+    """Configuration 0: one tensor of 2^20 parameters, 10 Adam steps with fresh gradients."""
+    gfmt, rfmt = FMT[fmt]
+    scale = 1.0 if fmt == "bf16" else 1024.0
+    rng = np.random.default_rng(100)
+    n = 1 << 20
+    w0 = synth.gen_weights(n, 1234, "cpu", 0.02).numpy()
+    w0[:6] = [0.0, -0.0, 1e-40, -3e-39, 1.0, -65000.0]
+    lib_cfg, ref_cfg = cfg_pair("adam", fmt, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, loss_scale=scale)
+    say("adam config0 fmt=%s" % fmt)
+    d = DevTensor(w0, gfmt)
+    h = HostTensor(w0, rfmt)
+    plan = mpo.Plan([d.spec()])
+    assert_state_equal(d, h, "after split")
+    for t in range(1, 11):
+        g = _edge_grads(fmt, n, rng, 1e-3, scale)
+        d.grad.copy_(dev_u16(g))
+        mpo.mpo_adam_step(plan, lib_cfg, t)
+        ref_adam(h.hi, h.res, g, h.m, h.v, ref_cfg, t)
+        assert_state_equal(d, h, "adam step %d" % t)
+    plan.destroy()
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "fp16"])
+@pytest.mark.parametrize("momentum,wd", [(0.9, 0.0), (0.9, 2e-4), (0.0, 0.0), (0.0, 1e-3)])
+def test_sgd_single_tensor_config0(fmt, momentum, wd):
+    gfmt, rfmt = FMT[fmt]
+    rng = np.random.default_rng(101)
+    n = 1 << 20
+    w0 = synth.gen_weights(n, 4321, "cpu", 0.02).numpy()
+    lib_cfg, ref_cfg = cfg_pair("sgd", fmt, lr=1e-2, momentum=momentum, weight_decay=wd)
+    say("sgd config0 fmt=%s mu=%g wd=%g" % (fmt, momentum, wd))
+    d = DevTensor(w0, gfmt, with_v=False)
+    h = HostTensor(w0, rfmt, with_v=False)
+    plan = mpo.Plan([d.spec()])
+    for t in range(1, 11):
+        g = _edge_grads(fmt, n, rng, 1e-3, 1.0)
+        d.grad.copy_(dev_u16(g))
+        mpo.mpo_sgd_step(plan, lib_cfg, t)
+        ref_sgd(h.hi, h.res, g, h.m, ref_cfg, t)
+        assert_state_equal(d, h, "sgd step %d" % t)
+    if momentum == 0.0:
+        assert not host_f32(d.m).any()          # the buffer is left alone
+    plan.destroy()
+
+
+def test_all_fp16_gradient_patterns_convert_exactly():
+    """After one momentum step from a zero buffer the buffer equals the gradient: every finite
+    fp16 and bf16 pattern must come out as the library cast reads it."""
+    for fmt in ("fp16", "bf16"):
+        gfmt, rfmt = FMT[fmt]
+        pats = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16)
+        if fmt == "fp16":
+            finite = (pats & 0x7C00) != 0x7C00
+        else:
+            finite = (pats & 0x7F80) != 0x7F80
+        pats = pats[finite & (pats != 0x8000)]      # (+0) + (-0) = +0: the buffer cannot show -0
+        n = pats.size
+        w0 = np.zeros(n, np.float32)
+        say("gradient conversion fmt=%s" % fmt)
+        d = DevTensor(w0, mpo.MPO_BF16, with_v=False)
+        d.grad.copy_(dev_u16(pats))
+        plan = mpo.Plan([d.spec()])
+        mpo.mpo_sgd_step(plan, mpo.SgdCfg(lr=1.0, momentum=0.5, grad_fmt=gfmt), 1)
+        torch.cuda.synchronize()
+        got = host_f32(d.m)
+        if fmt == "fp16":
+            want = pats.view(np.float16).astype(np.float32)
+        else:
+            want = torch.from_numpy(pats.view(np.int16)).view(torch.bfloat16).float().numpy()
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+        plan.destroy()
+
+
+# ---- multi-tensor lists ---------------------------------------------------------
+
+def _small_list(rng, count=41, total=1_500_000):
+    s = np.exp(rng.uniform(np.log(3.0), np.log(200000.0), size=count))
+    sizes = np.maximum(1, np.rint(s * total / s.sum())).astype(np.int64)
+    sizes[:6] = [1, 7, 8, CHUNK, CHUNK + 1, 2 * CHUNK - 1]
+    return [int(x) for x in sizes]
+
+
+LIST_CASES = [
+    ("adam", "bf16", dict(lr=1e-3, weight_decay=1e-4, decoupled_wd=True)),          # AdamW, configuration 1
+    ("adam", "bf16", dict(lr=3e-4, beta1=0.64, beta2=0.95, eps=1e-6, weight_decay=0.1, decoupled_wd=False)),
+    ("adam", "fp16", dict(lr=1e-3, loss_scale=1024.0)),
+    ("adam", "fp16", dict(lr=1e-3, weight_decay=1e-2, decoupled_wd=True, loss_scale=64.0)),
+    ("sgd", "bf16", dict(lr=0.3, momentum=0.9, weight_decay=2e-4)),
+    ("sgd", "fp16", dict(lr=0.1, momentum=0.9, loss_scale=128.0)),
+]
+
+
+@pytest.mark.parametrize("kind,fmt,kw", LIST_CASES, ids=["%s-%s-%d" % (c[0], c[1], i) for i, c in enumerate(LIST_CASES)])
+@pytest.mark.parametrize("misalign", [0, 1])
+def test_multi_tensor_list_matches_oracle(kind, fmt, kw, misalign):
+    """One launch over a ragged list (several chunks per tensor, tails of every residue) equals
+    the oracle tensor by tensor; with misalign=1 every array starts 2 or 4 bytes off 16-byte
+    alignment and takes the element-wise path."""
+    gfmt, rfmt = FMT[fmt]
+    rng = np.random.default_rng(7 + misalign)
+    sizes = _small_list(rng)
+    scale = kw.get("loss_scale", 1.0)
+    lib_cfg, ref_cfg = cfg_pair(kind, fmt, **kw)
+    say("list kind=%s fmt=%s kw=%s misalign=%d" % (kind, fmt, kw, misalign))
+    devs, hosts = [], []
+    for i, n in enumerate(sizes):
+        w0 = synth.gen_weights(n, synth.seed_for(9, i), "cpu", 0.02).numpy()
+        devs.append(DevTensor(w0, gfmt, with_v=(kind == "adam"), layer=i % 5, misalign=misalign))
+        hosts.append(HostTensor(w0, rfmt, with_v=(kind == "adam")))
+    plan = mpo.Plan([d.spec() for d in devs])
+    assert plan.num_params == sum(sizes)
+    for t in range(1, 6):
+        for i, (d, h) in enumerate(zip(devs, hosts)):
+            g = synth.bits16(synth.gen_grads(d.n, synth.seed_for(11, i, t), "cpu", 1e-3, fmt, scale))
+            d.grad.copy_(dev_u16(g))
+            if kind == "adam":
+                ref.adam_step(h.hi, h.res, g, h.m, h.v, ref_cfg, t)
+            else:
+                ref.sgd_step(h.hi, h.res, g, h.m, ref_cfg, t)
+        if kind == "adam":
+            mpo.mpo_adam_step(plan, lib_cfg, t)
+        else:
+            mpo.mpo_sgd_step(plan, lib_cfg, t)
+        for i, (d, h) in enumerate(zip(devs, hosts)):
+            assert_state_equal(d, h, "tensor %d (n=%d) step %d" % (i, d.n, t))
+    plan.destroy()
+
+
+def test_mixed_weight_and_gradient_formats():
+    rng = np.random.default_rng(3)
+    n = 50_001
+    for wf, gf in (("bf16", "fp16"), ("fp16", "bf16")):
+        say("mixed formats w=%s g=%s" % (wf, gf))
+        w0 = synth.gen_weights(n, 77, "cpu", 0.02).numpy()
+        lib_cfg, ref_cfg = cfg_pair("adam", wf, gfmt=gf, lr=1e-3, loss_scale=8.0)
+        d = DevTensor(w0, FMT[wf][0])
+        h = HostTensor(w0, FMT[wf][1])
+        plan = mpo.Plan([d.spec()])
+        for t in range(1, 4):
+            g = synth.bits16(synth.gen_grads(n, int(rng.integers(1 << 30)), "cpu", 1e-3, gf, 8.0))
+            d.grad.copy_(dev_u16(g))
+            mpo.mpo_adam_step(plan, lib_cfg, t)
+            ref.adam_step(h.hi, h.res, g, h.m, h.v, ref_cfg, t)
+            assert_state_equal(d, h, "step %d" % t)
+        plan.destroy()
+
+
+# ---- per-layer stepping (fused into backward) --------------------------------------
+
+def _layered_model(rng, fmt, layers=6):
+    """A small transformer-shaped list: per layer two matrices, a bias and a norm vector."""
+    gfmt, rfmt = FMT[fmt]
+    shapes = []
+    for ly in range(layers):
+        shapes += [(ly, 3 * CHUNK + 17), (ly, 2 * CHUNK), (ly, 257), (ly, 64)]
+    shapes += [(layers, 5 * CHUNK + 1)]
+    devs, hosts = [], []
+    for i, (ly, n) in enumerate(shapes):
+        w0 = synth.gen_weights(n, synth.seed_for(21, i), "cpu", 0.02).numpy()
+        devs.append((ly, n, w0))
+    return shapes, devs
+
+
+@pytest.mark.parametrize("kind,fmt", [("adam", "bf16"), ("adam", "fp16"), ("sgd", "bf16")])
+def test_step_layer_in_backward_order_equals_full_step_and_oracle(kind, fmt):
+    """Section 3.2: stepping layer by layer, last layer first, with ONE gradient buffer reused by
+    every layer, gives the same bits as one launch over the whole list and as the oracle."""
+    gfmt, rfmt = FMT[fmt]
+    rng = np.random.default_rng(5)
+    shapes, init = _layered_model(rng, fmt)
+    scale = 1.0 if fmt == "bf16" else 1024.0
+    kw = dict(lr=1e-3, loss_scale=scale) if kind == "adam" else dict(lr=1e-2, momentum=0.9, loss_scale=scale)
+    lib_cfg, ref_cfg = cfg_pair(kind, fmt, **kw)
+    layer_ids = sorted({ly for ly, _ in shapes})
+    # 16-byte aligned slots of the reused buffer, sized for the largest layer
+    def slots(ly):
+        out, off = [], 0
+        for (l2, n) in shapes:
+            if l2 == ly:
+                out.append((off, n))
+                off += (n + 7) // 8 * 8
+        return out, off
+    buf_len = max(slots(ly)[1] for ly in layer_ids)
+    gbuf = torch.zeros(buf_len, dtype=torch.int16, device=DEV)
+
+    say("step_layer kind=%s fmt=%s" % (kind, fmt))
+    A = [DevTensor(w0, gfmt, with_v=(kind == "adam"), layer=ly) for (ly, n, w0) in init]     # full-list path
+    B = [DevTensor(w0, gfmt, with_v=(kind == "adam"), layer=ly, grad=gbuf[:1]) for (ly, n, w0) in init]  # per layer
+    H = [HostTensor(w0, rfmt, with_v=(kind == "adam")) for (ly, n, w0) in init]
+    planA = mpo.Plan([d.spec() for d in A])
+    # plan B has no gradient pointers of its own: they are passed per call
+    planB = mpo.Plan([mpo.Tensor(d.hi, d.res, None, d.m, d.v, d.n, d.layer) for d in B])
+    # plan C: gradient pointers fixed at creation, all inside the one reused buffer
+    C = [DevTensor(w0, gfmt, with_v=(kind == "adam"), layer=ly, grad=gbuf[:1]) for (ly, n, w0) in init]
+    specC = []
+    for ly in layer_ids:
+        sl, _ = slots(ly)
+        members = [i for i, (l2, _) in enumerate(shapes) if l2 == ly]
+        for (off, n), i in zip(sl, members):
+            specC.append(mpo.Tensor(C[i].hi, C[i].res, gbuf[off:off + n], C[i].m, C[i].v, n, ly))
+    planC = mpo.Plan(specC)
+
+    for t in range(1, 4):
+        grads = [synth.bits16(synth.gen_grads(n, synth.seed_for(23, i, t), "cpu", 1e-3, fmt, scale))
+                 for i, (ly, n) in enumerate(shapes)]
+        for i, d in enumerate(A):
+            d.grad.copy_(dev_u16(grads[i]))
+            if kind == "adam":
+                ref.adam_step(H[i].hi, H[i].res, grads[i], H[i].m, H[i].v, ref_cfg, t)
+            else:
+                ref.sgd_step(H[i].hi, H[i].res, grads[i], H[i].m, ref_cfg, t)
+        (mpo.mpo_adam_step if kind == "adam" else mpo.mpo_sgd_step)(planA, lib_cfg, t)
+        for plan, use_override in ((planB, True), (planC, False)):
+            for ly in reversed(layer_ids):                      # backward order
+                sl, _ = slots(ly)
+                members = [i for i, (l2, _) in enumerate(shapes) if l2 == ly]
+                for (off, n), i in zip(sl, members):            # "backward" writes this layer's gradients
+                    gbuf[off:off + n].copy_(dev_u16(grads[i]))
+                ptrs = [gbuf[off:off + n] for (off, n) in sl] if use_override else None
+                mpo.mpo_step_layer(plan, ly, lib_cfg, t, grads=ptrs)
+        for i in range(len(shapes)):
+            assert_state_equal(A[i], H[i], "full list, tensor %d step %d" % (i, t))
+            assert_state_equal(B[i], H[i], "per layer (per-call grads), tensor %d step %d" % (i, t))
+            assert_state_equal(C[i], H[i], "per layer (plan grads in reused buffer), tensor %d step %d" % (i, t))
+    for p in (planA, planB, planC):
+        p.destroy()
+
+
+def test_step_layer_argument_checks_on_device():
+    n = 1000
+    w0 = np.zeros(n, np.float32)
+    ds = [DevTensor(w0, mpo.MPO_BF16, layer=0) for _ in range(2)]
+    plan = mpo.Plan([mpo.Tensor(d.hi, d.res, None, d.m, d.v, d.n, 0) for d in ds])
+
+    def status(*a, **k):
+        try:
+            mpo.mpo_step_layer(*a, **k)
+        except mpo.MpoError as e:
+            return e.status
+        return mpo.MPO_OK
+    g = torch.zeros(n, dtype=torch.int16, device=DEV)
+    assert status(plan, 0, mpo.AdamCfg(), 1) == mpo.MPO_ERR_INVALID_ARG                  # no gradients anywhere
+    assert status(plan, 0, mpo.AdamCfg(), 1, grads=[g]) == mpo.MPO_ERR_INVALID_ARG       # wrong count
+    assert status(plan, 3, mpo.AdamCfg(), 1, grads=[g, g]) == mpo.MPO_ERR_INVALID_ARG    # unknown layer
+    assert status(plan, 0, mpo.AdamCfg(), 1, grads=[g, ds[0].m]) == mpo.MPO_ERR_ALIAS    # gradient over state
+    assert status(plan, 0, mpo.AdamCfg(), 1, grads=[g, 0]) == mpo.MPO_ERR_INVALID_ARG
+    with pytest.raises(mpo.MpoError):
+        mpo.mpo_adam_step(plan, mpo.AdamCfg(), 1)                                        # plan has no gradients
+    assert status(plan, 0, mpo.AdamCfg(), 1, grads=[g, g]) == mpo.MPO_OK
+    # SGD-only plan (no v): Adam is refused, SGD runs
+    plan2 = mpo.Plan([mpo.Tensor(ds[0].hi, ds[0].res, g, ds[0].m, None, n, 0)])
+    with pytest.raises(mpo.MpoError):
+        mpo.mpo_adam_step(plan2, mpo.AdamCfg(), 1)
+    mpo.mpo_sgd_step(plan2, mpo.SgdCfg(), 1)
+    # more tensors in a layer than per-call gradient slots
+    many = [DevTensor(np.zeros(8, np.float32), mpo.MPO_BF16, layer=0) for _ in range(mpo.MPO_MAX_LAYER_GRADS + 1)]
+    plan3 = mpo.Plan([d.spec() for d in many])
+    assert status(plan3, 0, mpo.AdamCfg(), 1, grads=[d.grad for d in many]) == mpo.MPO_ERR_UNSUPPORTED
+    assert status(plan3, 0, mpo.AdamCfg(), 1) == mpo.MPO_OK                              # plan gradients: no limit
+    torch.cuda.synchronize()
+    for p in (plan, plan2, plan3):
+        p.destroy()
+
+
+def test_empty_plan_and_zero_length_tensors_are_noops():
+    plan = mpo.Plan([])
+    mpo.mpo_adam_step(plan, mpo.AdamCfg(), 1)
+    mpo.mpo_sgd_step(plan, mpo.SgdCfg(), 1)
+    plan.destroy()
+    d = DevTensor(np.ones(10, np.float32), mpo.MPO_BF16)
+    plan = mpo.Plan([mpo.Tensor(None, None, None, None, None, 0, 0), d.spec(), mpo.Tensor(None, None, None, None, None, 0, 2)])
+    assert plan.num_chunks == 1
+    mpo.mpo_adam_step(plan, mpo.AdamCfg(), 1)
+    mpo.mpo_step_layer(plan, 2, mpo.AdamCfg(), 1)
+    torch.cuda.synchronize()
+    h = HostTensor(np.ones(10, np.float32), ref.BF16)
+    ref.adam_step(h.hi, h.res, np.zeros(10, np.uint16), h.m, h.v, ref.AdamCfg(), 1)
+    assert_state_equal(d, h)
+    plan.destroy()
+
+
+def test_resume_from_saved_state_is_bit_identical():
+    """State is exactly (hi, res, m, v, step): 10 steps equal 5 steps, a new plan on copies
+    of the buffers, and 5 more."""
+    n = 3 * CHUNK + 11
+    w0 = synth.gen_weights(n, 5, "cpu", 0.02).numpy()
+    grads = [dev_u16(synth.bits16(synth.gen_grads(n, 100 + t, "cpu", 1e-3))) for t in range(10)]
+    say("resume")
+    a = DevTensor(w0, mpo.MPO_BF16)
+    pa = mpo.Plan([a.spec()])
+    for t in range(10):
+        a.grad.copy_(grads[t])
+        mpo.mpo_adam_step(pa, mpo.AdamCfg(weight_decay=1e-2), t + 1)
+    b = DevTensor(w0, mpo.MPO_BF16)
+    pb = mpo.Plan([b.spec()])
+    for t in range(5):
+        b.grad.copy_(grads[t])
+        mpo.mpo_adam_step(pb, mpo.AdamCfg(weight_decay=1e-2), t + 1)
+    torch.cuda.synchronize()
+    saved = [x.clone() for x in (b.hi, b.res, b.m, b.v)]
+    pb.destroy()
+    c = DevTensor(np.zeros(n, np.float32), mpo.MPO_BF16)
+    for dst, src in zip((c.hi, c.res, c.m, c.v), saved):
+        dst.copy_(src)
+    pc = mpo.Plan([c.spec()])
+    for t in range(5, 10):
+        c.grad.copy_(grads[t])
+        mpo.mpo_adam_step(pc, mpo.AdamCfg(weight_decay=1e-2), t + 1)
+    torch.cuda.synchronize()
+    for x, y in zip((a.hi, a.res, a.m, a.v), (c.hi, c.res, c.m, c.v)):
+        assert torch.equal(x, y)
+    pa.destroy()
+    pc.destroy()
+
+
+def test_runs_on_the_callers_stream():
+    n = 2 * CHUNK + 3
+    w0 = synth.gen_weights(n, 6, "cpu", 0.02).numpy()
+    g = synth.bits16(synth.gen_grads(n, 7, "cpu", 1e-3))
+    s = torch.cuda.Stream()
+    say("side stream")
+    with torch.cuda.stream(s):
+        d = DevTensor(w0, mpo.MPO_BF16, stream=s)
+        d.grad.copy_(dev_u16(g), non_blocking=False)
+        plan = mpo.Plan([d.spec()])
+        for t in (1, 2, 3):
+            mpo.mpo_adam_step(plan, mpo.AdamCfg(), t, stream=s)
+    s.synchronize()
+    h = HostTensor(w0, ref.BF16)
+    for t in (1, 2, 3):
+        ref.adam_step(h.hi, h.res, g, h.m, h.v, ref.AdamCfg(), t)
+    assert_state_equal(d, h, "side stream")
+    plan.destroy()
