@@ -12,7 +12,7 @@ namespace mpo {
 
 /* One workgroup (256 lanes = 4 wavefronts of 64) owns one chunk. */
 constexpr uint32_t kBlock = 256;
-constexpr uint32_t kChunkElems = 8192;
+constexpr uint32_t kChunkElems = 4096;
 
 /* Bits of TensorDesc::flags. */
 constexpr uint32_t kStateAligned = 1u; /* hi, res, m, v all 16-byte aligned          */

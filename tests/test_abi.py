@@ -107,12 +107,13 @@ def test_plan_alias_detection():
 
 
 def test_plan_layout_covers_every_element_once_in_layer_order():
-    sizes = [1, 8191, 8192, 8193, 3 * 8192 + 5, 0, 100000, 64]
+    ce0 = _host_plan([]).chunk_elems
+    sizes = [1, ce0 - 1, ce0, ce0 + 1, 3 * ce0 + 5, 0, 100000, 64]
     layers = [3, 0, 2, 0, 1, 1, 2, 0]
     ts = [T(i, n=n, layer=l) for i, (n, l) in enumerate(zip(sizes, layers))]
     p = _host_plan(ts)
     ce = p.chunk_elems
-    assert ce == 8192
+    assert ce == ce0 and ce % 1024 == 0
     assert p.num_params == sum(sizes)
     assert p.num_chunks == sum((n + ce - 1) // ce for n in sizes)
     seen = {}

@@ -20,7 +20,7 @@ from gpu_util import (DEV, FMT, DevTensor, HostTensor, assert_state_equal, cfg_p
 
 pytestmark = pytest.mark.gpu
 
-CHUNK = 8192
+CHUNK = int(mpo.lib.mpo_plan_chunk_elems(None))      # parameters per workgroup
 SIZES = [1, 7, 8, 9, 2047, 2048, CHUNK - 1, CHUNK, CHUNK + 1, 3 * CHUNK + 5, (1 << 20) + 3]
 
 
