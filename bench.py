@@ -22,6 +22,11 @@ sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBPS = 8000.0            # MI355X HBM3E, published peak
 ADAM_BYTES_PER_PARAM = 26         # read hi, res, grad (2 B each), m, v (4 B each); write hi, res, m, v
+# HBM-side bytes per parameter of the Adam step kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+# each scaled by what the same counter reads for a plain kernel of known size (FETCH_SIZE x 2.000, WRITE_SIZE
+# x 1.000 on this GPU): 14.03 read + 12.00 written.  Source: profiles/step_kernel_adam_bf16_c3_pmc_traffic.txt.
+# It cannot be collected inside a timed run, so the figure is carried here.
+MEASURED_TRAFFIC_BYTES_PER_PARAM = {"c3": 26.03}
 
 
 def cpu_baseline(wl, sample_params: int, steps: int):
@@ -71,6 +76,9 @@ def main():
                     help="regenerate each layer's gradients inside the loop (adds generator kernels to the timing)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 26)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain elementwise kernel that reads 1 GiB and writes 1 GiB (known traffic, "
+                         "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus %d is not supported"
@@ -129,13 +137,22 @@ def main():
                    "launches_per_step": launches // steps, "per_layer": wl.per_layer,
                    "fresh_grads_in_loop": bool(a.fresh_grads), "resident_GB": st.resident_bytes / 1e9},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                     "frac": achieved / PEAK_HBM_GBPS, "traffic": None,
+                     "frac": achieved / PEAK_HBM_GBPS,
+                     "traffic": (MEASURED_TRAFFIC_BYTES_PER_PARAM[wl.key] * P * steps / launches
+                                 if wl.key in MEASURED_TRAFFIC_BYTES_PER_PARAM else None),
                      "kernel": "step_kernel<adam,%s>" % wl.fmt, "bytes_per_param": ADAM_BYTES_PER_PARAM,
                      "bytes_per_launch": bytes_per_launch, "avg_launch_ms": ev_ms / launches,
                      "event_ms": ev_ms, "launches": launches},
         "setup_s": setup_s,
     }
     st.close()
+    if a.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)       # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)                                   # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        res["calibration"] = "3 x torch.add(src, 1.0, out=dst) on 2^28 fp32: 1 GiB read + 1 GiB written each"
     if not a.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl, a.cpu_sample, 5)
     print(json.dumps(res), flush=True)
