@@ -21,6 +21,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBPS = 8000.0            # MI355X HBM3E, published peak
+SGD_BYTES_PER_PARAM = 18          # read hi, res, grad, momentum buffer; write hi, res, buffer
 ADAM_BYTES_PER_PARAM = 26         # read hi, res, grad (2 B each), m, v (4 B each); write hi, res, m, v
 # HBM-side bytes per parameter of the Adam step kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # each scaled by what the same counter reads for a plain kernel of known size (FETCH_SIZE x 2.000, WRITE_SIZE
@@ -72,6 +73,8 @@ def main():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c3", choices=["c0", "c1", "c2", "c3", "c4"])
+    ap.add_argument("--optimizer", default="adam", choices=["adam", "sgd"],
+                    help="adam (the headline metric) or sgd with momentum 0.9 (18 B per parameter)")
     ap.add_argument("--fresh-grads", action="store_true",
                     help="regenerate each layer's gradients inside the loop (adds generator kernels to the timing)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -105,7 +108,8 @@ def main():
     setup_s = time.perf_counter() - t_setup
 
     stream = torch.cuda.current_stream()
-    cfg = st.adam_cfg()
+    cfg = st.adam_cfg() if a.optimizer == "adam" else st.sgd_cfg()
+    bpp = ADAM_BYTES_PER_PARAM if a.optimizer == "adam" else SGD_BYTES_PER_PARAM
     step_no = 0
     for _ in range(a.warmup):
         step_no += 1
@@ -125,22 +129,23 @@ def main():
 
     P = wl.num_params
     value = P * steps / wall
-    bytes_per_launch = ADAM_BYTES_PER_PARAM * P * steps / launches
-    achieved = ADAM_BYTES_PER_PARAM * P * steps / (ev_ms * 1e-3) / 1e9
+    bytes_per_launch = bpp * P * steps / launches
+    achieved = bpp * P * steps / (ev_ms * 1e-3) / 1e9
     res = {
-        "metric": "params updated/sec, split-precision Adam (achieved HBM GB/s and % of peak in roofline)",
+        "metric": "params updated/sec, split-precision %s (achieved HBM GB/s and %% of peak in roofline)"
+                  % ("Adam" if a.optimizer == "adam" else "SGD-momentum"),
         "value": value, "unit": "params/s", "n_gpus": 1, "steps": steps, "warmup": a.warmup,
         "ms_per_step": wall * 1e3 / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: %s" % (wl.key, wl.description), "params": P, "tensors": len(wl.tensors),
-                   "format": wl.fmt + "+16-bit residual", "optimizer": wl.optimizer, "loss_scale": wl.loss_scale,
+                   "format": wl.fmt + "+16-bit residual", "optimizer": wl.optimizer if a.optimizer == "adam" else "sgd-momentum", "loss_scale": wl.loss_scale,
                    "launches_per_step": launches // steps, "per_layer": wl.per_layer,
                    "fresh_grads_in_loop": bool(a.fresh_grads), "resident_GB": st.resident_bytes / 1e9},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                      "frac": achieved / PEAK_HBM_GBPS,
                      "traffic": (MEASURED_TRAFFIC_BYTES_PER_PARAM[wl.key] * P * steps / launches
-                                 if wl.key in MEASURED_TRAFFIC_BYTES_PER_PARAM else None),
-                     "kernel": "step_kernel<adam,%s>" % wl.fmt, "bytes_per_param": ADAM_BYTES_PER_PARAM,
+                                 if wl.key in MEASURED_TRAFFIC_BYTES_PER_PARAM and a.optimizer == "adam" else None),
+                     "kernel": "step_kernel<%s,%s>" % (a.optimizer, wl.fmt), "bytes_per_param": bpp,
                      "bytes_per_launch": bytes_per_launch, "avg_launch_ms": ev_ms / launches,
                      "event_ms": ev_ms, "launches": launches},
         "setup_s": setup_s,

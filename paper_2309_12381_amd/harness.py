@@ -86,6 +86,11 @@ class ModelState:
                            decoupled_wd=(wl.optimizer == "adamw"), loss_scale=wl.loss_scale,
                            weight_fmt=self.fmt, grad_fmt=self.fmt)
 
+    def sgd_cfg(self) -> mpo.SgdCfg:
+        wl = self.wl
+        return mpo.SgdCfg(lr=1e-2, momentum=0.9, weight_decay=wl.weight_decay, loss_scale=wl.loss_scale,
+                          weight_fmt=self.fmt, grad_fmt=self.fmt)
+
     def fill_grads(self, tensor_ids, step: int):
         """Stand-in for backward: fresh seeded gradients for these tensors, written into the buffer."""
         wl = self.wl
@@ -104,7 +109,10 @@ class ModelState:
                 self.fill_grads(range(len(self.views)), step)
             if before_layer:
                 before_layer(None, list(range(len(self.views))))
-            mpo.mpo_adam_step(self.plan, cfg, step, stream=stream)
+            if isinstance(cfg, mpo.SgdCfg):
+                mpo.mpo_sgd_step(self.plan, cfg, step, stream=stream)
+            else:
+                mpo.mpo_adam_step(self.plan, cfg, step, stream=stream)
             return 1
         for layer in self.layers_backward:
             ids = self.by_layer[layer]
