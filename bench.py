@@ -75,6 +75,9 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c0", "c1", "c2", "c3", "c4"])
     ap.add_argument("--optimizer", default="adam", choices=["adam", "sgd"],
                     help="adam (the headline metric) or sgd with momentum 0.9 (18 B per parameter)")
+    ap.add_argument("--res-bits", type=int, default=0,
+                    help="extra bits kept per weight: 0 = all (the headline), 8 = the paper's bf16+8 / fp16+8 "
+                         "(byte residual, 24 B per parameter for Adam)")
     ap.add_argument("--fresh-grads", action="store_true",
                     help="regenerate each layer's gradients inside the loop (adds generator kernels to the timing)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -98,7 +101,7 @@ def main():
     wl = synth.workload(a.workload)
     steps = a.steps if a.steps is not None else wl.steps
     t_setup = time.perf_counter()
-    st = harness.ModelState(wl, dev)
+    st = harness.ModelState(wl, dev, res_bits=a.res_bits)
     if wl.per_layer:
         # the reused buffer holds one (largest) layer's worth of gradient values, read by every layer
         st.grad.normal_(0.0, wl.grad_std * wl.loss_scale, generator=synth.generator(7, dev))
@@ -110,6 +113,7 @@ def main():
     stream = torch.cuda.current_stream()
     cfg = st.adam_cfg() if a.optimizer == "adam" else st.sgd_cfg()
     bpp = ADAM_BYTES_PER_PARAM if a.optimizer == "adam" else SGD_BYTES_PER_PARAM
+    bpp -= 2 * (2 - st.res_bytes)            # a byte residual is read and written as 1 B instead of 2
     step_no = 0
     for _ in range(a.warmup):
         step_no += 1
@@ -138,13 +142,15 @@ def main():
         "ms_per_step": wall * 1e3 / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: %s" % (wl.key, wl.description), "params": P, "tensors": len(wl.tensors),
-                   "format": wl.fmt + "+16-bit residual", "optimizer": wl.optimizer if a.optimizer == "adam" else "sgd-momentum", "loss_scale": wl.loss_scale,
+                   "format": "%s+%d extra bits (%d-bit residual)" % (wl.fmt, a.res_bits or (16 if wl.fmt == "bf16" else 13),
+                                                                      8 * st.res_bytes), "optimizer": wl.optimizer if a.optimizer == "adam" else "sgd-momentum", "loss_scale": wl.loss_scale,
                    "launches_per_step": launches // steps, "per_layer": wl.per_layer,
                    "fresh_grads_in_loop": bool(a.fresh_grads), "resident_GB": st.resident_bytes / 1e9},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                      "frac": achieved / PEAK_HBM_GBPS,
                      "traffic": (MEASURED_TRAFFIC_BYTES_PER_PARAM[wl.key] * P * steps / launches
-                                 if wl.key in MEASURED_TRAFFIC_BYTES_PER_PARAM and a.optimizer == "adam" else None),
+                                 if wl.key in MEASURED_TRAFFIC_BYTES_PER_PARAM and a.optimizer == "adam" and st.res_bytes == 2
+                                 else None),
                      "kernel": "step_kernel<%s,%s>" % (a.optimizer, wl.fmt), "bytes_per_param": bpp,
                      "bytes_per_launch": bytes_per_launch, "avg_launch_ms": ev_ms / launches,
                      "event_ms": ev_ms, "launches": launches},

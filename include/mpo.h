@@ -13,7 +13,8 @@
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers on the current HIP device, owned by
  *     the caller.  Arrays are dense, element i of every array of a tensor
- *     belongs to parameter i.  `hi`, `res`, `grad` are uint16_t bit patterns.
+ *     belongs to parameter i.  `hi` and `grad` are uint16_t bit patterns, `res`
+ *     is uint16_t or, with at most 8 extra bits kept, uint8_t (see res_bits).
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = default stream).
  *     Calls only enqueue work on that stream and return; they never wait for
  *     the device.  The step entry points allocate nothing.
@@ -56,6 +57,17 @@ typedef enum { MPO_ROUND_TRUNC = 0, MPO_ROUND_NEAREST = 1, MPO_ROUND_STOCHASTIC 
 
 typedef enum { MPO_OPT_ADAM = 0, MPO_OPT_SGD = 1 } mpo_opt;
 
+/* ---- how many extra bits are kept (Section 3.1) ---------------------------
+ *
+ * `res_bits` = E, the number of leading dropped significand bits that the
+ * residual keeps.  0 means all of them (16 for bf16, 13 for fp16): the pair
+ * is then as precise as fp32.  1 <= E < all keeps only part of them (the
+ * paper's fp16+8 / bf16+8 is E = 8): the fp32 value is cut toward zero to
+ * 16 + E bits.  Storage: one uint8_t per parameter when 1 <= E <= 8, else one
+ * uint16_t; the E bits are right-aligned in it.  E above the format's full
+ * count is MPO_ERR_INVALID_ARG.
+ */
+
 /* ---- split / merge (Section 3.1, Table 1) --------------------------------
  *
  * mpo_split: w32[i] -> (hi[i], res[i]).  bf16: hi = upper, res = lower half of
@@ -63,13 +75,13 @@ typedef enum { MPO_OPT_ADAM = 0, MPO_OPT_SGD = 1 } mpo_opt;
  * 2^-14 <= |x| < 65536 and for multiples of 2^-37 below that; other values are
  * cut toward zero to the 2^-37 grid, finite values of 65536 or more saturate
  * at the largest finite pair, +-inf and NaN map to fp16 +-inf / NaN.
- * mpo_merge: the inverse, (hi[i], res[i]) -> w32[i].
+ * mpo_merge: the inverse, (hi[i], res[i]) -> w32[i] (cut bits read as zero).
  * w32 must not overlap hi or res (MPO_ERR_ALIAS); n is a number of elements.
  */
-mpo_status mpo_split(const float *w32, uint16_t *hi, uint16_t *res, uint64_t n,
-                     mpo_fmt fmt, mpo_round round, void *hip_stream);
-mpo_status mpo_merge(const uint16_t *hi, const uint16_t *res, float *w32, uint64_t n,
-                     mpo_fmt fmt, void *hip_stream);
+mpo_status mpo_split(const float *w32, uint16_t *hi, void *res, uint64_t n,
+                     mpo_fmt fmt, int32_t res_bits, mpo_round round, void *hip_stream);
+mpo_status mpo_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n,
+                     mpo_fmt fmt, int32_t res_bits, void *hip_stream);
 
 /* ---- parameter list -------------------------------------------------------
  *
@@ -77,17 +89,22 @@ mpo_status mpo_merge(const uint16_t *hi, const uint16_t *res, float *w32, uint64
  * ever supplied per call (mpo_step_layer).  `v` may be NULL for a list that is
  * only stepped with SGD, `m` (the momentum buffer) too if momentum is 0.
  * `layer` (>= 0) groups tensors whose gradients become available together.
+ * `res_bits` is the number of extra bits this tensor's residual keeps (see
+ * above; it fixes whether `res` is a uint8_t or a uint16_t array).  All tensors
+ * of one list must use the same residual storage width, else
+ * MPO_ERR_UNSUPPORTED.
  * Gradient buffers may overlap each other (one reused buffer for all layers);
  * nothing may overlap hi, res, m or v.
  */
 typedef struct {
     uint16_t *hi;
-    uint16_t *res;
+    void *res;
     const uint16_t *grad;
     float *m;
     float *v;
     uint64_t n;
     int32_t layer;
+    int32_t res_bits;
 } mpo_tensor;
 
 /* Adam / AdamW (Section 3.1: the classic optimizer, hyper-parameters

@@ -99,20 +99,48 @@ static float merge_one(uint16_t hi, uint16_t res, int fmt)
     return fmt == MPO_REF_FP16 ? merge_fp16(hi, res) : merge_bf16(hi, res);
 }
 
+/* ---- keeping only the E leading extra bits (Sec. 3.1) ---------------------
+ * The residual that is stored is the full one with its trailing bits cut off;
+ * on merge the cut bits read as zero: the fp32 value is truncated toward zero
+ * to 16 + E bits. */
+
+static int full_bits(int fmt) { return fmt == MPO_REF_FP16 ? 13 : 16; }
+
+static int kept_bits(int fmt, int res_bits) { return res_bits == 0 ? full_bits(fmt) : res_bits; }
+
+static uint16_t load_res(const void *res, uint64_t i, int fmt, int res_bits)
+{
+    int E = kept_bits(fmt, res_bits);
+    uint16_t stored = E <= 8 ? ((const uint8_t *)res)[i] : ((const uint16_t *)res)[i];
+    if (fmt == MPO_REF_FP16) stored &= 0x1FFFu;        /* spare bits of a full fp16 residual */
+    return (uint16_t)(stored << (full_bits(fmt) - E));
+}
+
+static void store_res(void *res, uint64_t i, uint16_t full, int fmt, int res_bits)
+{
+    int E = kept_bits(fmt, res_bits);
+    uint16_t kept = (uint16_t)(full >> (full_bits(fmt) - E));
+    if (E <= 8) ((uint8_t *)res)[i] = (uint8_t)kept; else ((uint16_t *)res)[i] = kept;
+}
+
 /* A 16-bit float read as fp32: every bf16 and fp16 value is an fp32 value. */
 float mpo_ref_cvt16(uint16_t x, int fmt)
 {
     return fmt == MPO_REF_FP16 ? merge_fp16(x, 0) : merge_bf16(x, 0);
 }
 
-void mpo_ref_split(const float *w32, uint16_t *hi, uint16_t *res, uint64_t n, int fmt)
+void mpo_ref_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits)
 {
-    for (uint64_t i = 0; i < n; ++i) split_one(w32[i], &hi[i], &res[i], fmt);
+    for (uint64_t i = 0; i < n; ++i) {
+        uint16_t full;
+        split_one(w32[i], &hi[i], &full, fmt);
+        store_res(res, i, full, fmt, res_bits);
+    }
 }
 
-void mpo_ref_merge(const uint16_t *hi, const uint16_t *res, float *w32, uint64_t n, int fmt)
+void mpo_ref_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits)
 {
-    for (uint64_t i = 0; i < n; ++i) w32[i] = merge_one(hi[i], res[i], fmt);
+    for (uint64_t i = 0; i < n; ++i) w32[i] = merge_one(hi[i], load_res(res, i, fmt, res_bits), fmt);
 }
 
 /* ---- Adam (Sec. 3.1: the classic optimizer, hyper-parameters unchanged) ----
@@ -123,7 +151,7 @@ void mpo_ref_merge(const uint16_t *hi, const uint16_t *res, float *w32, uint64_t
  * Scalars are formed in double and rounded to fp32 once.  Per element every
  * line below is one rounded fp32 operation.
  */
-void mpo_ref_adam_step(uint16_t *hi, uint16_t *res, const uint16_t *grad, float *m, float *v,
+void mpo_ref_adam_step(uint16_t *hi, void *res, const uint16_t *grad, float *m, float *v,
                        uint64_t n, const mpo_ref_adam_cfg *cfg, uint64_t step)
 {
     const double t = (double)step;
@@ -140,7 +168,7 @@ void mpo_ref_adam_step(uint16_t *hi, uint16_t *res, const uint16_t *grad, float 
     const int has_wd = cfg->weight_decay != 0.0;
 
     for (uint64_t i = 0; i < n; ++i) {
-        float w = merge_one(hi[i], res[i], cfg->weight_fmt);
+        float w = merge_one(hi[i], load_res(res, i, cfg->weight_fmt, cfg->res_bits), cfg->weight_fmt);
         float g = mpo_ref_cvt16(grad[i], cfg->grad_fmt);
         g = g * IS;
         if (has_wd) {
@@ -166,12 +194,14 @@ void mpo_ref_adam_step(uint16_t *hi, uint16_t *res, const uint16_t *grad, float 
         float w1 = w - upd;
         m[i] = m1;
         v[i] = v1;
-        split_one(w1, &hi[i], &res[i], cfg->weight_fmt);
+        uint16_t full;
+        split_one(w1, &hi[i], &full, cfg->weight_fmt);
+        store_res(res, i, full, cfg->weight_fmt, cfg->res_bits);
     }
 }
 
 /* ---- SGD with momentum (Sec. 3.1; appendix: SGD with momentum, weight decay) */
-void mpo_ref_sgd_step(uint16_t *hi, uint16_t *res, const uint16_t *grad, float *buf,
+void mpo_ref_sgd_step(uint16_t *hi, void *res, const uint16_t *grad, float *buf,
                       uint64_t n, const mpo_ref_sgd_cfg *cfg, uint64_t step)
 {
     (void)step; /* momentum buffers start at zero, so step 1 needs no special case */
@@ -183,7 +213,7 @@ void mpo_ref_sgd_step(uint16_t *hi, uint16_t *res, const uint16_t *grad, float *
     const int has_mu = cfg->momentum != 0.0;
 
     for (uint64_t i = 0; i < n; ++i) {
-        float w = merge_one(hi[i], res[i], cfg->weight_fmt);
+        float w = merge_one(hi[i], load_res(res, i, cfg->weight_fmt, cfg->res_bits), cfg->weight_fmt);
         float g = mpo_ref_cvt16(grad[i], cfg->grad_fmt);
         g = g * IS;
         if (has_wd) {
@@ -198,6 +228,8 @@ void mpo_ref_sgd_step(uint16_t *hi, uint16_t *res, const uint16_t *grad, float *
         }
         float upd = LR * b;
         float w1 = w - upd;
-        split_one(w1, &hi[i], &res[i], cfg->weight_fmt);
+        uint16_t full;
+        split_one(w1, &hi[i], &full, cfg->weight_fmt);
+        store_res(res, i, full, cfg->weight_fmt, cfg->res_bits);
     }
 }

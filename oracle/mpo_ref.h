@@ -33,31 +33,39 @@ extern "C" {
 
 enum { MPO_REF_BF16 = 0, MPO_REF_FP16 = 1 };
 
+/* Section 3.1 also keeps "only part of those bits": res_bits = E keeps the E
+ * leading bits of the dropped significand bits (E = 8 is the paper's fp16+8 /
+ * bf16+8).  0 means all of them (16 for bf16, 13 for fp16).  The residual array
+ * has one uint8_t per element when 1 <= E <= 8, else one uint16_t; the E bits
+ * are right-aligned in it. */
+
 typedef struct {
     double lr, beta1, beta2, eps, weight_decay;
     int32_t decoupled_wd; /* 1: AdamW (w *= 1-lr*wd), 0: L2 (g += wd*w)      */
     double loss_scale;    /* gradients arrive multiplied by this              */
     int32_t weight_fmt;   /* format of hi                                     */
     int32_t grad_fmt;     /* format of grad                                   */
+    int32_t res_bits;     /* extra bits kept, 0 = all                         */
 } mpo_ref_adam_cfg;
 
 typedef struct {
     double lr, momentum, weight_decay; /* weight decay is L2 (added to g)     */
     double loss_scale;
     int32_t weight_fmt, grad_fmt;
+    int32_t res_bits;
 } mpo_ref_sgd_cfg;
 
 /* Section 3.1, Table 1: fp32 -> (16-bit float, extra bits), truncation. */
-void mpo_ref_split(const float *w32, uint16_t *hi, uint16_t *res, uint64_t n, int fmt);
+void mpo_ref_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits);
 /* Section 3.1: (16-bit float, extra bits) -> fp32. */
-void mpo_ref_merge(const uint16_t *hi, const uint16_t *res, float *w32, uint64_t n, int fmt);
+void mpo_ref_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits);
 
 /* Section 3.1 "classic optimizers": bias-corrected Adam / AdamW on one tensor. */
-void mpo_ref_adam_step(uint16_t *hi, uint16_t *res, const uint16_t *grad, float *m, float *v,
+void mpo_ref_adam_step(uint16_t *hi, void *res, const uint16_t *grad, float *m, float *v,
                        uint64_t n, const mpo_ref_adam_cfg *cfg, uint64_t step);
 /* Section 3.1 "classic optimizers": SGD with momentum (dampening 0, no Nesterov).
  * momentum == 0 leaves buf untouched (it may then be NULL). */
-void mpo_ref_sgd_step(uint16_t *hi, uint16_t *res, const uint16_t *grad, float *buf,
+void mpo_ref_sgd_step(uint16_t *hi, void *res, const uint16_t *grad, float *buf,
                       uint64_t n, const mpo_ref_sgd_cfg *cfg, uint64_t step);
 
 /* Exact conversion of one 16-bit float to fp32 (used for gradients). */

@@ -28,13 +28,18 @@ class _AdamCfg(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
                 ("eps", ctypes.c_double), ("weight_decay", ctypes.c_double),
                 ("decoupled_wd", ctypes.c_int32), ("loss_scale", ctypes.c_double),
-                ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32)]
+                ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32), ("res_bits", ctypes.c_int32)]
 
 
 class _SgdCfg(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_double), ("momentum", ctypes.c_double),
                 ("weight_decay", ctypes.c_double), ("loss_scale", ctypes.c_double),
-                ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32)]
+                ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32), ("res_bits", ctypes.c_int32)]
+
+
+def res_dtype(res_bits: int):
+    """Storage type of the residual: one byte per element for 1..8 kept bits, else two."""
+    return np.uint8 if 1 <= res_bits <= 8 else np.uint16
 
 
 @dataclass
@@ -48,10 +53,11 @@ class AdamCfg:
     loss_scale: float = 1.0
     weight_fmt: int = BF16
     grad_fmt: int = BF16
+    res_bits: int = 0
 
     def _c(self):
         return _AdamCfg(self.lr, self.beta1, self.beta2, self.eps, self.weight_decay,
-                        int(self.decoupled_wd), self.loss_scale, self.weight_fmt, self.grad_fmt)
+                        int(self.decoupled_wd), self.loss_scale, self.weight_fmt, self.grad_fmt, self.res_bits)
 
 
 @dataclass
@@ -62,10 +68,11 @@ class SgdCfg:
     loss_scale: float = 1.0
     weight_fmt: int = BF16
     grad_fmt: int = BF16
+    res_bits: int = 0
 
     def _c(self):
         return _SgdCfg(self.lr, self.momentum, self.weight_decay, self.loss_scale,
-                       self.weight_fmt, self.grad_fmt)
+                       self.weight_fmt, self.grad_fmt, self.res_bits)
 
 
 def _chk(a, dtype, n=None):
@@ -80,6 +87,10 @@ def _p16(a):
     return a.ctypes.data_as(_u16p)
 
 
+def _pv(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
 def _p32(a):
     return a.ctypes.data_as(_f32p)
 
@@ -92,54 +103,54 @@ class Oracle:
 
     def __init__(self, path):
         lib = ctypes.CDLL(path)
-        lib.mpo_ref_split.argtypes = [_f32p, _u16p, _u16p, ctypes.c_uint64, ctypes.c_int]
+        lib.mpo_ref_split.argtypes = [_f32p, _u16p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int, ctypes.c_int]
         lib.mpo_ref_split.restype = None
-        lib.mpo_ref_merge.argtypes = [_u16p, _u16p, _f32p, ctypes.c_uint64, ctypes.c_int]
+        lib.mpo_ref_merge.argtypes = [_u16p, ctypes.c_void_p, _f32p, ctypes.c_uint64, ctypes.c_int, ctypes.c_int]
         lib.mpo_ref_merge.restype = None
-        lib.mpo_ref_adam_step.argtypes = [_u16p, _u16p, _u16p, _f32p, _f32p, ctypes.c_uint64,
+        lib.mpo_ref_adam_step.argtypes = [_u16p, ctypes.c_void_p, _u16p, _f32p, _f32p, ctypes.c_uint64,
                                           ctypes.POINTER(_AdamCfg), ctypes.c_uint64]
         lib.mpo_ref_adam_step.restype = None
-        lib.mpo_ref_sgd_step.argtypes = [_u16p, _u16p, _u16p, _f32p, ctypes.c_uint64,
+        lib.mpo_ref_sgd_step.argtypes = [_u16p, ctypes.c_void_p, _u16p, _f32p, ctypes.c_uint64,
                                          ctypes.POINTER(_SgdCfg), ctypes.c_uint64]
         lib.mpo_ref_sgd_step.restype = None
         lib.mpo_ref_cvt16.argtypes = [ctypes.c_uint16, ctypes.c_int]
         lib.mpo_ref_cvt16.restype = ctypes.c_float
         self._lib = lib
 
-    def split(self, w32, fmt=BF16):
-        """fp32 array -> (hi, res) uint16 arrays."""
+    def split(self, w32, fmt=BF16, res_bits=0):
+        """fp32 array -> (hi uint16, res uint16 or uint8) arrays."""
         _chk(w32, np.float32)
         n = w32.shape[0]
         hi = np.empty(n, np.uint16)
-        res = np.empty(n, np.uint16)
-        self._lib.mpo_ref_split(_p32(w32), _p16(hi), _p16(res), n, fmt)
+        res = np.empty(n, res_dtype(res_bits))
+        self._lib.mpo_ref_split(_p32(w32), _p16(hi), _pv(res), n, fmt, res_bits)
         return hi, res
 
-    def merge(self, hi, res, fmt=BF16):
-        """(hi, res) uint16 arrays -> fp32 array."""
+    def merge(self, hi, res, fmt=BF16, res_bits=0):
+        """(hi, res) arrays -> fp32 array."""
         n = _chk(hi, np.uint16).shape[0]
-        _chk(res, np.uint16, n)
+        _chk(res, res_dtype(res_bits), n)
         w32 = np.empty(n, np.float32)
-        self._lib.mpo_ref_merge(_p16(hi), _p16(res), _p32(w32), n, fmt)
+        self._lib.mpo_ref_merge(_p16(hi), _pv(res), _p32(w32), n, fmt, res_bits)
         return w32
 
     def adam_step(self, hi, res, grad, m, v, cfg: AdamCfg, step: int):
         """One Adam step on one tensor, in place on hi, res, m, v."""
         n = _chk(hi, np.uint16).shape[0]
-        _chk(res, np.uint16, n)
+        _chk(res, res_dtype(cfg.res_bits), n)
         _chk(grad, np.uint16, n)
         _chk(m, np.float32, n)
         _chk(v, np.float32, n)
         if step < 1:
             raise ValueError("step counts from 1")
         c = cfg._c()
-        self._lib.mpo_ref_adam_step(_p16(hi), _p16(res), _p16(grad), _p32(m), _p32(v), n,
+        self._lib.mpo_ref_adam_step(_p16(hi), _pv(res), _p16(grad), _p32(m), _p32(v), n,
                                     ctypes.byref(c), step)
 
     def sgd_step(self, hi, res, grad, buf, cfg: SgdCfg, step: int):
         """One SGD(-momentum) step on one tensor, in place on hi, res, buf."""
         n = _chk(hi, np.uint16).shape[0]
-        _chk(res, np.uint16, n)
+        _chk(res, res_dtype(cfg.res_bits), n)
         _chk(grad, np.uint16, n)
         if cfg.momentum != 0.0:
             _chk(buf, np.float32, n)
@@ -147,11 +158,14 @@ class Oracle:
             raise ValueError("step counts from 1")
         c = cfg._c()
         bp = _p32(buf) if buf is not None else ctypes.cast(None, _f32p)
-        self._lib.mpo_ref_sgd_step(_p16(hi), _p16(res), _p16(grad), bp, n, ctypes.byref(c), step)
+        self._lib.mpo_ref_sgd_step(_p16(hi), _pv(res), _p16(grad), bp, n, ctypes.byref(c), step)
 
     def cvt16(self, x: int, fmt=BF16) -> float:
         """One 16-bit float pattern read as fp32."""
         return float(self._lib.mpo_ref_cvt16(int(x) & 0xFFFF, fmt))
+
+
+    res_dtype = staticmethod(res_dtype)
 
 
 _default = Oracle(_build.build())

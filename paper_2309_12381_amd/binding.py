@@ -35,7 +35,7 @@ MPO_MAX_LAYER_GRADS = 64
 class mpo_tensor(ctypes.Structure):
     _fields_ = [("hi", ctypes.c_void_p), ("res", ctypes.c_void_p), ("grad", ctypes.c_void_p),
                 ("m", ctypes.c_void_p), ("v", ctypes.c_void_p), ("n", ctypes.c_uint64),
-                ("layer", ctypes.c_int32)]
+                ("layer", ctypes.c_int32), ("res_bits", ctypes.c_int32)]
 
 
 class mpo_adam_cfg(ctypes.Structure):
@@ -53,9 +53,9 @@ class mpo_sgd_cfg(ctypes.Structure):
 
 EXPORTS = {
     "mpo_split": ([ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int,
-                   ctypes.c_int, ctypes.c_void_p], ctypes.c_int),
+                   ctypes.c_int32, ctypes.c_int, ctypes.c_void_p], ctypes.c_int),
     "mpo_merge": ([ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int,
-                   ctypes.c_void_p], ctypes.c_int),
+                   ctypes.c_int32, ctypes.c_void_p], ctypes.c_int),
     "mpo_plan_create": ([ctypes.POINTER(mpo_tensor), ctypes.c_uint64, ctypes.POINTER(ctypes.c_void_p)], ctypes.c_int),
     "mpo_plan_create_host": ([ctypes.POINTER(mpo_tensor), ctypes.c_uint64, ctypes.POINTER(ctypes.c_void_p)],
                              ctypes.c_int),
@@ -155,12 +155,13 @@ class SgdCfg:
                            self.grad_fmt, self.round)
 
 
-def mpo_split(w32, hi, res, n: int, fmt: int = MPO_BF16, round: int = MPO_ROUND_TRUNC, stream=None):
-    _check(lib.mpo_split(_ptr(w32), _ptr(hi), _ptr(res), n, fmt, round, _stream(stream)), "mpo_split")
+def mpo_split(w32, hi, res, n: int, fmt: int = MPO_BF16, res_bits: int = 0, round: int = MPO_ROUND_TRUNC,
+              stream=None):
+    _check(lib.mpo_split(_ptr(w32), _ptr(hi), _ptr(res), n, fmt, res_bits, round, _stream(stream)), "mpo_split")
 
 
-def mpo_merge(hi, res, w32, n: int, fmt: int = MPO_BF16, stream=None):
-    _check(lib.mpo_merge(_ptr(hi), _ptr(res), _ptr(w32), n, fmt, _stream(stream)), "mpo_merge")
+def mpo_merge(hi, res, w32, n: int, fmt: int = MPO_BF16, res_bits: int = 0, stream=None):
+    _check(lib.mpo_merge(_ptr(hi), _ptr(res), _ptr(w32), n, fmt, res_bits, _stream(stream)), "mpo_merge")
 
 
 @dataclass
@@ -173,6 +174,7 @@ class Tensor:
     v: object
     n: int
     layer: int = 0
+    res_bits: int = 0
 
 
 class Plan:
@@ -182,7 +184,7 @@ class Plan:
         self._keep = list(tensors)
         arr = (mpo_tensor * max(len(tensors), 1))()
         for i, t in enumerate(tensors):
-            arr[i] = mpo_tensor(_ptr(t.hi), _ptr(t.res), _ptr(t.grad), _ptr(t.m), _ptr(t.v), t.n, t.layer)
+            arr[i] = mpo_tensor(_ptr(t.hi), _ptr(t.res), _ptr(t.grad), _ptr(t.m), _ptr(t.v), t.n, t.layer, t.res_bits)
         handle = ctypes.c_void_p()
         create = lib.mpo_plan_create_host if host_only else lib.mpo_plan_create
         _check(create(arr, len(tensors), ctypes.byref(handle)), "mpo_plan_create")

@@ -45,6 +45,12 @@ struct Range {
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+/* Section 3.1, partial extra bits: at most 8 kept bits live in a byte, more in 16 bits. */
+inline uint32_t res_slot_bytes(int res_bits) { return (res_bits >= 1 && res_bits <= 8) ? 1u : 2u; }
+
+/* 0 means all; otherwise 1..full for the format. */
+inline bool valid_res_bits(int res_bits, int fmt) { return res_bits >= 0 && res_bits <= full_res_bits(fmt); }
+
 /* True if some written range overlaps any other range.  Read-only ranges
  * (gradients) may overlap each other: one buffer reused for every layer. */
 bool has_conflict(std::vector<Range> &r)
@@ -82,6 +88,9 @@ struct mpo_plan {
     std::vector<LayerInfo> layers;      /* sorted by id */
     uint64_t num_params = 0;
     bool all_have_grad = true, all_have_m = true, all_have_v = true;
+    uint32_t res_slot = 0;       /* bytes per residual: 1 or 2; 0 while no tensor has elements */
+    uint32_t max_res_bits = 0;   /* largest explicit res_bits in the list                       */
+    bool any_explicit_bits = false;
     bool on_device = false;
     int device = -1;
     TensorDesc *d_descs = nullptr;
@@ -98,6 +107,7 @@ mpo_status build_plan(const mpo_tensor *tensors, uint64_t nt, mpo_plan **out)
     if (nt > 0xFFFFFFFFull) return MPO_ERR_INVALID_ARG;
 
     std::vector<Range> ranges;
+    uint32_t res_slot = 0;
     try {
         ranges.reserve(nt * 5);
     } catch (const std::bad_alloc &) {
@@ -107,14 +117,18 @@ mpo_status build_plan(const mpo_tensor *tensors, uint64_t nt, mpo_plan **out)
         const mpo_tensor &t = tensors[i];
         if (t.layer < 0) return MPO_ERR_INVALID_ARG;
         if (t.n > kMaxElems) return MPO_ERR_INVALID_ARG;
+        if (t.res_bits < 0 || t.res_bits > 16) return MPO_ERR_INVALID_ARG;
         if (t.n == 0) continue;
         if (!t.hi || !t.res) return MPO_ERR_INVALID_ARG;
+        const uint32_t slot = res_slot_bytes(t.res_bits);
+        if (res_slot == 0) res_slot = slot;
+        else if (res_slot != slot) return MPO_ERR_UNSUPPORTED;
         auto add = [&](const void *p, uint64_t bytes, bool written) {
             const uintptr_t lo = reinterpret_cast<uintptr_t>(p);
             ranges.push_back(Range{lo, lo + bytes, written});
         };
         add(t.hi, t.n * 2, true);
-        add(t.res, t.n * 2, true);
+        add(t.res, t.n * slot, true);
         if (t.grad) add(t.grad, t.n * 2, false);
         if (t.m) add(t.m, t.n * 4, true);
         if (t.v) add(t.v, t.n * 4, true);
@@ -123,6 +137,7 @@ mpo_status build_plan(const mpo_tensor *tensors, uint64_t nt, mpo_plan **out)
 
     mpo_plan *p = new (std::nothrow) mpo_plan;
     if (!p) return MPO_ERR_NOMEM;
+    p->res_slot = res_slot;
     try {
         /* stable order by layer: a layer's tensors and chunks are contiguous */
         std::vector<uint64_t> order(nt);
@@ -136,6 +151,11 @@ mpo_status build_plan(const mpo_tensor *tensors, uint64_t nt, mpo_plan **out)
             TensorDesc d;
             std::memset(&d, 0, sizeof d);
             d.hi = t.hi; d.res = t.res; d.grad = t.grad; d.m = t.m; d.v = t.v; d.n = t.n;
+            d.res_bits = (uint32_t)t.res_bits;
+            if (t.n && t.res_bits) {
+                p->any_explicit_bits = true;
+                p->max_res_bits = std::max(p->max_res_bits, (uint32_t)t.res_bits);
+            }
             if (aligned16(t.hi) && aligned16(t.res) && aligned16(t.m) && aligned16(t.v)) d.flags |= kStateAligned;
             if (t.grad && aligned16(t.grad)) d.flags |= kGradAligned;
             p->descs.push_back(d);
@@ -244,6 +264,8 @@ bool state_present(const mpo_plan *p, uint64_t k0, uint64_t nk, const StepLaunch
 
 mpo_status run(mpo_plan *p, StepLaunch &L, void *stream)
 {
+    if ((int)p->max_res_bits > full_res_bits(L.wfmt)) return MPO_ERR_INVALID_ARG;
+    L.rmode = p->res_slot == 1 ? kResByte : (p->any_explicit_bits ? kResPartial : kResFull);
     L.descs = p->d_descs;
     L.chunks = p->d_chunks;
     L.stream = static_cast<hipStream_t>(stream);
@@ -265,10 +287,10 @@ mpo_status step_all(mpo_plan *p, StepLaunch &L, void *stream)
 
 extern "C" {
 
-mpo_status mpo_split(const float *w32, uint16_t *hi, uint16_t *res, uint64_t n, mpo_fmt fmt, mpo_round round,
-                     void *hip_stream)
+mpo_status mpo_split(const float *w32, uint16_t *hi, void *res, uint64_t n, mpo_fmt fmt, int32_t res_bits,
+                     mpo_round round, void *hip_stream)
 {
-    if (!valid_fmt(fmt)) return MPO_ERR_INVALID_ARG;
+    if (!valid_fmt(fmt) || !valid_res_bits(res_bits, fmt)) return MPO_ERR_INVALID_ARG;
     const mpo_status rs = check_round(round);
     if (rs != MPO_OK) return rs;
     if (n > kMaxElems) return MPO_ERR_INVALID_ARG;
@@ -278,15 +300,16 @@ mpo_status mpo_split(const float *w32, uint16_t *hi, uint16_t *res, uint64_t n, 
     const uintptr_t a = (uintptr_t)w32, b = (uintptr_t)hi, c = (uintptr_t)res;
     r.push_back(Range{a, a + n * 4, false});
     r.push_back(Range{b, b + n * 2, true});
-    r.push_back(Range{c, c + n * 2, true});
+    r.push_back(Range{c, c + n * res_slot_bytes(res_bits), true});
     if (has_conflict(r)) return MPO_ERR_ALIAS;
-    const hipError_t e = launch_split(w32, hi, res, n, fmt, static_cast<hipStream_t>(hip_stream));
+    const hipError_t e = launch_split(w32, hi, res, n, fmt, res_bits, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MPO_OK : hip_fail(e);
 }
 
-mpo_status mpo_merge(const uint16_t *hi, const uint16_t *res, float *w32, uint64_t n, mpo_fmt fmt, void *hip_stream)
+mpo_status mpo_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, mpo_fmt fmt, int32_t res_bits,
+                     void *hip_stream)
 {
-    if (!valid_fmt(fmt)) return MPO_ERR_INVALID_ARG;
+    if (!valid_fmt(fmt) || !valid_res_bits(res_bits, fmt)) return MPO_ERR_INVALID_ARG;
     if (n > kMaxElems) return MPO_ERR_INVALID_ARG;
     if (n == 0) return MPO_OK;
     if (!w32 || !hi || !res) return MPO_ERR_INVALID_ARG;
@@ -294,9 +317,9 @@ mpo_status mpo_merge(const uint16_t *hi, const uint16_t *res, float *w32, uint64
     const uintptr_t a = (uintptr_t)w32, b = (uintptr_t)hi, c = (uintptr_t)res;
     r.push_back(Range{a, a + n * 4, true});
     r.push_back(Range{b, b + n * 2, false});
-    r.push_back(Range{c, c + n * 2, false});
+    r.push_back(Range{c, c + n * res_slot_bytes(res_bits), false});
     if (has_conflict(r)) return MPO_ERR_ALIAS;
-    const hipError_t e = launch_merge(hi, res, w32, n, fmt, static_cast<hipStream_t>(hip_stream));
+    const hipError_t e = launch_merge(hi, res, w32, n, fmt, res_bits, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MPO_OK : hip_fail(e);
 }
 
@@ -407,7 +430,7 @@ mpo_status mpo_step_layer(mpo_plan *p, int32_t layer, const void *const *grads, 
             const uintptr_t g = (uintptr_t)grads[k];
             r.push_back(Range{g, g + d.n * 2, false});
             r.push_back(Range{(uintptr_t)d.hi, (uintptr_t)d.hi + d.n * 2, true});
-            r.push_back(Range{(uintptr_t)d.res, (uintptr_t)d.res + d.n * 2, true});
+            r.push_back(Range{(uintptr_t)d.res, (uintptr_t)d.res + d.n * res_slot_bytes((int)d.res_bits), true});
             if (d.m) r.push_back(Range{(uintptr_t)d.m, (uintptr_t)d.m + d.n * 4, true});
             if (d.v) r.push_back(Range{(uintptr_t)d.v, (uintptr_t)d.v + d.n * 4, true});
             L.ov.ptr[k] = static_cast<const uint16_t *>(grads[k]);

@@ -20,13 +20,13 @@ constexpr uint32_t kGradAligned = 2u;  /* the plan's own grad pointer 16-byte al
 
 struct TensorDesc {
     uint16_t *hi;
-    uint16_t *res;
+    void *res;           /* uint8_t per parameter when 1 <= res_bits <= 8, else uint16_t */
     const uint16_t *grad;
     float *m;
     float *v;
     uint64_t n;
     uint32_t flags;
-    uint32_t pad;
+    uint32_t res_bits;   /* extra bits kept, 0 = all (Section 3.1) */
 };
 static_assert(sizeof(TensorDesc) == 56, "descriptor layout is read by the kernels");
 
@@ -56,6 +56,15 @@ struct GradOverride {
 
 enum Decay { kNoDecay = 0, kDecoupled = 1, kL2 = 2 };
 
+/* How the residual is stored (Section 3.1: all extra bits, or only the leading E). */
+enum ResMode {
+    kResFull = 0,    /* uint16_t, every extra bit kept: no shifting                  */
+    kResPartial = 1, /* uint16_t, some tensor keeps fewer bits: shift per descriptor  */
+    kResByte = 2     /* uint8_t (1..8 bits kept)                                      */
+};
+
+inline int full_res_bits(int fmt) { return fmt == MPO_FP16 ? 13 : 16; }
+
 struct StepLaunch {
     const TensorDesc *descs; /* device */
     const Chunk *chunks;     /* device */
@@ -65,15 +74,16 @@ struct StepLaunch {
     int gfmt;     /* mpo_fmt of grad */
     int decay;    /* Decay           */
     int momentum; /* SGD: momentum != 0 */
+    int rmode;    /* ResMode         */
     StepScalars s;
     GradOverride ov;
     hipStream_t stream;
 };
 
 hipError_t launch_step(const StepLaunch &L);
-hipError_t launch_split(const float *w32, uint16_t *hi, uint16_t *res, uint64_t n, int fmt,
+hipError_t launch_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits,
                         hipStream_t stream);
-hipError_t launch_merge(const uint16_t *hi, const uint16_t *res, float *w32, uint64_t n, int fmt,
+hipError_t launch_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits,
                         hipStream_t stream);
 
 } // namespace mpo

@@ -92,6 +92,37 @@ __device__ __forceinline__ void store16(gu16p p, const uint32_t (&in)[EPL / 2])
     if (MPO_NT_STORE) __builtin_nontemporal_store(x, q); else *q = x;
 }
 
+/* EPL bytes (8-bit residuals) = EPL/4 dwords in one access. */
+typedef const MPO_GLOBAL uint8_t *gcu8p;
+typedef MPO_GLOBAL uint8_t *gu8p;
+
+__device__ __forceinline__ void load8(gcu8p p, uint32_t (&out)[EPL / 2])
+{
+    if (EPL == 4) {
+        const MPO_GLOBAL uint32_t *q = reinterpret_cast<const MPO_GLOBAL uint32_t *>(p);
+        out[0] = MPO_NT_LOAD ? __builtin_nontemporal_load(q) : *q;
+    } else {
+        const MPO_GLOBAL u32x2 *q = reinterpret_cast<const MPO_GLOBAL u32x2 *>(p);
+        u32x2 x = MPO_NT_LOAD ? __builtin_nontemporal_load(q) : *q;
+        out[0] = x[0];
+        out[EPL / 2 - 1 > 0 ? 1 : 0] = x[1];
+    }
+}
+
+__device__ __forceinline__ void store8(gu8p p, const uint32_t (&in)[EPL / 2])
+{
+    if (EPL == 4) {
+        MPO_GLOBAL uint32_t *q = reinterpret_cast<MPO_GLOBAL uint32_t *>(p);
+        if (MPO_NT_STORE) __builtin_nontemporal_store(in[0], q); else *q = in[0];
+    } else {
+        u32x2 x;
+        x[0] = in[0];
+        x[1] = in[EPL / 2 - 1 > 0 ? 1 : 0];
+        MPO_GLOBAL u32x2 *q = reinterpret_cast<MPO_GLOBAL u32x2 *>(p);
+        if (MPO_NT_STORE) __builtin_nontemporal_store(x, q); else *q = x;
+    }
+}
+
 __device__ __forceinline__ void load32(gcf32p p, float (&out)[EPL])
 {
     const MPO_GLOBAL f32x4 *q = reinterpret_cast<const MPO_GLOBAL f32x4 *>(p);
@@ -225,6 +256,28 @@ __device__ __forceinline__ void step_one(uint32_t &hi, uint32_t &res, uint32_t g
     split32<WFMT>(w, hi, res);
 }
 
+/* ---- residual storage (Section 3.1: all extra bits, or only the leading E) --
+ * kResFull: 16-bit slots, every bit kept.  kResPartial: 16-bit slots, the kept
+ * bits right-aligned, `sh` = number of cut bits.  kResByte: 8-bit slots.
+ * In registers the residual of element k of a row sits in x.r[] exactly as in
+ * memory; res_get widens it to the full residual (cut bits zero), res_put cuts. */
+template <int RMODE> __device__ __forceinline__ uint32_t res_get(const uint32_t *r, int k, uint32_t sh)
+{
+    if (RMODE == kResByte) return ((r[k / 4] >> (8 * (k % 4))) & 0xFFu) << sh;
+    const uint32_t x = (k & 1) ? (r[k / 2] >> 16) : (r[k / 2] & 0xFFFFu);
+    return RMODE == kResPartial ? (x << sh) : x;
+}
+template <int RMODE> __device__ __forceinline__ void res_put(uint32_t *r, int k, uint32_t full, uint32_t sh)
+{
+    /* r[] is cleared by the caller before the first put of a row */
+    if (RMODE == kResByte) r[k / 4] |= ((full >> sh) & 0xFFu) << (8 * (k % 4));
+    else r[k / 2] |= (RMODE == kResPartial ? ((full >> sh) & 0xFFFFu) : full) << (16 * (k & 1));
+}
+template <int RMODE> struct ResElem { typedef uint16_t T; };
+template <> struct ResElem<kResByte> { typedef uint8_t T; };
+
+template <int WFMT> struct FullBits { static constexpr uint32_t value = (WFMT == MPO_FP16) ? 13u : 16u; };
+
 template <int OPT, bool MOM> struct Uses {
     static constexpr bool m = (OPT == MPO_OPT_ADAM) || MOM;
     static constexpr bool v = (OPT == MPO_OPT_ADAM);
@@ -245,56 +298,62 @@ struct Row {
     float m[EPL], v[EPL];
 };
 
-template <int OPT, bool MOM>
-__device__ __forceinline__ void load_row(Row &x, gcu16p hi, gcu16p res, gcu16p grad, gcf32p m, gcf32p v, uint32_t e)
+template <int OPT, bool MOM, int RMODE>
+__device__ __forceinline__ void load_row(Row &x, gcu16p hi, const MPO_GLOBAL void *res, gcu16p grad, gcf32p m, gcf32p v,
+                                         uint32_t e)
 {
     load16(hi + e, x.h);
-    load16(res + e, x.r);
+    if (RMODE == kResByte) load8(static_cast<gcu8p>(res) + e, x.r); else load16(static_cast<gcu16p>(res) + e, x.r);
     load16(grad + e, x.g);
     if (Uses<OPT, MOM>::m) load32(m + e, x.m);
     if (Uses<OPT, MOM>::v) load32(v + e, x.v);
 }
 
-template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM>
-__device__ __forceinline__ void compute_row(Row &x, const StepScalars &s)
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE>
+__device__ __forceinline__ void compute_row(Row &x, const StepScalars &s, uint32_t sh)
 {
+    uint32_t rin[EPL / 2];
+#pragma unroll
+    for (int j = 0; j < EPL / 2; ++j) { rin[j] = x.r[j]; x.r[j] = 0u; }
 #pragma unroll
     for (int j = 0; j < EPL / 2; ++j) {
         uint32_t h0 = x.h[j] & 0xFFFFu, h1 = x.h[j] >> 16;
-        uint32_t r0 = x.r[j] & 0xFFFFu, r1 = x.r[j] >> 16;
+        uint32_t r0 = res_get<RMODE>(rin, 2 * j, sh), r1 = res_get<RMODE>(rin, 2 * j + 1, sh);
         step_one<OPT, WFMT, GFMT, DECAY, MOM>(h0, r0, x.g[j] & 0xFFFFu, x.m[2 * j], x.v[2 * j], s);
         step_one<OPT, WFMT, GFMT, DECAY, MOM>(h1, r1, x.g[j] >> 16, x.m[2 * j + 1], x.v[2 * j + 1], s);
         x.h[j] = h0 | (h1 << 16);
-        x.r[j] = r0 | (r1 << 16);
+        res_put<RMODE>(x.r, 2 * j, r0, sh);
+        res_put<RMODE>(x.r, 2 * j + 1, r1, sh);
     }
 }
 
-template <int OPT, bool MOM>
-__device__ __forceinline__ void store_row(const Row &x, gu16p hi, gu16p res, gf32p m, gf32p v, uint32_t e)
+template <int OPT, bool MOM, int RMODE>
+__device__ __forceinline__ void store_row(const Row &x, gu16p hi, MPO_GLOBAL void *res, gf32p m, gf32p v, uint32_t e)
 {
     store16(hi + e, x.h);
-    store16(res + e, x.r);
+    if (RMODE == kResByte) store8(static_cast<gu8p>(res) + e, x.r); else store16(static_cast<gu16p>(res) + e, x.r);
     if (Uses<OPT, MOM>::m) store32(m + e, x.m);
     if (Uses<OPT, MOM>::v) store32(v + e, x.v);
 }
 
 /* Parameters [e0, e1) one at a time: ragged tails and tensors that are not
  * 16-byte aligned.  Same arithmetic, 16- and 32-bit accesses. */
-template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM>
-__device__ __forceinline__ void step_scalar(gu16p hi, gu16p res, gcu16p grad, gf32p m, gf32p v, uint32_t e,
-                                            const StepScalars &s)
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE>
+__device__ __forceinline__ void step_scalar(gu16p hi, MPO_GLOBAL void *res_, gcu16p grad, gf32p m, gf32p v, uint32_t e,
+                                            const StepScalars &s, uint32_t sh)
 {
-    uint32_t h = hi[e], r = res[e];
+    MPO_GLOBAL typename ResElem<RMODE>::T *res = static_cast<MPO_GLOBAL typename ResElem<RMODE>::T *>(res_);
+    uint32_t h = hi[e], r = (uint32_t)res[e] << sh;
     float mm = Uses<OPT, MOM>::m ? m[e] : 0.0f;
     float vv = Uses<OPT, MOM>::v ? v[e] : 0.0f;
     step_one<OPT, WFMT, GFMT, DECAY, MOM>(h, r, grad[e], mm, vv, s);
     hi[e] = (uint16_t)h;
-    res[e] = (uint16_t)r;
+    res[e] = (typename ResElem<RMODE>::T)(r >> sh);
     if (Uses<OPT, MOM>::m) m[e] = mm;
     if (Uses<OPT, MOM>::v) v[e] = vv;
 }
 
-template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM>
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE>
 __global__ void __launch_bounds__(kBlock)
 step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chunks, uint64_t first_chunk,
             StepScalars s, GradOverride ov)
@@ -313,8 +372,11 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
     const uint64_t left = d.n - off;
     const uint32_t len = left < kChunkElems ? (uint32_t)left : kChunkElems;
 
+    /* cut bits of this tensor's residual (uniform); a full residual has none */
+    const uint32_t kept = d.res_bits ? d.res_bits : FullBits<WFMT>::value;
+    const uint32_t sh = RMODE == kResFull ? 0u : FullBits<WFMT>::value - kept;
     gu16p hi = (gu16p)(d.hi + off);
-    gu16p res = (gu16p)(d.res + off);
+    MPO_GLOBAL void *res = (MPO_GLOBAL void *)(static_cast<char *>(d.res) + off * sizeof(typename ResElem<RMODE>::T));
     gcu16p grad = (gcu16p)(gbase + off);
     gf32p m = Uses<OPT, MOM>::m ? (gf32p)(d.m + off) : (gf32p) nullptr;
     gf32p v = Uses<OPT, MOM>::v ? (gf32p)(d.v + off) : (gf32p) nullptr;
@@ -327,11 +389,11 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
             Row x[BATCH];
 #pragma unroll
             for (int b = 0; b < BATCH; ++b)
-                load_row<OPT, MOM>(x[b], hi, res, grad, m, v, row_elem(r0 + b, t));
+                load_row<OPT, MOM, RMODE>(x[b], hi, res, grad, m, v, row_elem(r0 + b, t));
 #pragma unroll
             for (int b = 0; b < BATCH; ++b) {
-                compute_row<OPT, WFMT, GFMT, DECAY, MOM>(x[b], s);
-                store_row<OPT, MOM>(x[b], hi, res, m, v, row_elem(r0 + b, t));
+                compute_row<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(x[b], s, sh);
+                store_row<OPT, MOM, RMODE>(x[b], hi, res, m, v, row_elem(r0 + b, t));
             }
         }
     } else if (aligned) {
@@ -341,40 +403,41 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
             const uint32_t e = row_elem(r, t);
             if (e + EPL <= len) {
                 Row x;
-                load_row<OPT, MOM>(x, hi, res, grad, m, v, e);
-                compute_row<OPT, WFMT, GFMT, DECAY, MOM>(x, s);
-                store_row<OPT, MOM>(x, hi, res, m, v, e);
+                load_row<OPT, MOM, RMODE>(x, hi, res, grad, m, v, e);
+                compute_row<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(x, s, sh);
+                store_row<OPT, MOM, RMODE>(x, hi, res, m, v, e);
             } else if (e < len) {
                 for (uint32_t i = e; i < len; ++i)
-                    step_scalar<OPT, WFMT, GFMT, DECAY, MOM>(hi, res, grad, m, v, i, s);
+                    step_scalar<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(hi, res, grad, m, v, i, s, sh);
             }
         }
     } else {
         for (uint32_t i = t; i < len; i += kBlock)
-            step_scalar<OPT, WFMT, GFMT, DECAY, MOM>(hi, res, grad, m, v, i, s);
+            step_scalar<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(hi, res, grad, m, v, i, s, sh);
     }
 }
 
-/* ---- split / merge: 8 B per parameter ------------------------------------ */
+/* ---- split / merge: 8 B per parameter (7 B with byte residuals) ------------ */
 
-template <int FMT>
+template <int FMT, int RMODE>
 __global__ void __launch_bounds__(kBlock)
-split_kernel(const float *__restrict__ w32_, uint16_t *__restrict__ hi_, uint16_t *__restrict__ res_, uint64_t n,
-             int aligned)
+split_kernel(const float *__restrict__ w32_, uint16_t *__restrict__ hi_, void *__restrict__ res_, uint64_t n,
+             int aligned, uint32_t sh)
 {
+    typedef typename ResElem<RMODE>::T R;
     const uint64_t off = (uint64_t)blockIdx.x * kChunkElems;
     const uint64_t left = n - off;
     const uint32_t len = left < kChunkElems ? (uint32_t)left : kChunkElems;
     gcf32p w32 = (gcf32p)(w32_ + off);
     gu16p hi = (gu16p)(hi_ + off);
-    gu16p res = (gu16p)(res_ + off);
+    MPO_GLOBAL R *res = (MPO_GLOBAL R *)(static_cast<R *>(res_) + off);
     const uint32_t t = threadIdx.x;
     if (!aligned) {
         for (uint32_t i = t; i < len; i += kBlock) {
             uint32_t h, r;
             split32<FMT>(w32[i], h, r);
             hi[i] = (uint16_t)h;
-            res[i] = (uint16_t)r;
+            res[i] = (R)(r >> sh);
         }
         return;
     }
@@ -386,40 +449,44 @@ split_kernel(const float *__restrict__ w32_, uint16_t *__restrict__ hi_, uint16_
             uint32_t h[EPL / 2], q[EPL / 2];
             load32(w32 + e, w);
 #pragma unroll
+            for (int j = 0; j < EPL / 2; ++j) q[j] = 0u;
+#pragma unroll
             for (int j = 0; j < EPL / 2; ++j) {
                 uint32_t h0, r0, h1, r1;
                 split32<FMT>(w[2 * j], h0, r0);
                 split32<FMT>(w[2 * j + 1], h1, r1);
                 h[j] = h0 | (h1 << 16);
-                q[j] = r0 | (r1 << 16);
+                res_put<RMODE>(q, 2 * j, r0, sh);
+                res_put<RMODE>(q, 2 * j + 1, r1, sh);
             }
             store16(hi + e, h);
-            store16(res + e, q);
+            if (RMODE == kResByte) store8((gu8p)res + e, q); else store16((gu16p)res + e, q);
         } else if (e < len) {
             for (uint32_t i = e; i < len; ++i) {
                 uint32_t h, q;
                 split32<FMT>(w32[i], h, q);
                 hi[i] = (uint16_t)h;
-                res[i] = (uint16_t)q;
+                res[i] = (R)(q >> sh);
             }
         }
     }
 }
 
-template <int FMT>
+template <int FMT, int RMODE>
 __global__ void __launch_bounds__(kBlock)
-merge_kernel(const uint16_t *__restrict__ hi_, const uint16_t *__restrict__ res_, float *__restrict__ w32_, uint64_t n,
-             int aligned)
+merge_kernel(const uint16_t *__restrict__ hi_, const void *__restrict__ res_, float *__restrict__ w32_, uint64_t n,
+             int aligned, uint32_t sh)
 {
+    typedef typename ResElem<RMODE>::T R;
     const uint64_t off = (uint64_t)blockIdx.x * kChunkElems;
     const uint64_t left = n - off;
     const uint32_t len = left < kChunkElems ? (uint32_t)left : kChunkElems;
     gf32p w32 = (gf32p)(w32_ + off);
     gcu16p hi = (gcu16p)(hi_ + off);
-    gcu16p res = (gcu16p)(res_ + off);
+    const MPO_GLOBAL R *res = (const MPO_GLOBAL R *)(static_cast<const R *>(res_) + off);
     const uint32_t t = threadIdx.x;
     if (!aligned) {
-        for (uint32_t i = t; i < len; i += kBlock) w32[i] = merge16<FMT>(hi[i], res[i]);
+        for (uint32_t i = t; i < len; i += kBlock) w32[i] = merge16<FMT>(hi[i], (uint32_t)res[i] << sh);
         return;
     }
 #pragma unroll
@@ -429,15 +496,15 @@ merge_kernel(const uint16_t *__restrict__ hi_, const uint16_t *__restrict__ res_
             float w[EPL];
             uint32_t h[EPL / 2], q[EPL / 2];
             load16(hi + e, h);
-            load16(res + e, q);
+            if (RMODE == kResByte) load8((gcu8p)res + e, q); else load16((gcu16p)res + e, q);
 #pragma unroll
             for (int j = 0; j < EPL / 2; ++j) {
-                w[2 * j] = merge16<FMT>(h[j] & 0xFFFFu, q[j] & 0xFFFFu);
-                w[2 * j + 1] = merge16<FMT>(h[j] >> 16, q[j] >> 16);
+                w[2 * j] = merge16<FMT>(h[j] & 0xFFFFu, res_get<RMODE>(q, 2 * j, sh));
+                w[2 * j + 1] = merge16<FMT>(h[j] >> 16, res_get<RMODE>(q, 2 * j + 1, sh));
             }
             store32(w32 + e, w);
         } else if (e < len) {
-            for (uint32_t i = e; i < len; ++i) w32[i] = merge16<FMT>(hi[i], res[i]);
+            for (uint32_t i = e; i < len; ++i) w32[i] = merge16<FMT>(hi[i], (uint32_t)res[i] << sh);
         }
     }
 }
@@ -445,13 +512,13 @@ merge_kernel(const uint16_t *__restrict__ hi_, const uint16_t *__restrict__ res_
 /* Grids are limited to 2^31-1 workgroups: longer lists go out in slices. */
 constexpr uint64_t kMaxGrid = 0x7FFFFFFFull;
 
-template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM>
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE>
 hipError_t launch_step_t(const StepLaunch &L)
 {
     uint64_t done = 0;
     while (done < L.num_chunks) {
         const uint64_t now = (L.num_chunks - done < kMaxGrid) ? (L.num_chunks - done) : kMaxGrid;
-        step_kernel<OPT, WFMT, GFMT, DECAY, MOM><<<dim3((uint32_t)now), dim3(kBlock), 0, L.stream>>>(
+        step_kernel<OPT, WFMT, GFMT, DECAY, MOM, RMODE><<<dim3((uint32_t)now), dim3(kBlock), 0, L.stream>>>(
             L.descs, L.chunks, L.first_chunk + done, L.s, L.ov);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -460,14 +527,72 @@ hipError_t launch_step_t(const StepLaunch &L)
     return hipSuccess;
 }
 
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM>
+hipError_t launch_step_res(const StepLaunch &L)
+{
+    switch (L.rmode) {
+    case kResFull: return launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResFull>(L);
+    case kResPartial: return launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResPartial>(L);
+    default: return launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResByte>(L);
+    }
+}
+
 template <int OPT, int DECAY, bool MOM>
 hipError_t launch_step_fmt(const StepLaunch &L)
 {
     if (L.wfmt == MPO_BF16)
-        return L.gfmt == MPO_BF16 ? launch_step_t<OPT, MPO_BF16, MPO_BF16, DECAY, MOM>(L)
-                                  : launch_step_t<OPT, MPO_BF16, MPO_FP16, DECAY, MOM>(L);
-    return L.gfmt == MPO_BF16 ? launch_step_t<OPT, MPO_FP16, MPO_BF16, DECAY, MOM>(L)
-                              : launch_step_t<OPT, MPO_FP16, MPO_FP16, DECAY, MOM>(L);
+        return L.gfmt == MPO_BF16 ? launch_step_res<OPT, MPO_BF16, MPO_BF16, DECAY, MOM>(L)
+                                  : launch_step_res<OPT, MPO_BF16, MPO_FP16, DECAY, MOM>(L);
+    return L.gfmt == MPO_BF16 ? launch_step_res<OPT, MPO_FP16, MPO_BF16, DECAY, MOM>(L)
+                              : launch_step_res<OPT, MPO_FP16, MPO_FP16, DECAY, MOM>(L);
+}
+
+template <int FMT, int RMODE>
+hipError_t launch_split_t(const float *w32, uint16_t *hi, void *res, uint64_t n, uint32_t sh, int al, hipStream_t stream)
+{
+    typedef typename ResElem<RMODE>::T R;
+    uint64_t done = 0;
+    const uint64_t blocks = (n + kChunkElems - 1) / kChunkElems;
+    while (done < blocks) {
+        const uint64_t now = (blocks - done < kMaxGrid) ? (blocks - done) : kMaxGrid;
+        const uint64_t e0 = done * kChunkElems;
+        split_kernel<FMT, RMODE><<<dim3((uint32_t)now), dim3(kBlock), 0, stream>>>(w32 + e0, hi + e0,
+                                                                                 static_cast<R *>(res) + e0, n - e0, al, sh);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        done += now;
+    }
+    return hipSuccess;
+}
+
+template <int FMT, int RMODE>
+hipError_t launch_merge_t(const uint16_t *hi, const void *res, float *w32, uint64_t n, uint32_t sh, int al,
+                          hipStream_t stream)
+{
+    typedef typename ResElem<RMODE>::T R;
+    uint64_t done = 0;
+    const uint64_t blocks = (n + kChunkElems - 1) / kChunkElems;
+    while (done < blocks) {
+        const uint64_t now = (blocks - done < kMaxGrid) ? (blocks - done) : kMaxGrid;
+        const uint64_t e0 = done * kChunkElems;
+        merge_kernel<FMT, RMODE><<<dim3((uint32_t)now), dim3(kBlock), 0, stream>>>(hi + e0, static_cast<const R *>(res) + e0,
+                                                                                 w32 + e0, n - e0, al, sh);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        done += now;
+    }
+    return hipSuccess;
+}
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+/* Storage mode and number of cut bits for a single-tensor call. */
+inline void res_layout(int fmt, int res_bits, int &rmode, uint32_t &sh)
+{
+    const int full = full_res_bits(fmt);
+    const int kept = res_bits ? res_bits : full;
+    sh = (uint32_t)(full - kept);
+    rmode = (res_bits >= 1 && res_bits <= 8) ? kResByte : (kept == full ? kResFull : kResPartial);
 }
 
 } // namespace
@@ -489,44 +614,36 @@ hipError_t launch_step(const StepLaunch &L)
                           : launch_step_fmt<MPO_OPT_SGD, kNoDecay, false>(L);
 }
 
-static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-
-hipError_t launch_split(const float *w32, uint16_t *hi, uint16_t *res, uint64_t n, int fmt, hipStream_t stream)
+hipError_t launch_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits, hipStream_t stream)
 {
     const int al = aligned16(w32) && aligned16(hi) && aligned16(res);
-    uint64_t done = 0;
-    const uint64_t blocks = (n + kChunkElems - 1) / kChunkElems;
-    while (done < blocks) {
-        const uint64_t now = (blocks - done < kMaxGrid) ? (blocks - done) : kMaxGrid;
-        const uint64_t e0 = done * kChunkElems;
-        if (fmt == MPO_BF16)
-            split_kernel<MPO_BF16><<<dim3((uint32_t)now), dim3(kBlock), 0, stream>>>(w32 + e0, hi + e0, res + e0, n - e0, al);
-        else
-            split_kernel<MPO_FP16><<<dim3((uint32_t)now), dim3(kBlock), 0, stream>>>(w32 + e0, hi + e0, res + e0, n - e0, al);
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        done += now;
+    int rmode;
+    uint32_t sh;
+    res_layout(fmt, res_bits, rmode, sh);
+    if (fmt == MPO_BF16) {
+        if (rmode == kResByte) return launch_split_t<MPO_BF16, kResByte>(w32, hi, res, n, sh, al, stream);
+        if (rmode == kResPartial) return launch_split_t<MPO_BF16, kResPartial>(w32, hi, res, n, sh, al, stream);
+        return launch_split_t<MPO_BF16, kResFull>(w32, hi, res, n, sh, al, stream);
     }
-    return hipSuccess;
+    if (rmode == kResByte) return launch_split_t<MPO_FP16, kResByte>(w32, hi, res, n, sh, al, stream);
+    if (rmode == kResPartial) return launch_split_t<MPO_FP16, kResPartial>(w32, hi, res, n, sh, al, stream);
+    return launch_split_t<MPO_FP16, kResFull>(w32, hi, res, n, sh, al, stream);
 }
 
-hipError_t launch_merge(const uint16_t *hi, const uint16_t *res, float *w32, uint64_t n, int fmt, hipStream_t stream)
+hipError_t launch_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits, hipStream_t stream)
 {
     const int al = aligned16(w32) && aligned16(hi) && aligned16(res);
-    uint64_t done = 0;
-    const uint64_t blocks = (n + kChunkElems - 1) / kChunkElems;
-    while (done < blocks) {
-        const uint64_t now = (blocks - done < kMaxGrid) ? (blocks - done) : kMaxGrid;
-        const uint64_t e0 = done * kChunkElems;
-        if (fmt == MPO_BF16)
-            merge_kernel<MPO_BF16><<<dim3((uint32_t)now), dim3(kBlock), 0, stream>>>(hi + e0, res + e0, w32 + e0, n - e0, al);
-        else
-            merge_kernel<MPO_FP16><<<dim3((uint32_t)now), dim3(kBlock), 0, stream>>>(hi + e0, res + e0, w32 + e0, n - e0, al);
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        done += now;
+    int rmode;
+    uint32_t sh;
+    res_layout(fmt, res_bits, rmode, sh);
+    if (fmt == MPO_BF16) {
+        if (rmode == kResByte) return launch_merge_t<MPO_BF16, kResByte>(hi, res, w32, n, sh, al, stream);
+        if (rmode == kResPartial) return launch_merge_t<MPO_BF16, kResPartial>(hi, res, w32, n, sh, al, stream);
+        return launch_merge_t<MPO_BF16, kResFull>(hi, res, w32, n, sh, al, stream);
     }
-    return hipSuccess;
+    if (rmode == kResByte) return launch_merge_t<MPO_FP16, kResByte>(hi, res, w32, n, sh, al, stream);
+    if (rmode == kResPartial) return launch_merge_t<MPO_FP16, kResPartial>(hi, res, w32, n, sh, al, stream);
+    return launch_merge_t<MPO_FP16, kResFull>(hi, res, w32, n, sh, al, stream);
 }
 
 } // namespace mpo

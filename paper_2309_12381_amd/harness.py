@@ -32,8 +32,11 @@ class ModelState:
     largest layer and reused by every layer (Section 3.2: a gradient is consumed as soon as it
     exists and never kept).  For workloads stepped in one launch the buffer holds all gradients."""
 
-    def __init__(self, wl: synth.Workload, device="cuda:0", seed: int = 2309, keep_w32_samples=None):
+    def __init__(self, wl: synth.Workload, device="cuda:0", seed: int = 2309, keep_w32_samples=None,
+                 res_bits: int = 0):
         self.wl = wl
+        self.res_bits = res_bits            # extra bits kept per weight, 0 = all (Section 3.1)
+        self.res_bytes = 1 if 1 <= res_bits <= 8 else 2
         self.device = device
         self.fmt = FMT[wl.fmt]
         self.views: List[TensorView] = []
@@ -50,7 +53,7 @@ class ModelState:
         self.total = off
         self.grad_len = max(layer_fill.values()) if wl.per_layer else off
         self.hi = torch.empty(self.total, dtype=torch.int16, device=device)
-        self.res = torch.empty(self.total, dtype=torch.int16, device=device)
+        self.res = torch.empty(self.total, dtype=torch.uint8 if self.res_bytes == 1 else torch.int16, device=device)
         self.m = torch.zeros(self.total, dtype=torch.float32, device=device)
         self.v = torch.zeros(self.total, dtype=torch.float32, device=device)
         self.gdtype = torch.bfloat16 if wl.fmt == "bf16" else torch.float16
@@ -65,11 +68,11 @@ class ModelState:
                 idx = keep_w32_samples(i, n)
                 if idx is not None:
                     self.w32_samples[i] = (idx, w[idx].cpu())
-            mpo.mpo_split(w, self.hi[tv.off:], self.res[tv.off:], n, fmt=self.fmt)
+            mpo.mpo_split(w, self.hi[tv.off:], self.res[tv.off:], n, fmt=self.fmt, res_bits=res_bits)
             del w
         torch.cuda.synchronize(device)
         self.plan = mpo.Plan([mpo.Tensor(self.hi[tv.off:], self.res[tv.off:], self.grad[tv.goff:],
-                                         self.m[tv.off:], self.v[tv.off:], tv.spec.n, tv.spec.layer)
+                                         self.m[tv.off:], self.v[tv.off:], tv.spec.n, tv.spec.layer, res_bits)
                               for tv in self.views])
         self.layers_backward = wl.layers_backward
         self.by_layer: Dict[int, List[int]] = {}
@@ -78,7 +81,7 @@ class ModelState:
 
     @property
     def resident_bytes(self) -> int:
-        return self.total * 12 + self.grad_len * 2
+        return self.total * (10 + self.res_bytes) + self.grad_len * 2
 
     def adam_cfg(self) -> mpo.AdamCfg:
         wl = self.wl

@@ -45,12 +45,29 @@ def parallel_slices(n, fn, min_chunk=1 << 18):
         list(ex.map(lambda i: fn(int(bounds[i]), int(bounds[i + 1])), range(k)))
 
 
-def ref_split(w32, rfmt):
+def dev_res(a: np.ndarray) -> torch.Tensor:
+    """Residual array (uint8 or uint16 on the host) as a device tensor of the same width."""
+    if a.dtype == np.uint8:
+        return torch.from_numpy(a.copy()).to(DEV)
+    return dev_u16(a)
+
+
+def host_res(t: torch.Tensor) -> np.ndarray:
+    if t.dtype == torch.uint8:
+        return t.detach().cpu().numpy().copy()
+    return host_u16(t)
+
+
+def res_torch_dtype(res_bits: int):
+    return torch.uint8 if 1 <= res_bits <= 8 else torch.int16
+
+
+def ref_split(w32, rfmt, res_bits=0):
     hi = np.empty(w32.shape[0], np.uint16)
-    res = np.empty(w32.shape[0], np.uint16)
+    res = np.empty(w32.shape[0], ref.res_dtype(res_bits))
 
     def f(lo, up):
-        h, r = ref.split(w32[lo:up], rfmt)
+        h, r = ref.split(w32[lo:up], rfmt, res_bits)
         hi[lo:up] = h
         res[lo:up] = r
     parallel_slices(w32.shape[0], f)
@@ -67,22 +84,24 @@ def ref_sgd(hi, res, g, buf, cfg, step):
                                                              None if buf is None else buf[lo:up], cfg, step))
 
 
-def cfg_pair(kind, fmt="bf16", gfmt=None, **kw):
-    """The same hyper-parameters for the library and for the oracle."""
+def cfg_pair(kind, fmt="bf16", gfmt=None, res_bits=0, **kw):
+    """The same hyper-parameters for the library and for the oracle.  The number of extra bits
+    kept is a property of each tensor in the library and of the step in the oracle."""
     gfmt = gfmt or fmt
     if kind == "adam":
         return (mpo.AdamCfg(weight_fmt=FMT[fmt][0], grad_fmt=FMT[gfmt][0], **kw),
-                ref.AdamCfg(weight_fmt=FMT[fmt][1], grad_fmt=FMT[gfmt][1], **kw))
+                ref.AdamCfg(weight_fmt=FMT[fmt][1], grad_fmt=FMT[gfmt][1], res_bits=res_bits, **kw))
     return (mpo.SgdCfg(weight_fmt=FMT[fmt][0], grad_fmt=FMT[gfmt][0], **kw),
-            ref.SgdCfg(weight_fmt=FMT[fmt][1], grad_fmt=FMT[gfmt][1], **kw))
+            ref.SgdCfg(weight_fmt=FMT[fmt][1], grad_fmt=FMT[gfmt][1], res_bits=res_bits, **kw))
 
 
 class HostTensor:
     """Oracle-side state of one tensor."""
 
-    def __init__(self, w32: np.ndarray, rfmt, with_v=True):
+    def __init__(self, w32: np.ndarray, rfmt, with_v=True, res_bits=0):
         self.n = w32.shape[0]
-        self.hi, self.res = ref_split(w32, rfmt)
+        self.res_bits = res_bits
+        self.hi, self.res = ref_split(w32, rfmt, res_bits)
         self.m = np.zeros(self.n, np.float32)
         self.v = np.zeros(self.n, np.float32) if with_v else None
 
@@ -90,28 +109,28 @@ class HostTensor:
 class DevTensor:
     """GPU-side state of one tensor, split by the library itself."""
 
-    def __init__(self, w32: np.ndarray, fmt, with_v=True, layer=0, grad=None, misalign=0, stream=None):
+    def __init__(self, w32: np.ndarray, fmt, with_v=True, layer=0, grad=None, misalign=0, stream=None, res_bits=0):
         n = w32.shape[0]
-        self.n, self.layer = n, layer
+        self.n, self.layer, self.res_bits = n, layer, res_bits
         # optional misalignment: carve each array out of a larger one at an odd element offset
         def alloc(dtype):
             full = torch.zeros(n + misalign + 8, dtype=dtype, device=DEV)
             return full[misalign:misalign + n]
-        self.hi, self.res = alloc(torch.int16), alloc(torch.int16)
+        self.hi, self.res = alloc(torch.int16), alloc(res_torch_dtype(res_bits))
         self.m = alloc(torch.float32)
         self.v = alloc(torch.float32) if with_v else None
         self.grad = grad if grad is not None else alloc(torch.int16)
         w = torch.zeros(n + misalign + 8, dtype=torch.float32, device=DEV)[misalign:misalign + n]
         w.copy_(torch.from_numpy(w32))
-        mpo.mpo_split(w, self.hi, self.res, n, fmt=fmt, stream=stream)
+        mpo.mpo_split(w, self.hi, self.res, n, fmt=fmt, res_bits=res_bits, stream=stream)
 
     def spec(self):
-        return mpo.Tensor(self.hi, self.res, self.grad, self.m, self.v, self.n, self.layer)
+        return mpo.Tensor(self.hi, self.res, self.grad, self.m, self.v, self.n, self.layer, self.res_bits)
 
 
 def assert_state_equal(d: DevTensor, h: HostTensor, what=""):
     torch.cuda.synchronize()
-    ghi, gres = host_u16(d.hi), host_u16(d.res)
+    ghi, gres = host_u16(d.hi), host_res(d.res)
     bad = np.flatnonzero((ghi != h.hi) | (gres != h.res))
     assert bad.size == 0, "%s: %d of %d stored weights differ, first at %d: gpu %04x/%04x oracle %04x/%04x" % (
         what, bad.size, h.n, bad[0] if bad.size else -1, *((ghi[bad[0]], gres[bad[0]], h.hi[bad[0]], h.res[bad[0]])

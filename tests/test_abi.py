@@ -69,6 +69,13 @@ def test_split_merge_argument_validation():
     assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x1000 + 10, 10) == mpo.MPO_ERR_ALIAS  # res inside hi
     assert _status(mpo.mpo_merge, A, A + 0x1000, A + 0x1000 + 8, 10) == mpo.MPO_ERR_ALIAS
     assert _status(mpo.mpo_merge, A, A + 0x1000, 0, 10) == mpo.MPO_ERR_INVALID_ARG
+    # extra bits kept: 0 = all, else 1..16 (bf16) / 1..13 (fp16); a byte per element up to 8
+    assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, res_bits=17) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, res_bits=-1) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, fmt=mpo.MPO_FP16, res_bits=14) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_merge, A, A + 0x1000, A + 0x2000, 10, fmt=mpo.MPO_FP16, res_bits=16) == mpo.MPO_ERR_INVALID_ARG
+    # res [A+0x1000, +10 bytes) with 8 bits does not reach hi at A+0x100a; with 16 bits it does
+    assert _status(mpo.mpo_split, A, A + 0x100a, A + 0x1000, 10, res_bits=9) == mpo.MPO_ERR_ALIAS
     # zero elements: a legal no-op even with null pointers
     assert _status(mpo.mpo_split, 0, 0, 0, 0) == mpo.MPO_OK
     assert _status(mpo.mpo_merge, 0, 0, 0, 0, fmt=mpo.MPO_FP16) == mpo.MPO_OK
@@ -86,6 +93,11 @@ def test_plan_validation():
     # optional buffers may be absent at creation
     assert _status(_host_plan, [T(grad=0, v=0)]) == mpo.MPO_OK
     assert _status(_host_plan, [T(m=0, v=0)]) == mpo.MPO_OK
+    assert _status(_host_plan, [T(res_bits=17)]) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(_host_plan, [T(res_bits=-2)]) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(_host_plan, [T(0, res_bits=8), T(1, res_bits=3)]) == mpo.MPO_OK          # both in bytes
+    assert _status(_host_plan, [T(0, res_bits=12), T(1, res_bits=0)]) == mpo.MPO_OK         # both in 16 bits
+    assert _status(_host_plan, [T(0, res_bits=8), T(1, res_bits=0)]) == mpo.MPO_ERR_UNSUPPORTED   # mixed widths
     # a zero-length tensor needs no pointers
     assert _status(_host_plan, [T(n=0, hi=0, res=0, grad=0, m=0, v=0)]) == mpo.MPO_OK
     assert _status(_host_plan, []) == mpo.MPO_OK
@@ -100,6 +112,9 @@ def test_plan_alias_detection():
     assert _status(_host_plan, [a, T(1, m=a.v + 3996)]) == mpo.MPO_ERR_ALIAS
     assert _status(_host_plan, [a, T(1, grad=a.m)]) == mpo.MPO_ERR_ALIAS          # gradient over written state
     assert _status(_host_plan, [T(0, grad=a.hi)]) == mpo.MPO_ERR_ALIAS
+    # byte residuals take n bytes, not 2n: the next array may start right after them
+    assert _status(_host_plan, [T(0, res_bits=8), T(1, res_bits=8, hi=a.res + 1000)]) == mpo.MPO_OK
+    assert _status(_host_plan, [T(0, res_bits=9), T(1, res_bits=9, hi=a.res + 1000)]) == mpo.MPO_ERR_ALIAS
     # gradients may share one buffer (one layer's gradient alive at a time)
     assert _status(_host_plan, [a, T(1, grad=a.grad), T(2, grad=a.grad + 10)]) == mpo.MPO_OK
     # a written range nested inside a long read-only range that starts earlier

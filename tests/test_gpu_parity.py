@@ -15,8 +15,8 @@ import paper_2309_12381_amd as mpo
 from paper_2309_12381_amd import synth
 from oracle import ref
 
-from gpu_util import (DEV, FMT, DevTensor, HostTensor, assert_state_equal, cfg_pair, dev_f32, dev_u16, host_f32,
-                      host_u16, parallel_slices, ref_adam, ref_sgd, ref_split, say)
+from gpu_util import (DEV, FMT, DevTensor, HostTensor, assert_state_equal, cfg_pair, dev_f32, dev_res, dev_u16,
+                      host_f32, host_res, host_u16, parallel_slices, ref_adam, ref_sgd, ref_split, res_torch_dtype, say)
 
 pytestmark = pytest.mark.gpu
 
@@ -493,4 +493,95 @@ def test_runs_on_the_callers_stream():
     for t in (1, 2, 3):
         ref.adam_step(h.hi, h.res, g, h.m, h.v, ref.AdamCfg(), t)
     assert_state_equal(d, h, "side stream")
+    plan.destroy()
+
+
+# ---- keeping only E of the extra bits (Section 3.1; the paper's fp16+8 / bf16+8) --------------
+
+@pytest.mark.parametrize("fmt,res_bits", [("bf16", 8), ("bf16", 3), ("bf16", 12), ("bf16", 16), ("fp16", 8), ("fp16", 1),
+                                          ("fp16", 11), ("fp16", 13)])
+@pytest.mark.parametrize("misalign", [0, 1])
+def test_split_merge_partial_bits(fmt, res_bits, misalign):
+    gfmt, rfmt = FMT[fmt]
+    rng = np.random.default_rng(31)
+    rdt = res_torch_dtype(res_bits)
+    fill = 0x55 if rdt == torch.uint8 else 0x5555
+    for n in SIZES:
+        say("split/merge fmt=%s res_bits=%d n=%d misalign=%d" % (fmt, res_bits, n, misalign))
+        x = interesting_f32(rng, n)
+        w = torch.zeros(n + misalign + 8, dtype=torch.float32, device=DEV)[misalign:misalign + n]
+        w.copy_(torch.from_numpy(x))
+        hi = torch.full((n + misalign + 8,), 0x5555, dtype=torch.int16, device=DEV)
+        res = torch.full((n + misalign + 8,), fill, dtype=rdt, device=DEV)
+        mpo.mpo_split(w, hi[misalign:], res[misalign:], n, fmt=gfmt, res_bits=res_bits)
+        want_hi, want_res = ref.split(x, rfmt, res_bits)
+        assert np.array_equal(host_u16(hi[misalign:misalign + n]), want_hi)
+        assert np.array_equal(host_res(res[misalign:misalign + n]), want_res)
+        full = host_res(res)
+        assert np.all(full[:misalign] == fill) and np.all(full[misalign + n:] == fill)
+        out = torch.full((n + misalign + 8,), -7.0, dtype=torch.float32, device=DEV)
+        mpo.mpo_merge(hi[misalign:], res[misalign:], out[misalign:], n, fmt=gfmt, res_bits=res_bits)
+        want = ref.merge(want_hi, want_res, rfmt, res_bits)
+        got = host_f32(out)
+        assert np.array_equal(got[misalign:misalign + n].view(np.uint32), want.view(np.uint32))
+        assert np.all(got[:misalign] == -7.0) and np.all(got[misalign + n:] == -7.0)
+
+
+PARTIAL_CASES = [
+    ("adam", "bf16", [8], dict(lr=1e-3, weight_decay=1e-2, decoupled_wd=True)),          # bf16+8, byte residuals
+    ("adam", "fp16", [8], dict(lr=1e-3, loss_scale=1024.0)),                             # fp16+8
+    ("adam", "bf16", [8, 3, 5], dict(lr=1e-3)),                                          # different E, all in bytes
+    ("adam", "bf16", [12, 0, 16, 9], dict(lr=1e-3, weight_decay=0.1, decoupled_wd=False)),  # 16-bit slots, some cut
+    ("adam", "fp16", [12, 0, 13], dict(lr=1e-3, loss_scale=64.0)),
+    ("sgd", "bf16", [8], dict(lr=0.3, momentum=0.9, weight_decay=2e-4)),
+    ("sgd", "fp16", [8, 2], dict(lr=0.1, momentum=0.0, loss_scale=128.0)),
+]
+
+
+@pytest.mark.parametrize("kind,fmt,bits,kw", PARTIAL_CASES,
+                         ids=["%s-%s-%s" % (c[0], c[1], "_".join(map(str, c[2]))) for c in PARTIAL_CASES])
+@pytest.mark.parametrize("misalign", [0, 1])
+def test_multi_tensor_list_partial_bits(kind, fmt, bits, kw, misalign):
+    """Lists whose tensors keep only E extra bits (bytes for E <= 8), several E in one list."""
+    gfmt, rfmt = FMT[fmt]
+    rng = np.random.default_rng(17 + misalign)
+    sizes = _small_list(rng, count=23, total=700_000)
+    scale = kw.get("loss_scale", 1.0)
+    say("partial-bits list kind=%s fmt=%s bits=%s kw=%s misalign=%d" % (kind, fmt, bits, kw, misalign))
+    devs, hosts, cfgs = [], [], []
+    for i, n in enumerate(sizes):
+        E = bits[i % len(bits)]
+        w0 = synth.gen_weights(n, synth.seed_for(19, i), "cpu", 0.02).numpy()
+        devs.append(DevTensor(w0, gfmt, with_v=(kind == "adam"), layer=i % 4, misalign=misalign, res_bits=E))
+        hosts.append(HostTensor(w0, rfmt, with_v=(kind == "adam"), res_bits=E))
+        cfgs.append(cfg_pair(kind, fmt, res_bits=E, **kw))
+    plan = mpo.Plan([d.spec() for d in devs])
+    lib_cfg = cfgs[0][0]
+    for t in range(1, 5):
+        for i, (d, h) in enumerate(zip(devs, hosts)):
+            g = synth.bits16(synth.gen_grads(d.n, synth.seed_for(29, i, t), "cpu", 1e-3, fmt, scale))
+            d.grad.copy_(dev_u16(g))
+            if kind == "adam":
+                ref.adam_step(h.hi, h.res, g, h.m, h.v, cfgs[i][1], t)
+            else:
+                ref.sgd_step(h.hi, h.res, g, h.m, cfgs[i][1], t)
+        if t % 2:
+            (mpo.mpo_adam_step if kind == "adam" else mpo.mpo_sgd_step)(plan, lib_cfg, t)
+        else:
+            for ly in (3, 2, 1, 0):
+                mpo.mpo_step_layer(plan, ly, lib_cfg, t)
+        for i, (d, h) in enumerate(zip(devs, hosts)):
+            assert_state_equal(d, h, "tensor %d (n=%d, E=%d) step %d" % (i, d.n, d.res_bits, t))
+    plan.destroy()
+
+
+def test_partial_bits_argument_checks_on_device():
+    w0 = np.ones(100, np.float32)
+    d = DevTensor(w0, mpo.MPO_BF16, res_bits=14)
+    plan = mpo.Plan([d.spec()])
+    mpo.mpo_adam_step(plan, mpo.AdamCfg(), 1)                                        # 14 of 16 bits: fine for bf16
+    with pytest.raises(mpo.MpoError) as e:
+        mpo.mpo_adam_step(plan, mpo.AdamCfg(weight_fmt=mpo.MPO_FP16), 2)               # fp16 has only 13
+    assert e.value.status == mpo.MPO_ERR_INVALID_ARG
+    torch.cuda.synchronize()
     plan.destroy()

@@ -26,17 +26,18 @@ def _ref_cfg(st):
     c = st.adam_cfg()
     rf = ref.BF16 if st.wl.fmt == "bf16" else ref.FP16
     return ref.AdamCfg(lr=c.lr, beta1=c.beta1, beta2=c.beta2, eps=c.eps, weight_decay=c.weight_decay,
-                       decoupled_wd=c.decoupled_wd, loss_scale=c.loss_scale, weight_fmt=rf, grad_fmt=rf), rf
+                       decoupled_wd=c.decoupled_wd, loss_scale=c.loss_scale, weight_fmt=rf, grad_fmt=rf,
+                       res_bits=st.res_bits), rf
 
 
-def _run_and_compare(key, steps, sampler):
+def _run_and_compare(key, steps, sampler, res_bits=0):
     wl = synth.workload(key)
-    say("full-size %s: %d params, %d steps" % (key, wl.num_params, steps))
-    st = harness.ModelState(wl, DEV, seed=2309, keep_w32_samples=sampler)
+    say("full-size %s: %d params, %d steps, res_bits %d" % (key, wl.num_params, steps, res_bits))
+    st = harness.ModelState(wl, DEV, seed=2309, keep_w32_samples=sampler, res_bits=res_bits)
     rcfg, rf = _ref_cfg(st)
     host = {}
     for i, (idx, w) in st.w32_samples.items():
-        hi, res = ref_split(np.ascontiguousarray(w.numpy()), rf)
+        hi, res = ref_split(np.ascontiguousarray(w.numpy()), rf, res_bits)
         host[i] = [hi, res, np.zeros(hi.size, np.float32), np.zeros(hi.size, np.float32)]
 
     for t in range(1, steps + 1):
@@ -60,7 +61,8 @@ def _run_and_compare(key, steps, sampler):
         idx = st.w32_samples[i][0]
         n = tv.spec.n
         got_hi = synth.bits16(st.hi[tv.off:tv.off + n][idx])
-        got_res = synth.bits16(st.res[tv.off:tv.off + n][idx])
+        got_res = st.res[tv.off:tv.off + n][idx]
+        got_res = got_res.cpu().numpy().copy() if got_res.dtype == torch.uint8 else synth.bits16(got_res)
         got_m = st.m[tv.off:tv.off + n][idx].cpu().numpy()
         got_v = st.v[tv.off:tv.off + n][idx].cpu().numpy()
         name = "%s tensor %d (%s)" % (key, i, tv.spec.name)
@@ -102,6 +104,17 @@ def test_c2_gpt2_medium_full():
 def test_c3_llama7b_per_layer_sampled():
     checked, wl = _run_and_compare("c3", 2, _blocks_sampler())
     assert wl.num_params == 6_738_415_616 and checked > 40_000_000
+
+
+def test_c3_llama7b_bf16_plus_8_per_layer_sampled():
+    """The paper's bf16+8: byte residuals, 11 B resident and 24 B moved per parameter."""
+    checked, wl = _run_and_compare("c3", 2, _blocks_sampler(seed=6), res_bits=8)
+    assert checked > 40_000_000
+
+
+def test_c1_bf16_plus_8_full():
+    checked, wl = _run_and_compare("c1", 3, _everything, res_bits=8)
+    assert checked == wl.num_params
 
 
 def test_c4_llama13b_fp16_per_layer_sampled():

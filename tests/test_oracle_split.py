@@ -238,3 +238,77 @@ def test_cvt16_matches_library_cast(ref, fmt):
     assert np.all(np.isnan(got[nan]))
     for p in (0x0001, 0x03FF, 0x0400, 0x3C00, 0x7BFF, 0x8001, 0xBA83, 0x3A80):
         assert ref.cvt16(p, f) == float(lib[p])
+
+
+# ---- keeping only E of the extra bits (Section 3.1: "keeping only part of those bits") ----
+
+FULL = {"bf16": 16, "fp16": 13}
+
+
+def pins_partial_bits_value_definition(ref, fmt):
+    """res_bits = E keeps the E leading extra bits: hi is unchanged, the residual is the full
+    one divided by 2^(full-E) rounded down, and merge gives hi + res * 2^(full-E) grid units."""
+    f = ref.FP16 if fmt == "fp16" else ref.BF16
+    ebits, mbits = FIELDS[fmt]
+    full = FULL[fmt]
+    rng = np.random.default_rng(8)
+    pats = [p for p in _sample_patterns(rng, 300)[::7] if ((p >> 23) & 0xFF) != 255]
+    x = np.array(pats, np.uint32).view(np.float32)
+    for E in (1, 4, 8, 9, 12, full):
+        hi, res = ref.split(x, f, E)
+        assert res.dtype == (np.uint8 if E <= 8 else np.uint16)
+        w = ref.merge(hi, res, f, E)
+        for i, p in enumerate(pats):
+            xv = Fraction(float_of(p))
+            exp_hi, exp_res = _expected_split_value(xv, fmt)
+            kept = exp_res >> (full - E)
+            assert abs(decode(int(hi[i]), ebits, mbits)) == exp_hi, (fmt, E, hex(p))
+            assert int(res[i]) == kept, (fmt, E, hex(p), int(res[i]), kept)
+            e16 = max((int(hi[i]) >> mbits) & ((1 << ebits) - 1), 1) - ((1 << (ebits - 1)) - 1)
+            unit = Fraction(2) ** (e16 - 23)
+            sign = -1 if p >> 31 else 1
+            assert Fraction(float(w[i])) == sign * (exp_hi + (kept << (full - E)) * unit), (fmt, E, hex(p))
+    # E = 0 and E = full are the same thing
+    h0, r0 = ref.split(x, f, 0)
+    h1, r1 = ref.split(x, f, full)
+    assert np.array_equal(h0, h1) and np.array_equal(r0, r1)
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "fp16"])
+def test_partial_bits_value_definition(ref, fmt):
+    pins_partial_bits_value_definition(ref, fmt)
+
+
+def _trunc_to_bits(x, sig_bits, emin):
+    """|x| cut toward zero to `sig_bits` significant bits (grid fixed below 2^emin): library
+    frexp / trunc in binary64, exact for binary32 inputs."""
+    a = np.abs(x.astype(np.float64))
+    m, e = np.frexp(a)                                  # a = m * 2^e, m in [0.5, 1)
+    e = np.maximum(e, emin + 1)
+    ulp = np.ldexp(1.0, e - sig_bits)
+    return np.copysign(np.trunc(a / ulp) * ulp, x.astype(np.float64)).astype(np.float32)
+
+
+def pins_partial_bits_is_truncation(ref):
+    """merge(split(x, E)) is x cut toward zero to 8+E (bf16) or 11+E (fp16) significant bits."""
+    rng = np.random.default_rng(9)
+    x = rng.integers(0, 1 << 32, size=1 << 22, dtype=np.uint64).astype(np.uint32).view(np.float32)
+    x = x[np.isfinite(x)]
+    for E in (8, 3, 12):
+        hi, res = ref.split(x, ref.BF16, E)
+        got = ref.merge(hi, res, ref.BF16, E)
+        want = _trunc_to_bits(x, 8 + E, -126)
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), E
+    inr = x[(np.abs(x) >= 2.0 ** -14) & (np.abs(x) < 65536.0)]
+    for E in (8, 5, 12):
+        hi, res = ref.split(inr, ref.FP16, E)
+        got = ref.merge(hi, res, ref.FP16, E)
+        want = _trunc_to_bits(inr, 11 + E, -14)
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), E
+        # what is kept is stable
+        h2, r2 = ref.split(got, ref.FP16, E)
+        assert np.array_equal(h2, hi) and np.array_equal(r2, res)
+
+
+def test_partial_bits_is_truncation(ref):
+    pins_partial_bits_is_truncation(ref)

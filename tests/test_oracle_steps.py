@@ -551,3 +551,80 @@ def test_tiny_lengths(ref, n):
     m = np.zeros(n, np.float32); v = np.zeros(n, np.float32)
     ref.adam_step(hi, res, np.zeros(n, np.uint16), m, v, ref.AdamCfg(), 1)
     assert np.array_equal(ref.merge(hi, res), w0)
+
+
+# ---- keeping only E extra bits (Section 3.1; the paper's fp16+8 / bf16+8) ---------------
+
+def _cut(x, sig_bits, emin):
+    a = np.abs(x.astype(np.float64))
+    m, e = np.frexp(a)
+    e = np.maximum(e, emin + 1)
+    ulp = np.ldexp(1.0, e - sig_bits)
+    return np.copysign(np.trunc(a / ulp) * ulp, x.astype(np.float64)).astype(np.float32)
+
+
+def pins_partial_bits_master_equivalence(ref):
+    """With E extra bits the weights follow an fp32-master optimizer whose master is cut toward
+    zero to 16+E bits after every step (numpy float32, library frexp/trunc for the cut)."""
+    rng = np.random.default_rng(47)
+    n = 4096
+    for fmt, tobits, tof32, sig, emin, scale in ((ref.BF16, to_bf16_bits, bf16_to_f32, 8, -126, 1.0),
+                                                 (ref.FP16, to_fp16_bits, fp16_to_f32, 11, -14, 512.0)):
+        for E in (8, 4, 12):
+            w0 = (0.05 + 0.5 * rng.random(n)).astype(np.float32) * np.where(rng.random(n) < 0.5, -1, 1).astype(np.float32)
+            cfg = ref.AdamCfg(lr=1e-3, weight_decay=1e-2, decoupled_wd=True, loss_scale=scale,
+                              weight_fmt=fmt, grad_fmt=fmt, res_bits=E)
+            hi, res = ref.split(w0, fmt, E)
+            master = _cut(w0, sig + E, emin)
+            assert np.array_equal(ref.merge(hi, res, fmt, E).view(np.uint32), master.view(np.uint32))
+            m = np.zeros(n, np.float32); v = np.zeros(n, np.float32)
+            mm = np.zeros(n, np.float32); mv = np.zeros(n, np.float32)
+            for t in range(1, 21):
+                gb = tobits((make_state(rng, n)[1] * np.float32(scale)).astype(np.float32))
+                ref.adam_step(hi, res, gb, m, v, cfg, t)
+                master = _cut(_master_adam(master, tof32(gb), mm, mv, 1e-3, 0.9, 0.999, 1e-8, 1e-2, True, t,
+                                           1.0 / scale), sig + E, emin)
+                assert np.array_equal(ref.merge(hi, res, fmt, E).view(np.uint32), master.view(np.uint32)), (fmt, E, t)
+                assert np.array_equal(m.view(np.uint32), mm.view(np.uint32))
+                assert np.array_equal(v.view(np.uint32), mv.view(np.uint32))
+            # SGD, same idea
+            scfg = ref.SgdCfg(lr=1e-2, momentum=0.9, weight_fmt=fmt, grad_fmt=fmt, res_bits=E, loss_scale=scale)
+            hi, res = ref.split(w0, fmt, E)
+            master = _cut(w0, sig + E, emin)
+            buf = np.zeros(n, np.float32); mb = np.zeros(n, np.float32)
+            f = np.float32
+            for t in range(1, 11):
+                gb = tobits((make_state(rng, n)[1] * np.float32(scale)).astype(np.float32))
+                ref.sgd_step(hi, res, gb, buf, scfg, t)
+                mb = f(0.9) * mb + tof32(gb) * f(1.0 / scale)
+                master = _cut(master - f(1e-2) * mb, sig + E, emin)
+                assert np.array_equal(ref.merge(hi, res, fmt, E).view(np.uint32), master.view(np.uint32)), (fmt, E, t)
+
+
+def test_partial_bits_master_equivalence(ref):
+    pins_partial_bits_master_equivalence(ref)
+
+
+def pins_partial_bits_torch_optim(ref):
+    """bf16+8 against torch.optim.AdamW on fp32 masters: the only difference is the cut of at
+    most 2^-16 of the weight per step, always toward zero."""
+    rng = np.random.default_rng(53)
+    n, steps = 2048, 20
+    w0, _ = make_state(rng, n)
+    gbits = [to_bf16_bits(make_state(rng, n)[1]) for _ in range(steps)]
+    want = _torch_run("adamw", w0, [bf16_to_f32(b) for b in gbits], lr=1e-3, betas=(0.9, 0.999), eps=1e-8,
+                      weight_decay=0.01)
+    cfg = ref.AdamCfg(lr=1e-3, weight_decay=0.01, decoupled_wd=True, res_bits=8)
+    hi, res = ref.split(w0, ref.BF16, 8)
+    m = np.zeros(n, np.float32); v = np.zeros(n, np.float32)
+    for t, gb in enumerate(gbits, 1):
+        ref.adam_step(hi, res, gb, m, v, cfg, t)
+    got = ref.merge(hi, res, ref.BF16, 8).astype(np.float64)
+    bound = 2 * (steps + 1) * 2.0 ** -16 * (np.maximum(np.abs(want), np.abs(w0)) + steps * 1e-3) + 2e-5 * steps * 1e-3
+    assert np.all(np.abs(got - want) <= bound)
+    # the cut is toward zero: nearly all weights (those that did not change sign) end up smaller in magnitude
+    assert np.mean(np.abs(got) < np.abs(want)) > 0.8
+
+
+def test_partial_bits_torch_optim(ref):
+    pins_partial_bits_torch_optim(ref)
