@@ -99,28 +99,100 @@ static float merge_one(uint16_t hi, uint16_t res, int fmt)
     return fmt == MPO_REF_FP16 ? merge_fp16(hi, res) : merge_bf16(hi, res);
 }
 
-/* ---- keeping only the E leading extra bits (Sec. 3.1) ---------------------
- * The residual that is stored is the full one with its trailing bits cut off;
- * on merge the cut bits read as zero: the fp32 value is truncated toward zero
- * to 16 + E bits. */
+/* ---- Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as
+ * easy as 1, 2, 3", SC'11): ten rounds of two 32x32->64 multiplications. ---- */
 
-static int full_bits(int fmt) { return fmt == MPO_REF_FP16 ? 13 : 16; }
-
-static int kept_bits(int fmt, int res_bits) { return res_bits == 0 ? full_bits(fmt) : res_bits; }
-
-static uint16_t load_res(const void *res, uint64_t i, int fmt, int res_bits)
+void mpo_ref_philox4x32_10(const uint32_t counter[4], const uint32_t key[2], uint32_t out[4])
 {
-    int E = kept_bits(fmt, res_bits);
-    uint16_t stored = E <= 8 ? ((const uint8_t *)res)[i] : ((const uint16_t *)res)[i];
-    if (fmt == MPO_REF_FP16) stored &= 0x1FFFu;        /* spare bits of a full fp16 residual */
-    return (uint16_t)(stored << (full_bits(fmt) - E));
+    uint32_t c0 = counter[0], c1 = counter[1], c2 = counter[2], c3 = counter[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        if (round > 0) {
+            k0 += 0x9E3779B9u;             /* golden ratio   */
+            k1 += 0xBB67AE85u;             /* sqrt(3) - 1    */
+        }
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-static void store_res(void *res, uint64_t i, uint16_t full, int fmt, int res_bits)
+/* ---- residual storage, rounding of the 16-bit value (Sec. 3.1) -------------
+ * The stored residual is the full one with its trailing bits cut off (E kept
+ * bits, right-aligned); on merge the cut bits read as zero: the fp32 value is
+ * truncated toward zero to 16 + E bits.  NEAREST / STOCHASTIC add one to the
+ * 16-bit pattern of hi (the next value away from zero) and remember it. */
+
+typedef struct {
+    int fmt, round;
+    int full;      /* dropped bits of the format: 16 (bf16) or 13 (fp16) */
+    int kept;      /* E: bits of them that are stored                    */
+    int byte_slot; /* residual array is uint8_t                          */
+    uint64_t seed;
+    uint32_t tensor_id, step32;
+} res_layout;
+
+static res_layout make_layout(int fmt, int res_bits, int round, uint64_t seed, uint32_t tensor_id, uint64_t step)
 {
-    int E = kept_bits(fmt, res_bits);
-    uint16_t kept = (uint16_t)(full >> (full_bits(fmt) - E));
-    if (E <= 8) ((uint8_t *)res)[i] = (uint8_t)kept; else ((uint16_t *)res)[i] = kept;
+    res_layout L;
+    L.fmt = fmt;
+    L.round = round;
+    L.full = fmt == MPO_REF_FP16 ? 13 : 16;
+    L.kept = res_bits != 0 ? res_bits : (round == MPO_REF_STOCHASTIC && L.full == 16 ? 15 : L.full);
+    L.byte_slot = res_bits >= 1 && res_bits <= 8;
+    L.seed = seed;
+    L.tensor_id = tensor_id;
+    L.step32 = (uint32_t)step;
+    return L;
+}
+
+static uint16_t max_finite_hi(int fmt) { return fmt == MPO_REF_FP16 ? 0x7BFFu : 0x7F7Fu; }
+
+/* Uniform integer in [0, 2^full) for element i of this tensor at this step. */
+static uint32_t draw(const res_layout *L, uint64_t i)
+{
+    uint64_t block = i / 4;
+    uint32_t counter[4] = { (uint32_t)block, (uint32_t)(block >> 32), L->step32, L->tensor_id };
+    uint32_t key[2] = { (uint32_t)L->seed, (uint32_t)(L->seed >> 32) };
+    uint32_t out[4];
+    mpo_ref_philox4x32_10(counter, key, out);
+    return out[i % 4] >> (32 - L->full);
+}
+
+/* (hi, res) as stored -> the truncated 16-bit value and the full residual. */
+static void load_pair(const uint16_t *hi, const void *res, uint64_t i, const res_layout *L,
+                      uint16_t *hi_trunc, uint16_t *res_full)
+{
+    uint16_t stored = L->byte_slot ? ((const uint8_t *)res)[i] : ((const uint16_t *)res)[i];
+    uint16_t kept = (uint16_t)(stored & ((1u << L->kept) - 1u));
+    uint16_t full = (uint16_t)(kept << (L->full - L->kept));
+    int was_rounded_up = 0;
+    if (L->round == MPO_REF_STOCHASTIC) was_rounded_up = (stored >> L->kept) & 1;
+    if (L->round == MPO_REF_NEAREST) was_rounded_up = (full >> (L->full - 1)) & 1;
+    *hi_trunc = (uint16_t)(hi[i] - was_rounded_up);     /* un-round */
+    *res_full = full;
+}
+
+/* the truncated 16-bit value and the full residual -> (hi, res) as stored */
+static void store_pair(uint16_t *hi, void *res, uint64_t i, const res_layout *L, uint16_t hi_trunc, uint16_t res_full)
+{
+    int up = 0;
+    /* NEAREST: the leading dropped bit decides, always (it is also what tells merge to undo it);
+     * like IEEE rounding, a value within half a unit of overflow becomes infinity. */
+    if (L->round == MPO_REF_NEAREST) up = (res_full >> (L->full - 1)) & 1;
+    /* STOCHASTIC: up with probability res_full / 2^full, but never out of the finite range
+     * (the stored flag keeps this invertible) */
+    if (L->round == MPO_REF_STOCHASTIC)
+        up = (uint16_t)(hi_trunc & 0x7FFFu) < max_finite_hi(L->fmt) && draw(L, i) < res_full;
+    uint16_t kept = (uint16_t)(res_full >> (L->full - L->kept));
+    if (L->round == MPO_REF_STOCHASTIC) kept = (uint16_t)(kept | (up << L->kept));
+    hi[i] = (uint16_t)(hi_trunc + up);
+    if (L->byte_slot) ((uint8_t *)res)[i] = (uint8_t)kept; else ((uint16_t *)res)[i] = kept;
 }
 
 /* A 16-bit float read as fp32: every bf16 and fp16 value is an fp32 value. */
@@ -129,18 +201,25 @@ float mpo_ref_cvt16(uint16_t x, int fmt)
     return fmt == MPO_REF_FP16 ? merge_fp16(x, 0) : merge_bf16(x, 0);
 }
 
-void mpo_ref_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits)
+void mpo_ref_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits,
+                   int round, uint64_t seed, uint32_t tensor_id)
 {
+    res_layout L = make_layout(fmt, res_bits, round, seed, tensor_id, 0);
     for (uint64_t i = 0; i < n; ++i) {
-        uint16_t full;
-        split_one(w32[i], &hi[i], &full, fmt);
-        store_res(res, i, full, fmt, res_bits);
+        uint16_t h, full;
+        split_one(w32[i], &h, &full, fmt);
+        store_pair(hi, res, i, &L, h, full);
     }
 }
 
-void mpo_ref_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits)
+void mpo_ref_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits, int round)
 {
-    for (uint64_t i = 0; i < n; ++i) w32[i] = merge_one(hi[i], load_res(res, i, fmt, res_bits), fmt);
+    res_layout L = make_layout(fmt, res_bits, round, 0, 0, 0);
+    for (uint64_t i = 0; i < n; ++i) {
+        uint16_t h, full;
+        load_pair(hi, res, i, &L, &h, &full);
+        w32[i] = merge_one(h, full, fmt);
+    }
 }
 
 /* ---- Adam (Sec. 3.1: the classic optimizer, hyper-parameters unchanged) ----
@@ -152,8 +231,9 @@ void mpo_ref_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, 
  * line below is one rounded fp32 operation.
  */
 void mpo_ref_adam_step(uint16_t *hi, void *res, const uint16_t *grad, float *m, float *v,
-                       uint64_t n, const mpo_ref_adam_cfg *cfg, uint64_t step)
+                       uint64_t n, const mpo_ref_adam_cfg *cfg, uint64_t step, uint32_t tensor_id)
 {
+    const res_layout L = make_layout(cfg->weight_fmt, cfg->res_bits, cfg->round, cfg->seed, tensor_id, step);
     const double t = (double)step;
     const float B1 = (float)cfg->beta1;
     const float B2 = (float)cfg->beta2;
@@ -168,7 +248,9 @@ void mpo_ref_adam_step(uint16_t *hi, void *res, const uint16_t *grad, float *m, 
     const int has_wd = cfg->weight_decay != 0.0;
 
     for (uint64_t i = 0; i < n; ++i) {
-        float w = merge_one(hi[i], load_res(res, i, cfg->weight_fmt, cfg->res_bits), cfg->weight_fmt);
+        uint16_t h16, full;
+        load_pair(hi, res, i, &L, &h16, &full);
+        float w = merge_one(h16, full, cfg->weight_fmt);
         float g = mpo_ref_cvt16(grad[i], cfg->grad_fmt);
         g = g * IS;
         if (has_wd) {
@@ -194,17 +276,17 @@ void mpo_ref_adam_step(uint16_t *hi, void *res, const uint16_t *grad, float *m, 
         float w1 = w - upd;
         m[i] = m1;
         v[i] = v1;
-        uint16_t full;
-        split_one(w1, &hi[i], &full, cfg->weight_fmt);
-        store_res(res, i, full, cfg->weight_fmt, cfg->res_bits);
+        split_one(w1, &h16, &full, cfg->weight_fmt);
+        store_pair(hi, res, i, &L, h16, full);
     }
 }
 
 /* ---- SGD with momentum (Sec. 3.1; appendix: SGD with momentum, weight decay) */
 void mpo_ref_sgd_step(uint16_t *hi, void *res, const uint16_t *grad, float *buf,
-                      uint64_t n, const mpo_ref_sgd_cfg *cfg, uint64_t step)
+                      uint64_t n, const mpo_ref_sgd_cfg *cfg, uint64_t step, uint32_t tensor_id)
 {
-    (void)step; /* momentum buffers start at zero, so step 1 needs no special case */
+    /* momentum buffers start at zero, so step 1 needs no special case */
+    const res_layout L = make_layout(cfg->weight_fmt, cfg->res_bits, cfg->round, cfg->seed, tensor_id, step);
     const float LR = (float)cfg->lr;
     const float MU = (float)cfg->momentum;
     const float WD = (float)cfg->weight_decay;
@@ -213,7 +295,9 @@ void mpo_ref_sgd_step(uint16_t *hi, void *res, const uint16_t *grad, float *buf,
     const int has_mu = cfg->momentum != 0.0;
 
     for (uint64_t i = 0; i < n; ++i) {
-        float w = merge_one(hi[i], load_res(res, i, cfg->weight_fmt, cfg->res_bits), cfg->weight_fmt);
+        uint16_t h16, full;
+        load_pair(hi, res, i, &L, &h16, &full);
+        float w = merge_one(h16, full, cfg->weight_fmt);
         float g = mpo_ref_cvt16(grad[i], cfg->grad_fmt);
         g = g * IS;
         if (has_wd) {
@@ -228,8 +312,7 @@ void mpo_ref_sgd_step(uint16_t *hi, void *res, const uint16_t *grad, float *buf,
         }
         float upd = LR * b;
         float w1 = w - upd;
-        uint16_t full;
-        split_one(w1, &hi[i], &full, cfg->weight_fmt);
-        store_res(res, i, full, cfg->weight_fmt, cfg->res_bits);
+        split_one(w1, &h16, &full, cfg->weight_fmt);
+        store_pair(hi, res, i, &L, h16, full);
     }
 }

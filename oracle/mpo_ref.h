@@ -39,6 +39,26 @@ enum { MPO_REF_BF16 = 0, MPO_REF_FP16 = 1 };
  * has one uint8_t per element when 1 <= E <= 8, else one uint16_t; the E bits
  * are right-aligned in it. */
 
+/* Section 3.1, last paragraph: how the 16-bit value is rounded.
+ *   TRUNC      hi = the leading bits (round toward zero): the method's base mode.
+ *   NEAREST    hi is rounded up in magnitude when the dropped bits are at least
+ *              half a unit; the leading dropped bit tells whether that happened,
+ *              so no extra storage is needed to undo it.
+ *   STOCHASTIC hi is rounded up in magnitude with probability (dropped bits) /
+ *              2^full; one more bit, stored just above the kept residual bits,
+ *              records it so that the value can be "un-rounded" before the update.
+ * In every mode merge gives back the same fp32 value as TRUNC would: only the
+ * 16-bit value seen by forward / backward differs.  STOCHASTIC never rounds a
+ * value up out of the finite range; NEAREST, like IEEE rounding, turns a value
+ * within half a unit of overflow into infinity (merge still undoes it).
+ * In STOCHASTIC mode res_bits = 0 means 15 kept bits
+ * for bf16 (15 + 1 flag fill the 16-bit slot) and 13 for fp16; at most 7 kept
+ * bits fit a byte slot and 15 a 16-bit slot.
+ * Random numbers: Philox4x32-10 (Salmon et al., SC'11), key = the 64-bit seed,
+ * counter = (i/4 low, i/4 high, step low 32 bits, tensor_id); element i uses
+ * word i%4, its top `full` bits.  The initial split uses step 0. */
+enum { MPO_REF_TRUNC = 0, MPO_REF_NEAREST = 1, MPO_REF_STOCHASTIC = 2 };
+
 typedef struct {
     double lr, beta1, beta2, eps, weight_decay;
     int32_t decoupled_wd; /* 1: AdamW (w *= 1-lr*wd), 0: L2 (g += wd*w)      */
@@ -46,6 +66,8 @@ typedef struct {
     int32_t weight_fmt;   /* format of hi                                     */
     int32_t grad_fmt;     /* format of grad                                   */
     int32_t res_bits;     /* extra bits kept, 0 = all                         */
+    int32_t round;        /* MPO_REF_TRUNC / NEAREST / STOCHASTIC             */
+    uint64_t seed;        /* STOCHASTIC only                                  */
 } mpo_ref_adam_cfg;
 
 typedef struct {
@@ -53,20 +75,27 @@ typedef struct {
     double loss_scale;
     int32_t weight_fmt, grad_fmt;
     int32_t res_bits;
+    int32_t round;
+    uint64_t seed;
 } mpo_ref_sgd_cfg;
 
 /* Section 3.1, Table 1: fp32 -> (16-bit float, extra bits), truncation. */
-void mpo_ref_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits);
+void mpo_ref_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits,
+                   int round, uint64_t seed, uint32_t tensor_id);
 /* Section 3.1: (16-bit float, extra bits) -> fp32. */
-void mpo_ref_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits);
+void mpo_ref_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits,
+                   int round);
 
 /* Section 3.1 "classic optimizers": bias-corrected Adam / AdamW on one tensor. */
 void mpo_ref_adam_step(uint16_t *hi, void *res, const uint16_t *grad, float *m, float *v,
-                       uint64_t n, const mpo_ref_adam_cfg *cfg, uint64_t step);
+                       uint64_t n, const mpo_ref_adam_cfg *cfg, uint64_t step, uint32_t tensor_id);
 /* Section 3.1 "classic optimizers": SGD with momentum (dampening 0, no Nesterov).
  * momentum == 0 leaves buf untouched (it may then be NULL). */
 void mpo_ref_sgd_step(uint16_t *hi, void *res, const uint16_t *grad, float *buf,
-                      uint64_t n, const mpo_ref_sgd_cfg *cfg, uint64_t step);
+                      uint64_t n, const mpo_ref_sgd_cfg *cfg, uint64_t step, uint32_t tensor_id);
+
+/* One Philox4x32-10 block: out = philox(counter, key). */
+void mpo_ref_philox4x32_10(const uint32_t counter[4], const uint32_t key[2], uint32_t out[4]);
 
 /* Exact conversion of one 16-bit float to fp32 (used for gradients). */
 float mpo_ref_cvt16(uint16_t x, int fmt);

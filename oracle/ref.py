@@ -20,6 +20,10 @@ from . import build as _build
 BF16 = 0
 FP16 = 1
 
+TRUNC = 0
+NEAREST = 1
+STOCHASTIC = 2
+
 _u16p = ctypes.POINTER(ctypes.c_uint16)
 _f32p = ctypes.POINTER(ctypes.c_float)
 
@@ -28,13 +32,15 @@ class _AdamCfg(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
                 ("eps", ctypes.c_double), ("weight_decay", ctypes.c_double),
                 ("decoupled_wd", ctypes.c_int32), ("loss_scale", ctypes.c_double),
-                ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32), ("res_bits", ctypes.c_int32)]
+                ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32), ("res_bits", ctypes.c_int32),
+                ("round", ctypes.c_int32), ("seed", ctypes.c_uint64)]
 
 
 class _SgdCfg(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_double), ("momentum", ctypes.c_double),
                 ("weight_decay", ctypes.c_double), ("loss_scale", ctypes.c_double),
-                ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32), ("res_bits", ctypes.c_int32)]
+                ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32), ("res_bits", ctypes.c_int32),
+                ("round", ctypes.c_int32), ("seed", ctypes.c_uint64)]
 
 
 def res_dtype(res_bits: int):
@@ -54,10 +60,13 @@ class AdamCfg:
     weight_fmt: int = BF16
     grad_fmt: int = BF16
     res_bits: int = 0
+    round: int = TRUNC
+    seed: int = 0
 
     def _c(self):
         return _AdamCfg(self.lr, self.beta1, self.beta2, self.eps, self.weight_decay,
-                        int(self.decoupled_wd), self.loss_scale, self.weight_fmt, self.grad_fmt, self.res_bits)
+                        int(self.decoupled_wd), self.loss_scale, self.weight_fmt, self.grad_fmt, self.res_bits,
+                        self.round, self.seed)
 
 
 @dataclass
@@ -69,10 +78,12 @@ class SgdCfg:
     weight_fmt: int = BF16
     grad_fmt: int = BF16
     res_bits: int = 0
+    round: int = TRUNC
+    seed: int = 0
 
     def _c(self):
         return _SgdCfg(self.lr, self.momentum, self.weight_decay, self.loss_scale,
-                       self.weight_fmt, self.grad_fmt, self.res_bits)
+                       self.weight_fmt, self.grad_fmt, self.res_bits, self.round, self.seed)
 
 
 def _chk(a, dtype, n=None):
@@ -98,43 +109,58 @@ def _p32(a):
 class Oracle:
     BF16 = BF16
     FP16 = FP16
+    TRUNC = TRUNC
+    NEAREST = NEAREST
+    STOCHASTIC = STOCHASTIC
     AdamCfg = AdamCfg
     SgdCfg = SgdCfg
 
     def __init__(self, path):
         lib = ctypes.CDLL(path)
-        lib.mpo_ref_split.argtypes = [_f32p, _u16p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int, ctypes.c_int]
+        lib.mpo_ref_split.argtypes = [_f32p, _u16p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int, ctypes.c_int,
+                                      ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32]
         lib.mpo_ref_split.restype = None
-        lib.mpo_ref_merge.argtypes = [_u16p, ctypes.c_void_p, _f32p, ctypes.c_uint64, ctypes.c_int, ctypes.c_int]
+        lib.mpo_ref_merge.argtypes = [_u16p, ctypes.c_void_p, _f32p, ctypes.c_uint64, ctypes.c_int, ctypes.c_int,
+                                      ctypes.c_int]
         lib.mpo_ref_merge.restype = None
         lib.mpo_ref_adam_step.argtypes = [_u16p, ctypes.c_void_p, _u16p, _f32p, _f32p, ctypes.c_uint64,
-                                          ctypes.POINTER(_AdamCfg), ctypes.c_uint64]
+                                          ctypes.POINTER(_AdamCfg), ctypes.c_uint64, ctypes.c_uint32]
         lib.mpo_ref_adam_step.restype = None
         lib.mpo_ref_sgd_step.argtypes = [_u16p, ctypes.c_void_p, _u16p, _f32p, ctypes.c_uint64,
-                                         ctypes.POINTER(_SgdCfg), ctypes.c_uint64]
+                                         ctypes.POINTER(_SgdCfg), ctypes.c_uint64, ctypes.c_uint32]
         lib.mpo_ref_sgd_step.restype = None
         lib.mpo_ref_cvt16.argtypes = [ctypes.c_uint16, ctypes.c_int]
         lib.mpo_ref_cvt16.restype = ctypes.c_float
+        lib.mpo_ref_philox4x32_10.argtypes = [ctypes.POINTER(ctypes.c_uint32)] * 3
+        lib.mpo_ref_philox4x32_10.restype = None
         self._lib = lib
 
-    def split(self, w32, fmt=BF16, res_bits=0):
+    def philox(self, counter, key):
+        """One Philox4x32-10 block."""
+        c = (ctypes.c_uint32 * 4)(*counter)
+        k = (ctypes.c_uint32 * 2)(*key)
+        o = (ctypes.c_uint32 * 4)()
+        self._lib.mpo_ref_philox4x32_10(c, k, o)
+        return list(o)
+
+    def split(self, w32, fmt=BF16, res_bits=0, round=TRUNC, seed=0, tensor_id=0):
         """fp32 array -> (hi uint16, res uint16 or uint8) arrays."""
         _chk(w32, np.float32)
         n = w32.shape[0]
         hi = np.empty(n, np.uint16)
         res = np.empty(n, res_dtype(res_bits))
-        self._lib.mpo_ref_split(_p32(w32), _p16(hi), _pv(res), n, fmt, res_bits)
+        self._lib.mpo_ref_split(_p32(w32), _p16(hi), _pv(res), n, fmt, res_bits, round, seed, tensor_id)
         return hi, res
 
-    def merge(self, hi, res, fmt=BF16, res_bits=0):
+    def merge(self, hi, res, fmt=BF16, res_bits=0, round=TRUNC):
         """(hi, res) arrays -> fp32 array."""
         n = _chk(hi, np.uint16).shape[0]
         _chk(res, res_dtype(res_bits), n)
         w32 = np.empty(n, np.float32)
-        self._lib.mpo_ref_merge(_p16(hi), _pv(res), _p32(w32), n, fmt, res_bits)
+        self._lib.mpo_ref_merge(_p16(hi), _pv(res), _p32(w32), n, fmt, res_bits, round)
         return w32
 
-    def adam_step(self, hi, res, grad, m, v, cfg: AdamCfg, step: int):
+    def adam_step(self, hi, res, grad, m, v, cfg: AdamCfg, step: int, tensor_id: int = 0):
         """One Adam step on one tensor, in place on hi, res, m, v."""
         n = _chk(hi, np.uint16).shape[0]
         _chk(res, res_dtype(cfg.res_bits), n)
@@ -145,9 +171,9 @@ class Oracle:
             raise ValueError("step counts from 1")
         c = cfg._c()
         self._lib.mpo_ref_adam_step(_p16(hi), _pv(res), _p16(grad), _p32(m), _p32(v), n,
-                                    ctypes.byref(c), step)
+                                    ctypes.byref(c), step, tensor_id)
 
-    def sgd_step(self, hi, res, grad, buf, cfg: SgdCfg, step: int):
+    def sgd_step(self, hi, res, grad, buf, cfg: SgdCfg, step: int, tensor_id: int = 0):
         """One SGD(-momentum) step on one tensor, in place on hi, res, buf."""
         n = _chk(hi, np.uint16).shape[0]
         _chk(res, res_dtype(cfg.res_bits), n)
@@ -158,7 +184,7 @@ class Oracle:
             raise ValueError("step counts from 1")
         c = cfg._c()
         bp = _p32(buf) if buf is not None else ctypes.cast(None, _f32p)
-        self._lib.mpo_ref_sgd_step(_p16(hi), _pv(res), _p16(grad), bp, n, ctypes.byref(c), step)
+        self._lib.mpo_ref_sgd_step(_p16(hi), _pv(res), _p16(grad), bp, n, ctypes.byref(c), step, tensor_id)
 
     def cvt16(self, x: int, fmt=BF16) -> float:
         """One 16-bit float pattern read as fp32."""
@@ -174,3 +200,4 @@ merge = _default.merge
 adam_step = _default.adam_step
 sgd_step = _default.sgd_step
 cvt16 = _default.cvt16
+philox = _default.philox

@@ -14,6 +14,7 @@ import pytest
 from oracle import build as obuild
 from oracle import ref as oref
 
+import test_oracle_rounding as tr
 import test_oracle_split as ts
 import test_oracle_steps as tp
 
@@ -40,6 +41,12 @@ PINS = [
     ts.pins_partial_bits_is_truncation,
     tp.pins_partial_bits_master_equivalence,
     tp.pins_partial_bits_torch_optim,
+    tr.pins_philox,
+    tr.pins_value_is_mode_independent,
+    tr.pins_nearest_matches_library_cast,
+    tr.pins_stochastic_statistics,
+    tr.pins_stochastic_stream,
+    tr.pins_trajectory_is_mode_independent,
 ]
 
 # (name, text in mpo_ref.c, what it is replaced with, occurrences expected)
@@ -76,16 +83,29 @@ MUTANTS = [
     ("fp16 subnormal scale", "ldexpf((float)((k << 13) | r), -37)", "ldexpf((float)((k << 13) | r), -36)", 1),
     ("fp16 no saturation", "if (e > 15) {", "if (e > 16) {", 1),
     ("fp16 sign lost in subnormal merge", "return s ? -mag : mag;", "return mag;", 1),
-    ("partial bits: kept bits left-aligned on load", "return (uint16_t)(stored << (full_bits(fmt) - E));",
-     "return (uint16_t)(stored << (16 - E));", 1),
-    ("partial bits: trailing bits kept instead of leading", "uint16_t kept = (uint16_t)(full >> (full_bits(fmt) - E));",
-     "uint16_t kept = (uint16_t)(full & ((1u << E) - 1u));", 1),
-    ("partial bits: byte slot boundary", "if (E <= 8) ((uint8_t *)res)[i] = (uint8_t)kept;",
-     "if (E < 8) ((uint8_t *)res)[i] = (uint8_t)kept;", 1),
-    ("partial bits: rounds up", "uint16_t kept = (uint16_t)(full >> (full_bits(fmt) - E));",
-     "uint16_t kept = (uint16_t)((full + (E < full_bits(fmt) ? (1u << (full_bits(fmt) - E - 1)) : 0u)) >> (full_bits(fmt) - E));", 1),
-    ("partial bits: fp16 uses the bf16 width", "static int full_bits(int fmt) { return fmt == MPO_REF_FP16 ? 13 : 16; }",
-     "static int full_bits(int fmt) { (void)fmt; return 16; }", 1),
+    ("partial bits: kept bits left-aligned on load", "uint16_t full = (uint16_t)(kept << (L->full - L->kept));",
+     "uint16_t full = (uint16_t)(kept << (16 - L->kept));", 1),
+    ("partial bits: trailing bits kept instead of leading", "uint16_t kept = (uint16_t)(res_full >> (L->full - L->kept));",
+     "uint16_t kept = (uint16_t)(res_full & ((1u << L->kept) - 1u));", 1),
+    ("partial bits: byte slot boundary", "L.byte_slot = res_bits >= 1 && res_bits <= 8;",
+     "L.byte_slot = res_bits >= 1 && res_bits < 8;", 1),
+    ("partial bits: rounds up", "uint16_t kept = (uint16_t)(res_full >> (L->full - L->kept));",
+     "uint16_t kept = (uint16_t)((res_full + (L->kept < L->full ? (1u << (L->full - L->kept - 1)) : 0u)) >> (L->full - L->kept));", 1),
+    ("partial bits: fp16 uses the bf16 width", "L.full = fmt == MPO_REF_FP16 ? 13 : 16;", "L.full = 16;", 1),
+    ("rounding: value not un-rounded", "*hi_trunc = (uint16_t)(hi[i] - was_rounded_up);", "*hi_trunc = hi[i];", 1),
+    ("rounding: probability inverted", "draw(L, i) < res_full;", "draw(L, i) >= res_full;", 1),
+    ("rounding: flag in the wrong bit", "kept = (uint16_t)(kept | (up << L->kept));", "kept = (uint16_t)(kept | (up << 15));", 1),
+    ("rounding: step not in the counter", "(uint32_t)(block >> 32), L->step32, L->tensor_id", "(uint32_t)(block >> 32), 0u, L->tensor_id", 1),
+    ("rounding: tensor not in the counter", "(uint32_t)(block >> 32), L->step32, L->tensor_id", "(uint32_t)(block >> 32), L->step32, 0u", 1),
+    ("rounding: one draw per block of four", "return out[i % 4] >> (32 - L->full);", "return out[0] >> (32 - L->full);", 1),
+    ("rounding: low bits of the draw", "return out[i % 4] >> (32 - L->full);", "return out[i % 4] & ((1u << L->full) - 1u);", 1),
+    ("rounding: nearest at a quarter", "if (L->round == MPO_REF_NEAREST) up = (res_full >> (L->full - 1)) & 1;",
+     "if (L->round == MPO_REF_NEAREST) up = (res_full >> (L->full - 2)) != 0;", 1),
+    ("rounding: stochastic may overflow", "(uint16_t)(hi_trunc & 0x7FFFu) < max_finite_hi(L->fmt) && draw(L, i) < res_full;",
+     "draw(L, i) < res_full;", 1),
+    ("rounding: philox multiplier", "(uint64_t)0xCD9E8D57u * c2", "(uint64_t)0xCD9E8D57u * c0", 1),
+    ("rounding: philox key schedule", "k1 += 0xBB67AE85u;", "k1 += 0x9E3779B9u;", 1),
+    ("rounding: philox nine rounds", "for (int round = 0; round < 10; ++round) {", "for (int round = 0; round < 9; ++round) {", 1),
 ]
 
 
