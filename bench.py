@@ -78,6 +78,8 @@ def main():
     ap.add_argument("--res-bits", type=int, default=0,
                     help="extra bits kept per weight: 0 = all (the headline), 8 = the paper's bf16+8 / fp16+8 "
                          "(byte residual, 24 B per parameter for Adam)")
+    ap.add_argument("--round", default="trunc", choices=["trunc", "nearest", "stochastic"],
+                    help="rounding of the 16-bit value: trunc is the method's base mode and the headline")
     ap.add_argument("--fresh-grads", action="store_true",
                     help="regenerate each layer's gradients inside the loop (adds generator kernels to the timing)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -101,7 +103,8 @@ def main():
     wl = synth.workload(a.workload)
     steps = a.steps if a.steps is not None else wl.steps
     t_setup = time.perf_counter()
-    st = harness.ModelState(wl, dev, res_bits=a.res_bits)
+    st = harness.ModelState(wl, dev, res_bits=a.res_bits,
+                            round={"trunc": 0, "nearest": 1, "stochastic": 2}[a.round])
     if wl.per_layer:
         # the reused buffer holds one (largest) layer's worth of gradient values, read by every layer
         st.grad.normal_(0.0, wl.grad_std * wl.loss_scale, generator=synth.generator(7, dev))
@@ -142,8 +145,9 @@ def main():
         "ms_per_step": wall * 1e3 / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: %s" % (wl.key, wl.description), "params": P, "tensors": len(wl.tensors),
-                   "format": "%s+%d extra bits (%d-bit residual)" % (wl.fmt, a.res_bits or (16 if wl.fmt == "bf16" else 13),
-                                                                      8 * st.res_bytes), "optimizer": wl.optimizer if a.optimizer == "adam" else "sgd-momentum", "loss_scale": wl.loss_scale,
+                   "format": "%s+%d extra bits (%d-bit residual)" % (wl.fmt, a.res_bits or (13 if wl.fmt == "fp16" else
+                                                                                        15 if a.round == "stochastic" else 16),
+                                                                      8 * st.res_bytes), "optimizer": wl.optimizer if a.optimizer == "adam" else "sgd-momentum", "round": a.round, "loss_scale": wl.loss_scale,
                    "launches_per_step": launches // steps, "per_layer": wl.per_layer,
                    "fresh_grads_in_loop": bool(a.fresh_grads), "resident_GB": st.resident_bytes / 1e9},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBPS, "unit": "GB/s",

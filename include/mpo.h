@@ -38,7 +38,7 @@ extern "C" {
 typedef enum {
     MPO_OK = 0,
     MPO_ERR_INVALID_ARG = 1, /* null pointer with n > 0, step == 0, unknown enum, bad size   */
-    MPO_ERR_UNSUPPORTED = 2, /* a mode that is declared but not built yet                    */
+    MPO_ERR_UNSUPPORTED = 2, /* a combination that is not built (mixed residual widths, ...)  */
     MPO_ERR_ALIAS = 3,       /* buffers that are written overlap each other or an input      */
     MPO_ERR_HIP = 4,         /* a HIP runtime call failed (see mpo_last_hip_error)           */
     MPO_ERR_NOMEM = 5        /* host or device allocation for a plan failed                  */
@@ -49,10 +49,26 @@ typedef enum {
  * top three bits are written as zero and ignored when read). */
 typedef enum { MPO_BF16 = 0, MPO_FP16 = 1 } mpo_fmt;
 
-/* How `hi` is derived from the fp32 value.  Section 3.1: keeping the leading
- * bits is a round-toward-zero (MPO_ROUND_TRUNC, the method's base mode).
- * NEAREST and STOCHASTIC (Section 3.1, last paragraph) are declared for later
- * and return MPO_ERR_UNSUPPORTED. */
+/* How `hi` is derived from the fp32 value (Section 3.1, last paragraph).
+ *   MPO_ROUND_TRUNC       hi = the leading bits, a round-toward-zero: the method's base mode.
+ *   MPO_ROUND_STOCHASTIC  hi is moved to the next 16-bit value away from zero with probability
+ *                         (dropped bits) / 2^full; one more bit, stored just above the kept
+ *                         residual bits, records it, and the step un-rounds hi before the
+ *                         update.  Never rounds out of the finite range.  When res_bits is 0,
+ *                         bf16 keeps 15 extra bits (15 + flag fill the 16-bit slot), fp16 13.
+ *                         At most 7 kept bits fit a byte slot and 15 a 16-bit slot, else
+ *                         MPO_ERR_INVALID_ARG.
+ *   MPO_ROUND_NEAREST     the deterministic counterpart: up when the dropped bits are at least
+ *                         half a unit (ties away from zero; like IEEE rounding a value within
+ *                         half a unit of overflow becomes infinity).  The leading dropped bit
+ *                         tells the step to undo it; nothing extra is stored.
+ * In every mode the fp32 value held by (hi, res), and therefore the whole fp32 trajectory of a
+ * training run, is the same as with MPO_ROUND_TRUNC; only the 16-bit value that forward and
+ * backward see differs.  The mode is a property of the stored data: use the same one in
+ * mpo_split, every step and mpo_merge.
+ * Random numbers: Philox4x32-10 (Salmon et al., SC'11), key = the 64-bit seed, counter =
+ * (i/4 low, i/4 high, low 32 bits of step, index of the tensor in its list); parameter i takes
+ * word i%4, its top `full` bits.  mpo_split draws with step 0. */
 typedef enum { MPO_ROUND_TRUNC = 0, MPO_ROUND_NEAREST = 1, MPO_ROUND_STOCHASTIC = 2 } mpo_round;
 
 typedef enum { MPO_OPT_ADAM = 0, MPO_OPT_SGD = 1 } mpo_opt;
@@ -77,11 +93,15 @@ typedef enum { MPO_OPT_ADAM = 0, MPO_OPT_SGD = 1 } mpo_opt;
  * at the largest finite pair, +-inf and NaN map to fp16 +-inf / NaN.
  * mpo_merge: the inverse, (hi[i], res[i]) -> w32[i] (cut bits read as zero).
  * w32 must not overlap hi or res (MPO_ERR_ALIAS); n is a number of elements.
+ * `seed` and `tensor_id` select the random stream (MPO_ROUND_STOCHASTIC only):
+ * give mpo_split the seed of the optimizer configuration and the index the
+ * tensor has in the list passed to mpo_plan_create.
  */
 mpo_status mpo_split(const float *w32, uint16_t *hi, void *res, uint64_t n,
-                     mpo_fmt fmt, int32_t res_bits, mpo_round round, void *hip_stream);
+                     mpo_fmt fmt, int32_t res_bits, mpo_round round, uint64_t seed, uint32_t tensor_id,
+                     void *hip_stream);
 mpo_status mpo_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n,
-                     mpo_fmt fmt, int32_t res_bits, void *hip_stream);
+                     mpo_fmt fmt, int32_t res_bits, mpo_round round, void *hip_stream);
 
 /* ---- parameter list -------------------------------------------------------
  *
@@ -121,6 +141,7 @@ typedef struct {
     int32_t weight_fmt; /* mpo_fmt of hi   */
     int32_t grad_fmt;   /* mpo_fmt of grad */
     int32_t round;      /* mpo_round       */
+    uint64_t seed;      /* random stream of MPO_ROUND_STOCHASTIC */
 } mpo_adam_cfg;
 
 /* SGD with momentum (dampening 0, no Nesterov), L2 weight decay.
@@ -129,6 +150,7 @@ typedef struct {
     double lr, momentum, weight_decay;
     double loss_scale;
     int32_t weight_fmt, grad_fmt, round;
+    uint64_t seed;
 } mpo_sgd_cfg;
 
 typedef struct mpo_plan mpo_plan;

@@ -42,20 +42,22 @@ class mpo_adam_cfg(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
                 ("eps", ctypes.c_double), ("weight_decay", ctypes.c_double),
                 ("decoupled_wd", ctypes.c_int32), ("loss_scale", ctypes.c_double),
-                ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32), ("round", ctypes.c_int32)]
+                ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32), ("round", ctypes.c_int32),
+                ("seed", ctypes.c_uint64)]
 
 
 class mpo_sgd_cfg(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_double), ("momentum", ctypes.c_double), ("weight_decay", ctypes.c_double),
                 ("loss_scale", ctypes.c_double),
-                ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32), ("round", ctypes.c_int32)]
+                ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32), ("round", ctypes.c_int32),
+                ("seed", ctypes.c_uint64)]
 
 
 EXPORTS = {
     "mpo_split": ([ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int,
-                   ctypes.c_int32, ctypes.c_int, ctypes.c_void_p], ctypes.c_int),
+                   ctypes.c_int32, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p], ctypes.c_int),
     "mpo_merge": ([ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int,
-                   ctypes.c_int32, ctypes.c_void_p], ctypes.c_int),
+                   ctypes.c_int32, ctypes.c_int, ctypes.c_void_p], ctypes.c_int),
     "mpo_plan_create": ([ctypes.POINTER(mpo_tensor), ctypes.c_uint64, ctypes.POINTER(ctypes.c_void_p)], ctypes.c_int),
     "mpo_plan_create_host": ([ctypes.POINTER(mpo_tensor), ctypes.c_uint64, ctypes.POINTER(ctypes.c_void_p)],
                              ctypes.c_int),
@@ -134,10 +136,11 @@ class AdamCfg:
     weight_fmt: int = MPO_BF16
     grad_fmt: int = MPO_BF16
     round: int = MPO_ROUND_TRUNC
+    seed: int = 0
 
     def c(self) -> mpo_adam_cfg:
         return mpo_adam_cfg(self.lr, self.beta1, self.beta2, self.eps, self.weight_decay, int(self.decoupled_wd),
-                            self.loss_scale, self.weight_fmt, self.grad_fmt, self.round)
+                            self.loss_scale, self.weight_fmt, self.grad_fmt, self.round, self.seed)
 
 
 @dataclass
@@ -149,19 +152,22 @@ class SgdCfg:
     weight_fmt: int = MPO_BF16
     grad_fmt: int = MPO_BF16
     round: int = MPO_ROUND_TRUNC
+    seed: int = 0
 
     def c(self) -> mpo_sgd_cfg:
         return mpo_sgd_cfg(self.lr, self.momentum, self.weight_decay, self.loss_scale, self.weight_fmt,
-                           self.grad_fmt, self.round)
+                           self.grad_fmt, self.round, self.seed)
 
 
 def mpo_split(w32, hi, res, n: int, fmt: int = MPO_BF16, res_bits: int = 0, round: int = MPO_ROUND_TRUNC,
+              seed: int = 0, tensor_id: int = 0, stream=None):
+    _check(lib.mpo_split(_ptr(w32), _ptr(hi), _ptr(res), n, fmt, res_bits, round, seed, tensor_id, _stream(stream)),
+           "mpo_split")
+
+
+def mpo_merge(hi, res, w32, n: int, fmt: int = MPO_BF16, res_bits: int = 0, round: int = MPO_ROUND_TRUNC,
               stream=None):
-    _check(lib.mpo_split(_ptr(w32), _ptr(hi), _ptr(res), n, fmt, res_bits, round, _stream(stream)), "mpo_split")
-
-
-def mpo_merge(hi, res, w32, n: int, fmt: int = MPO_BF16, res_bits: int = 0, stream=None):
-    _check(lib.mpo_merge(_ptr(hi), _ptr(res), _ptr(w32), n, fmt, res_bits, _stream(stream)), "mpo_merge")
+    _check(lib.mpo_merge(_ptr(hi), _ptr(res), _ptr(w32), n, fmt, res_bits, round, _stream(stream)), "mpo_merge")
 
 
 @dataclass

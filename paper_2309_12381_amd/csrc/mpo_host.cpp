@@ -28,12 +28,9 @@ mpo_status hip_fail(hipError_t e)
 
 bool valid_fmt(int f) { return f == MPO_BF16 || f == MPO_FP16; }
 
-/* MPO_OK for the mode that is built, UNSUPPORTED for the declared ones. */
 mpo_status check_round(int r)
 {
-    if (r == MPO_ROUND_TRUNC) return MPO_OK;
-    if (r == MPO_ROUND_NEAREST || r == MPO_ROUND_STOCHASTIC) return MPO_ERR_UNSUPPORTED;
-    return MPO_ERR_INVALID_ARG;
+    return (r == MPO_ROUND_TRUNC || r == MPO_ROUND_NEAREST || r == MPO_ROUND_STOCHASTIC) ? MPO_OK : MPO_ERR_INVALID_ARG;
 }
 
 constexpr uint64_t kMaxElems = 1ull << 48; /* keeps every byte count far from overflow */
@@ -48,8 +45,14 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 /* Section 3.1, partial extra bits: at most 8 kept bits live in a byte, more in 16 bits. */
 inline uint32_t res_slot_bytes(int res_bits) { return (res_bits >= 1 && res_bits <= 8) ? 1u : 2u; }
 
-/* 0 means all; otherwise 1..full for the format. */
-inline bool valid_res_bits(int res_bits, int fmt) { return res_bits >= 0 && res_bits <= full_res_bits(fmt); }
+/* 0 means all; otherwise 1..full for the format.  Stochastic rounding stores one flag above
+ * the kept bits: they must leave room for it in the slot. */
+inline bool valid_res_bits(int res_bits, int fmt, int round)
+{
+    if (res_bits < 0 || res_bits > full_res_bits(fmt)) return false;
+    if (round != MPO_ROUND_STOCHASTIC) return true;
+    return kept_res_bits(fmt, res_bits, round) + 1 <= 8 * (int)res_slot_bytes(res_bits);
+}
 
 /* True if some written range overlaps any other range.  Read-only ranges
  * (gradients) may overlap each other: one buffer reused for every layer. */
@@ -152,6 +155,7 @@ mpo_status build_plan(const mpo_tensor *tensors, uint64_t nt, mpo_plan **out)
             std::memset(&d, 0, sizeof d);
             d.hi = t.hi; d.res = t.res; d.grad = t.grad; d.m = t.m; d.v = t.v; d.n = t.n;
             d.res_bits = (uint32_t)t.res_bits;
+            d.tensor_id = (uint32_t)order[k];
             if (t.n && t.res_bits) {
                 p->any_explicit_bits = true;
                 p->max_res_bits = std::max(p->max_res_bits, (uint32_t)t.res_bits);
@@ -217,6 +221,10 @@ mpo_status adam_scalars(const mpo_adam_cfg *c, uint64_t step, StepLaunch &L)
     s.DEC = (float)(1.0 - c->lr * c->weight_decay);
     s.WD = (float)c->weight_decay;
     s.IS = (float)(1.0 / c->loss_scale);
+    s.round = (uint32_t)c->round;
+    s.seed_lo = (uint32_t)c->seed;
+    s.seed_hi = (uint32_t)(c->seed >> 32);
+    s.step32 = (uint32_t)step;
     L.opt = MPO_OPT_ADAM;
     L.wfmt = c->weight_fmt;
     L.gfmt = c->grad_fmt;
@@ -239,6 +247,10 @@ mpo_status sgd_scalars(const mpo_sgd_cfg *c, uint64_t step, StepLaunch &L)
     s.MU = (float)c->momentum;
     s.WD = (float)c->weight_decay;
     s.IS = (float)(1.0 / c->loss_scale);
+    s.round = (uint32_t)c->round;
+    s.seed_lo = (uint32_t)c->seed;
+    s.seed_hi = (uint32_t)(c->seed >> 32);
+    s.step32 = (uint32_t)step;
     L.opt = MPO_OPT_SGD;
     L.wfmt = c->weight_fmt;
     L.gfmt = c->grad_fmt;
@@ -265,6 +277,7 @@ bool state_present(const mpo_plan *p, uint64_t k0, uint64_t nk, const StepLaunch
 mpo_status run(mpo_plan *p, StepLaunch &L, void *stream)
 {
     if ((int)p->max_res_bits > full_res_bits(L.wfmt)) return MPO_ERR_INVALID_ARG;
+    if (L.s.round == MPO_ROUND_STOCHASTIC && p->max_res_bits > (p->res_slot == 1 ? 7u : 15u)) return MPO_ERR_INVALID_ARG;
     L.rmode = p->res_slot == 1 ? kResByte : (p->any_explicit_bits ? kResPartial : kResFull);
     L.descs = p->d_descs;
     L.chunks = p->d_chunks;
@@ -288,11 +301,10 @@ mpo_status step_all(mpo_plan *p, StepLaunch &L, void *stream)
 extern "C" {
 
 mpo_status mpo_split(const float *w32, uint16_t *hi, void *res, uint64_t n, mpo_fmt fmt, int32_t res_bits,
-                     mpo_round round, void *hip_stream)
+                     mpo_round round, uint64_t seed, uint32_t tensor_id, void *hip_stream)
 {
-    if (!valid_fmt(fmt) || !valid_res_bits(res_bits, fmt)) return MPO_ERR_INVALID_ARG;
-    const mpo_status rs = check_round(round);
-    if (rs != MPO_OK) return rs;
+    if (!valid_fmt(fmt) || check_round(round) != MPO_OK) return MPO_ERR_INVALID_ARG;
+    if (!valid_res_bits(res_bits, fmt, round)) return MPO_ERR_INVALID_ARG;
     if (n > kMaxElems) return MPO_ERR_INVALID_ARG;
     if (n == 0) return MPO_OK;
     if (!w32 || !hi || !res) return MPO_ERR_INVALID_ARG;
@@ -302,14 +314,16 @@ mpo_status mpo_split(const float *w32, uint16_t *hi, void *res, uint64_t n, mpo_
     r.push_back(Range{b, b + n * 2, true});
     r.push_back(Range{c, c + n * res_slot_bytes(res_bits), true});
     if (has_conflict(r)) return MPO_ERR_ALIAS;
-    const hipError_t e = launch_split(w32, hi, res, n, fmt, res_bits, static_cast<hipStream_t>(hip_stream));
+    const hipError_t e = launch_split(w32, hi, res, n, fmt, res_bits, round, seed, tensor_id,
+                                      static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MPO_OK : hip_fail(e);
 }
 
 mpo_status mpo_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, mpo_fmt fmt, int32_t res_bits,
-                     void *hip_stream)
+                     mpo_round round, void *hip_stream)
 {
-    if (!valid_fmt(fmt) || !valid_res_bits(res_bits, fmt)) return MPO_ERR_INVALID_ARG;
+    if (!valid_fmt(fmt) || check_round(round) != MPO_OK) return MPO_ERR_INVALID_ARG;
+    if (!valid_res_bits(res_bits, fmt, round)) return MPO_ERR_INVALID_ARG;
     if (n > kMaxElems) return MPO_ERR_INVALID_ARG;
     if (n == 0) return MPO_OK;
     if (!w32 || !hi || !res) return MPO_ERR_INVALID_ARG;
@@ -319,7 +333,7 @@ mpo_status mpo_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n
     r.push_back(Range{b, b + n * 2, false});
     r.push_back(Range{c, c + n * res_slot_bytes(res_bits), false});
     if (has_conflict(r)) return MPO_ERR_ALIAS;
-    const hipError_t e = launch_merge(hi, res, w32, n, fmt, res_bits, static_cast<hipStream_t>(hip_stream));
+    const hipError_t e = launch_merge(hi, res, w32, n, fmt, res_bits, round, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MPO_OK : hip_fail(e);
 }
 

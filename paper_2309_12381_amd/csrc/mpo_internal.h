@@ -27,8 +27,10 @@ struct TensorDesc {
     uint64_t n;
     uint32_t flags;
     uint32_t res_bits;   /* extra bits kept, 0 = all (Section 3.1) */
+    uint32_t tensor_id;  /* index in the caller's list: selects the random stream */
+    uint32_t pad;
 };
-static_assert(sizeof(TensorDesc) == 56, "descriptor layout is read by the kernels");
+static_assert(sizeof(TensorDesc) == 64, "descriptor layout is read by the kernels");
 
 /* Chunk table entry: which tensor (index into the plan's layer-ordered
  * descriptor array) and which chunk of it. */
@@ -44,6 +46,9 @@ struct StepScalars {
     float SS, SQ, EPS;    /* lr/(1-beta1^t), sqrt(1-beta2^t), eps                */
     float DEC, WD, IS;    /* 1-lr*wd, wd, 1/loss_scale                           */
     float LR, MU;         /* SGD learning rate and momentum                      */
+    /* rounding of the 16-bit value (Section 3.1, last paragraph) */
+    uint32_t round;       /* mpo_round                                           */
+    uint32_t seed_lo, seed_hi, step32;
 };
 
 /* Per-call gradient pointers for one layer (Section 3.2), passed by value. */
@@ -81,10 +86,18 @@ struct StepLaunch {
 };
 
 hipError_t launch_step(const StepLaunch &L);
-hipError_t launch_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits,
+hipError_t launch_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits, int round,
+                        uint64_t seed, uint32_t tensor_id, hipStream_t stream);
+hipError_t launch_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits, int round,
                         hipStream_t stream);
-hipError_t launch_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits,
-                        hipStream_t stream);
+
+/* Extra bits actually stored: an explicit count, else all of them; stochastic rounding of
+ * bf16 keeps 15 so that the flag fits the 16-bit slot. */
+inline int kept_res_bits(int fmt, int res_bits, int round)
+{
+    if (res_bits) return res_bits;
+    return (round == MPO_ROUND_STOCHASTIC && fmt == MPO_BF16) ? 15 : full_res_bits(fmt);
+}
 
 } // namespace mpo
 #endif

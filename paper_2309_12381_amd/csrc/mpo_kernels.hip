@@ -278,6 +278,79 @@ template <> struct ResElem<kResByte> { typedef uint8_t T; };
 
 template <int WFMT> struct FullBits { static constexpr uint32_t value = (WFMT == MPO_FP16) ? 13u : 16u; };
 
+/* ---- rounding of the 16-bit value (Section 3.1, last paragraph) -------------
+ * Philox4x32-10 (Salmon et al., SC'11): counter-based, so every lane computes
+ * the four words of its own four parameters and nothing is stored. */
+struct Rng {
+    uint32_t seed_lo, seed_hi, step32, tensor_id;
+};
+
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                              uint32_t k1, uint32_t (&out)[4])
+{
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        if (round > 0) {
+            k0 += 0x9E3779B9u;
+            k1 += 0xBB67AE85u;
+        }
+        const uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
+        const uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
+        const uint32_t n0 = h1 ^ c1 ^ k0, n2 = h0 ^ c3 ^ k1;
+        c0 = n0; c1 = l1; c2 = n2; c3 = l0;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The four draws of parameters 4*block .. 4*block+3 of a tensor, each in [0, 2^FULL). */
+template <uint32_t FULL>
+__device__ __forceinline__ void draw4(const Rng &g, uint64_t block, uint32_t (&u)[4])
+{
+    philox4x32_10((uint32_t)block, (uint32_t)(block >> 32), g.step32, g.tensor_id, g.seed_lo, g.seed_hi, u);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) u[j] >>= (32u - FULL);
+}
+
+/* What a stored (hi, slot) pair means: the truncated 16-bit value and the full residual. */
+template <int WFMT>
+__device__ __forceinline__ void unround(uint32_t &hi, uint32_t slot, uint32_t &res_full, uint32_t kept, uint32_t sh,
+                                        uint32_t round)
+{
+    constexpr uint32_t FULL = FullBits<WFMT>::value;
+    res_full = (slot & ((1u << kept) - 1u)) << sh;
+    const uint32_t flag = (round == MPO_ROUND_STOCHASTIC) ? ((slot >> kept) & 1u)
+                        : (round == MPO_ROUND_NEAREST)    ? ((res_full >> (FULL - 1u)) & 1u) : 0u;
+    hi = (hi - flag) & 0xFFFFu;
+}
+
+/* The reverse: round the truncated value and build the slot.  `u` is this parameter's draw. */
+template <int WFMT>
+__device__ __forceinline__ uint32_t reround(uint32_t &hi, uint32_t res_full, uint32_t kept, uint32_t sh, uint32_t round,
+                                            uint32_t u)
+{
+    constexpr uint32_t FULL = FullBits<WFMT>::value;
+    constexpr uint32_t MAXFIN = (WFMT == MPO_FP16) ? 0x7BFFu : 0x7F7Fu;
+    uint32_t up = 0u;
+    if (round == MPO_ROUND_NEAREST) up = (res_full >> (FULL - 1u)) & 1u;
+    if (round == MPO_ROUND_STOCHASTIC) up = ((hi & 0x7FFFu) < MAXFIN && u < res_full) ? 1u : 0u;
+    hi = (hi + up) & 0xFFFFu;
+    uint32_t slot = res_full >> sh;
+    if (round == MPO_ROUND_STOCHASTIC) slot |= up << kept;
+    return slot;
+}
+
+/* raw slot k of a row as it sits in registers / memory */
+template <int RMODE> __device__ __forceinline__ uint32_t slot_get(const uint32_t *r, int k)
+{
+    if (RMODE == kResByte) return (r[k / 4] >> (8 * (k % 4))) & 0xFFu;
+    return (k & 1) ? (r[k / 2] >> 16) : (r[k / 2] & 0xFFFFu);
+}
+template <int RMODE> __device__ __forceinline__ void slot_put(uint32_t *r, int k, uint32_t slot)
+{
+    if (RMODE == kResByte) r[k / 4] |= (slot & 0xFFu) << (8 * (k % 4));
+    else r[k / 2] |= (slot & 0xFFFFu) << (16 * (k & 1));
+}
+
 template <int OPT, bool MOM> struct Uses {
     static constexpr bool m = (OPT == MPO_OPT_ADAM) || MOM;
     static constexpr bool v = (OPT == MPO_OPT_ADAM);
@@ -307,6 +380,37 @@ __device__ __forceinline__ void load_row(Row &x, gcu16p hi, const MPO_GLOBAL voi
     load16(grad + e, x.g);
     if (Uses<OPT, MOM>::m) load32(m + e, x.m);
     if (Uses<OPT, MOM>::v) load32(v + e, x.v);
+}
+
+/* The same with the 16-bit value rounded to nearest or stochastically: un-round, update,
+ * round again with this step's draws.  `first` is the tensor-relative index of the row's
+ * first parameter (a multiple of 4). */
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE>
+__device__ __forceinline__ void compute_row_rounded(Row &x, const StepScalars &s, uint32_t kept, uint32_t sh,
+                                                    const Rng &g, uint64_t first)
+{
+    uint32_t rin[EPL / 2];
+#pragma unroll
+    for (int j = 0; j < EPL / 2; ++j) { rin[j] = x.r[j]; x.r[j] = 0u; }
+#pragma unroll
+    for (int q = 0; q < EPL / 4; ++q) {
+        uint32_t u[4] = {0u, 0u, 0u, 0u};
+        if (s.round == MPO_ROUND_STOCHASTIC) draw4<FullBits<WFMT>::value>(g, first / 4 + q, u);
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const int j = 2 * q + jj;
+            uint32_t h0 = x.h[j] & 0xFFFFu, h1 = x.h[j] >> 16, r0, r1;
+            unround<WFMT>(h0, slot_get<RMODE>(rin, 2 * j), r0, kept, sh, s.round);
+            unround<WFMT>(h1, slot_get<RMODE>(rin, 2 * j + 1), r1, kept, sh, s.round);
+            step_one<OPT, WFMT, GFMT, DECAY, MOM>(h0, r0, x.g[j] & 0xFFFFu, x.m[2 * j], x.v[2 * j], s);
+            step_one<OPT, WFMT, GFMT, DECAY, MOM>(h1, r1, x.g[j] >> 16, x.m[2 * j + 1], x.v[2 * j + 1], s);
+            const uint32_t s0 = reround<WFMT>(h0, r0, kept, sh, s.round, u[2 * jj]);
+            const uint32_t s1 = reround<WFMT>(h1, r1, kept, sh, s.round, u[2 * jj + 1]);
+            x.h[j] = h0 | (h1 << 16);
+            slot_put<RMODE>(x.r, 2 * j, s0);
+            slot_put<RMODE>(x.r, 2 * j + 1, s1);
+        }
+    }
 }
 
 template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE>
@@ -354,6 +458,26 @@ __device__ __forceinline__ void step_scalar(gu16p hi, MPO_GLOBAL void *res_, gcu
 }
 
 template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE>
+__device__ __forceinline__ void step_scalar_rounded(gu16p hi, MPO_GLOBAL void *res_, gcu16p grad, gf32p m, gf32p v,
+                                                    uint32_t e, const StepScalars &s, uint32_t kept, uint32_t sh,
+                                                    const Rng &g, uint64_t index)
+{
+    MPO_GLOBAL typename ResElem<RMODE>::T *res = static_cast<MPO_GLOBAL typename ResElem<RMODE>::T *>(res_);
+    uint32_t h = hi[e], r;
+    unround<WFMT>(h, (uint32_t)res[e], r, kept, sh, s.round);
+    float mm = Uses<OPT, MOM>::m ? m[e] : 0.0f;
+    float vv = Uses<OPT, MOM>::v ? v[e] : 0.0f;
+    step_one<OPT, WFMT, GFMT, DECAY, MOM>(h, r, grad[e], mm, vv, s);
+    uint32_t u[4] = {0u, 0u, 0u, 0u};
+    if (s.round == MPO_ROUND_STOCHASTIC) draw4<FullBits<WFMT>::value>(g, index / 4, u);
+    const uint32_t slot = reround<WFMT>(h, r, kept, sh, s.round, u[index % 4]);
+    hi[e] = (uint16_t)h;
+    res[e] = (typename ResElem<RMODE>::T)slot;
+    if (Uses<OPT, MOM>::m) m[e] = mm;
+    if (Uses<OPT, MOM>::v) v[e] = vv;
+}
+
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE, bool RND>
 __global__ void __launch_bounds__(kBlock)
 step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chunks, uint64_t first_chunk,
             StepScalars s, GradOverride ov)
@@ -373,8 +497,10 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
     const uint32_t len = left < kChunkElems ? (uint32_t)left : kChunkElems;
 
     /* cut bits of this tensor's residual (uniform); a full residual has none */
-    const uint32_t kept = d.res_bits ? d.res_bits : FullBits<WFMT>::value;
-    const uint32_t sh = RMODE == kResFull ? 0u : FullBits<WFMT>::value - kept;
+    const uint32_t all = (RND && s.round == MPO_ROUND_STOCHASTIC && WFMT == MPO_BF16) ? 15u : FullBits<WFMT>::value;
+    const uint32_t kept = d.res_bits ? d.res_bits : all;
+    const uint32_t sh = (RMODE == kResFull && !RND) ? 0u : FullBits<WFMT>::value - kept;
+    const Rng rng = {s.seed_lo, s.seed_hi, s.step32, d.tensor_id};
     gu16p hi = (gu16p)(d.hi + off);
     MPO_GLOBAL void *res = (MPO_GLOBAL void *)(static_cast<char *>(d.res) + off * sizeof(typename ResElem<RMODE>::T));
     gcu16p grad = (gcu16p)(gbase + off);
@@ -392,7 +518,8 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
                 load_row<OPT, MOM, RMODE>(x[b], hi, res, grad, m, v, row_elem(r0 + b, t));
 #pragma unroll
             for (int b = 0; b < BATCH; ++b) {
-                compute_row<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(x[b], s, sh);
+                if (RND) compute_row_rounded<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(x[b], s, kept, sh, rng, off + row_elem(r0 + b, t));
+                else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(x[b], s, sh);
                 store_row<OPT, MOM, RMODE>(x[b], hi, res, m, v, row_elem(r0 + b, t));
             }
         }
@@ -404,25 +531,46 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
             if (e + EPL <= len) {
                 Row x;
                 load_row<OPT, MOM, RMODE>(x, hi, res, grad, m, v, e);
-                compute_row<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(x, s, sh);
+                if (RND) compute_row_rounded<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(x, s, kept, sh, rng, off + e);
+                else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(x, s, sh);
                 store_row<OPT, MOM, RMODE>(x, hi, res, m, v, e);
             } else if (e < len) {
-                for (uint32_t i = e; i < len; ++i)
-                    step_scalar<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(hi, res, grad, m, v, i, s, sh);
+                for (uint32_t i = e; i < len; ++i) {
+                    if (RND) step_scalar_rounded<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(hi, res, grad, m, v, i, s, kept, sh, rng, off + i);
+                    else step_scalar<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(hi, res, grad, m, v, i, s, sh);
+                }
             }
         }
     } else {
-        for (uint32_t i = t; i < len; i += kBlock)
-            step_scalar<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(hi, res, grad, m, v, i, s, sh);
+        for (uint32_t i = t; i < len; i += kBlock) {
+            if (RND) step_scalar_rounded<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(hi, res, grad, m, v, i, s, kept, sh, rng, off + i);
+            else step_scalar<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(hi, res, grad, m, v, i, s, sh);
+        }
     }
 }
 
-/* ---- split / merge: 8 B per parameter (7 B with byte residuals) ------------ */
+/* ---- split / merge: 8 B per parameter (7 B with byte residuals) ------------
+ * RND: the 16-bit value is rounded to nearest or stochastically (split) and
+ * un-rounded (merge); `rs` carries mode, seed and tensor id, step32 is 0. */
 
-template <int FMT, int RMODE>
+struct RoundArgs {
+    uint32_t round, seed_lo, seed_hi, tensor_id;
+};
+
+template <int FMT, int RMODE, bool RND>
+__device__ __forceinline__ void split_store_one(float w, uint32_t &h, uint32_t &slot, uint32_t kept, uint32_t sh,
+                                                const RoundArgs &rs, uint32_t u)
+{
+    uint32_t r;
+    split32<FMT>(w, h, r);
+    if (RND) slot = reround<FMT>(h, r, kept, sh, rs.round, u);
+    else slot = r >> sh;
+}
+
+template <int FMT, int RMODE, bool RND>
 __global__ void __launch_bounds__(kBlock)
 split_kernel(const float *__restrict__ w32_, uint16_t *__restrict__ hi_, void *__restrict__ res_, uint64_t n,
-             int aligned, uint32_t sh)
+             uint64_t first, int aligned, uint32_t kept, uint32_t sh, RoundArgs rs)
 {
     typedef typename ResElem<RMODE>::T R;
     const uint64_t off = (uint64_t)blockIdx.x * kChunkElems;
@@ -431,14 +579,19 @@ split_kernel(const float *__restrict__ w32_, uint16_t *__restrict__ hi_, void *_
     gcf32p w32 = (gcf32p)(w32_ + off);
     gu16p hi = (gu16p)(hi_ + off);
     MPO_GLOBAL R *res = (MPO_GLOBAL R *)(static_cast<R *>(res_) + off);
+    const Rng rng = {rs.seed_lo, rs.seed_hi, 0u, rs.tensor_id};
+    const uint64_t base = first + off;           /* tensor-relative index of this chunk's first parameter */
     const uint32_t t = threadIdx.x;
+    auto one = [&](uint32_t i) {
+        uint32_t u[4] = {0u, 0u, 0u, 0u};
+        if (RND && rs.round == MPO_ROUND_STOCHASTIC) draw4<FullBits<FMT>::value>(rng, (base + i) / 4, u);
+        uint32_t h, slot;
+        split_store_one<FMT, RMODE, RND>(w32[i], h, slot, kept, sh, rs, u[(base + i) % 4]);
+        hi[i] = (uint16_t)h;
+        res[i] = (R)slot;
+    };
     if (!aligned) {
-        for (uint32_t i = t; i < len; i += kBlock) {
-            uint32_t h, r;
-            split32<FMT>(w32[i], h, r);
-            hi[i] = (uint16_t)h;
-            res[i] = (R)(r >> sh);
-        }
+        for (uint32_t i = t; i < len; i += kBlock) one(i);
         return;
     }
 #pragma unroll
@@ -451,31 +604,41 @@ split_kernel(const float *__restrict__ w32_, uint16_t *__restrict__ hi_, void *_
 #pragma unroll
             for (int j = 0; j < EPL / 2; ++j) q[j] = 0u;
 #pragma unroll
-            for (int j = 0; j < EPL / 2; ++j) {
-                uint32_t h0, r0, h1, r1;
-                split32<FMT>(w[2 * j], h0, r0);
-                split32<FMT>(w[2 * j + 1], h1, r1);
-                h[j] = h0 | (h1 << 16);
-                res_put<RMODE>(q, 2 * j, r0, sh);
-                res_put<RMODE>(q, 2 * j + 1, r1, sh);
+            for (int g4 = 0; g4 < EPL / 4; ++g4) {
+                uint32_t u[4] = {0u, 0u, 0u, 0u};
+                if (RND && rs.round == MPO_ROUND_STOCHASTIC) draw4<FullBits<FMT>::value>(rng, (base + e) / 4 + g4, u);
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    const int j = 2 * g4 + jj;
+                    uint32_t h0, s0, h1, s1;
+                    split_store_one<FMT, RMODE, RND>(w[2 * j], h0, s0, kept, sh, rs, u[2 * jj]);
+                    split_store_one<FMT, RMODE, RND>(w[2 * j + 1], h1, s1, kept, sh, rs, u[2 * jj + 1]);
+                    h[j] = h0 | (h1 << 16);
+                    slot_put<RMODE>(q, 2 * j, s0);
+                    slot_put<RMODE>(q, 2 * j + 1, s1);
+                }
             }
             store16(hi + e, h);
             if (RMODE == kResByte) store8((gu8p)res + e, q); else store16((gu16p)res + e, q);
         } else if (e < len) {
-            for (uint32_t i = e; i < len; ++i) {
-                uint32_t h, q;
-                split32<FMT>(w32[i], h, q);
-                hi[i] = (uint16_t)h;
-                res[i] = (R)(q >> sh);
-            }
+            for (uint32_t i = e; i < len; ++i) one(i);
         }
     }
 }
 
-template <int FMT, int RMODE>
+template <int FMT, int RMODE, bool RND>
+__device__ __forceinline__ float merge_load_one(uint32_t h, uint32_t slot, uint32_t kept, uint32_t sh, uint32_t round)
+{
+    uint32_t r;
+    if (RND) unround<FMT>(h, slot, r, kept, sh, round);
+    else r = slot << sh;
+    return merge16<FMT>(h, r);
+}
+
+template <int FMT, int RMODE, bool RND>
 __global__ void __launch_bounds__(kBlock)
 merge_kernel(const uint16_t *__restrict__ hi_, const void *__restrict__ res_, float *__restrict__ w32_, uint64_t n,
-             int aligned, uint32_t sh)
+             int aligned, uint32_t kept, uint32_t sh, uint32_t round)
 {
     typedef typename ResElem<RMODE>::T R;
     const uint64_t off = (uint64_t)blockIdx.x * kChunkElems;
@@ -486,7 +649,8 @@ merge_kernel(const uint16_t *__restrict__ hi_, const void *__restrict__ res_, fl
     const MPO_GLOBAL R *res = (const MPO_GLOBAL R *)(static_cast<const R *>(res_) + off);
     const uint32_t t = threadIdx.x;
     if (!aligned) {
-        for (uint32_t i = t; i < len; i += kBlock) w32[i] = merge16<FMT>(hi[i], (uint32_t)res[i] << sh);
+        for (uint32_t i = t; i < len; i += kBlock)
+            w32[i] = merge_load_one<FMT, RMODE, RND>(hi[i], (uint32_t)res[i], kept, sh, round);
         return;
     }
 #pragma unroll
@@ -499,12 +663,13 @@ merge_kernel(const uint16_t *__restrict__ hi_, const void *__restrict__ res_, fl
             if (RMODE == kResByte) load8((gcu8p)res + e, q); else load16((gcu16p)res + e, q);
 #pragma unroll
             for (int j = 0; j < EPL / 2; ++j) {
-                w[2 * j] = merge16<FMT>(h[j] & 0xFFFFu, res_get<RMODE>(q, 2 * j, sh));
-                w[2 * j + 1] = merge16<FMT>(h[j] >> 16, res_get<RMODE>(q, 2 * j + 1, sh));
+                w[2 * j] = merge_load_one<FMT, RMODE, RND>(h[j] & 0xFFFFu, slot_get<RMODE>(q, 2 * j), kept, sh, round);
+                w[2 * j + 1] = merge_load_one<FMT, RMODE, RND>(h[j] >> 16, slot_get<RMODE>(q, 2 * j + 1), kept, sh, round);
             }
             store32(w32 + e, w);
         } else if (e < len) {
-            for (uint32_t i = e; i < len; ++i) w32[i] = merge16<FMT>(hi[i], (uint32_t)res[i] << sh);
+            for (uint32_t i = e; i < len; ++i)
+                w32[i] = merge_load_one<FMT, RMODE, RND>(hi[i], (uint32_t)res[i], kept, sh, round);
         }
     }
 }
@@ -512,13 +677,13 @@ merge_kernel(const uint16_t *__restrict__ hi_, const void *__restrict__ res_, fl
 /* Grids are limited to 2^31-1 workgroups: longer lists go out in slices. */
 constexpr uint64_t kMaxGrid = 0x7FFFFFFFull;
 
-template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE>
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE, bool RND>
 hipError_t launch_step_t(const StepLaunch &L)
 {
     uint64_t done = 0;
     while (done < L.num_chunks) {
         const uint64_t now = (L.num_chunks - done < kMaxGrid) ? (L.num_chunks - done) : kMaxGrid;
-        step_kernel<OPT, WFMT, GFMT, DECAY, MOM, RMODE><<<dim3((uint32_t)now), dim3(kBlock), 0, L.stream>>>(
+        step_kernel<OPT, WFMT, GFMT, DECAY, MOM, RMODE, RND><<<dim3((uint32_t)now), dim3(kBlock), 0, L.stream>>>(
             L.descs, L.chunks, L.first_chunk + done, L.s, L.ov);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -530,10 +695,15 @@ hipError_t launch_step_t(const StepLaunch &L)
 template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM>
 hipError_t launch_step_res(const StepLaunch &L)
 {
+    if (L.s.round != MPO_ROUND_TRUNC) {
+        /* rounded modes always go through the general residual path */
+        return L.rmode == kResByte ? launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResByte, true>(L)
+                                   : launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResPartial, true>(L);
+    }
     switch (L.rmode) {
-    case kResFull: return launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResFull>(L);
-    case kResPartial: return launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResPartial>(L);
-    default: return launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResByte>(L);
+    case kResFull: return launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResFull, false>(L);
+    case kResPartial: return launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResPartial, false>(L);
+    default: return launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResByte, false>(L);
     }
 }
 
@@ -547,17 +717,29 @@ hipError_t launch_step_fmt(const StepLaunch &L)
                               : launch_step_res<OPT, MPO_FP16, MPO_FP16, DECAY, MOM>(L);
 }
 
-template <int FMT, int RMODE>
-hipError_t launch_split_t(const float *w32, uint16_t *hi, void *res, uint64_t n, uint32_t sh, int al, hipStream_t stream)
+struct SplitMergeArgs {
+    const float *w32_in;
+    float *w32_out;
+    uint16_t *hi;
+    void *res;
+    uint64_t n;
+    int al;
+    uint32_t kept, sh;
+    RoundArgs rs;
+    hipStream_t stream;
+};
+
+template <int FMT, int RMODE, bool RND>
+hipError_t launch_split_t(const SplitMergeArgs &a)
 {
     typedef typename ResElem<RMODE>::T R;
     uint64_t done = 0;
-    const uint64_t blocks = (n + kChunkElems - 1) / kChunkElems;
+    const uint64_t blocks = (a.n + kChunkElems - 1) / kChunkElems;
     while (done < blocks) {
         const uint64_t now = (blocks - done < kMaxGrid) ? (blocks - done) : kMaxGrid;
         const uint64_t e0 = done * kChunkElems;
-        split_kernel<FMT, RMODE><<<dim3((uint32_t)now), dim3(kBlock), 0, stream>>>(w32 + e0, hi + e0,
-                                                                                 static_cast<R *>(res) + e0, n - e0, al, sh);
+        split_kernel<FMT, RMODE, RND><<<dim3((uint32_t)now), dim3(kBlock), 0, a.stream>>>(
+            a.w32_in + e0, a.hi + e0, static_cast<R *>(a.res) + e0, a.n - e0, e0, a.al, a.kept, a.sh, a.rs);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         done += now;
@@ -565,34 +747,47 @@ hipError_t launch_split_t(const float *w32, uint16_t *hi, void *res, uint64_t n,
     return hipSuccess;
 }
 
-template <int FMT, int RMODE>
-hipError_t launch_merge_t(const uint16_t *hi, const void *res, float *w32, uint64_t n, uint32_t sh, int al,
-                          hipStream_t stream)
+template <int FMT, int RMODE, bool RND>
+hipError_t launch_merge_t(const SplitMergeArgs &a)
 {
     typedef typename ResElem<RMODE>::T R;
     uint64_t done = 0;
-    const uint64_t blocks = (n + kChunkElems - 1) / kChunkElems;
+    const uint64_t blocks = (a.n + kChunkElems - 1) / kChunkElems;
     while (done < blocks) {
         const uint64_t now = (blocks - done < kMaxGrid) ? (blocks - done) : kMaxGrid;
         const uint64_t e0 = done * kChunkElems;
-        merge_kernel<FMT, RMODE><<<dim3((uint32_t)now), dim3(kBlock), 0, stream>>>(hi + e0, static_cast<const R *>(res) + e0,
-                                                                                 w32 + e0, n - e0, al, sh);
+        merge_kernel<FMT, RMODE, RND><<<dim3((uint32_t)now), dim3(kBlock), 0, a.stream>>>(
+            a.hi + e0, static_cast<const R *>(a.res) + e0, a.w32_out + e0, a.n - e0, a.al, a.kept, a.sh, a.rs.round);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         done += now;
     }
     return hipSuccess;
+}
+
+template <int FMT, bool SPLIT>
+hipError_t launch_sm(const SplitMergeArgs &a, int rmode)
+{
+    const bool rnd = a.rs.round != MPO_ROUND_TRUNC;
+    if (rnd && rmode == kResFull) rmode = kResPartial;     /* rounded modes: general residual path */
+#define MPO_SM(RM, RN) (SPLIT ? launch_split_t<FMT, RM, RN>(a) : launch_merge_t<FMT, RM, RN>(a))
+    if (rnd) return rmode == kResByte ? MPO_SM(kResByte, true) : MPO_SM(kResPartial, true);
+    if (rmode == kResByte) return MPO_SM(kResByte, false);
+    if (rmode == kResPartial) return MPO_SM(kResPartial, false);
+    return MPO_SM(kResFull, false);
+#undef MPO_SM
 }
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-/* Storage mode and number of cut bits for a single-tensor call. */
-inline void res_layout(int fmt, int res_bits, int &rmode, uint32_t &sh)
+/* Storage mode, kept bits and number of cut bits for a single-tensor call. */
+inline void res_layout(int fmt, int res_bits, int round, int &rmode, uint32_t &kept, uint32_t &sh)
 {
     const int full = full_res_bits(fmt);
-    const int kept = res_bits ? res_bits : full;
-    sh = (uint32_t)(full - kept);
-    rmode = (res_bits >= 1 && res_bits <= 8) ? kResByte : (kept == full ? kResFull : kResPartial);
+    const int k = kept_res_bits(fmt, res_bits, round);
+    kept = (uint32_t)k;
+    sh = (uint32_t)(full - k);
+    rmode = (res_bits >= 1 && res_bits <= 8) ? kResByte : (k == full ? kResFull : kResPartial);
 }
 
 } // namespace
@@ -614,36 +809,30 @@ hipError_t launch_step(const StepLaunch &L)
                           : launch_step_fmt<MPO_OPT_SGD, kNoDecay, false>(L);
 }
 
-hipError_t launch_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits, hipStream_t stream)
+hipError_t launch_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits, int round,
+                        uint64_t seed, uint32_t tensor_id, hipStream_t stream)
 {
-    const int al = aligned16(w32) && aligned16(hi) && aligned16(res);
+    SplitMergeArgs a;
+    a.w32_in = w32; a.w32_out = nullptr; a.hi = hi; a.res = res; a.n = n;
+    a.al = aligned16(w32) && aligned16(hi) && aligned16(res);
     int rmode;
-    uint32_t sh;
-    res_layout(fmt, res_bits, rmode, sh);
-    if (fmt == MPO_BF16) {
-        if (rmode == kResByte) return launch_split_t<MPO_BF16, kResByte>(w32, hi, res, n, sh, al, stream);
-        if (rmode == kResPartial) return launch_split_t<MPO_BF16, kResPartial>(w32, hi, res, n, sh, al, stream);
-        return launch_split_t<MPO_BF16, kResFull>(w32, hi, res, n, sh, al, stream);
-    }
-    if (rmode == kResByte) return launch_split_t<MPO_FP16, kResByte>(w32, hi, res, n, sh, al, stream);
-    if (rmode == kResPartial) return launch_split_t<MPO_FP16, kResPartial>(w32, hi, res, n, sh, al, stream);
-    return launch_split_t<MPO_FP16, kResFull>(w32, hi, res, n, sh, al, stream);
+    res_layout(fmt, res_bits, round, rmode, a.kept, a.sh);
+    a.rs = RoundArgs{(uint32_t)round, (uint32_t)seed, (uint32_t)(seed >> 32), tensor_id};
+    a.stream = stream;
+    return fmt == MPO_BF16 ? launch_sm<MPO_BF16, true>(a, rmode) : launch_sm<MPO_FP16, true>(a, rmode);
 }
 
-hipError_t launch_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits, hipStream_t stream)
+hipError_t launch_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits, int round,
+                        hipStream_t stream)
 {
-    const int al = aligned16(w32) && aligned16(hi) && aligned16(res);
+    SplitMergeArgs a;
+    a.w32_in = nullptr; a.w32_out = w32; a.hi = const_cast<uint16_t *>(hi); a.res = const_cast<void *>(res); a.n = n;
+    a.al = aligned16(w32) && aligned16(hi) && aligned16(res);
     int rmode;
-    uint32_t sh;
-    res_layout(fmt, res_bits, rmode, sh);
-    if (fmt == MPO_BF16) {
-        if (rmode == kResByte) return launch_merge_t<MPO_BF16, kResByte>(hi, res, w32, n, sh, al, stream);
-        if (rmode == kResPartial) return launch_merge_t<MPO_BF16, kResPartial>(hi, res, w32, n, sh, al, stream);
-        return launch_merge_t<MPO_BF16, kResFull>(hi, res, w32, n, sh, al, stream);
-    }
-    if (rmode == kResByte) return launch_merge_t<MPO_FP16, kResByte>(hi, res, w32, n, sh, al, stream);
-    if (rmode == kResPartial) return launch_merge_t<MPO_FP16, kResPartial>(hi, res, w32, n, sh, al, stream);
-    return launch_merge_t<MPO_FP16, kResFull>(hi, res, w32, n, sh, al, stream);
+    res_layout(fmt, res_bits, round, rmode, a.kept, a.sh);
+    a.rs = RoundArgs{(uint32_t)round, 0u, 0u, 0u};
+    a.stream = stream;
+    return fmt == MPO_BF16 ? launch_sm<MPO_BF16, false>(a, rmode) : launch_sm<MPO_FP16, false>(a, rmode);
 }
 
 } // namespace mpo

@@ -33,8 +33,10 @@ class ModelState:
     exists and never kept).  For workloads stepped in one launch the buffer holds all gradients."""
 
     def __init__(self, wl: synth.Workload, device="cuda:0", seed: int = 2309, keep_w32_samples=None,
-                 res_bits: int = 0):
+                 res_bits: int = 0, round: int = mpo.MPO_ROUND_TRUNC, rng_seed: int = 0x2309_12381):
         self.wl = wl
+        self.round = round                  # how hi is rounded (Section 3.1, last paragraph)
+        self.rng_seed = rng_seed            # random stream of stochastic rounding
         self.res_bits = res_bits            # extra bits kept per weight, 0 = all (Section 3.1)
         self.res_bytes = 1 if 1 <= res_bits <= 8 else 2
         self.device = device
@@ -68,7 +70,8 @@ class ModelState:
                 idx = keep_w32_samples(i, n)
                 if idx is not None:
                     self.w32_samples[i] = (idx, w[idx].cpu())
-            mpo.mpo_split(w, self.hi[tv.off:], self.res[tv.off:], n, fmt=self.fmt, res_bits=res_bits)
+            mpo.mpo_split(w, self.hi[tv.off:], self.res[tv.off:], n, fmt=self.fmt, res_bits=res_bits,
+                          round=round, seed=rng_seed, tensor_id=i)
             del w
         torch.cuda.synchronize(device)
         self.plan = mpo.Plan([mpo.Tensor(self.hi[tv.off:], self.res[tv.off:], self.grad[tv.goff:],
@@ -87,12 +90,12 @@ class ModelState:
         wl = self.wl
         return mpo.AdamCfg(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=wl.weight_decay,
                            decoupled_wd=(wl.optimizer == "adamw"), loss_scale=wl.loss_scale,
-                           weight_fmt=self.fmt, grad_fmt=self.fmt)
+                           weight_fmt=self.fmt, grad_fmt=self.fmt, round=self.round, seed=self.rng_seed)
 
     def sgd_cfg(self) -> mpo.SgdCfg:
         wl = self.wl
         return mpo.SgdCfg(lr=1e-2, momentum=0.9, weight_decay=wl.weight_decay, loss_scale=wl.loss_scale,
-                          weight_fmt=self.fmt, grad_fmt=self.fmt)
+                          weight_fmt=self.fmt, grad_fmt=self.fmt, round=self.round, seed=self.rng_seed)
 
     def fill_grads(self, tensor_ids, step: int):
         """Stand-in for backward: fresh seeded gradients for these tensors, written into the buffer."""

@@ -84,24 +84,31 @@ def ref_sgd(hi, res, g, buf, cfg, step):
                                                              None if buf is None else buf[lo:up], cfg, step))
 
 
-def cfg_pair(kind, fmt="bf16", gfmt=None, res_bits=0, **kw):
+ROUND = {"trunc": (mpo.MPO_ROUND_TRUNC, ref.TRUNC), "nearest": (mpo.MPO_ROUND_NEAREST, ref.NEAREST),
+         "stochastic": (mpo.MPO_ROUND_STOCHASTIC, ref.STOCHASTIC)}
+
+
+def cfg_pair(kind, fmt="bf16", gfmt=None, res_bits=0, round="trunc", seed=0, **kw):
     """The same hyper-parameters for the library and for the oracle.  The number of extra bits
     kept is a property of each tensor in the library and of the step in the oracle."""
     gfmt = gfmt or fmt
     if kind == "adam":
-        return (mpo.AdamCfg(weight_fmt=FMT[fmt][0], grad_fmt=FMT[gfmt][0], **kw),
-                ref.AdamCfg(weight_fmt=FMT[fmt][1], grad_fmt=FMT[gfmt][1], res_bits=res_bits, **kw))
-    return (mpo.SgdCfg(weight_fmt=FMT[fmt][0], grad_fmt=FMT[gfmt][0], **kw),
-            ref.SgdCfg(weight_fmt=FMT[fmt][1], grad_fmt=FMT[gfmt][1], res_bits=res_bits, **kw))
+        return (mpo.AdamCfg(weight_fmt=FMT[fmt][0], grad_fmt=FMT[gfmt][0], round=ROUND[round][0], seed=seed, **kw),
+                ref.AdamCfg(weight_fmt=FMT[fmt][1], grad_fmt=FMT[gfmt][1], res_bits=res_bits, round=ROUND[round][1],
+                            seed=seed, **kw))
+    return (mpo.SgdCfg(weight_fmt=FMT[fmt][0], grad_fmt=FMT[gfmt][0], round=ROUND[round][0], seed=seed, **kw),
+            ref.SgdCfg(weight_fmt=FMT[fmt][1], grad_fmt=FMT[gfmt][1], res_bits=res_bits, round=ROUND[round][1],
+                       seed=seed, **kw))
 
 
 class HostTensor:
     """Oracle-side state of one tensor."""
 
-    def __init__(self, w32: np.ndarray, rfmt, with_v=True, res_bits=0):
+    def __init__(self, w32: np.ndarray, rfmt, with_v=True, res_bits=0, round="trunc", seed=0, tensor_id=0):
         self.n = w32.shape[0]
         self.res_bits = res_bits
-        self.hi, self.res = ref_split(w32, rfmt, res_bits)
+        self.tensor_id = tensor_id
+        self.hi, self.res = ref.split(w32, rfmt, res_bits, ROUND[round][1], seed, tensor_id)
         self.m = np.zeros(self.n, np.float32)
         self.v = np.zeros(self.n, np.float32) if with_v else None
 
@@ -109,7 +116,8 @@ class HostTensor:
 class DevTensor:
     """GPU-side state of one tensor, split by the library itself."""
 
-    def __init__(self, w32: np.ndarray, fmt, with_v=True, layer=0, grad=None, misalign=0, stream=None, res_bits=0):
+    def __init__(self, w32: np.ndarray, fmt, with_v=True, layer=0, grad=None, misalign=0, stream=None, res_bits=0,
+                 round="trunc", seed=0, tensor_id=0):
         n = w32.shape[0]
         self.n, self.layer, self.res_bits = n, layer, res_bits
         # optional misalignment: carve each array out of a larger one at an odd element offset
@@ -122,7 +130,8 @@ class DevTensor:
         self.grad = grad if grad is not None else alloc(torch.int16)
         w = torch.zeros(n + misalign + 8, dtype=torch.float32, device=DEV)[misalign:misalign + n]
         w.copy_(torch.from_numpy(w32))
-        mpo.mpo_split(w, self.hi, self.res, n, fmt=fmt, res_bits=res_bits, stream=stream)
+        mpo.mpo_split(w, self.hi, self.res, n, fmt=fmt, res_bits=res_bits, round=ROUND[round][0], seed=seed,
+                      tensor_id=tensor_id, stream=stream)
 
     def spec(self):
         return mpo.Tensor(self.hi, self.res, self.grad, self.m, self.v, self.n, self.layer, self.res_bits)

@@ -61,9 +61,13 @@ def test_split_merge_argument_validation():
     assert _status(mpo.mpo_split, 0, A, A + 0x1000, 10) == mpo.MPO_ERR_INVALID_ARG
     assert _status(mpo.mpo_split, A, 0, A + 0x1000, 10) == mpo.MPO_ERR_INVALID_ARG
     assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, fmt=7) == mpo.MPO_ERR_INVALID_ARG
-    assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, round=mpo.MPO_ROUND_NEAREST) == mpo.MPO_ERR_UNSUPPORTED
-    assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, round=mpo.MPO_ROUND_STOCHASTIC) == mpo.MPO_ERR_UNSUPPORTED
     assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, round=5) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_merge, A, A + 0x1000, A + 0x2000, 10, round=-1) == mpo.MPO_ERR_INVALID_ARG
+    # stochastic rounding stores a flag above the kept bits: 8 + 1 do not fit a byte, 16 + 1 not 16 bits
+    S = mpo.MPO_ROUND_STOCHASTIC
+    assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, res_bits=8, round=S) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, res_bits=16, round=S) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_merge, A, A + 0x1000, A + 0x2000, 10, res_bits=8, round=S) == mpo.MPO_ERR_INVALID_ARG
     assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 1 << 60) == mpo.MPO_ERR_INVALID_ARG
     assert _status(mpo.mpo_split, A, A + 16, A + 0x2000, 10) == mpo.MPO_ERR_ALIAS       # hi inside w32
     assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x1000 + 10, 10) == mpo.MPO_ERR_ALIAS  # res inside hi
@@ -165,12 +169,12 @@ def test_step_calls_validate_before_touching_the_gpu():
     assert _status(mpo.mpo_step_layer, p, 0, mpo.AdamCfg(), 1) == mpo.MPO_ERR_INVALID_ARG
     # config errors are reported first
     assert _status(mpo.mpo_adam_step, p, mpo.AdamCfg(), 0) == mpo.MPO_ERR_INVALID_ARG
-    assert _status(mpo.mpo_adam_step, p, mpo.AdamCfg(round=mpo.MPO_ROUND_STOCHASTIC), 1) == mpo.MPO_ERR_UNSUPPORTED
+    assert _status(mpo.mpo_adam_step, p, mpo.AdamCfg(round=7), 1) == mpo.MPO_ERR_INVALID_ARG
     assert _status(mpo.mpo_adam_step, p, mpo.AdamCfg(weight_fmt=3), 1) == mpo.MPO_ERR_INVALID_ARG
     assert _status(mpo.mpo_adam_step, p, mpo.AdamCfg(beta1=1.0), 1) == mpo.MPO_ERR_INVALID_ARG
     assert _status(mpo.mpo_adam_step, p, mpo.AdamCfg(loss_scale=0.0), 1) == mpo.MPO_ERR_INVALID_ARG
     assert _status(mpo.mpo_adam_step, p, mpo.AdamCfg(lr=float("nan")), 1) == mpo.MPO_ERR_INVALID_ARG
-    assert _status(mpo.mpo_sgd_step, p, mpo.SgdCfg(round=mpo.MPO_ROUND_NEAREST), 1) == mpo.MPO_ERR_UNSUPPORTED
+    assert _status(mpo.mpo_sgd_step, p, mpo.SgdCfg(round=-3), 1) == mpo.MPO_ERR_INVALID_ARG
     assert _status(mpo.mpo_sgd_step, p, mpo.SgdCfg(loss_scale=float("inf")), 1) == mpo.MPO_ERR_INVALID_ARG
     # null plan / null cfg through the raw entry points
     cfg = mpo.AdamCfg().c()

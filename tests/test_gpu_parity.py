@@ -15,7 +15,7 @@ import paper_2309_12381_amd as mpo
 from paper_2309_12381_amd import synth
 from oracle import ref
 
-from gpu_util import (DEV, FMT, DevTensor, HostTensor, assert_state_equal, cfg_pair, dev_f32, dev_res, dev_u16,
+from gpu_util import (DEV, FMT, ROUND, DevTensor, HostTensor, assert_state_equal, cfg_pair, dev_f32, dev_res, dev_u16,
                       host_f32, host_res, host_u16, parallel_slices, ref_adam, ref_sgd, ref_split, res_torch_dtype, say)
 
 pytestmark = pytest.mark.gpu
@@ -583,5 +583,126 @@ def test_partial_bits_argument_checks_on_device():
     with pytest.raises(mpo.MpoError) as e:
         mpo.mpo_adam_step(plan, mpo.AdamCfg(weight_fmt=mpo.MPO_FP16), 2)               # fp16 has only 13
     assert e.value.status == mpo.MPO_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    plan.destroy()
+
+
+# ---- rounding of the 16-bit value: nearest, stochastic with an un-round flag (Section 3.1) -----
+
+@pytest.mark.parametrize("fmt,res_bits", [("bf16", 0), ("bf16", 7), ("bf16", 12), ("fp16", 0), ("fp16", 5), ("fp16", 10)])
+@pytest.mark.parametrize("mode", ["nearest", "stochastic"])
+@pytest.mark.parametrize("misalign", [0, 1])
+def test_split_merge_rounding_modes(fmt, res_bits, mode, misalign):
+    gfmt, rfmt = FMT[fmt]
+    gmode, rmode = ROUND[mode]
+    rng = np.random.default_rng(41)
+    rdt = res_torch_dtype(res_bits)
+    for k, n in enumerate(SIZES):
+        say("split/merge fmt=%s res_bits=%d mode=%s n=%d misalign=%d" % (fmt, res_bits, mode, n, misalign))
+        x = interesting_f32(rng, n)
+        seed, tid = 0x1234567890ABCDEF ^ k, 3 + k
+        w = torch.zeros(n + misalign + 8, dtype=torch.float32, device=DEV)[misalign:misalign + n]
+        w.copy_(torch.from_numpy(x))
+        hi = torch.zeros(n + misalign + 8, dtype=torch.int16, device=DEV)
+        res = torch.zeros(n + misalign + 8, dtype=rdt, device=DEV)
+        mpo.mpo_split(w, hi[misalign:], res[misalign:], n, fmt=gfmt, res_bits=res_bits, round=gmode, seed=seed, tensor_id=tid)
+        want_hi, want_res = ref.split(x, rfmt, res_bits, rmode, seed, tid)
+        assert np.array_equal(host_u16(hi[misalign:misalign + n]), want_hi)
+        assert np.array_equal(host_res(res[misalign:misalign + n]), want_res)
+        out = torch.zeros(n + misalign + 8, dtype=torch.float32, device=DEV)
+        mpo.mpo_merge(hi[misalign:], res[misalign:], out[misalign:], n, fmt=gfmt, res_bits=res_bits, round=gmode)
+        want = ref.merge(want_hi, want_res, rfmt, res_bits, rmode)
+        assert np.array_equal(host_f32(out)[misalign:misalign + n].view(np.uint32), want.view(np.uint32))
+
+
+ROUND_CASES = [
+    ("adam", "bf16", "stochastic", [0], dict(lr=1e-3, weight_decay=1e-2, decoupled_wd=True)),
+    ("adam", "bf16", "nearest", [0], dict(lr=1e-3)),
+    ("adam", "fp16", "stochastic", [0], dict(lr=1e-3, loss_scale=1024.0)),          # the paper's fp16+13 stochastic
+    ("adam", "fp16", "nearest", [0, 9], dict(lr=1e-3, loss_scale=64.0)),
+    ("adam", "bf16", "stochastic", [7, 3], dict(lr=1e-3)),                            # byte slots: 7 bits + flag
+    ("adam", "bf16", "nearest", [8, 2], dict(lr=1e-3, weight_decay=0.1, decoupled_wd=False)),
+    ("adam", "bf16", "stochastic", [12, 0, 15], dict(lr=1e-3)),
+    ("sgd", "bf16", "stochastic", [0], dict(lr=0.3, momentum=0.9, weight_decay=2e-4)),
+    ("sgd", "fp16", "stochastic", [6], dict(lr=0.1, momentum=0.0, loss_scale=128.0)),
+    ("sgd", "fp16", "nearest", [0], dict(lr=0.1, momentum=0.9)),
+]
+
+
+@pytest.mark.parametrize("kind,fmt,mode,bits,kw", ROUND_CASES,
+                         ids=["%s-%s-%s-%s" % (c[0], c[1], c[2], "_".join(map(str, c[3]))) for c in ROUND_CASES])
+@pytest.mark.parametrize("misalign", [0, 1])
+def test_multi_tensor_list_rounding_modes(kind, fmt, mode, bits, kw, misalign):
+    """Steps with nearest / stochastic rounding of hi: every stored bit (hi, residual, flag, m, v)
+    equals the oracle's; the random stream is selected by seed, step, tensor index and element,
+    so stepping the whole list and stepping layer by layer give the same bits."""
+    gfmt, rfmt = FMT[fmt]
+    rng = np.random.default_rng(23 + misalign)
+    sizes = _small_list(rng, count=19, total=500_000)
+    scale = kw.get("loss_scale", 1.0)
+    seed = 0xC0FFEE0000 + misalign
+    say("rounding list kind=%s fmt=%s mode=%s bits=%s misalign=%d" % (kind, fmt, mode, bits, misalign))
+    devs, hosts, cfgs = [], [], []
+    for i, n in enumerate(sizes):
+        E = bits[i % len(bits)]
+        w0 = synth.gen_weights(n, synth.seed_for(37, i), "cpu", 0.02).numpy()
+        devs.append(DevTensor(w0, gfmt, with_v=(kind == "adam"), layer=i % 4, misalign=misalign, res_bits=E,
+                              round=mode, seed=seed, tensor_id=i))
+        hosts.append(HostTensor(w0, rfmt, with_v=(kind == "adam"), res_bits=E, round=mode, seed=seed, tensor_id=i))
+        cfgs.append(cfg_pair(kind, fmt, res_bits=E, round=mode, seed=seed, **kw))
+        assert_state_equal(devs[-1], hosts[-1], "after split, tensor %d" % i)
+    plan = mpo.Plan([d.spec() for d in devs])
+    lib_cfg = cfgs[0][0]
+    for t in range(1, 5):
+        for i, (d, h) in enumerate(zip(devs, hosts)):
+            g = synth.bits16(synth.gen_grads(d.n, synth.seed_for(43, i, t), "cpu", 1e-3, fmt, scale))
+            d.grad.copy_(dev_u16(g))
+            if kind == "adam":
+                ref.adam_step(h.hi, h.res, g, h.m, h.v, cfgs[i][1], t, tensor_id=i)
+            else:
+                ref.sgd_step(h.hi, h.res, g, h.m, cfgs[i][1], t, tensor_id=i)
+        if t % 2:
+            (mpo.mpo_adam_step if kind == "adam" else mpo.mpo_sgd_step)(plan, lib_cfg, t)
+        else:
+            for ly in (3, 2, 1, 0):
+                mpo.mpo_step_layer(plan, ly, lib_cfg, t)
+        for i, (d, h) in enumerate(zip(devs, hosts)):
+            assert_state_equal(d, h, "tensor %d (n=%d, E=%d) step %d" % (i, d.n, d.res_bits, t))
+    plan.destroy()
+
+
+def test_rounding_mode_does_not_change_the_fp32_trajectory():
+    """The fp32 value held by (hi, res), m and v are the same in every mode; only hi differs."""
+    n = 5 * CHUNK + 77
+    w0 = synth.gen_weights(n, 71, "cpu", 0.02).numpy()
+    grads = [dev_u16(synth.bits16(synth.gen_grads(n, 500 + t, "cpu", 1e-3))) for t in range(6)]
+    outs = {}
+    for mode in ("trunc", "nearest", "stochastic"):
+        E = 15                                   # what stochastic bf16 keeps; ask the others for the same
+        d = DevTensor(w0, mpo.MPO_BF16, res_bits=E, round=mode, seed=5, tensor_id=0)
+        plan = mpo.Plan([d.spec()])
+        for t, g in enumerate(grads, 1):
+            d.grad.copy_(g)
+            mpo.mpo_adam_step(plan, mpo.AdamCfg(round=ROUND[mode][0], seed=5, weight_decay=1e-2), t)
+        w = torch.empty(n, dtype=torch.float32, device=DEV)
+        mpo.mpo_merge(d.hi, d.res, w, n, res_bits=E, round=ROUND[mode][0])
+        torch.cuda.synchronize()
+        outs[mode] = (host_f32(w), host_f32(d.m), host_f32(d.v), host_u16(d.hi))
+        plan.destroy()
+    for mode in ("nearest", "stochastic"):
+        for a, b in zip(outs[mode][:3], outs["trunc"][:3]):
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), mode
+        diff = (outs[mode][3].astype(np.int32) - outs["trunc"][3].astype(np.int32)) & 0xFFFF
+        assert np.all((diff == 0) | (diff == 1)) and 0.3 < diff.mean() < 0.7
+
+
+def test_stochastic_argument_checks_on_device():
+    w0 = np.ones(100, np.float32)
+    d = DevTensor(w0, mpo.MPO_BF16, res_bits=8)
+    plan = mpo.Plan([d.spec()])
+    with pytest.raises(mpo.MpoError) as e:       # 8 bits + flag do not fit the byte slot
+        mpo.mpo_adam_step(plan, mpo.AdamCfg(round=mpo.MPO_ROUND_STOCHASTIC), 1)
+    assert e.value.status == mpo.MPO_ERR_INVALID_ARG
+    mpo.mpo_adam_step(plan, mpo.AdamCfg(round=mpo.MPO_ROUND_NEAREST), 1)
     torch.cuda.synchronize()
     plan.destroy()

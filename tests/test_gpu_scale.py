@@ -27,17 +27,25 @@ def _ref_cfg(st):
     rf = ref.BF16 if st.wl.fmt == "bf16" else ref.FP16
     return ref.AdamCfg(lr=c.lr, beta1=c.beta1, beta2=c.beta2, eps=c.eps, weight_decay=c.weight_decay,
                        decoupled_wd=c.decoupled_wd, loss_scale=c.loss_scale, weight_fmt=rf, grad_fmt=rf,
-                       res_bits=st.res_bits), rf
+                       res_bits=st.res_bits, round=st.round, seed=st.rng_seed), rf
 
 
-def _run_and_compare(key, steps, sampler, res_bits=0):
+def _run_and_compare(key, steps, sampler, res_bits=0, round=0):
+    """round: 0 truncation, 1 nearest, 2 stochastic.  With stochastic rounding the sampler must
+    pick whole tensors only: the oracle numbers the elements of the array it is given, and the
+    random stream is indexed by the element's position in its tensor."""
     wl = synth.workload(key)
-    say("full-size %s: %d params, %d steps, res_bits %d" % (key, wl.num_params, steps, res_bits))
-    st = harness.ModelState(wl, DEV, seed=2309, keep_w32_samples=sampler, res_bits=res_bits)
+    say("full-size %s: %d params, %d steps, res_bits %d, round %d" % (key, wl.num_params, steps, res_bits, round))
+    st = harness.ModelState(wl, DEV, seed=2309, keep_w32_samples=sampler, res_bits=res_bits, round=round)
     rcfg, rf = _ref_cfg(st)
     host = {}
     for i, (idx, w) in st.w32_samples.items():
-        hi, res = ref_split(np.ascontiguousarray(w.numpy()), rf, res_bits)
+        if round == 2:
+            assert isinstance(idx, slice)
+            hi, res = ref.split(np.ascontiguousarray(w.numpy()), rf, res_bits, round, st.rng_seed, i)
+        else:
+            hi, res = ref.split(np.ascontiguousarray(w.numpy()), rf, res_bits, round) if round else \
+                ref_split(np.ascontiguousarray(w.numpy()), rf, res_bits)
         host[i] = [hi, res, np.zeros(hi.size, np.float32), np.zeros(hi.size, np.float32)]
 
     for t in range(1, steps + 1):
@@ -51,7 +59,10 @@ def _run_and_compare(key, steps, sampler, res_bits=0):
                 g = st.grad[tv.goff:tv.goff + tv.spec.n][idx]
                 gb = synth.bits16(g)
                 h = host[i]
-                ref_adam(h[0], h[1], gb, h[2], h[3], rcfg, t)
+                if round == 2:
+                    ref.adam_step(h[0], h[1], gb, h[2], h[3], rcfg, t, tensor_id=i)     # whole tensor, in order
+                else:
+                    ref_adam(h[0], h[1], gb, h[2], h[3], rcfg, t)
         st.step(t, fresh_grads=True, before_layer=grab)
     torch.cuda.synchronize()
 
@@ -115,6 +126,24 @@ def test_c3_llama7b_bf16_plus_8_per_layer_sampled():
 def test_c1_bf16_plus_8_full():
     checked, wl = _run_and_compare("c1", 3, _everything, res_bits=8)
     assert checked == wl.num_params
+
+
+def _whole_tensors(i, n):
+    return slice(None) if (n <= 4 * BLOCK or i % 89 == 2 or i == 0) else None
+
+
+def test_c3_llama7b_nearest_per_layer_sampled():
+    checked, wl = _run_and_compare("c3", 2, _blocks_sampler(seed=7), round=1)
+    assert checked > 40_000_000
+
+
+def test_c4_llama13b_fp16_stochastic_whole_tensors():
+    """The paper's "fp16+13 rstoc": stochastic rounding with the un-round flag in bit 13."""
+    free, total = torch.cuda.mem_get_info()
+    if total < 200e9:
+        pytest.skip("needs about 160 GB of device memory")
+    checked, wl = _run_and_compare("c4", 2, _whole_tensors, round=2)
+    assert checked > 200_000_000
 
 
 def test_c4_llama13b_fp16_per_layer_sampled():
