@@ -133,6 +133,9 @@ typedef struct {
  * fp32 once.  decoupled_wd != 0: w *= 1 - lr*wd before the update (AdamW);
  * else g += wd*w (L2).  Gradients arrive multiplied by loss_scale and are
  * divided by it inside the step (Section 4.1); loss_scale must be finite, > 0.
+ * grad_clip > 0 clamps every un-scaled gradient element to [-grad_clip,
+ * grad_clip] inside the step (Section 4.1: with the step fused into backward,
+ * clipping has to happen there); 0 switches it off; NaN stays NaN.
  */
 typedef struct {
     double lr, beta1, beta2, eps, weight_decay;
@@ -142,6 +145,7 @@ typedef struct {
     int32_t grad_fmt;   /* mpo_fmt of grad */
     int32_t round;      /* mpo_round       */
     uint64_t seed;      /* random stream of MPO_ROUND_STOCHASTIC */
+    double grad_clip;   /* element-wise clamp of the gradient, 0 = off */
 } mpo_adam_cfg;
 
 /* SGD with momentum (dampening 0, no Nesterov), L2 weight decay.
@@ -151,6 +155,7 @@ typedef struct {
     double loss_scale;
     int32_t weight_fmt, grad_fmt, round;
     uint64_t seed;
+    double grad_clip;
 } mpo_sgd_cfg;
 
 typedef struct mpo_plan mpo_plan;

@@ -245,6 +245,8 @@ void mpo_ref_adam_step(uint16_t *hi, void *res, const uint16_t *grad, float *m, 
     const float DEC = (float)(1.0 - cfg->lr * cfg->weight_decay);
     const float WD = (float)cfg->weight_decay;
     const float IS = (float)(1.0 / cfg->loss_scale);
+    const float CLIP = (float)cfg->grad_clip;
+    const int has_clip = cfg->grad_clip != 0.0;
     const int has_wd = cfg->weight_decay != 0.0;
 
     for (uint64_t i = 0; i < n; ++i) {
@@ -253,6 +255,10 @@ void mpo_ref_adam_step(uint16_t *hi, void *res, const uint16_t *grad, float *m, 
         float w = merge_one(h16, full, cfg->weight_fmt);
         float g = mpo_ref_cvt16(grad[i], cfg->grad_fmt);
         g = g * IS;
+        if (has_clip) {                    /* Sec. 4.1: element-wise clipping inside the step */
+            if (g > CLIP) g = CLIP;
+            if (g < -CLIP) g = -CLIP;
+        }
         if (has_wd) {
             if (cfg->decoupled_wd) {
                 w = w * DEC;
@@ -291,6 +297,8 @@ void mpo_ref_sgd_step(uint16_t *hi, void *res, const uint16_t *grad, float *buf,
     const float MU = (float)cfg->momentum;
     const float WD = (float)cfg->weight_decay;
     const float IS = (float)(1.0 / cfg->loss_scale);
+    const float CLIP = (float)cfg->grad_clip;
+    const int has_clip = cfg->grad_clip != 0.0;
     const int has_wd = cfg->weight_decay != 0.0;
     const int has_mu = cfg->momentum != 0.0;
 
@@ -300,6 +308,10 @@ void mpo_ref_sgd_step(uint16_t *hi, void *res, const uint16_t *grad, float *buf,
         float w = merge_one(h16, full, cfg->weight_fmt);
         float g = mpo_ref_cvt16(grad[i], cfg->grad_fmt);
         g = g * IS;
+        if (has_clip) {                    /* Sec. 4.1: element-wise clipping inside the step */
+            if (g > CLIP) g = CLIP;
+            if (g < -CLIP) g = -CLIP;
+        }
         if (has_wd) {
             float wdw = WD * w;
             g = g + wdw;

@@ -68,6 +68,7 @@ typedef struct {
     int32_t res_bits;     /* extra bits kept, 0 = all                         */
     int32_t round;        /* MPO_REF_TRUNC / NEAREST / STOCHASTIC             */
     uint64_t seed;        /* STOCHASTIC only                                  */
+    double grad_clip;     /* Section 4.1: clamp the un-scaled gradient to [-c, c]; 0 = off */
 } mpo_ref_adam_cfg;
 
 typedef struct {
@@ -77,6 +78,7 @@ typedef struct {
     int32_t res_bits;
     int32_t round;
     uint64_t seed;
+    double grad_clip;
 } mpo_ref_sgd_cfg;
 
 /* Section 3.1, Table 1: fp32 -> (16-bit float, extra bits), truncation. */

@@ -33,14 +33,14 @@ class _AdamCfg(ctypes.Structure):
                 ("eps", ctypes.c_double), ("weight_decay", ctypes.c_double),
                 ("decoupled_wd", ctypes.c_int32), ("loss_scale", ctypes.c_double),
                 ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32), ("res_bits", ctypes.c_int32),
-                ("round", ctypes.c_int32), ("seed", ctypes.c_uint64)]
+                ("round", ctypes.c_int32), ("seed", ctypes.c_uint64), ("grad_clip", ctypes.c_double)]
 
 
 class _SgdCfg(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_double), ("momentum", ctypes.c_double),
                 ("weight_decay", ctypes.c_double), ("loss_scale", ctypes.c_double),
                 ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32), ("res_bits", ctypes.c_int32),
-                ("round", ctypes.c_int32), ("seed", ctypes.c_uint64)]
+                ("round", ctypes.c_int32), ("seed", ctypes.c_uint64), ("grad_clip", ctypes.c_double)]
 
 
 def res_dtype(res_bits: int):
@@ -62,11 +62,12 @@ class AdamCfg:
     res_bits: int = 0
     round: int = TRUNC
     seed: int = 0
+    grad_clip: float = 0.0
 
     def _c(self):
         return _AdamCfg(self.lr, self.beta1, self.beta2, self.eps, self.weight_decay,
                         int(self.decoupled_wd), self.loss_scale, self.weight_fmt, self.grad_fmt, self.res_bits,
-                        self.round, self.seed)
+                        self.round, self.seed, self.grad_clip)
 
 
 @dataclass
@@ -80,10 +81,11 @@ class SgdCfg:
     res_bits: int = 0
     round: int = TRUNC
     seed: int = 0
+    grad_clip: float = 0.0
 
     def _c(self):
         return _SgdCfg(self.lr, self.momentum, self.weight_decay, self.loss_scale,
-                       self.weight_fmt, self.grad_fmt, self.res_bits, self.round, self.seed)
+                       self.weight_fmt, self.grad_fmt, self.res_bits, self.round, self.seed, self.grad_clip)
 
 
 def _chk(a, dtype, n=None):

@@ -43,14 +43,14 @@ class mpo_adam_cfg(ctypes.Structure):
                 ("eps", ctypes.c_double), ("weight_decay", ctypes.c_double),
                 ("decoupled_wd", ctypes.c_int32), ("loss_scale", ctypes.c_double),
                 ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32), ("round", ctypes.c_int32),
-                ("seed", ctypes.c_uint64)]
+                ("seed", ctypes.c_uint64), ("grad_clip", ctypes.c_double)]
 
 
 class mpo_sgd_cfg(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_double), ("momentum", ctypes.c_double), ("weight_decay", ctypes.c_double),
                 ("loss_scale", ctypes.c_double),
                 ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32), ("round", ctypes.c_int32),
-                ("seed", ctypes.c_uint64)]
+                ("seed", ctypes.c_uint64), ("grad_clip", ctypes.c_double)]
 
 
 EXPORTS = {
@@ -137,10 +137,11 @@ class AdamCfg:
     grad_fmt: int = MPO_BF16
     round: int = MPO_ROUND_TRUNC
     seed: int = 0
+    grad_clip: float = 0.0
 
     def c(self) -> mpo_adam_cfg:
         return mpo_adam_cfg(self.lr, self.beta1, self.beta2, self.eps, self.weight_decay, int(self.decoupled_wd),
-                            self.loss_scale, self.weight_fmt, self.grad_fmt, self.round, self.seed)
+                            self.loss_scale, self.weight_fmt, self.grad_fmt, self.round, self.seed, self.grad_clip)
 
 
 @dataclass
@@ -153,10 +154,11 @@ class SgdCfg:
     grad_fmt: int = MPO_BF16
     round: int = MPO_ROUND_TRUNC
     seed: int = 0
+    grad_clip: float = 0.0
 
     def c(self) -> mpo_sgd_cfg:
         return mpo_sgd_cfg(self.lr, self.momentum, self.weight_decay, self.loss_scale, self.weight_fmt,
-                           self.grad_fmt, self.round, self.seed)
+                           self.grad_fmt, self.round, self.seed, self.grad_clip)
 
 
 def mpo_split(w32, hi, res, n: int, fmt: int = MPO_BF16, res_bits: int = 0, round: int = MPO_ROUND_TRUNC,

@@ -206,6 +206,7 @@ mpo_status adam_scalars(const mpo_adam_cfg *c, uint64_t step, StepLaunch &L)
     if (!std::isfinite(c->lr) || !std::isfinite(c->eps) || !std::isfinite(c->weight_decay)) return MPO_ERR_INVALID_ARG;
     if (!(c->beta1 >= 0.0 && c->beta1 < 1.0) || !(c->beta2 >= 0.0 && c->beta2 < 1.0)) return MPO_ERR_INVALID_ARG;
     if (!finite_pos(c->loss_scale)) return MPO_ERR_INVALID_ARG;
+    if (!(c->grad_clip >= 0.0) || !std::isfinite(c->grad_clip)) return MPO_ERR_INVALID_ARG;
     const double t = (double)step;
     const double bc1 = 1.0 - std::pow(c->beta1, t);
     const double bc2 = 1.0 - std::pow(c->beta2, t);
@@ -221,6 +222,7 @@ mpo_status adam_scalars(const mpo_adam_cfg *c, uint64_t step, StepLaunch &L)
     s.DEC = (float)(1.0 - c->lr * c->weight_decay);
     s.WD = (float)c->weight_decay;
     s.IS = (float)(1.0 / c->loss_scale);
+    s.CLIP = c->grad_clip != 0.0 ? (float)c->grad_clip : INFINITY;
     s.round = (uint32_t)c->round;
     s.seed_lo = (uint32_t)c->seed;
     s.seed_hi = (uint32_t)(c->seed >> 32);
@@ -241,12 +243,14 @@ mpo_status sgd_scalars(const mpo_sgd_cfg *c, uint64_t step, StepLaunch &L)
     if (rs != MPO_OK) return rs;
     if (!std::isfinite(c->lr) || !std::isfinite(c->momentum) || !std::isfinite(c->weight_decay)) return MPO_ERR_INVALID_ARG;
     if (!finite_pos(c->loss_scale)) return MPO_ERR_INVALID_ARG;
+    if (!(c->grad_clip >= 0.0) || !std::isfinite(c->grad_clip)) return MPO_ERR_INVALID_ARG;
     StepScalars &s = L.s;
     std::memset(&s, 0, sizeof s);
     s.LR = (float)c->lr;
     s.MU = (float)c->momentum;
     s.WD = (float)c->weight_decay;
     s.IS = (float)(1.0 / c->loss_scale);
+    s.CLIP = c->grad_clip != 0.0 ? (float)c->grad_clip : INFINITY;
     s.round = (uint32_t)c->round;
     s.seed_lo = (uint32_t)c->seed;
     s.seed_hi = (uint32_t)(c->seed >> 32);

@@ -46,6 +46,7 @@ struct StepScalars {
     float SS, SQ, EPS;    /* lr/(1-beta1^t), sqrt(1-beta2^t), eps                */
     float DEC, WD, IS;    /* 1-lr*wd, wd, 1/loss_scale                           */
     float LR, MU;         /* SGD learning rate and momentum                      */
+    float CLIP;           /* gradient clamp bound, +infinity when off (Section 4.1) */
     /* rounding of the 16-bit value (Section 3.1, last paragraph) */
     uint32_t round;       /* mpo_round                                           */
     uint32_t seed_lo, seed_hi, step32;

@@ -219,6 +219,10 @@ __device__ __forceinline__ void step_one(uint32_t &hi, uint32_t &res, uint32_t g
     float w = merge16<WFMT>(hi, res);
     float g = cvt16<GFMT>(g16);
     g = g * s.IS;
+    /* Section 4.1: element-wise clipping inside the step; the bound is +infinity when off,
+     * and a NaN gradient stays NaN */
+    g = g > s.CLIP ? s.CLIP : g;
+    g = g < -s.CLIP ? -s.CLIP : g;
     if (OPT == MPO_OPT_ADAM) {
         if (DECAY == kDecoupled) {
             w = w * s.DEC;

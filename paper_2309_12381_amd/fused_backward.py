@@ -1,0 +1,129 @@
+"""The optimizer step fused into PyTorch's backward pass (arXiv 2309.12381, Section 3.2).
+
+Each parameter's step runs in a post-accumulate-grad hook, as soon as autograd has produced
+that parameter's gradient, and the gradient is released right there: no gradient outlives
+the backward of its own layer.  The 16-bit parameter tensor of the model IS the `hi` array of
+the split weight (the library updates it in place); the extra bits and the moments are
+optimizer state (Section 3.1).  Clipping and loss scaling happen inside the step (Section 4.1).
+
+PyTorch provides memory, streams and autograd; every arithmetic step is `mpo_step_layer`.
+"""
+from typing import Callable, Iterable, Optional, Sequence
+
+import torch
+
+from . import binding as mpo
+
+_FMT = {torch.bfloat16: mpo.MPO_BF16, torch.float16: mpo.MPO_FP16}
+
+
+def _round_up(x: int, k: int) -> int:
+    return (x + k - 1) // k * k
+
+
+class FusedBackwardOptimizer:
+    """Split-precision Adam / SGD whose step runs inside backward.
+
+    params      bf16 or fp16 CUDA parameters (all of one dtype), contiguous.
+    cfg         mpo.AdamCfg or mpo.SgdCfg; its weight_fmt / grad_fmt are set from the dtype.
+    res_bits    extra bits kept per weight (0 = all).
+    init_fp32   optional fp32 tensors to start from (else the 16-bit values, residual 0).
+    fused       True: step in the hook and free the gradient (Section 3.2).  False: keep gradients
+                and step them all in `step()`, the classical schedule, for comparison.
+    observer    optional callable(index, grad) invoked just before a parameter is stepped.
+
+    Call `start_step()` before every backward: all parameters stepped during one backward share
+    the step count.
+    """
+
+    def __init__(self, params: Iterable[torch.nn.Parameter], cfg, res_bits: int = 0,
+                 init_fp32: Optional[Sequence[torch.Tensor]] = None, fused: bool = True,
+                 observer: Optional[Callable] = None):
+        self.params = [p for p in params if p.requires_grad]
+        if not self.params:
+            raise ValueError("no parameters")
+        dtype = self.params[0].dtype
+        if dtype not in _FMT:
+            raise TypeError("parameters must be bfloat16 or float16")
+        for p in self.params:
+            if p.dtype != dtype or not p.is_cuda or not p.is_contiguous():
+                raise TypeError("parameters must be contiguous CUDA tensors of one 16-bit dtype")
+        self.cfg = cfg
+        self.cfg.weight_fmt = self.cfg.grad_fmt = _FMT[dtype]
+        self.is_adam = isinstance(cfg, mpo.AdamCfg)
+        self.res_bits = res_bits
+        self.fused = fused
+        self.observer = observer
+        self.step_no = 0
+        dev = self.params[0].device
+        offs, total = [], 0
+        for p in self.params:
+            offs.append(total)
+            total += _round_up(p.numel(), 8)
+        res_dtype = torch.uint8 if 1 <= res_bits <= 8 else torch.int16
+        self.res = torch.zeros(total, dtype=res_dtype, device=dev)
+        self.m = torch.zeros(total, dtype=torch.float32, device=dev)
+        self.v = torch.zeros(total, dtype=torch.float32, device=dev) if self.is_adam else None
+        self.offs = offs
+        specs = []
+        for i, (p, off) in enumerate(zip(self.params, offs)):
+            n = p.numel()
+            master = init_fp32[i].to(dev, torch.float32).reshape(-1).contiguous() if init_fp32 is not None \
+                else p.detach().float().reshape(-1)
+            mpo.mpo_split(master, p.data, self.res[off:], n, fmt=_FMT[dtype], res_bits=res_bits, round=cfg.round,
+                          seed=cfg.seed, tensor_id=i)
+            specs.append(mpo.Tensor(p.data, self.res[off:], None, self.m[off:],
+                                    self.v[off:] if self.is_adam else None, n, i, res_bits))
+        torch.cuda.synchronize(dev)
+        self.plan = mpo.Plan(specs)          # one layer id per parameter: the paper steps per parameter
+        self._index = {id(p): i for i, p in enumerate(self.params)}
+        self._handles = []
+        if fused:
+            for p in self.params:
+                self._handles.append(p.register_post_accumulate_grad_hook(self._on_grad))
+
+    def start_step(self):
+        self.step_no += 1
+
+    def _step_param(self, i: int, p: torch.nn.Parameter):
+        g = p.grad
+        if g.dtype != p.dtype:
+            raise TypeError("gradient dtype differs from the parameter's")
+        if not g.is_contiguous():
+            g = g.contiguous()
+        if self.observer is not None:
+            self.observer(i, g)
+        mpo.mpo_step_layer(self.plan, i, self.cfg, self.step_no, grads=[g], stream=torch.cuda.current_stream(p.device))
+
+    def _on_grad(self, p: torch.nn.Parameter):
+        if self.step_no == 0:
+            raise RuntimeError("call start_step() before backward")
+        self._step_param(self._index[id(p)], p)
+        p.grad = None                       # the gradient is consumed: never kept (Section 3.2)
+
+    def step(self):
+        """Classical schedule (fused=False): step every parameter after backward has finished."""
+        if self.fused:
+            raise RuntimeError("steps already ran inside backward")
+        for i, p in enumerate(self.params):
+            if p.grad is not None:
+                self._step_param(i, p)
+                p.grad = None
+
+    def master_fp32(self, i: int) -> torch.Tensor:
+        """The fp32 value of parameter i held by (hi, res)."""
+        p = self.params[i]
+        out = torch.empty(p.numel(), dtype=torch.float32, device=p.device)
+        mpo.mpo_merge(p.data, self.res[self.offs[i]:], out, p.numel(), fmt=_FMT[p.dtype], res_bits=self.res_bits,
+                      round=self.cfg.round)
+        return out.view_as(p)
+
+    def state_of(self, i: int):
+        n, off = self.params[i].numel(), self.offs[i]
+        return self.res[off:off + n], self.m[off:off + n], (self.v[off:off + n] if self.is_adam else None)
+
+    def close(self):
+        for h in self._handles:
+            h.remove()
+        self._handles = []
+        self.plan.destroy()

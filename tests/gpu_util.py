@@ -92,6 +92,7 @@ def cfg_pair(kind, fmt="bf16", gfmt=None, res_bits=0, round="trunc", seed=0, **k
     """The same hyper-parameters for the library and for the oracle.  The number of extra bits
     kept is a property of each tensor in the library and of the step in the oracle."""
     gfmt = gfmt or fmt
+    # remaining keywords (lr, betas, decay, loss_scale, grad_clip, ...) have the same names on both sides
     if kind == "adam":
         return (mpo.AdamCfg(weight_fmt=FMT[fmt][0], grad_fmt=FMT[gfmt][0], round=ROUND[round][0], seed=seed, **kw),
                 ref.AdamCfg(weight_fmt=FMT[fmt][1], grad_fmt=FMT[gfmt][1], res_bits=res_bits, round=ROUND[round][1],

@@ -174,6 +174,8 @@ def test_step_calls_validate_before_touching_the_gpu():
     assert _status(mpo.mpo_adam_step, p, mpo.AdamCfg(beta1=1.0), 1) == mpo.MPO_ERR_INVALID_ARG
     assert _status(mpo.mpo_adam_step, p, mpo.AdamCfg(loss_scale=0.0), 1) == mpo.MPO_ERR_INVALID_ARG
     assert _status(mpo.mpo_adam_step, p, mpo.AdamCfg(lr=float("nan")), 1) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_adam_step, p, mpo.AdamCfg(grad_clip=-1.0), 1) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_sgd_step, p, mpo.SgdCfg(grad_clip=float("inf")), 1) == mpo.MPO_ERR_INVALID_ARG
     assert _status(mpo.mpo_sgd_step, p, mpo.SgdCfg(round=-3), 1) == mpo.MPO_ERR_INVALID_ARG
     assert _status(mpo.mpo_sgd_step, p, mpo.SgdCfg(loss_scale=float("inf")), 1) == mpo.MPO_ERR_INVALID_ARG
     # null plan / null cfg through the raw entry points

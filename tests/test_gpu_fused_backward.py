@@ -1,0 +1,135 @@
+"""The step fused into a real PyTorch backward (arXiv 2309.12381, Section 3.2): every parameter is
+stepped in its post-accumulate-grad hook and its gradient released there.  The gradients autograd
+produced are copied to the host inside the hook, so the oracle replays exactly the same bytes."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2309_12381_amd as mpo
+from paper_2309_12381_amd.fused_backward import FusedBackwardOptimizer
+from paper_2309_12381_amd import synth
+from oracle import ref
+
+from gpu_util import DEV, FMT, ROUND, host_f32, host_res, host_u16, say
+
+pytestmark = pytest.mark.gpu
+
+
+def _model(dtype, width=384, depth=3, seed=0):
+    torch.manual_seed(seed)
+    layers = [torch.nn.Linear(128, width), torch.nn.GELU()]
+    for _ in range(depth):
+        layers += [torch.nn.Linear(width, width), torch.nn.GELU(), torch.nn.LayerNorm(width)]
+    layers += [torch.nn.Linear(width, 10)]
+    return torch.nn.Sequential(*layers).to(DEV).to(dtype)
+
+
+@pytest.mark.parametrize("dtype,kind,kw", [
+    (torch.bfloat16, "adam", dict(lr=1e-3, weight_decay=1e-2)),
+    (torch.bfloat16, "adam", dict(lr=1e-3, grad_clip=1e-3, round=mpo.MPO_ROUND_STOCHASTIC, seed=77)),
+    (torch.float16, "adam", dict(lr=1e-3, loss_scale=256.0, grad_clip=0.01)),
+    (torch.bfloat16, "sgd", dict(lr=1e-2, momentum=0.9, weight_decay=2e-4)),
+], ids=["bf16-adamw", "bf16-adam-clip-stochastic", "fp16-adam-scaled-clip", "bf16-sgd"])
+@pytest.mark.parametrize("res_bits", [0, 7])
+def test_hooks_step_every_parameter_and_match_the_oracle(dtype, kind, kw, res_bits):
+    fmt = "bf16" if dtype == torch.bfloat16 else "fp16"
+    say("fused backward dtype=%s kind=%s kw=%s res_bits=%d" % (fmt, kind, kw, res_bits))
+    model = _model(dtype)
+    params = [p for p in model.parameters()]
+    w0 = [p.detach().float().cpu().numpy().reshape(-1).copy() for p in params]
+    ptrs = [p.data_ptr() for p in params]
+    cfg = (mpo.AdamCfg if kind == "adam" else mpo.SgdCfg)(**kw)
+    seen = []                                       # (index, gradient bits) in the order the hooks fired
+
+    def observer(i, g):
+        seen.append((i, synth.bits16(g.reshape(-1))))
+    opt = FusedBackwardOptimizer(params, cfg, res_bits=res_bits, observer=observer)
+    scale = kw.get("loss_scale", 1.0)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(5)
+    steps = 3
+    per_step = []
+    for t in range(steps):
+        x = torch.randn(64, 128, device=DEV, dtype=dtype, generator=g)
+        y = torch.randn(64, 10, device=DEV, dtype=dtype, generator=g)
+        opt.start_step()
+        seen.clear()
+        loss = torch.nn.functional.mse_loss(model(x).float(), y.float()) * scale
+        loss.backward()
+        torch.cuda.synchronize()
+        assert all(p.grad is None for p in params), "a gradient outlived backward"
+        assert sorted(i for i, _ in seen) == list(range(len(params))), "every parameter is stepped exactly once"
+        # autograd reaches the last layer's parameters first
+        assert seen[0][0] >= len(params) - 2 and seen[-1][0] <= 1
+        per_step.append(list(seen))
+    assert [p.data_ptr() for p in params] == ptrs, "the parameters were updated in place"
+
+    rf = FMT[fmt][1]
+    rkw = dict(kw)
+    rkw["round"] = {0: ref.TRUNC, 1: ref.NEAREST, 2: ref.STOCHASTIC}[kw.get("round", 0)]
+    rcfg = (ref.AdamCfg if kind == "adam" else ref.SgdCfg)(weight_fmt=rf, grad_fmt=rf, res_bits=res_bits, **rkw)
+    for i, p in enumerate(params):
+        hi, res = ref.split(w0[i], rf, res_bits, rcfg.round, rcfg.seed, i)
+        m = np.zeros(hi.size, np.float32)
+        v = np.zeros(hi.size, np.float32)
+        for t in range(steps):
+            gb = dict(per_step[t])[i]
+            if kind == "adam":
+                ref.adam_step(hi, res, gb, m, v, rcfg, t + 1, tensor_id=i)
+            else:
+                ref.sgd_step(hi, res, gb, m, rcfg, t + 1, tensor_id=i)
+        gres, gm, gv = opt.state_of(i)
+        assert np.array_equal(synth.bits16(p.detach().reshape(-1)), hi), "parameter %d: 16-bit weights differ" % i
+        assert np.array_equal(host_res(gres), res), "parameter %d: residual differs" % i
+        assert np.array_equal(host_f32(gm).view(np.uint32), m.view(np.uint32)), "parameter %d: m differs" % i
+        if kind == "adam":
+            assert np.array_equal(host_f32(gv).view(np.uint32), v.view(np.uint32)), "parameter %d: v differs" % i
+        want32 = ref.merge(hi, res, rf, res_bits, rcfg.round)
+        assert np.array_equal(host_f32(opt.master_fp32(i).reshape(-1)).view(np.uint32), want32.view(np.uint32))
+    opt.close()
+
+
+def test_start_step_is_required():
+    model = _model(torch.bfloat16, width=64, depth=1)
+    opt = FusedBackwardOptimizer(model.parameters(), mpo.AdamCfg())
+    x = torch.randn(4, 128, device=DEV, dtype=torch.bfloat16)
+    with pytest.raises(RuntimeError):
+        model(x).float().sum().backward()
+    opt.close()
+
+
+def test_fused_backward_lowers_peak_memory():
+    """Section 3.2: with the step fused into backward only one gradient is alive at a time.  Same
+    model, same data: the peak during backward drops by about the size of all gradients but one."""
+    width, depth = 2048, 12
+
+    def run(fused):
+        torch.manual_seed(1)
+        model = torch.nn.Sequential(*[torch.nn.Linear(width, width, bias=False) for _ in range(depth)]).to(DEV).to(torch.bfloat16)
+        opt = FusedBackwardOptimizer(model.parameters(), mpo.AdamCfg(lr=1e-4), fused=fused)
+        x = torch.randn(32, width, device=DEV, dtype=torch.bfloat16)
+        peaks = []
+        for _ in range(3):
+            opt.start_step()
+            torch.cuda.synchronize()
+            torch.cuda.reset_peak_memory_stats()
+            base = torch.cuda.memory_allocated()
+            model(x).float().pow(2).mean().backward()
+            if not fused:
+                opt.step()
+            torch.cuda.synchronize()
+            peaks.append(torch.cuda.max_memory_allocated() - base)
+        w = [p.detach().clone() for p in model.parameters()]
+        opt.close()
+        del model, opt
+        torch.cuda.empty_cache()
+        return max(peaks), w
+    say("peak memory, fused vs unfused backward")
+    peak_fused, w_fused = run(True)
+    peak_unfused, w_unfused = run(False)
+    grad_bytes = depth * width * width * 2
+    print("peak above resident state during forward+backward: fused %.1f MB, unfused %.1f MB, all gradients %.1f MB"
+          % (peak_fused / 1e6, peak_unfused / 1e6, grad_bytes / 1e6))
+    assert peak_unfused - peak_fused > 0.75 * grad_bytes * (depth - 1) / depth
+    for a, b in zip(w_fused, w_unfused):               # and the schedule does not change the result
+        assert torch.equal(a, b)

@@ -244,6 +244,8 @@ def _small_list(rng, count=41, total=1_500_000):
 
 
 LIST_CASES = [
+    ("adam", "bf16", dict(lr=1e-3, grad_clip=5e-4)),                                  # element clamp (Section 4.1)
+    ("sgd", "fp16", dict(lr=0.1, momentum=0.9, loss_scale=1024.0, grad_clip=1e-3)),
     ("adam", "bf16", dict(lr=1e-3, weight_decay=1e-4, decoupled_wd=True)),          # AdamW, configuration 1
     ("adam", "bf16", dict(lr=3e-4, beta1=0.64, beta2=0.95, eps=1e-6, weight_decay=0.1, decoupled_wd=False)),
     ("adam", "fp16", dict(lr=1e-3, loss_scale=1024.0)),

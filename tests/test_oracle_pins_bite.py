@@ -41,6 +41,7 @@ PINS = [
     ts.pins_partial_bits_is_truncation,
     tp.pins_partial_bits_master_equivalence,
     tp.pins_partial_bits_torch_optim,
+    tp.pins_grad_clip,
     tr.pins_philox,
     tr.pins_value_is_mode_independent,
     tr.pins_nearest_matches_library_cast,
@@ -92,6 +93,9 @@ MUTANTS = [
     ("partial bits: rounds up", "uint16_t kept = (uint16_t)(res_full >> (L->full - L->kept));",
      "uint16_t kept = (uint16_t)((res_full + (L->kept < L->full ? (1u << (L->full - L->kept - 1)) : 0u)) >> (L->full - L->kept));", 1),
     ("partial bits: fp16 uses the bf16 width", "L.full = fmt == MPO_REF_FP16 ? 13 : 16;", "L.full = 16;", 1),
+    ("clip: lower bound missing", "            if (g < -CLIP) g = -CLIP;\n", "", 2),
+    ("clip: applied to the scaled gradient", "        g = g * IS;\n        if (has_clip) {                    /* Sec. 4.1: element-wise clipping inside the step */\n            if (g > CLIP) g = CLIP;\n            if (g < -CLIP) g = -CLIP;\n        }\n",
+     "        if (has_clip) {\n            if (g > CLIP) g = CLIP;\n            if (g < -CLIP) g = -CLIP;\n        }\n        g = g * IS;\n", 2),
     ("rounding: value not un-rounded", "*hi_trunc = (uint16_t)(hi[i] - was_rounded_up);", "*hi_trunc = hi[i];", 1),
     ("rounding: probability inverted", "draw(L, i) < res_full;", "draw(L, i) >= res_full;", 1),
     ("rounding: flag in the wrong bit", "kept = (uint16_t)(kept | (up << L->kept));", "kept = (uint16_t)(kept | (up << 15));", 1),

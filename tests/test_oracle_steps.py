@@ -628,3 +628,60 @@ def pins_partial_bits_torch_optim(ref):
 
 def test_partial_bits_torch_optim(ref):
     pins_partial_bits_torch_optim(ref)
+
+
+# ---- element-wise gradient clipping inside the step (Section 4.1) ---------------------------------
+
+def pins_grad_clip(ref):
+    """Clipping the gradient in the step equals clamping it beforehand (torch.clamp on the un-scaled
+    gradient, then an unclipped step), bit for bit; a huge bound changes nothing."""
+    rng = np.random.default_rng(59)
+    n = 4096
+    w0, _ = make_state(rng, n)
+    for scale in (1.0, 128.0):
+        for clip in (5e-4, 2.0 ** -12):
+            out = []
+            for fused in (True, False):
+                hi, res = ref.split(w0)
+                m = np.zeros(n, np.float32); v = np.zeros(n, np.float32)
+                buf = np.zeros(n, np.float32)
+                hs, rs = ref.split(w0)
+                r2 = np.random.default_rng(61)
+                for t in range(1, 8):
+                    g32 = (r2.standard_normal(n) * 1e-3).astype(np.float32)
+                    g32[:4] = [clip, -clip, np.float32(clip) * 2, -1.0]
+                    gb = to_bf16_bits(g32 * np.float32(scale))
+                    if fused:
+                        ref.adam_step(hi, res, gb, m, v, ref.AdamCfg(loss_scale=scale, grad_clip=clip), t)
+                        ref.sgd_step(hs, rs, gb, buf, ref.SgdCfg(loss_scale=scale, grad_clip=clip), t)
+                    else:
+                        # clamp outside: un-scale exactly (power of two), clamp with the library, hand over unscaled
+                        g = torch.clamp(torch.from_numpy(bf16_to_f32(gb) / np.float32(scale)), -np.float32(clip), np.float32(clip))
+                        gb2 = to_bf16_bits(g.numpy())
+                        exact = np.array_equal(bf16_to_f32(gb2), g.numpy())
+                        assert exact or clip != 2.0 ** -12          # a power-of-two bound stays on the bf16 grid
+                        if not exact:
+                            break
+                        ref.adam_step(hi, res, gb2, m, v, ref.AdamCfg(), t)
+                        ref.sgd_step(hs, rs, gb2, buf, ref.SgdCfg(), t)
+                else:
+                    out.append([a.copy() for a in (hi, res, m, v, hs, rs, buf)])
+            if len(out) == 2:
+                for a, b in zip(*out):
+                    assert np.array_equal(a.view(np.uint8), b.view(np.uint8)), (scale, clip)
+    # clipped gradients bound the first Adam step's moments: |m| <= (1-b1)*clip
+    hi, res = ref.split(w0)
+    m = np.zeros(n, np.float32); v = np.zeros(n, np.float32)
+    gb = to_bf16_bits((rng.standard_normal(n)).astype(np.float32))
+    ref.adam_step(hi, res, gb, m, v, ref.AdamCfg(grad_clip=0.25), 1)
+    assert np.all(np.abs(m) <= np.float32(0.1) * np.float32(0.25) * (1 + 1e-6)) and np.mean(np.abs(m) > 0.02) > 0.5
+    # a bound nothing reaches leaves the step unchanged
+    a = ref.split(w0); b = ref.split(w0)
+    ma = np.zeros(n, np.float32); va = np.zeros(n, np.float32); mb = np.zeros(n, np.float32); vb = np.zeros(n, np.float32)
+    ref.adam_step(a[0], a[1], gb, ma, va, ref.AdamCfg(grad_clip=1e30), 1)
+    ref.adam_step(b[0], b[1], gb, mb, vb, ref.AdamCfg(), 1)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(ma, mb)
+
+
+def test_grad_clip(ref):
+    pins_grad_clip(ref)
