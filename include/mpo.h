@@ -166,7 +166,10 @@ typedef struct mpo_plan mpo_plan;
  * chunk table and tensor descriptors to the current device once.  The plan
  * owns only that table (a few MB); free it with mpo_plan_destroy.  The list is
  * copied: `tensors` may be freed after the call.  nt == 0 gives a valid empty
- * plan.  mpo_plan_destroy(NULL) is a no-op. */
+ * plan.  mpo_plan_destroy(NULL) is a no-op.  A plan belongs to the device that
+ * was current when it was created: stepping it with another device current is
+ * MPO_ERR_INVALID_ARG.  Step calls are plain kernel launches and may be
+ * captured into a HIP graph (the step number is then fixed in the graph). */
 mpo_status mpo_plan_create(const mpo_tensor *tensors, uint64_t nt, mpo_plan **out);
 mpo_status mpo_plan_destroy(mpo_plan *plan);
 

@@ -280,6 +280,11 @@ bool state_present(const mpo_plan *p, uint64_t k0, uint64_t nk, const StepLaunch
 
 mpo_status run(mpo_plan *p, StepLaunch &L, void *stream)
 {
+    /* the table and the descriptors live on the device the plan was created on */
+    int dev = -1;
+    const hipError_t de = hipGetDevice(&dev);
+    if (de != hipSuccess) return hip_fail(de);
+    if (dev != p->device) return MPO_ERR_INVALID_ARG;
     if ((int)p->max_res_bits > full_res_bits(L.wfmt)) return MPO_ERR_INVALID_ARG;
     if (L.s.round == MPO_ROUND_STOCHASTIC && p->max_res_bits > (p->res_slot == 1 ? 7u : 15u)) return MPO_ERR_INVALID_ARG;
     L.rmode = p->res_slot == 1 ? kResByte : (p->any_explicit_bits ? kResPartial : kResFull);

@@ -708,3 +708,44 @@ def test_stochastic_argument_checks_on_device():
     mpo.mpo_adam_step(plan, mpo.AdamCfg(round=mpo.MPO_ROUND_NEAREST), 1)
     torch.cuda.synchronize()
     plan.destroy()
+
+
+def test_step_can_be_captured_in_a_hip_graph_and_replayed():
+    """A step is nothing but kernel launches on the caller's stream: it can be captured and
+    replayed.  The step number is part of the captured arguments, so every replay applies the
+    same step's scalars; each replay is checked against the oracle, with eager work and
+    synchronisation between the replays."""
+    n = 3 * CHUNK + 5
+    shapes = [(0, n), (1, 2 * CHUNK), (1, 77)]
+    w0s = [synth.gen_weights(k, 90 + i, "cpu", 0.02).numpy() for i, (_, k) in enumerate(shapes)]
+    devs = [DevTensor(w, mpo.MPO_BF16, layer=ly) for w, (ly, _) in zip(w0s, shapes)]
+    hosts = [HostTensor(w, ref.BF16) for w in w0s]
+    gs = [synth.bits16(synth.gen_grads(k, 95 + i, "cpu", 1e-3)) for i, (_, k) in enumerate(shapes)]
+    for d, g in zip(devs, gs):
+        d.grad.copy_(dev_u16(g))
+    plan = mpo.Plan([d.spec() for d in devs])
+    cfg, rcfg = cfg_pair("adam", "bf16", lr=1e-3, weight_decay=1e-2)
+    say("hip graph capture")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        mpo.mpo_adam_step(plan, cfg, 1, stream=side)          # eager, also warms everything up
+    side.synchronize()
+    for h, g in zip(hosts, gs):
+        ref.adam_step(h.hi, h.res, g, h.m, h.v, rcfg, 1)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        mpo.mpo_step_layer(plan, 1, cfg, 2, stream=torch.cuda.current_stream())
+        mpo.mpo_step_layer(plan, 0, cfg, 2, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for d, h in zip(devs, hosts):
+        assert_state_equal(d, h, "capture must not execute")
+    for replay in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        for h, g in zip(hosts, gs):
+            ref.adam_step(h.hi, h.res, g, h.m, h.v, rcfg, 2)
+        for i, (d, h) in enumerate(zip(devs, hosts)):
+            assert_state_equal(d, h, "replay %d tensor %d" % (replay, i))
+        junk = torch.randn(1 << 20, device=DEV).sum().item()          # eager work between replays
+    plan.destroy()
