@@ -133,13 +133,66 @@ typedef struct {
     int full;      /* dropped bits of the format: 16 (bf16) or 13 (fp16) */
     int kept;      /* E: bits of them that are stored                    */
     int byte_slot; /* residual array is uint8_t                          */
+    int packed;    /* residual stored in bit planes (Figure 1)           */
+    uint64_t n;    /* number of values: fixes where each plane starts    */
     uint64_t seed;
     uint32_t tensor_id, step32;
 } res_layout;
 
-static res_layout make_layout(int fmt, int res_bits, int round, uint64_t seed, uint32_t tensor_id, uint64_t step)
+static uint64_t round16(uint64_t x) { return (x + 15u) / 16u * 16u; }
+
+/* Packed storage: value i of a plane of width w (8, 4 or 2 bits) */
+static uint32_t plane_get(const uint8_t *plane, uint64_t i, int w)
+{
+    uint64_t bit = i * (uint64_t)w;
+    return (plane[bit / 8] >> (bit % 8)) & ((1u << w) - 1u);
+}
+
+static void plane_put(uint8_t *plane, uint64_t i, int w, uint32_t x)
+{
+    uint64_t bit = i * (uint64_t)w;
+    uint8_t mask = (uint8_t)(((1u << w) - 1u) << (bit % 8));
+    plane[bit / 8] = (uint8_t)((plane[bit / 8] & ~mask) | ((x << (bit % 8)) & mask));
+}
+
+/* The E kept bits of value i, assembled from / distributed to the planes: the 8-bit piece holds
+ * the leading bits, then the 4-bit piece, then the 2-bit piece. */
+static uint16_t packed_get(const uint8_t *base, uint64_t n, uint64_t i, int E)
+{
+    uint32_t r = 0;
+    const uint8_t *plane = base;
+    if (E & 8) { r = (r << 8) | plane_get(plane, i, 8); plane += round16(n); }
+    if (E & 4) { r = (r << 4) | plane_get(plane, i, 4); plane += round16((n + 1) / 2); }
+    if (E & 2) { r = (r << 2) | plane_get(plane, i, 2); }
+    return (uint16_t)r;
+}
+
+static void packed_put(uint8_t *base, uint64_t n, uint64_t i, int E, uint16_t r)
+{
+    uint8_t *plane = base;
+    int left = E;
+    if (E & 8) { left -= 8; plane_put(plane, i, 8, (r >> left) & 0xFFu); plane += round16(n); }
+    if (E & 4) { left -= 4; plane_put(plane, i, 4, (r >> left) & 0xFu); plane += round16((n + 1) / 2); }
+    if (E & 2) { left -= 2; plane_put(plane, i, 2, (r >> left) & 0x3u); }
+}
+
+uint64_t mpo_ref_res_bytes(uint64_t n, int fmt, int res_bits, int res_packed)
+{
+    (void)fmt;
+    if (!res_packed) return n * (uint64_t)((res_bits >= 1 && res_bits <= 8) ? 1 : 2);
+    uint64_t b = 0;
+    if (res_bits & 8) b += round16(n);
+    if (res_bits & 4) b += round16((n + 1) / 2);
+    if (res_bits & 2) b += round16((n + 3) / 4);
+    return b;
+}
+
+static res_layout make_layout(int fmt, int res_bits, int packed, uint64_t n, int round, uint64_t seed,
+                              uint32_t tensor_id, uint64_t step)
 {
     res_layout L;
+    L.packed = packed;
+    L.n = n;
     L.fmt = fmt;
     L.round = round;
     L.full = fmt == MPO_REF_FP16 ? 13 : 16;
@@ -168,7 +221,8 @@ static uint32_t draw(const res_layout *L, uint64_t i)
 static void load_pair(const uint16_t *hi, const void *res, uint64_t i, const res_layout *L,
                       uint16_t *hi_trunc, uint16_t *res_full)
 {
-    uint16_t stored = L->byte_slot ? ((const uint8_t *)res)[i] : ((const uint16_t *)res)[i];
+    uint16_t stored = L->packed ? packed_get((const uint8_t *)res, L->n, i, L->kept)
+                    : L->byte_slot ? ((const uint8_t *)res)[i] : ((const uint16_t *)res)[i];
     uint16_t kept = (uint16_t)(stored & ((1u << L->kept) - 1u));
     uint16_t full = (uint16_t)(kept << (L->full - L->kept));
     int was_rounded_up = 0;
@@ -192,7 +246,9 @@ static void store_pair(uint16_t *hi, void *res, uint64_t i, const res_layout *L,
     uint16_t kept = (uint16_t)(res_full >> (L->full - L->kept));
     if (L->round == MPO_REF_STOCHASTIC) kept = (uint16_t)(kept | (up << L->kept));
     hi[i] = (uint16_t)(hi_trunc + up);
-    if (L->byte_slot) ((uint8_t *)res)[i] = (uint8_t)kept; else ((uint16_t *)res)[i] = kept;
+    if (L->packed) packed_put((uint8_t *)res, L->n, i, L->kept, kept);
+    else if (L->byte_slot) ((uint8_t *)res)[i] = (uint8_t)kept;
+    else ((uint16_t *)res)[i] = kept;
 }
 
 /* A 16-bit float read as fp32: every bf16 and fp16 value is an fp32 value. */
@@ -201,10 +257,10 @@ float mpo_ref_cvt16(uint16_t x, int fmt)
     return fmt == MPO_REF_FP16 ? merge_fp16(x, 0) : merge_bf16(x, 0);
 }
 
-void mpo_ref_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits,
+void mpo_ref_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits, int res_packed,
                    int round, uint64_t seed, uint32_t tensor_id)
 {
-    res_layout L = make_layout(fmt, res_bits, round, seed, tensor_id, 0);
+    res_layout L = make_layout(fmt, res_bits, res_packed, n, round, seed, tensor_id, 0);
     for (uint64_t i = 0; i < n; ++i) {
         uint16_t h, full;
         split_one(w32[i], &h, &full, fmt);
@@ -212,9 +268,10 @@ void mpo_ref_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fm
     }
 }
 
-void mpo_ref_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits, int round)
+void mpo_ref_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits, int res_packed,
+                   int round)
 {
-    res_layout L = make_layout(fmt, res_bits, round, 0, 0, 0);
+    res_layout L = make_layout(fmt, res_bits, res_packed, n, round, 0, 0, 0);
     for (uint64_t i = 0; i < n; ++i) {
         uint16_t h, full;
         load_pair(hi, res, i, &L, &h, &full);
@@ -233,7 +290,7 @@ void mpo_ref_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, 
 void mpo_ref_adam_step(uint16_t *hi, void *res, const uint16_t *grad, float *m, float *v,
                        uint64_t n, const mpo_ref_adam_cfg *cfg, uint64_t step, uint32_t tensor_id)
 {
-    const res_layout L = make_layout(cfg->weight_fmt, cfg->res_bits, cfg->round, cfg->seed, tensor_id, step);
+    const res_layout L = make_layout(cfg->weight_fmt, cfg->res_bits, cfg->res_packed, n, cfg->round, cfg->seed, tensor_id, step);
     const double t = (double)step;
     const float B1 = (float)cfg->beta1;
     const float B2 = (float)cfg->beta2;
@@ -292,7 +349,7 @@ void mpo_ref_sgd_step(uint16_t *hi, void *res, const uint16_t *grad, float *buf,
                       uint64_t n, const mpo_ref_sgd_cfg *cfg, uint64_t step, uint32_t tensor_id)
 {
     /* momentum buffers start at zero, so step 1 needs no special case */
-    const res_layout L = make_layout(cfg->weight_fmt, cfg->res_bits, cfg->round, cfg->seed, tensor_id, step);
+    const res_layout L = make_layout(cfg->weight_fmt, cfg->res_bits, cfg->res_packed, n, cfg->round, cfg->seed, tensor_id, step);
     const float LR = (float)cfg->lr;
     const float MU = (float)cfg->momentum;
     const float WD = (float)cfg->weight_decay;

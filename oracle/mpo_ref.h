@@ -59,6 +59,16 @@ enum { MPO_REF_BF16 = 0, MPO_REF_FP16 = 1 };
  * word i%4, its top `full` bits.  The initial split uses step 0. */
 enum { MPO_REF_TRUNC = 0, MPO_REF_NEAREST = 1, MPO_REF_STOCHASTIC = 2 };
 
+/* Packed storage (Section 3.1, Figure 1: the extra bits of many values packed without
+ * padding).  With res_packed != 0 and an even E in 2..14 the residual is stored in bit planes
+ * instead of one slot per value: the E kept bits are cut, from the top, into an 8-bit, a 4-bit
+ * and a 2-bit piece (those that E contains: E = 8a + 4b + 2c); each piece has its own dense
+ * array ("plane") in which value i occupies bits [w*i, w*i + w) (w = 8, 4, 2; little-endian
+ * within a byte).  The planes follow each other in the residual buffer in that order, each
+ * starting at a multiple of 16 bytes: sizes round16(n), round16(ceil(n/2)), round16(ceil(n/4)).
+ * E bits per value, nothing wasted: 12 extra bits take 1.5 bytes. */
+uint64_t mpo_ref_res_bytes(uint64_t n, int fmt, int res_bits, int res_packed);
+
 typedef struct {
     double lr, beta1, beta2, eps, weight_decay;
     int32_t decoupled_wd; /* 1: AdamW (w *= 1-lr*wd), 0: L2 (g += wd*w)      */
@@ -66,6 +76,7 @@ typedef struct {
     int32_t weight_fmt;   /* format of hi                                     */
     int32_t grad_fmt;     /* format of grad                                   */
     int32_t res_bits;     /* extra bits kept, 0 = all                         */
+    int32_t res_packed;   /* residual stored in bit planes                    */
     int32_t round;        /* MPO_REF_TRUNC / NEAREST / STOCHASTIC             */
     uint64_t seed;        /* STOCHASTIC only                                  */
     double grad_clip;     /* Section 4.1: clamp the un-scaled gradient to [-c, c]; 0 = off */
@@ -76,16 +87,17 @@ typedef struct {
     double loss_scale;
     int32_t weight_fmt, grad_fmt;
     int32_t res_bits;
+    int32_t res_packed;
     int32_t round;
     uint64_t seed;
     double grad_clip;
 } mpo_ref_sgd_cfg;
 
 /* Section 3.1, Table 1: fp32 -> (16-bit float, extra bits), truncation. */
-void mpo_ref_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits,
+void mpo_ref_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits, int res_packed,
                    int round, uint64_t seed, uint32_t tensor_id);
 /* Section 3.1: (16-bit float, extra bits) -> fp32. */
-void mpo_ref_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits,
+void mpo_ref_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits, int res_packed,
                    int round);
 
 /* Section 3.1 "classic optimizers": bias-corrected Adam / AdamW on one tensor. */

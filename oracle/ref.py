@@ -33,14 +33,16 @@ class _AdamCfg(ctypes.Structure):
                 ("eps", ctypes.c_double), ("weight_decay", ctypes.c_double),
                 ("decoupled_wd", ctypes.c_int32), ("loss_scale", ctypes.c_double),
                 ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32), ("res_bits", ctypes.c_int32),
-                ("round", ctypes.c_int32), ("seed", ctypes.c_uint64), ("grad_clip", ctypes.c_double)]
+                ("res_packed", ctypes.c_int32), ("round", ctypes.c_int32), ("seed", ctypes.c_uint64),
+                ("grad_clip", ctypes.c_double)]
 
 
 class _SgdCfg(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_double), ("momentum", ctypes.c_double),
                 ("weight_decay", ctypes.c_double), ("loss_scale", ctypes.c_double),
                 ("weight_fmt", ctypes.c_int32), ("grad_fmt", ctypes.c_int32), ("res_bits", ctypes.c_int32),
-                ("round", ctypes.c_int32), ("seed", ctypes.c_uint64), ("grad_clip", ctypes.c_double)]
+                ("res_packed", ctypes.c_int32), ("round", ctypes.c_int32), ("seed", ctypes.c_uint64),
+                ("grad_clip", ctypes.c_double)]
 
 
 def res_dtype(res_bits: int):
@@ -63,11 +65,12 @@ class AdamCfg:
     round: int = TRUNC
     seed: int = 0
     grad_clip: float = 0.0
+    res_packed: bool = False
 
     def _c(self):
         return _AdamCfg(self.lr, self.beta1, self.beta2, self.eps, self.weight_decay,
                         int(self.decoupled_wd), self.loss_scale, self.weight_fmt, self.grad_fmt, self.res_bits,
-                        self.round, self.seed, self.grad_clip)
+                        int(self.res_packed), self.round, self.seed, self.grad_clip)
 
 
 @dataclass
@@ -82,10 +85,12 @@ class SgdCfg:
     round: int = TRUNC
     seed: int = 0
     grad_clip: float = 0.0
+    res_packed: bool = False
 
     def _c(self):
         return _SgdCfg(self.lr, self.momentum, self.weight_decay, self.loss_scale,
-                       self.weight_fmt, self.grad_fmt, self.res_bits, self.round, self.seed, self.grad_clip)
+                       self.weight_fmt, self.grad_fmt, self.res_bits, int(self.res_packed), self.round, self.seed,
+                       self.grad_clip)
 
 
 def _chk(a, dtype, n=None):
@@ -120,10 +125,12 @@ class Oracle:
     def __init__(self, path):
         lib = ctypes.CDLL(path)
         lib.mpo_ref_split.argtypes = [_f32p, _u16p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int, ctypes.c_int,
-                                      ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32]
+                                      ctypes.c_int, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32]
+        lib.mpo_ref_res_bytes.argtypes = [ctypes.c_uint64, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        lib.mpo_ref_res_bytes.restype = ctypes.c_uint64
         lib.mpo_ref_split.restype = None
         lib.mpo_ref_merge.argtypes = [_u16p, ctypes.c_void_p, _f32p, ctypes.c_uint64, ctypes.c_int, ctypes.c_int,
-                                      ctypes.c_int]
+                                      ctypes.c_int, ctypes.c_int]
         lib.mpo_ref_merge.restype = None
         lib.mpo_ref_adam_step.argtypes = [_u16p, ctypes.c_void_p, _u16p, _f32p, _f32p, ctypes.c_uint64,
                                           ctypes.POINTER(_AdamCfg), ctypes.c_uint64, ctypes.c_uint32]
@@ -145,27 +152,37 @@ class Oracle:
         self._lib.mpo_ref_philox4x32_10(c, k, o)
         return list(o)
 
-    def split(self, w32, fmt=BF16, res_bits=0, round=TRUNC, seed=0, tensor_id=0):
-        """fp32 array -> (hi uint16, res uint16 or uint8) arrays."""
+    def res_bytes(self, n, fmt=BF16, res_bits=0, packed=False):
+        return int(self._lib.mpo_ref_res_bytes(n, fmt, res_bits, int(packed)))
+
+    def _res_ok(self, res, n, fmt, res_bits, packed):
+        if packed:
+            _chk(res, np.uint8, self.res_bytes(n, fmt, res_bits, True))
+        else:
+            _chk(res, res_dtype(res_bits), n)
+
+    def split(self, w32, fmt=BF16, res_bits=0, round=TRUNC, seed=0, tensor_id=0, packed=False):
+        """fp32 array -> (hi uint16, res) arrays; res is uint16 or uint8 per value, or with
+        packed=True the bit planes as one uint8 array."""
         _chk(w32, np.float32)
         n = w32.shape[0]
         hi = np.empty(n, np.uint16)
-        res = np.empty(n, res_dtype(res_bits))
-        self._lib.mpo_ref_split(_p32(w32), _p16(hi), _pv(res), n, fmt, res_bits, round, seed, tensor_id)
+        res = np.zeros(self.res_bytes(n, fmt, res_bits, True), np.uint8) if packed else np.empty(n, res_dtype(res_bits))
+        self._lib.mpo_ref_split(_p32(w32), _p16(hi), _pv(res), n, fmt, res_bits, int(packed), round, seed, tensor_id)
         return hi, res
 
-    def merge(self, hi, res, fmt=BF16, res_bits=0, round=TRUNC):
+    def merge(self, hi, res, fmt=BF16, res_bits=0, round=TRUNC, packed=False):
         """(hi, res) arrays -> fp32 array."""
         n = _chk(hi, np.uint16).shape[0]
-        _chk(res, res_dtype(res_bits), n)
+        self._res_ok(res, n, fmt, res_bits, packed)
         w32 = np.empty(n, np.float32)
-        self._lib.mpo_ref_merge(_p16(hi), _pv(res), _p32(w32), n, fmt, res_bits, round)
+        self._lib.mpo_ref_merge(_p16(hi), _pv(res), _p32(w32), n, fmt, res_bits, int(packed), round)
         return w32
 
     def adam_step(self, hi, res, grad, m, v, cfg: AdamCfg, step: int, tensor_id: int = 0):
         """One Adam step on one tensor, in place on hi, res, m, v."""
         n = _chk(hi, np.uint16).shape[0]
-        _chk(res, res_dtype(cfg.res_bits), n)
+        self._res_ok(res, n, cfg.weight_fmt, cfg.res_bits, cfg.res_packed)
         _chk(grad, np.uint16, n)
         _chk(m, np.float32, n)
         _chk(v, np.float32, n)
@@ -178,7 +195,7 @@ class Oracle:
     def sgd_step(self, hi, res, grad, buf, cfg: SgdCfg, step: int, tensor_id: int = 0):
         """One SGD(-momentum) step on one tensor, in place on hi, res, buf."""
         n = _chk(hi, np.uint16).shape[0]
-        _chk(res, res_dtype(cfg.res_bits), n)
+        self._res_ok(res, n, cfg.weight_fmt, cfg.res_bits, cfg.res_packed)
         _chk(grad, np.uint16, n)
         if cfg.momentum != 0.0:
             _chk(buf, np.float32, n)
@@ -203,3 +220,4 @@ adam_step = _default.adam_step
 sgd_step = _default.sgd_step
 cvt16 = _default.cvt16
 philox = _default.philox
+res_bytes = _default.res_bytes

@@ -39,6 +39,7 @@ PINS = [
     lambda r: ts.pins_partial_bits_value_definition(r, "bf16"),
     lambda r: ts.pins_partial_bits_value_definition(r, "fp16"),
     ts.pins_partial_bits_is_truncation,
+    ts.pins_packed_storage,
     tp.pins_partial_bits_master_equivalence,
     tp.pins_partial_bits_torch_optim,
     tp.pins_grad_clip,
@@ -93,6 +94,16 @@ MUTANTS = [
     ("partial bits: rounds up", "uint16_t kept = (uint16_t)(res_full >> (L->full - L->kept));",
      "uint16_t kept = (uint16_t)((res_full + (L->kept < L->full ? (1u << (L->full - L->kept - 1)) : 0u)) >> (L->full - L->kept));", 1),
     ("partial bits: fp16 uses the bf16 width", "L.full = fmt == MPO_REF_FP16 ? 13 : 16;", "L.full = 16;", 1),
+    ("packed: pieces in the wrong order", "    if (E & 8) { left -= 8; plane_put(plane, i, 8, (r >> left) & 0xFFu); plane += round16(n); }",
+     "    if (E & 8) { plane_put(plane, i, 8, r & 0xFFu); plane += round16(n); }", 1),
+    ("packed: planes not aligned", "static uint64_t round16(uint64_t x) { return (x + 15u) / 16u * 16u; }",
+     "static uint64_t round16(uint64_t x) { return x; }", 1),
+    ("packed: high nibble first", "    return (plane[bit / 8] >> (bit % 8)) & ((1u << w) - 1u);",
+     "    return (plane[bit / 8] >> ((8 - w) - bit % 8)) & ((1u << w) - 1u);", 1),
+    ("packed: put clobbers the neighbours", "    plane[bit / 8] = (uint8_t)((plane[bit / 8] & ~mask) | ((x << (bit % 8)) & mask));",
+     "    plane[bit / 8] = (uint8_t)((x << (bit % 8)) & mask);", 1),
+    ("packed: nibble plane offset", "    if (E & 4) { r = (r << 4) | plane_get(plane, i, 4); plane += round16((n + 1) / 2); }",
+     "    if (E & 4) { r = (r << 4) | plane_get(plane, i, 4); plane += round16(n); }", 1),
     ("clip: lower bound missing", "            if (g < -CLIP) g = -CLIP;\n", "", 2),
     ("clip: applied to the scaled gradient", "        g = g * IS;\n        if (has_clip) {                    /* Sec. 4.1: element-wise clipping inside the step */\n            if (g > CLIP) g = CLIP;\n            if (g < -CLIP) g = -CLIP;\n        }\n",
      "        if (has_clip) {\n            if (g > CLIP) g = CLIP;\n            if (g < -CLIP) g = -CLIP;\n        }\n        g = g * IS;\n", 2),

@@ -312,3 +312,64 @@ def pins_partial_bits_is_truncation(ref):
 
 def test_partial_bits_is_truncation(ref):
     pins_partial_bits_is_truncation(ref)
+
+
+# ---- packed storage of the extra bits (Section 3.1, Figure 1) -----------------------------------
+
+def unpack_planes(buf: np.ndarray, n: int, E: int) -> np.ndarray:
+    """Independent decoder of the packed layout, from its description: an 8-bit, a 4-bit and a
+    2-bit plane (those E contains), in that order, each starting at a multiple of 16 bytes, value i
+    at bits [w*i, w*i+w) of its plane, little-endian; the 8-bit piece holds the leading bits."""
+    bits = np.unpackbits(buf, bitorder="little")
+    out = np.zeros(n, np.uint32)
+    pos = 0                                             # byte offset of the current plane
+    for w in (8, 4, 2):
+        if not E & w:
+            continue
+        plane = bits[8 * pos: 8 * pos + w * n].reshape(n, w)
+        val = (plane.astype(np.uint32) << np.arange(w, dtype=np.uint32)).sum(axis=1)
+        out = (out << w) | val
+        pos += (((n * w + 7) // 8) + 15) // 16 * 16
+    assert pos == buf.size
+    return out
+
+
+def pins_packed_storage(ref):
+    rng = np.random.default_rng(71)
+    for fmt, full in ((ref.BF16, 16), (ref.FP16, 13)):
+        for n in (1, 2, 3, 5, 16, 31, 33, 4099):
+            x = (rng.standard_normal(n) * 0.02).astype(np.float32)
+            for E in (2, 4, 6, 8, 10, 12) + ((14,) if full == 16 else ()):
+                hi_s, res_s = ref.split(x, fmt, E)                       # one slot per value
+                hi_p, buf = ref.split(x, fmt, E, packed=True)
+                assert buf.dtype == np.uint8 and buf.size == ref.res_bytes(n, fmt, E, True)
+                # E bits per value and nothing more (up to the 16-byte rounding of each plane)
+                assert buf.size <= (n * E + 7) // 8 + 3 * 16
+                assert np.array_equal(hi_p, hi_s)
+                assert np.array_equal(unpack_planes(buf, n, E), res_s.astype(np.uint32)), (fmt, n, E)
+                assert np.array_equal(ref.merge(hi_p, buf, fmt, E, packed=True).view(np.uint32),
+                                      ref.merge(hi_s, res_s, fmt, E).view(np.uint32))
+    # steps on packed storage hold the same values as steps on slots
+    n = 1003
+    x = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    for E in (12, 4, 10):
+        a_hi, a_res = ref.split(x, ref.BF16, E)
+        b_hi, b_buf = ref.split(x, ref.BF16, E, packed=True)
+        ma = np.zeros(n, np.float32); va = np.zeros(n, np.float32); mb = np.zeros(n, np.float32); vb = np.zeros(n, np.float32)
+        sa_hi, sa_res = ref.split(x, ref.BF16, E)
+        sb_hi, sb_buf = ref.split(x, ref.BF16, E, packed=True)
+        ba = np.zeros(n, np.float32); bb = np.zeros(n, np.float32)
+        for t in range(1, 6):
+            g = rng.integers(0x3800, 0x3A00, n).astype(np.uint16)
+            ref.adam_step(a_hi, a_res, g, ma, va, ref.AdamCfg(res_bits=E), t)
+            ref.adam_step(b_hi, b_buf, g, mb, vb, ref.AdamCfg(res_bits=E, res_packed=True), t)
+            ref.sgd_step(sa_hi, sa_res, g, ba, ref.SgdCfg(res_bits=E), t)
+            ref.sgd_step(sb_hi, sb_buf, g, bb, ref.SgdCfg(res_bits=E, res_packed=True), t)
+        assert np.array_equal(a_hi, b_hi) and np.array_equal(ma, mb) and np.array_equal(va, vb)
+        assert np.array_equal(unpack_planes(b_buf, n, E), a_res.astype(np.uint32))
+        assert np.array_equal(sa_hi, sb_hi) and np.array_equal(ba, bb)
+        assert np.array_equal(unpack_planes(sb_buf, n, E), sa_res.astype(np.uint32))
+
+
+def test_packed_storage(ref):
+    pins_packed_storage(ref)
