@@ -78,6 +78,8 @@ def main():
     ap.add_argument("--res-bits", type=int, default=0,
                     help="extra bits kept per weight: 0 = all (the headline), 8 = the paper's bf16+8 / fp16+8 "
                          "(byte residual, 24 B per parameter for Adam)")
+    ap.add_argument("--res-packed", action="store_true",
+                    help="store the extra bits in packed planes (even --res-bits from 2 to 14, e.g. 12: 1.5 B per weight)")
     ap.add_argument("--round", default="trunc", choices=["trunc", "nearest", "stochastic"],
                     help="rounding of the 16-bit value: trunc is the method's base mode and the headline")
     ap.add_argument("--fresh-grads", action="store_true",
@@ -103,7 +105,7 @@ def main():
     wl = synth.workload(a.workload)
     steps = a.steps if a.steps is not None else wl.steps
     t_setup = time.perf_counter()
-    st = harness.ModelState(wl, dev, res_bits=a.res_bits,
+    st = harness.ModelState(wl, dev, res_bits=a.res_bits, res_packed=a.res_packed,
                             round={"trunc": 0, "nearest": 1, "stochastic": 2}[a.round])
     if wl.per_layer:
         # the reused buffer holds one (largest) layer's worth of gradient values, read by every layer
@@ -116,7 +118,10 @@ def main():
     stream = torch.cuda.current_stream()
     cfg = st.adam_cfg() if a.optimizer == "adam" else st.sgd_cfg()
     bpp = ADAM_BYTES_PER_PARAM if a.optimizer == "adam" else SGD_BYTES_PER_PARAM
-    bpp -= 2 * (2 - st.res_bytes)            # a byte residual is read and written as 1 B instead of 2
+    if a.res_packed:
+        bpp += 2 * (a.res_bits / 8.0 - 2.0)  # packed planes: res_bits/8 bytes read and written instead of 2
+    else:
+        bpp -= 2 * (2 - st.res_bytes)        # a byte residual is read and written as 1 B instead of 2
     step_no = 0
     for _ in range(a.warmup):
         step_no += 1
@@ -145,16 +150,16 @@ def main():
         "ms_per_step": wall * 1e3 / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: %s" % (wl.key, wl.description), "params": P, "tensors": len(wl.tensors),
-                   "format": "%s+%d extra bits (%d-bit residual)" % (wl.fmt, a.res_bits or (13 if wl.fmt == "fp16" else
-                                                                                        15 if a.round == "stochastic" else 16),
-                                                                      8 * st.res_bytes), "optimizer": wl.optimizer if a.optimizer == "adam" else "sgd-momentum", "round": a.round, "loss_scale": wl.loss_scale,
+                   "format": "%s+%d extra bits (%s)" % (wl.fmt, a.res_bits or (13 if wl.fmt == "fp16" else
+                                                                           15 if a.round == "stochastic" else 16),
+                                                        "packed planes" if a.res_packed else "%d-bit residual" % (8 * st.res_bytes)), "optimizer": wl.optimizer if a.optimizer == "adam" else "sgd-momentum", "round": a.round, "loss_scale": wl.loss_scale,
                    "launches_per_step": launches // steps, "per_layer": wl.per_layer,
                    "fresh_grads_in_loop": bool(a.fresh_grads), "resident_GB": st.resident_bytes / 1e9},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                      "frac": achieved / PEAK_HBM_GBPS,
                      "traffic": (MEASURED_TRAFFIC_BYTES_PER_PARAM[wl.key] * P * steps / launches
                                  if wl.key in MEASURED_TRAFFIC_BYTES_PER_PARAM and a.optimizer == "adam" and st.res_bytes == 2
-                                 else None),
+                                 and not a.res_packed else None),
                      "kernel": "step_kernel<%s,%s>" % (a.optimizer, wl.fmt), "bytes_per_param": bpp,
                      "bytes_per_launch": bytes_per_launch, "avg_launch_ms": ev_ms / launches,
                      "event_ms": ev_ms, "launches": launches},

@@ -82,7 +82,20 @@ typedef enum { MPO_OPT_ADAM = 0, MPO_OPT_SGD = 1 } mpo_opt;
  * 16 + E bits.  Storage: one uint8_t per parameter when 1 <= E <= 8, else one
  * uint16_t; the E bits are right-aligned in it.  E above the format's full
  * count is MPO_ERR_INVALID_ARG.
+ *
+ * `res_packed` != 0 stores the E bits without padding (Section 3.1, Figure 1),
+ * for even E from 2 to 14, truncation mode only (else MPO_ERR_INVALID_ARG /
+ * MPO_ERR_UNSUPPORTED).  The layout is planar rather than one bit string, so
+ * that every lane reads and writes whole bytes of its own: the E bits are
+ * cut, from the top, into an 8-bit, a 4-bit and a 2-bit piece (those that E
+ * contains: E = 8a + 4b + 2c); each piece has its own dense plane in which
+ * value i occupies bits [w*i, w*i + w) (w = 8, 4, 2; little-endian in a byte);
+ * the planes follow each other in `res` in that order, each starting at a
+ * multiple of 16 bytes (sizes round16(n), round16(ceil(n/2)), round16(ceil(n/4))).
+ * `res` must then be 16-byte aligned and hold mpo_res_bytes() bytes: 12 extra
+ * bits take 1.5 bytes per parameter.
  */
+uint64_t mpo_res_bytes(uint64_t n, int32_t res_bits, int32_t res_packed);
 
 /* ---- split / merge (Section 3.1, Table 1) --------------------------------
  *
@@ -98,10 +111,10 @@ typedef enum { MPO_OPT_ADAM = 0, MPO_OPT_SGD = 1 } mpo_opt;
  * tensor has in the list passed to mpo_plan_create.
  */
 mpo_status mpo_split(const float *w32, uint16_t *hi, void *res, uint64_t n,
-                     mpo_fmt fmt, int32_t res_bits, mpo_round round, uint64_t seed, uint32_t tensor_id,
-                     void *hip_stream);
+                     mpo_fmt fmt, int32_t res_bits, int32_t res_packed, mpo_round round, uint64_t seed,
+                     uint32_t tensor_id, void *hip_stream);
 mpo_status mpo_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n,
-                     mpo_fmt fmt, int32_t res_bits, mpo_round round, void *hip_stream);
+                     mpo_fmt fmt, int32_t res_bits, int32_t res_packed, mpo_round round, void *hip_stream);
 
 /* ---- parameter list -------------------------------------------------------
  *
@@ -110,9 +123,9 @@ mpo_status mpo_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n
  * only stepped with SGD, `m` (the momentum buffer) too if momentum is 0.
  * `layer` (>= 0) groups tensors whose gradients become available together.
  * `res_bits` is the number of extra bits this tensor's residual keeps (see
- * above; it fixes whether `res` is a uint8_t or a uint16_t array).  All tensors
- * of one list must use the same residual storage width, else
- * MPO_ERR_UNSUPPORTED.
+ * above; with `res_packed` it fixes whether `res` is a uint8_t array, a uint16_t
+ * array or packed planes).  All tensors of one list must use the same kind of
+ * residual storage, else MPO_ERR_UNSUPPORTED.
  * Gradient buffers may overlap each other (one reused buffer for all layers);
  * nothing may overlap hi, res, m or v.
  */
@@ -125,6 +138,7 @@ typedef struct {
     uint64_t n;
     int32_t layer;
     int32_t res_bits;
+    int32_t res_packed;
 } mpo_tensor;
 
 /* Adam / AdamW (Section 3.1: the classic optimizer, hyper-parameters

@@ -35,7 +35,7 @@ MPO_MAX_LAYER_GRADS = 64
 class mpo_tensor(ctypes.Structure):
     _fields_ = [("hi", ctypes.c_void_p), ("res", ctypes.c_void_p), ("grad", ctypes.c_void_p),
                 ("m", ctypes.c_void_p), ("v", ctypes.c_void_p), ("n", ctypes.c_uint64),
-                ("layer", ctypes.c_int32), ("res_bits", ctypes.c_int32)]
+                ("layer", ctypes.c_int32), ("res_bits", ctypes.c_int32), ("res_packed", ctypes.c_int32)]
 
 
 class mpo_adam_cfg(ctypes.Structure):
@@ -54,10 +54,12 @@ class mpo_sgd_cfg(ctypes.Structure):
 
 
 EXPORTS = {
+    "mpo_res_bytes": ([ctypes.c_uint64, ctypes.c_int32, ctypes.c_int32], ctypes.c_uint64),
     "mpo_split": ([ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int,
-                   ctypes.c_int32, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p], ctypes.c_int),
+                   ctypes.c_int32, ctypes.c_int32, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p],
+                  ctypes.c_int),
     "mpo_merge": ([ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int,
-                   ctypes.c_int32, ctypes.c_int, ctypes.c_void_p], ctypes.c_int),
+                   ctypes.c_int32, ctypes.c_int32, ctypes.c_int, ctypes.c_void_p], ctypes.c_int),
     "mpo_plan_create": ([ctypes.POINTER(mpo_tensor), ctypes.c_uint64, ctypes.POINTER(ctypes.c_void_p)], ctypes.c_int),
     "mpo_plan_create_host": ([ctypes.POINTER(mpo_tensor), ctypes.c_uint64, ctypes.POINTER(ctypes.c_void_p)],
                              ctypes.c_int),
@@ -161,15 +163,21 @@ class SgdCfg:
                            self.grad_fmt, self.round, self.seed, self.grad_clip)
 
 
+def mpo_res_bytes(n: int, res_bits: int = 0, res_packed: bool = False) -> int:
+    """Bytes of the residual buffer of a tensor of n parameters."""
+    return int(lib.mpo_res_bytes(n, res_bits, int(res_packed)))
+
+
 def mpo_split(w32, hi, res, n: int, fmt: int = MPO_BF16, res_bits: int = 0, round: int = MPO_ROUND_TRUNC,
-              seed: int = 0, tensor_id: int = 0, stream=None):
-    _check(lib.mpo_split(_ptr(w32), _ptr(hi), _ptr(res), n, fmt, res_bits, round, seed, tensor_id, _stream(stream)),
-           "mpo_split")
+              seed: int = 0, tensor_id: int = 0, res_packed: bool = False, stream=None):
+    _check(lib.mpo_split(_ptr(w32), _ptr(hi), _ptr(res), n, fmt, res_bits, int(res_packed), round, seed, tensor_id,
+                         _stream(stream)), "mpo_split")
 
 
 def mpo_merge(hi, res, w32, n: int, fmt: int = MPO_BF16, res_bits: int = 0, round: int = MPO_ROUND_TRUNC,
-              stream=None):
-    _check(lib.mpo_merge(_ptr(hi), _ptr(res), _ptr(w32), n, fmt, res_bits, round, _stream(stream)), "mpo_merge")
+              res_packed: bool = False, stream=None):
+    _check(lib.mpo_merge(_ptr(hi), _ptr(res), _ptr(w32), n, fmt, res_bits, int(res_packed), round, _stream(stream)),
+           "mpo_merge")
 
 
 @dataclass
@@ -183,6 +191,7 @@ class Tensor:
     n: int
     layer: int = 0
     res_bits: int = 0
+    res_packed: bool = False
 
 
 class Plan:
@@ -192,7 +201,8 @@ class Plan:
         self._keep = list(tensors)
         arr = (mpo_tensor * max(len(tensors), 1))()
         for i, t in enumerate(tensors):
-            arr[i] = mpo_tensor(_ptr(t.hi), _ptr(t.res), _ptr(t.grad), _ptr(t.m), _ptr(t.v), t.n, t.layer, t.res_bits)
+            arr[i] = mpo_tensor(_ptr(t.hi), _ptr(t.res), _ptr(t.grad), _ptr(t.m), _ptr(t.v), t.n, t.layer, t.res_bits,
+                                int(t.res_packed))
         handle = ctypes.c_void_p()
         create = lib.mpo_plan_create_host if host_only else lib.mpo_plan_create
         _check(create(arr, len(tensors), ctypes.byref(handle)), "mpo_plan_create")

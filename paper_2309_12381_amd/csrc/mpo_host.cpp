@@ -47,6 +47,12 @@ inline uint32_t res_slot_bytes(int res_bits) { return (res_bits >= 1 && res_bits
 
 /* 0 means all; otherwise 1..full for the format.  Stochastic rounding stores one flag above
  * the kept bits: they must leave room for it in the slot. */
+/* Packed planes: even E from 2 to 14 (Figure 1 of the paper is E = 12). */
+inline bool valid_packed_bits(int res_bits) { return res_bits >= 2 && res_bits <= 14 && (res_bits & 1) == 0; }
+
+/* Kind of residual storage: 1 = bytes, 2 = 16-bit slots, 3 = packed planes. */
+inline uint32_t res_kind(int res_bits, int packed) { return packed ? 3u : res_slot_bytes(res_bits); }
+
 inline bool valid_res_bits(int res_bits, int fmt, int round)
 {
     if (res_bits < 0 || res_bits > full_res_bits(fmt)) return false;
@@ -91,7 +97,7 @@ struct mpo_plan {
     std::vector<LayerInfo> layers;      /* sorted by id */
     uint64_t num_params = 0;
     bool all_have_grad = true, all_have_m = true, all_have_v = true;
-    uint32_t res_slot = 0;       /* bytes per residual: 1 or 2; 0 while no tensor has elements */
+    uint32_t res_slot = 0;       /* residual storage: 1 bytes, 2 16-bit slots, 3 packed planes; 0 = no elements yet */
     uint32_t max_res_bits = 0;   /* largest explicit res_bits in the list                       */
     bool any_explicit_bits = false;
     bool on_device = false;
@@ -121,9 +127,11 @@ mpo_status build_plan(const mpo_tensor *tensors, uint64_t nt, mpo_plan **out)
         if (t.layer < 0) return MPO_ERR_INVALID_ARG;
         if (t.n > kMaxElems) return MPO_ERR_INVALID_ARG;
         if (t.res_bits < 0 || t.res_bits > 16) return MPO_ERR_INVALID_ARG;
+        if (t.res_packed && !valid_packed_bits(t.res_bits)) return MPO_ERR_INVALID_ARG;
         if (t.n == 0) continue;
         if (!t.hi || !t.res) return MPO_ERR_INVALID_ARG;
-        const uint32_t slot = res_slot_bytes(t.res_bits);
+        if (t.res_packed && !aligned16(t.res)) return MPO_ERR_INVALID_ARG;
+        const uint32_t slot = res_kind(t.res_bits, t.res_packed);
         if (res_slot == 0) res_slot = slot;
         else if (res_slot != slot) return MPO_ERR_UNSUPPORTED;
         auto add = [&](const void *p, uint64_t bytes, bool written) {
@@ -131,7 +139,7 @@ mpo_status build_plan(const mpo_tensor *tensors, uint64_t nt, mpo_plan **out)
             ranges.push_back(Range{lo, lo + bytes, written});
         };
         add(t.hi, t.n * 2, true);
-        add(t.res, t.n * slot, true);
+        add(t.res, res_bytes(t.n, t.res_bits, t.res_packed), true);
         if (t.grad) add(t.grad, t.n * 2, false);
         if (t.m) add(t.m, t.n * 4, true);
         if (t.v) add(t.v, t.n * 4, true);
@@ -287,7 +295,8 @@ mpo_status run(mpo_plan *p, StepLaunch &L, void *stream)
     if (dev != p->device) return MPO_ERR_INVALID_ARG;
     if ((int)p->max_res_bits > full_res_bits(L.wfmt)) return MPO_ERR_INVALID_ARG;
     if (L.s.round == MPO_ROUND_STOCHASTIC && p->max_res_bits > (p->res_slot == 1 ? 7u : 15u)) return MPO_ERR_INVALID_ARG;
-    L.rmode = p->res_slot == 1 ? kResByte : (p->any_explicit_bits ? kResPartial : kResFull);
+    if (p->res_slot == 3 && L.s.round != MPO_ROUND_TRUNC) return MPO_ERR_UNSUPPORTED;
+    L.rmode = p->res_slot == 3 ? kResPlanes : p->res_slot == 1 ? kResByte : (p->any_explicit_bits ? kResPartial : kResFull);
     L.descs = p->d_descs;
     L.chunks = p->d_chunks;
     L.stream = static_cast<hipStream_t>(stream);
@@ -310,10 +319,13 @@ mpo_status step_all(mpo_plan *p, StepLaunch &L, void *stream)
 extern "C" {
 
 mpo_status mpo_split(const float *w32, uint16_t *hi, void *res, uint64_t n, mpo_fmt fmt, int32_t res_bits,
-                     mpo_round round, uint64_t seed, uint32_t tensor_id, void *hip_stream)
+                     int32_t res_packed, mpo_round round, uint64_t seed, uint32_t tensor_id, void *hip_stream)
 {
     if (!valid_fmt(fmt) || check_round(round) != MPO_OK) return MPO_ERR_INVALID_ARG;
     if (!valid_res_bits(res_bits, fmt, round)) return MPO_ERR_INVALID_ARG;
+    if (res_packed && !valid_packed_bits(res_bits)) return MPO_ERR_INVALID_ARG;
+    if (res_packed && round != MPO_ROUND_TRUNC) return MPO_ERR_UNSUPPORTED;
+    if (res_packed && n > 0 && !aligned16(res)) return MPO_ERR_INVALID_ARG;
     if (n > kMaxElems) return MPO_ERR_INVALID_ARG;
     if (n == 0) return MPO_OK;
     if (!w32 || !hi || !res) return MPO_ERR_INVALID_ARG;
@@ -321,18 +333,21 @@ mpo_status mpo_split(const float *w32, uint16_t *hi, void *res, uint64_t n, mpo_
     const uintptr_t a = (uintptr_t)w32, b = (uintptr_t)hi, c = (uintptr_t)res;
     r.push_back(Range{a, a + n * 4, false});
     r.push_back(Range{b, b + n * 2, true});
-    r.push_back(Range{c, c + n * res_slot_bytes(res_bits), true});
+    r.push_back(Range{c, c + res_bytes(n, res_bits, res_packed), true});
     if (has_conflict(r)) return MPO_ERR_ALIAS;
-    const hipError_t e = launch_split(w32, hi, res, n, fmt, res_bits, round, seed, tensor_id,
+    const hipError_t e = launch_split(w32, hi, res, n, fmt, res_bits, res_packed, round, seed, tensor_id,
                                       static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MPO_OK : hip_fail(e);
 }
 
 mpo_status mpo_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, mpo_fmt fmt, int32_t res_bits,
-                     mpo_round round, void *hip_stream)
+                     int32_t res_packed, mpo_round round, void *hip_stream)
 {
     if (!valid_fmt(fmt) || check_round(round) != MPO_OK) return MPO_ERR_INVALID_ARG;
     if (!valid_res_bits(res_bits, fmt, round)) return MPO_ERR_INVALID_ARG;
+    if (res_packed && !valid_packed_bits(res_bits)) return MPO_ERR_INVALID_ARG;
+    if (res_packed && round != MPO_ROUND_TRUNC) return MPO_ERR_UNSUPPORTED;
+    if (res_packed && n > 0 && !aligned16(res)) return MPO_ERR_INVALID_ARG;
     if (n > kMaxElems) return MPO_ERR_INVALID_ARG;
     if (n == 0) return MPO_OK;
     if (!w32 || !hi || !res) return MPO_ERR_INVALID_ARG;
@@ -340,9 +355,10 @@ mpo_status mpo_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n
     const uintptr_t a = (uintptr_t)w32, b = (uintptr_t)hi, c = (uintptr_t)res;
     r.push_back(Range{a, a + n * 4, true});
     r.push_back(Range{b, b + n * 2, false});
-    r.push_back(Range{c, c + n * res_slot_bytes(res_bits), false});
+    r.push_back(Range{c, c + res_bytes(n, res_bits, res_packed), false});
     if (has_conflict(r)) return MPO_ERR_ALIAS;
-    const hipError_t e = launch_merge(hi, res, w32, n, fmt, res_bits, round, static_cast<hipStream_t>(hip_stream));
+    const hipError_t e = launch_merge(hi, res, w32, n, fmt, res_bits, res_packed, round,
+                                      static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MPO_OK : hip_fail(e);
 }
 
@@ -386,6 +402,8 @@ mpo_status mpo_plan_destroy(mpo_plan *p)
     delete p;
     return s;
 }
+
+uint64_t mpo_res_bytes(uint64_t n, int32_t res_bits, int32_t res_packed) { return res_bytes(n, res_bits, res_packed); }
 
 uint64_t mpo_plan_chunk_elems(const mpo_plan *) { return kChunkElems; }
 uint64_t mpo_plan_num_chunks(const mpo_plan *p) { return p ? p->chunks.size() : 0; }
@@ -453,7 +471,7 @@ mpo_status mpo_step_layer(mpo_plan *p, int32_t layer, const void *const *grads, 
             const uintptr_t g = (uintptr_t)grads[k];
             r.push_back(Range{g, g + d.n * 2, false});
             r.push_back(Range{(uintptr_t)d.hi, (uintptr_t)d.hi + d.n * 2, true});
-            r.push_back(Range{(uintptr_t)d.res, (uintptr_t)d.res + d.n * res_slot_bytes((int)d.res_bits), true});
+            r.push_back(Range{(uintptr_t)d.res, (uintptr_t)d.res + res_bytes(d.n, (int)d.res_bits, p->res_slot == 3), true});
             if (d.m) r.push_back(Range{(uintptr_t)d.m, (uintptr_t)d.m + d.n * 4, true});
             if (d.v) r.push_back(Range{(uintptr_t)d.v, (uintptr_t)d.v + d.n * 4, true});
             L.ov.ptr[k] = static_cast<const uint16_t *>(grads[k]);

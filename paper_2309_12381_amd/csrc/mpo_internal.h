@@ -66,8 +66,22 @@ enum Decay { kNoDecay = 0, kDecoupled = 1, kL2 = 2 };
 enum ResMode {
     kResFull = 0,    /* uint16_t, every extra bit kept: no shifting                  */
     kResPartial = 1, /* uint16_t, some tensor keeps fewer bits: shift per descriptor  */
-    kResByte = 2     /* uint8_t (1..8 bits kept)                                      */
+    kResByte = 2,    /* uint8_t (1..8 bits kept)                                      */
+    kResPlanes = 3   /* packed bit planes of 8, 4 and 2 bits (even E, Figure 1)        */
 };
+
+inline uint64_t round16(uint64_t x) { return (x + 15u) / 16u * 16u; }
+
+/* Bytes of the residual buffer of one tensor. */
+inline uint64_t res_bytes(uint64_t n, int res_bits, int packed)
+{
+    if (!packed) return n * ((res_bits >= 1 && res_bits <= 8) ? 1u : 2u);
+    uint64_t b = 0;
+    if (res_bits & 8) b += round16(n);
+    if (res_bits & 4) b += round16((n + 1) / 2);
+    if (res_bits & 2) b += round16((n + 3) / 4);
+    return b;
+}
 
 inline int full_res_bits(int fmt) { return fmt == MPO_FP16 ? 13 : 16; }
 
@@ -87,10 +101,10 @@ struct StepLaunch {
 };
 
 hipError_t launch_step(const StepLaunch &L);
-hipError_t launch_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits, int round,
-                        uint64_t seed, uint32_t tensor_id, hipStream_t stream);
-hipError_t launch_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits, int round,
-                        hipStream_t stream);
+hipError_t launch_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits, int packed,
+                        int round, uint64_t seed, uint32_t tensor_id, hipStream_t stream);
+hipError_t launch_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits, int packed,
+                        int round, hipStream_t stream);
 
 /* Extra bits actually stored: an explicit count, else all of them; stochastic rounding of
  * bf16 keeps 15 so that the flag fits the 16-bit slot. */

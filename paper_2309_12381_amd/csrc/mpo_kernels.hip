@@ -280,6 +280,90 @@ template <int RMODE> __device__ __forceinline__ void res_put(uint32_t *r, int k,
 template <int RMODE> struct ResElem { typedef uint16_t T; };
 template <> struct ResElem<kResByte> { typedef uint8_t T; };
 
+/* ---- packed planes (Section 3.1, Figure 1: extra bits stored without padding) --
+ * The E kept bits are cut from the top into an 8-bit, a 4-bit and a 2-bit piece (those E
+ * contains), each in a dense plane of its own, so that the EPL values of a lane occupy
+ * whole bytes in every plane: no byte is shared between lanes, nothing has to be
+ * exchanged or combined.  In registers the kept bits are held as in a cut 16-bit slot
+ * (kResPartial), so the arithmetic path is shared. */
+constexpr int reg_mode(int rmode) { return rmode == kResPlanes ? kResPartial : rmode; }
+
+struct ResRef {
+    MPO_GLOBAL void *slots;           /* slot storage at the chunk's first parameter        */
+    MPO_GLOBAL uint8_t *p8, *p4, *p2; /* planes at the chunk's first parameter              */
+    uint32_t E;                       /* kept bits (planes)                                  */
+};
+
+/* base: start of the tensor's residual buffer, n: its length, off: first parameter of the chunk */
+template <int RMODE>
+__device__ __forceinline__ ResRef res_ref(void *base, uint64_t n, uint64_t off, uint32_t E)
+{
+    ResRef R;
+    R.E = E;
+    R.slots = nullptr;
+    R.p8 = R.p4 = R.p2 = nullptr;
+    if (RMODE == kResPlanes) {
+        MPO_GLOBAL uint8_t *b = (MPO_GLOBAL uint8_t *)base;
+        R.p8 = b + off;
+        if (E & 8u) b += (n + 15u) / 16u * 16u;
+        R.p4 = b + off / 2;
+        if (E & 4u) b += ((n + 1u) / 2u + 15u) / 16u * 16u;
+        R.p2 = b + off / 4;
+    } else {
+        R.slots = (MPO_GLOBAL void *)(static_cast<char *>(base) + off * sizeof(typename ResElem<RMODE>::T));
+    }
+    return R;
+}
+
+template <int NBYTES> __device__ __forceinline__ uint64_t ld_bytes(const MPO_GLOBAL uint8_t *p)
+{
+    if (NBYTES == 1) return *p;
+    if (NBYTES == 2) return *reinterpret_cast<const MPO_GLOBAL uint16_t *>(p);
+    if (NBYTES == 4) return *reinterpret_cast<const MPO_GLOBAL uint32_t *>(p);
+    return *reinterpret_cast<const MPO_GLOBAL uint64_t *>(p);
+}
+template <int NBYTES> __device__ __forceinline__ void st_bytes(MPO_GLOBAL uint8_t *p, uint64_t x)
+{
+    if (NBYTES == 1) *p = (uint8_t)x;
+    else if (NBYTES == 2) *reinterpret_cast<MPO_GLOBAL uint16_t *>(p) = (uint16_t)x;
+    else if (NBYTES == 4) *reinterpret_cast<MPO_GLOBAL uint32_t *>(p) = (uint32_t)x;
+    else *reinterpret_cast<MPO_GLOBAL uint64_t *>(p) = x;
+}
+
+/* The EPL values that start at chunk-local parameter e (a multiple of EPL): planes -> 16-bit pairs. */
+__device__ __forceinline__ void planes_load(const ResRef &R, uint32_t e, uint32_t (&r)[EPL / 2])
+{
+    const uint64_t b8 = (R.E & 8u) ? ld_bytes<EPL>(R.p8 + e) : 0u;
+    const uint64_t b4 = (R.E & 4u) ? ld_bytes<EPL / 2>(R.p4 + e / 2) : 0u;
+    const uint64_t b2 = (R.E & 2u) ? ld_bytes<EPL / 4>(R.p2 + e / 4) : 0u;
+#pragma unroll
+    for (int j = 0; j < EPL / 2; ++j) r[j] = 0u;
+#pragma unroll
+    for (int k = 0; k < EPL; ++k) {
+        uint32_t x = 0u;
+        if (R.E & 8u) x = (uint32_t)(b8 >> (8 * k)) & 0xFFu;
+        if (R.E & 4u) x = (x << 4) | ((uint32_t)(b4 >> (4 * k)) & 0xFu);
+        if (R.E & 2u) x = (x << 2) | ((uint32_t)(b2 >> (2 * k)) & 0x3u);
+        r[k / 2] |= x << (16 * (k & 1));
+    }
+}
+
+__device__ __forceinline__ void planes_store(const ResRef &R, uint32_t e, const uint32_t (&r)[EPL / 2])
+{
+    uint64_t b8 = 0u, b4 = 0u, b2 = 0u;
+#pragma unroll
+    for (int k = 0; k < EPL; ++k) {
+        const uint32_t x = (r[k / 2] >> (16 * (k & 1))) & 0xFFFFu;
+        uint32_t left = R.E;
+        if (R.E & 8u) { left -= 8u; b8 |= (uint64_t)((x >> left) & 0xFFu) << (8 * k); }
+        if (R.E & 4u) { left -= 4u; b4 |= (uint64_t)((x >> left) & 0xFu) << (4 * k); }
+        if (R.E & 2u) { left -= 2u; b2 |= (uint64_t)((x >> left) & 0x3u) << (2 * k); }
+    }
+    if (R.E & 8u) st_bytes<EPL>(R.p8 + e, b8);
+    if (R.E & 4u) st_bytes<EPL / 2>(R.p4 + e / 2, b4);
+    if (R.E & 2u) st_bytes<EPL / 4>(R.p2 + e / 4, b2);
+}
+
 template <int WFMT> struct FullBits { static constexpr uint32_t value = (WFMT == MPO_FP16) ? 13u : 16u; };
 
 /* ---- rounding of the 16-bit value (Section 3.1, last paragraph) -------------
@@ -376,11 +460,12 @@ struct Row {
 };
 
 template <int OPT, bool MOM, int RMODE>
-__device__ __forceinline__ void load_row(Row &x, gcu16p hi, const MPO_GLOBAL void *res, gcu16p grad, gcf32p m, gcf32p v,
-                                         uint32_t e)
+__device__ __forceinline__ void load_row(Row &x, gcu16p hi, const ResRef &R, gcu16p grad, gcf32p m, gcf32p v, uint32_t e)
 {
     load16(hi + e, x.h);
-    if (RMODE == kResByte) load8(static_cast<gcu8p>(res) + e, x.r); else load16(static_cast<gcu16p>(res) + e, x.r);
+    if (RMODE == kResPlanes) planes_load(R, e, x.r);
+    else if (RMODE == kResByte) load8(static_cast<gcu8p>(R.slots) + e, x.r);
+    else load16(static_cast<gcu16p>(R.slots) + e, x.r);
     load16(grad + e, x.g);
     if (Uses<OPT, MOM>::m) load32(m + e, x.m);
     if (Uses<OPT, MOM>::v) load32(v + e, x.v);
@@ -436,10 +521,12 @@ __device__ __forceinline__ void compute_row(Row &x, const StepScalars &s, uint32
 }
 
 template <int OPT, bool MOM, int RMODE>
-__device__ __forceinline__ void store_row(const Row &x, gu16p hi, MPO_GLOBAL void *res, gf32p m, gf32p v, uint32_t e)
+__device__ __forceinline__ void store_row(const Row &x, gu16p hi, const ResRef &R, gf32p m, gf32p v, uint32_t e)
 {
     store16(hi + e, x.h);
-    if (RMODE == kResByte) store8(static_cast<gu8p>(res) + e, x.r); else store16(static_cast<gu16p>(res) + e, x.r);
+    if (RMODE == kResPlanes) planes_store(R, e, x.r);
+    else if (RMODE == kResByte) store8(static_cast<gu8p>(R.slots) + e, x.r);
+    else store16(static_cast<gu16p>(R.slots) + e, x.r);
     if (Uses<OPT, MOM>::m) store32(m + e, x.m);
     if (Uses<OPT, MOM>::v) store32(v + e, x.v);
 }
@@ -459,6 +546,32 @@ __device__ __forceinline__ void step_scalar(gu16p hi, MPO_GLOBAL void *res_, gcu
     res[e] = (typename ResElem<RMODE>::T)(r >> sh);
     if (Uses<OPT, MOM>::m) m[e] = mm;
     if (Uses<OPT, MOM>::v) v[e] = vv;
+}
+
+/* Packed planes, up to EPL parameters starting at chunk-local parameter e (a multiple of EPL),
+ * one at a time: ragged ends and tensors whose other arrays are not 16-byte aligned.  The lane
+ * still owns whole bytes of every plane (the planes are padded to 16 bytes). */
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM>
+__device__ __forceinline__ void step_group_planes(gu16p hi, const ResRef &R, gcu16p grad, gf32p m, gf32p v, uint32_t e,
+                                                  uint32_t count, const StepScalars &s, uint32_t sh)
+{
+    uint32_t r[EPL / 2];
+    planes_load(R, e, r);
+#pragma unroll
+    for (int k = 0; k < EPL; ++k) {
+        if ((uint32_t)k < count) {
+            uint32_t h = hi[e + k];
+            uint32_t rr = ((r[k / 2] >> (16 * (k & 1))) & 0xFFFFu) << sh;
+            float mm = Uses<OPT, MOM>::m ? m[e + k] : 0.0f;
+            float vv = Uses<OPT, MOM>::v ? v[e + k] : 0.0f;
+            step_one<OPT, WFMT, GFMT, DECAY, MOM>(h, rr, grad[e + k], mm, vv, s);
+            hi[e + k] = (uint16_t)h;
+            if (Uses<OPT, MOM>::m) m[e + k] = mm;
+            if (Uses<OPT, MOM>::v) v[e + k] = vv;
+            r[k / 2] = (r[k / 2] & ~(0xFFFFu << (16 * (k & 1)))) | (((rr >> sh) & 0xFFFFu) << (16 * (k & 1)));
+        }
+    }
+    planes_store(R, e, r);
 }
 
 template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE>
@@ -504,9 +617,12 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
     const uint32_t all = (RND && s.round == MPO_ROUND_STOCHASTIC && WFMT == MPO_BF16) ? 15u : FullBits<WFMT>::value;
     const uint32_t kept = d.res_bits ? d.res_bits : all;
     const uint32_t sh = (RMODE == kResFull && !RND) ? 0u : FullBits<WFMT>::value - kept;
+    static_assert(!(RND && RMODE == kResPlanes), "packed planes are built for truncation mode only");
     const Rng rng = {s.seed_lo, s.seed_hi, s.step32, d.tensor_id};
     gu16p hi = (gu16p)(d.hi + off);
-    MPO_GLOBAL void *res = (MPO_GLOBAL void *)(static_cast<char *>(d.res) + off * sizeof(typename ResElem<RMODE>::T));
+    const ResRef R = res_ref<RMODE>(d.res, d.n, off, kept);
+    MPO_GLOBAL void *res = R.slots;
+    constexpr int RREG = reg_mode(RMODE);          /* how the kept bits sit in registers */
     gcu16p grad = (gcu16p)(gbase + off);
     gf32p m = Uses<OPT, MOM>::m ? (gf32p)(d.m + off) : (gf32p) nullptr;
     gf32p v = Uses<OPT, MOM>::v ? (gf32p)(d.v + off) : (gf32p) nullptr;
@@ -519,14 +635,18 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
             Row x[BATCH];
 #pragma unroll
             for (int b = 0; b < BATCH; ++b)
-                load_row<OPT, MOM, RMODE>(x[b], hi, res, grad, m, v, row_elem(r0 + b, t));
+                load_row<OPT, MOM, RMODE>(x[b], hi, R, grad, m, v, row_elem(r0 + b, t));
 #pragma unroll
             for (int b = 0; b < BATCH; ++b) {
-                if (RND) compute_row_rounded<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(x[b], s, kept, sh, rng, off + row_elem(r0 + b, t));
-                else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(x[b], s, sh);
-                store_row<OPT, MOM, RMODE>(x[b], hi, res, m, v, row_elem(r0 + b, t));
+                if (RND) compute_row_rounded<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x[b], s, kept, sh, rng, off + row_elem(r0 + b, t));
+                else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x[b], s, sh);
+                store_row<OPT, MOM, RMODE>(x[b], hi, R, m, v, row_elem(r0 + b, t));
             }
         }
+    } else if (RMODE == kResPlanes) {
+        /* packed planes outside the fast path: every lane walks whole groups of EPL parameters */
+        for (uint32_t e = t * EPL; e < len; e += kBlock * EPL)
+            step_group_planes<OPT, WFMT, GFMT, DECAY, MOM>(hi, R, grad, m, v, e, len - e < (uint32_t)EPL ? len - e : (uint32_t)EPL, s, sh);
     } else if (aligned) {
         /* last chunk of a tensor: full vectors, then one lane finishes the ragged end */
 #pragma unroll 1
@@ -534,10 +654,10 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
             const uint32_t e = row_elem(r, t);
             if (e + EPL <= len) {
                 Row x;
-                load_row<OPT, MOM, RMODE>(x, hi, res, grad, m, v, e);
-                if (RND) compute_row_rounded<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(x, s, kept, sh, rng, off + e);
-                else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(x, s, sh);
-                store_row<OPT, MOM, RMODE>(x, hi, res, m, v, e);
+                load_row<OPT, MOM, RMODE>(x, hi, R, grad, m, v, e);
+                if (RND) compute_row_rounded<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x, s, kept, sh, rng, off + e);
+                else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x, s, sh);
+                store_row<OPT, MOM, RMODE>(x, hi, R, m, v, e);
             } else if (e < len) {
                 for (uint32_t i = e; i < len; ++i) {
                     if (RND) step_scalar_rounded<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(hi, res, grad, m, v, i, s, kept, sh, rng, off + i);
@@ -571,31 +691,54 @@ __device__ __forceinline__ void split_store_one(float w, uint32_t &h, uint32_t &
     else slot = r >> sh;
 }
 
+/* w32, hi, res point at the tensor's first parameter; this launch covers chunks from `first`. */
 template <int FMT, int RMODE, bool RND>
 __global__ void __launch_bounds__(kBlock)
 split_kernel(const float *__restrict__ w32_, uint16_t *__restrict__ hi_, void *__restrict__ res_, uint64_t n,
              uint64_t first, int aligned, uint32_t kept, uint32_t sh, RoundArgs rs)
 {
     typedef typename ResElem<RMODE>::T R;
-    const uint64_t off = (uint64_t)blockIdx.x * kChunkElems;
+    constexpr int RREG = reg_mode(RMODE);
+    const uint64_t off = first + (uint64_t)blockIdx.x * kChunkElems;   /* tensor-relative */
     const uint64_t left = n - off;
     const uint32_t len = left < kChunkElems ? (uint32_t)left : kChunkElems;
     gcf32p w32 = (gcf32p)(w32_ + off);
     gu16p hi = (gu16p)(hi_ + off);
-    MPO_GLOBAL R *res = (MPO_GLOBAL R *)(static_cast<R *>(res_) + off);
+    const ResRef ref = res_ref<RMODE>(res_, n, off, kept);
+    MPO_GLOBAL R *res = (MPO_GLOBAL R *)ref.slots;
     const Rng rng = {rs.seed_lo, rs.seed_hi, 0u, rs.tensor_id};
-    const uint64_t base = first + off;           /* tensor-relative index of this chunk's first parameter */
     const uint32_t t = threadIdx.x;
-    auto one = [&](uint32_t i) {
+    auto one = [&](uint32_t i, uint32_t &h, uint32_t &slot) {
         uint32_t u[4] = {0u, 0u, 0u, 0u};
-        if (RND && rs.round == MPO_ROUND_STOCHASTIC) draw4<FullBits<FMT>::value>(rng, (base + i) / 4, u);
-        uint32_t h, slot;
-        split_store_one<FMT, RMODE, RND>(w32[i], h, slot, kept, sh, rs, u[(base + i) % 4]);
-        hi[i] = (uint16_t)h;
-        res[i] = (R)slot;
+        if (RND && rs.round == MPO_ROUND_STOCHASTIC) draw4<FullBits<FMT>::value>(rng, (off + i) / 4, u);
+        split_store_one<FMT, RREG, RND>(w32[i], h, slot, kept, sh, rs, u[(off + i) % 4]);
     };
+    if (RMODE == kResPlanes && !(aligned && len == kChunkElems)) {
+        /* whole groups of EPL parameters per lane, one parameter at a time */
+        for (uint32_t e = t * EPL; e < len; e += kBlock * EPL) {
+            uint32_t q[EPL / 2];
+#pragma unroll
+            for (int j = 0; j < EPL / 2; ++j) q[j] = 0u;
+#pragma unroll
+            for (int k = 0; k < EPL; ++k) {
+                if (e + k < len) {
+                    uint32_t h, slot;
+                    one(e + k, h, slot);
+                    hi[e + k] = (uint16_t)h;
+                    q[k / 2] |= (slot & 0xFFFFu) << (16 * (k & 1));
+                }
+            }
+            planes_store(ref, e, q);
+        }
+        return;
+    }
     if (!aligned) {
-        for (uint32_t i = t; i < len; i += kBlock) one(i);
+        for (uint32_t i = t; i < len; i += kBlock) {
+            uint32_t h, slot;
+            one(i, h, slot);
+            hi[i] = (uint16_t)h;
+            res[i] = (R)slot;
+        }
         return;
     }
 #pragma unroll
@@ -610,22 +753,29 @@ split_kernel(const float *__restrict__ w32_, uint16_t *__restrict__ hi_, void *_
 #pragma unroll
             for (int g4 = 0; g4 < EPL / 4; ++g4) {
                 uint32_t u[4] = {0u, 0u, 0u, 0u};
-                if (RND && rs.round == MPO_ROUND_STOCHASTIC) draw4<FullBits<FMT>::value>(rng, (base + e) / 4 + g4, u);
+                if (RND && rs.round == MPO_ROUND_STOCHASTIC) draw4<FullBits<FMT>::value>(rng, (off + e) / 4 + g4, u);
 #pragma unroll
                 for (int jj = 0; jj < 2; ++jj) {
                     const int j = 2 * g4 + jj;
                     uint32_t h0, s0, h1, s1;
-                    split_store_one<FMT, RMODE, RND>(w[2 * j], h0, s0, kept, sh, rs, u[2 * jj]);
-                    split_store_one<FMT, RMODE, RND>(w[2 * j + 1], h1, s1, kept, sh, rs, u[2 * jj + 1]);
+                    split_store_one<FMT, RREG, RND>(w[2 * j], h0, s0, kept, sh, rs, u[2 * jj]);
+                    split_store_one<FMT, RREG, RND>(w[2 * j + 1], h1, s1, kept, sh, rs, u[2 * jj + 1]);
                     h[j] = h0 | (h1 << 16);
-                    slot_put<RMODE>(q, 2 * j, s0);
-                    slot_put<RMODE>(q, 2 * j + 1, s1);
+                    slot_put<RREG>(q, 2 * j, s0);
+                    slot_put<RREG>(q, 2 * j + 1, s1);
                 }
             }
             store16(hi + e, h);
-            if (RMODE == kResByte) store8((gu8p)res + e, q); else store16((gu16p)res + e, q);
+            if (RMODE == kResPlanes) planes_store(ref, e, q);
+            else if (RMODE == kResByte) store8((gu8p)res + e, q);
+            else store16((gu16p)res + e, q);
         } else if (e < len) {
-            for (uint32_t i = e; i < len; ++i) one(i);
+            for (uint32_t i = e; i < len; ++i) {
+                uint32_t h, slot;
+                one(i, h, slot);
+                hi[i] = (uint16_t)h;
+                res[i] = (R)slot;
+            }
         }
     }
 }
@@ -642,19 +792,31 @@ __device__ __forceinline__ float merge_load_one(uint32_t h, uint32_t slot, uint3
 template <int FMT, int RMODE, bool RND>
 __global__ void __launch_bounds__(kBlock)
 merge_kernel(const uint16_t *__restrict__ hi_, const void *__restrict__ res_, float *__restrict__ w32_, uint64_t n,
-             int aligned, uint32_t kept, uint32_t sh, uint32_t round)
+             uint64_t first, int aligned, uint32_t kept, uint32_t sh, uint32_t round)
 {
     typedef typename ResElem<RMODE>::T R;
-    const uint64_t off = (uint64_t)blockIdx.x * kChunkElems;
+    constexpr int RREG = reg_mode(RMODE);
+    const uint64_t off = first + (uint64_t)blockIdx.x * kChunkElems;
     const uint64_t left = n - off;
     const uint32_t len = left < kChunkElems ? (uint32_t)left : kChunkElems;
     gf32p w32 = (gf32p)(w32_ + off);
     gcu16p hi = (gcu16p)(hi_ + off);
-    const MPO_GLOBAL R *res = (const MPO_GLOBAL R *)(static_cast<const R *>(res_) + off);
+    const ResRef ref = res_ref<RMODE>(const_cast<void *>(res_), n, off, kept);
+    const MPO_GLOBAL R *res = (const MPO_GLOBAL R *)ref.slots;
     const uint32_t t = threadIdx.x;
+    if (RMODE == kResPlanes && !(aligned && len == kChunkElems)) {
+        for (uint32_t e = t * EPL; e < len; e += kBlock * EPL) {
+            uint32_t q[EPL / 2];
+            planes_load(ref, e, q);
+#pragma unroll
+            for (int k = 0; k < EPL; ++k)
+                if (e + k < len) w32[e + k] = merge_load_one<FMT, RREG, RND>(hi[e + k], slot_get<RREG>(q, k), kept, sh, round);
+        }
+        return;
+    }
     if (!aligned) {
         for (uint32_t i = t; i < len; i += kBlock)
-            w32[i] = merge_load_one<FMT, RMODE, RND>(hi[i], (uint32_t)res[i], kept, sh, round);
+            w32[i] = merge_load_one<FMT, RREG, RND>(hi[i], (uint32_t)res[i], kept, sh, round);
         return;
     }
 #pragma unroll
@@ -664,16 +826,18 @@ merge_kernel(const uint16_t *__restrict__ hi_, const void *__restrict__ res_, fl
             float w[EPL];
             uint32_t h[EPL / 2], q[EPL / 2];
             load16(hi + e, h);
-            if (RMODE == kResByte) load8((gcu8p)res + e, q); else load16((gcu16p)res + e, q);
+            if (RMODE == kResPlanes) planes_load(ref, e, q);
+            else if (RMODE == kResByte) load8((gcu8p)res + e, q);
+            else load16((gcu16p)res + e, q);
 #pragma unroll
             for (int j = 0; j < EPL / 2; ++j) {
-                w[2 * j] = merge_load_one<FMT, RMODE, RND>(h[j] & 0xFFFFu, slot_get<RMODE>(q, 2 * j), kept, sh, round);
-                w[2 * j + 1] = merge_load_one<FMT, RMODE, RND>(h[j] >> 16, slot_get<RMODE>(q, 2 * j + 1), kept, sh, round);
+                w[2 * j] = merge_load_one<FMT, RREG, RND>(h[j] & 0xFFFFu, slot_get<RREG>(q, 2 * j), kept, sh, round);
+                w[2 * j + 1] = merge_load_one<FMT, RREG, RND>(h[j] >> 16, slot_get<RREG>(q, 2 * j + 1), kept, sh, round);
             }
             store32(w32 + e, w);
         } else if (e < len) {
             for (uint32_t i = e; i < len; ++i)
-                w32[i] = merge_load_one<FMT, RMODE, RND>(hi[i], (uint32_t)res[i], kept, sh, round);
+                w32[i] = merge_load_one<FMT, RREG, RND>(hi[i], (uint32_t)res[i], kept, sh, round);
         }
     }
 }
@@ -707,6 +871,7 @@ hipError_t launch_step_res(const StepLaunch &L)
     switch (L.rmode) {
     case kResFull: return launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResFull, false>(L);
     case kResPartial: return launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResPartial, false>(L);
+    case kResPlanes: return launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResPlanes, false>(L);
     default: return launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResByte, false>(L);
     }
 }
@@ -736,14 +901,13 @@ struct SplitMergeArgs {
 template <int FMT, int RMODE, bool RND>
 hipError_t launch_split_t(const SplitMergeArgs &a)
 {
-    typedef typename ResElem<RMODE>::T R;
     uint64_t done = 0;
     const uint64_t blocks = (a.n + kChunkElems - 1) / kChunkElems;
     while (done < blocks) {
         const uint64_t now = (blocks - done < kMaxGrid) ? (blocks - done) : kMaxGrid;
         const uint64_t e0 = done * kChunkElems;
         split_kernel<FMT, RMODE, RND><<<dim3((uint32_t)now), dim3(kBlock), 0, a.stream>>>(
-            a.w32_in + e0, a.hi + e0, static_cast<R *>(a.res) + e0, a.n - e0, e0, a.al, a.kept, a.sh, a.rs);
+            a.w32_in, a.hi, a.res, a.n, e0, a.al, a.kept, a.sh, a.rs);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         done += now;
@@ -754,14 +918,13 @@ hipError_t launch_split_t(const SplitMergeArgs &a)
 template <int FMT, int RMODE, bool RND>
 hipError_t launch_merge_t(const SplitMergeArgs &a)
 {
-    typedef typename ResElem<RMODE>::T R;
     uint64_t done = 0;
     const uint64_t blocks = (a.n + kChunkElems - 1) / kChunkElems;
     while (done < blocks) {
         const uint64_t now = (blocks - done < kMaxGrid) ? (blocks - done) : kMaxGrid;
         const uint64_t e0 = done * kChunkElems;
         merge_kernel<FMT, RMODE, RND><<<dim3((uint32_t)now), dim3(kBlock), 0, a.stream>>>(
-            a.hi + e0, static_cast<const R *>(a.res) + e0, a.w32_out + e0, a.n - e0, a.al, a.kept, a.sh, a.rs.round);
+            a.hi, a.res, a.w32_out, a.n, e0, a.al, a.kept, a.sh, a.rs.round);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         done += now;
@@ -776,6 +939,7 @@ hipError_t launch_sm(const SplitMergeArgs &a, int rmode)
     if (rnd && rmode == kResFull) rmode = kResPartial;     /* rounded modes: general residual path */
 #define MPO_SM(RM, RN) (SPLIT ? launch_split_t<FMT, RM, RN>(a) : launch_merge_t<FMT, RM, RN>(a))
     if (rnd) return rmode == kResByte ? MPO_SM(kResByte, true) : MPO_SM(kResPartial, true);
+    if (rmode == kResPlanes) return MPO_SM(kResPlanes, false);
     if (rmode == kResByte) return MPO_SM(kResByte, false);
     if (rmode == kResPartial) return MPO_SM(kResPartial, false);
     return MPO_SM(kResFull, false);
@@ -785,13 +949,13 @@ hipError_t launch_sm(const SplitMergeArgs &a, int rmode)
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 /* Storage mode, kept bits and number of cut bits for a single-tensor call. */
-inline void res_layout(int fmt, int res_bits, int round, int &rmode, uint32_t &kept, uint32_t &sh)
+inline void res_layout(int fmt, int res_bits, int packed, int round, int &rmode, uint32_t &kept, uint32_t &sh)
 {
     const int full = full_res_bits(fmt);
     const int k = kept_res_bits(fmt, res_bits, round);
     kept = (uint32_t)k;
     sh = (uint32_t)(full - k);
-    rmode = (res_bits >= 1 && res_bits <= 8) ? kResByte : (k == full ? kResFull : kResPartial);
+    rmode = packed ? kResPlanes : (res_bits >= 1 && res_bits <= 8) ? kResByte : (k == full ? kResFull : kResPartial);
 }
 
 } // namespace
@@ -813,27 +977,27 @@ hipError_t launch_step(const StepLaunch &L)
                           : launch_step_fmt<MPO_OPT_SGD, kNoDecay, false>(L);
 }
 
-hipError_t launch_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits, int round,
-                        uint64_t seed, uint32_t tensor_id, hipStream_t stream)
+hipError_t launch_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits, int packed,
+                        int round, uint64_t seed, uint32_t tensor_id, hipStream_t stream)
 {
     SplitMergeArgs a;
     a.w32_in = w32; a.w32_out = nullptr; a.hi = hi; a.res = res; a.n = n;
     a.al = aligned16(w32) && aligned16(hi) && aligned16(res);
     int rmode;
-    res_layout(fmt, res_bits, round, rmode, a.kept, a.sh);
+    res_layout(fmt, res_bits, packed, round, rmode, a.kept, a.sh);
     a.rs = RoundArgs{(uint32_t)round, (uint32_t)seed, (uint32_t)(seed >> 32), tensor_id};
     a.stream = stream;
     return fmt == MPO_BF16 ? launch_sm<MPO_BF16, true>(a, rmode) : launch_sm<MPO_FP16, true>(a, rmode);
 }
 
-hipError_t launch_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits, int round,
-                        hipStream_t stream)
+hipError_t launch_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits, int packed,
+                        int round, hipStream_t stream)
 {
     SplitMergeArgs a;
     a.w32_in = nullptr; a.w32_out = w32; a.hi = const_cast<uint16_t *>(hi); a.res = const_cast<void *>(res); a.n = n;
     a.al = aligned16(w32) && aligned16(hi) && aligned16(res);
     int rmode;
-    res_layout(fmt, res_bits, round, rmode, a.kept, a.sh);
+    res_layout(fmt, res_bits, packed, round, rmode, a.kept, a.sh);
     a.rs = RoundArgs{(uint32_t)round, 0u, 0u, 0u};
     a.stream = stream;
     return fmt == MPO_BF16 ? launch_sm<MPO_BF16, false>(a, rmode) : launch_sm<MPO_FP16, false>(a, rmode);

@@ -33,8 +33,10 @@ class ModelState:
     exists and never kept).  For workloads stepped in one launch the buffer holds all gradients."""
 
     def __init__(self, wl: synth.Workload, device="cuda:0", seed: int = 2309, keep_w32_samples=None,
-                 res_bits: int = 0, round: int = mpo.MPO_ROUND_TRUNC, rng_seed: int = 0x2309_12381):
+                 res_bits: int = 0, round: int = mpo.MPO_ROUND_TRUNC, rng_seed: int = 0x2309_12381,
+                 res_packed: bool = False):
         self.wl = wl
+        self.res_packed = res_packed        # extra bits stored in packed planes (Section 3.1, Figure 1)
         self.round = round                  # how hi is rounded (Section 3.1, last paragraph)
         self.rng_seed = rng_seed            # random stream of stochastic rounding
         self.res_bits = res_bits            # extra bits kept per weight, 0 = all (Section 3.1)
@@ -55,7 +57,16 @@ class ModelState:
         self.total = off
         self.grad_len = max(layer_fill.values()) if wl.per_layer else off
         self.hi = torch.empty(self.total, dtype=torch.int16, device=device)
-        self.res = torch.empty(self.total, dtype=torch.uint8 if self.res_bytes == 1 else torch.int16, device=device)
+        if res_packed:
+            # one byte buffer; each tensor's planes start at a multiple of 16 bytes
+            self.res_off, fill = [], 0
+            for tv in self.views:
+                self.res_off.append(fill)
+                fill += mpo.mpo_res_bytes(tv.spec.n, res_bits, True)
+            self.res = torch.zeros(fill, dtype=torch.uint8, device=device)
+        else:
+            self.res_off = [tv.off for tv in self.views]
+            self.res = torch.empty(self.total, dtype=torch.uint8 if self.res_bytes == 1 else torch.int16, device=device)
         self.m = torch.zeros(self.total, dtype=torch.float32, device=device)
         self.v = torch.zeros(self.total, dtype=torch.float32, device=device)
         self.gdtype = torch.bfloat16 if wl.fmt == "bf16" else torch.float16
@@ -70,13 +81,14 @@ class ModelState:
                 idx = keep_w32_samples(i, n)
                 if idx is not None:
                     self.w32_samples[i] = (idx, w[idx].cpu())
-            mpo.mpo_split(w, self.hi[tv.off:], self.res[tv.off:], n, fmt=self.fmt, res_bits=res_bits,
-                          round=round, seed=rng_seed, tensor_id=i)
+            mpo.mpo_split(w, self.hi[tv.off:], self.res[self.res_off[i]:], n, fmt=self.fmt, res_bits=res_bits,
+                          round=round, seed=rng_seed, tensor_id=i, res_packed=res_packed)
             del w
         torch.cuda.synchronize(device)
-        self.plan = mpo.Plan([mpo.Tensor(self.hi[tv.off:], self.res[tv.off:], self.grad[tv.goff:],
-                                         self.m[tv.off:], self.v[tv.off:], tv.spec.n, tv.spec.layer, res_bits)
-                              for tv in self.views])
+        self.plan = mpo.Plan([mpo.Tensor(self.hi[tv.off:], self.res[self.res_off[i]:], self.grad[tv.goff:],
+                                         self.m[tv.off:], self.v[tv.off:], tv.spec.n, tv.spec.layer, res_bits,
+                                         res_packed)
+                              for i, tv in enumerate(self.views)])
         self.layers_backward = wl.layers_backward
         self.by_layer: Dict[int, List[int]] = {}
         for i, tv in enumerate(self.views):
@@ -84,7 +96,7 @@ class ModelState:
 
     @property
     def resident_bytes(self) -> int:
-        return self.total * (10 + self.res_bytes) + self.grad_len * 2
+        return self.total * 10 + self.res.numel() * self.res.element_size() + self.grad_len * 2
 
     def adam_cfg(self) -> mpo.AdamCfg:
         wl = self.wl

@@ -88,7 +88,7 @@ ROUND = {"trunc": (mpo.MPO_ROUND_TRUNC, ref.TRUNC), "nearest": (mpo.MPO_ROUND_NE
          "stochastic": (mpo.MPO_ROUND_STOCHASTIC, ref.STOCHASTIC)}
 
 
-def cfg_pair(kind, fmt="bf16", gfmt=None, res_bits=0, round="trunc", seed=0, **kw):
+def cfg_pair(kind, fmt="bf16", gfmt=None, res_bits=0, round="trunc", seed=0, packed=False, **kw):
     """The same hyper-parameters for the library and for the oracle.  The number of extra bits
     kept is a property of each tensor in the library and of the step in the oracle."""
     gfmt = gfmt or fmt
@@ -96,20 +96,20 @@ def cfg_pair(kind, fmt="bf16", gfmt=None, res_bits=0, round="trunc", seed=0, **k
     if kind == "adam":
         return (mpo.AdamCfg(weight_fmt=FMT[fmt][0], grad_fmt=FMT[gfmt][0], round=ROUND[round][0], seed=seed, **kw),
                 ref.AdamCfg(weight_fmt=FMT[fmt][1], grad_fmt=FMT[gfmt][1], res_bits=res_bits, round=ROUND[round][1],
-                            seed=seed, **kw))
+                            seed=seed, res_packed=packed, **kw))
     return (mpo.SgdCfg(weight_fmt=FMT[fmt][0], grad_fmt=FMT[gfmt][0], round=ROUND[round][0], seed=seed, **kw),
             ref.SgdCfg(weight_fmt=FMT[fmt][1], grad_fmt=FMT[gfmt][1], res_bits=res_bits, round=ROUND[round][1],
-                       seed=seed, **kw))
+                       seed=seed, res_packed=packed, **kw))
 
 
 class HostTensor:
     """Oracle-side state of one tensor."""
 
-    def __init__(self, w32: np.ndarray, rfmt, with_v=True, res_bits=0, round="trunc", seed=0, tensor_id=0):
+    def __init__(self, w32: np.ndarray, rfmt, with_v=True, res_bits=0, round="trunc", seed=0, tensor_id=0, packed=False):
         self.n = w32.shape[0]
         self.res_bits = res_bits
         self.tensor_id = tensor_id
-        self.hi, self.res = ref.split(w32, rfmt, res_bits, ROUND[round][1], seed, tensor_id)
+        self.hi, self.res = ref.split(w32, rfmt, res_bits, ROUND[round][1], seed, tensor_id, packed)
         self.m = np.zeros(self.n, np.float32)
         self.v = np.zeros(self.n, np.float32) if with_v else None
 
@@ -118,33 +118,40 @@ class DevTensor:
     """GPU-side state of one tensor, split by the library itself."""
 
     def __init__(self, w32: np.ndarray, fmt, with_v=True, layer=0, grad=None, misalign=0, stream=None, res_bits=0,
-                 round="trunc", seed=0, tensor_id=0):
+                 round="trunc", seed=0, tensor_id=0, packed=False):
         n = w32.shape[0]
-        self.n, self.layer, self.res_bits = n, layer, res_bits
+        self.n, self.layer, self.res_bits, self.packed = n, layer, res_bits, packed
         # optional misalignment: carve each array out of a larger one at an odd element offset
         def alloc(dtype):
             full = torch.zeros(n + misalign + 8, dtype=dtype, device=DEV)
             return full[misalign:misalign + n]
-        self.hi, self.res = alloc(torch.int16), alloc(res_torch_dtype(res_bits))
+        self.hi = alloc(torch.int16)
+        if packed:      # planes: one byte buffer, 16-byte aligned whatever the other arrays are
+            self.res = torch.zeros(mpo.mpo_res_bytes(n, res_bits, True), dtype=torch.uint8, device=DEV)
+        else:
+            self.res = alloc(res_torch_dtype(res_bits))
         self.m = alloc(torch.float32)
         self.v = alloc(torch.float32) if with_v else None
         self.grad = grad if grad is not None else alloc(torch.int16)
         w = torch.zeros(n + misalign + 8, dtype=torch.float32, device=DEV)[misalign:misalign + n]
         w.copy_(torch.from_numpy(w32))
         mpo.mpo_split(w, self.hi, self.res, n, fmt=fmt, res_bits=res_bits, round=ROUND[round][0], seed=seed,
-                      tensor_id=tensor_id, stream=stream)
+                      tensor_id=tensor_id, res_packed=packed, stream=stream)
 
     def spec(self):
-        return mpo.Tensor(self.hi, self.res, self.grad, self.m, self.v, self.n, self.layer, self.res_bits)
+        return mpo.Tensor(self.hi, self.res, self.grad, self.m, self.v, self.n, self.layer, self.res_bits, self.packed)
 
 
 def assert_state_equal(d: DevTensor, h: HostTensor, what=""):
     torch.cuda.synchronize()
     ghi, gres = host_u16(d.hi), host_res(d.res)
-    bad = np.flatnonzero((ghi != h.hi) | (gres != h.res))
-    assert bad.size == 0, "%s: %d of %d stored weights differ, first at %d: gpu %04x/%04x oracle %04x/%04x" % (
-        what, bad.size, h.n, bad[0] if bad.size else -1, *((ghi[bad[0]], gres[bad[0]], h.hi[bad[0]], h.res[bad[0]])
-                                                          if bad.size else (0, 0, 0, 0)))
+    bad = np.flatnonzero(ghi != h.hi)
+    assert bad.size == 0, "%s: %d of %d 16-bit weights differ, first at %d: gpu %04x oracle %04x" % (
+        what, bad.size, h.n, bad[0], ghi[bad[0]], h.hi[bad[0]])
+    # residual: one slot per parameter, or (packed) the plane bytes
+    bad = np.flatnonzero(gres != h.res)
+    assert bad.size == 0, "%s: %d of %d residual entries differ, first at %d: gpu %x oracle %x" % (
+        what, bad.size, h.res.size, bad[0], gres[bad[0]], h.res[bad[0]])
     gm = host_f32(d.m)
     assert np.array_equal(gm.view(np.uint32), h.m.view(np.uint32)), what + ": m differs"
     if h.v is not None and d.v is not None:

@@ -80,6 +80,14 @@ def test_split_merge_argument_validation():
     assert _status(mpo.mpo_merge, A, A + 0x1000, A + 0x2000, 10, fmt=mpo.MPO_FP16, res_bits=16) == mpo.MPO_ERR_INVALID_ARG
     # res [A+0x1000, +10 bytes) with 8 bits does not reach hi at A+0x100a; with 16 bits it does
     assert _status(mpo.mpo_split, A, A + 0x100a, A + 0x1000, 10, res_bits=9) == mpo.MPO_ERR_ALIAS
+    # packed planes: even E from 2 to 14, truncation only, 16-byte aligned buffer
+    assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, res_bits=12, res_packed=True,
+                   round=mpo.MPO_ROUND_NEAREST) == mpo.MPO_ERR_UNSUPPORTED
+    for bad in (0, 1, 3, 7, 16):
+        assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, res_bits=bad, res_packed=True) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_merge, A, A + 0x1004, A + 0x2000, 10, res_bits=12, res_packed=True) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, fmt=mpo.MPO_FP16, res_bits=14, res_packed=True) \
+        == mpo.MPO_ERR_INVALID_ARG
     # zero elements: a legal no-op even with null pointers
     assert _status(mpo.mpo_split, 0, 0, 0, 0) == mpo.MPO_OK
     assert _status(mpo.mpo_merge, 0, 0, 0, 0, fmt=mpo.MPO_FP16) == mpo.MPO_OK
@@ -105,6 +113,22 @@ def test_plan_validation():
     # a zero-length tensor needs no pointers
     assert _status(_host_plan, [T(n=0, hi=0, res=0, grad=0, m=0, v=0)]) == mpo.MPO_OK
     assert _status(_host_plan, []) == mpo.MPO_OK
+
+
+def test_res_bytes():
+    assert mpo.mpo_res_bytes(1000) == 2000 and mpo.mpo_res_bytes(1000, 8) == 1000 and mpo.mpo_res_bytes(1000, 9) == 2000
+    r16 = lambda x: (x + 15) // 16 * 16
+    assert mpo.mpo_res_bytes(1000, 12, True) == r16(1000) + r16(500)             # 1.5 bytes per parameter
+    assert mpo.mpo_res_bytes(1001, 14, True) == r16(1001) + r16(501) + r16(251)
+    assert mpo.mpo_res_bytes(7, 2, True) == 16 and mpo.mpo_res_bytes(1 << 30, 4, True) == 1 << 29
+    # a packed list: the next tensor may start right after the planes, not before
+    a = T(0, n=1000, res_bits=12, res_packed=True)
+    nb = mpo.mpo_res_bytes(1000, 12, True)
+    assert _status(_host_plan, [a, T(1, res_bits=12, res_packed=True, hi=a.res + nb)]) == mpo.MPO_OK
+    assert _status(_host_plan, [a, T(1, res_bits=12, res_packed=True, hi=a.res + nb - 2)]) == mpo.MPO_ERR_ALIAS
+    assert _status(_host_plan, [a, T(1, res_bits=12)]) == mpo.MPO_ERR_UNSUPPORTED           # packed and slots mixed
+    assert _status(_host_plan, [T(0, res_bits=5, res_packed=True)]) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(_host_plan, [T(0, res_bits=12, res_packed=True, res=A + 0x100008)]) == mpo.MPO_ERR_INVALID_ARG
 
 
 def test_plan_alias_detection():

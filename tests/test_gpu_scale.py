@@ -27,20 +27,25 @@ def _ref_cfg(st):
     rf = ref.BF16 if st.wl.fmt == "bf16" else ref.FP16
     return ref.AdamCfg(lr=c.lr, beta1=c.beta1, beta2=c.beta2, eps=c.eps, weight_decay=c.weight_decay,
                        decoupled_wd=c.decoupled_wd, loss_scale=c.loss_scale, weight_fmt=rf, grad_fmt=rf,
-                       res_bits=st.res_bits, round=st.round, seed=st.rng_seed), rf
+                       res_bits=st.res_bits, round=st.round, seed=st.rng_seed, res_packed=st.res_packed), rf
 
 
-def _run_and_compare(key, steps, sampler, res_bits=0, round=0):
+def _run_and_compare(key, steps, sampler, res_bits=0, round=0, packed=False):
     """round: 0 truncation, 1 nearest, 2 stochastic.  With stochastic rounding the sampler must
     pick whole tensors only: the oracle numbers the elements of the array it is given, and the
     random stream is indexed by the element's position in its tensor."""
     wl = synth.workload(key)
     say("full-size %s: %d params, %d steps, res_bits %d, round %d" % (key, wl.num_params, steps, res_bits, round))
-    st = harness.ModelState(wl, DEV, seed=2309, keep_w32_samples=sampler, res_bits=res_bits, round=round)
+    st = harness.ModelState(wl, DEV, seed=2309, keep_w32_samples=sampler, res_bits=res_bits, round=round,
+                            res_packed=packed)
+    if packed:
+        assert all(isinstance(st.w32_samples[i][0], slice) for i in st.w32_samples), "packed: whole tensors only"
     rcfg, rf = _ref_cfg(st)
     host = {}
     for i, (idx, w) in st.w32_samples.items():
-        if round == 2:
+        if packed:
+            hi, res = ref.split(np.ascontiguousarray(w.numpy()), rf, res_bits, packed=True)
+        elif round == 2:
             assert isinstance(idx, slice)
             hi, res = ref.split(np.ascontiguousarray(w.numpy()), rf, res_bits, round, st.rng_seed, i)
         else:
@@ -59,7 +64,7 @@ def _run_and_compare(key, steps, sampler, res_bits=0, round=0):
                 g = st.grad[tv.goff:tv.goff + tv.spec.n][idx]
                 gb = synth.bits16(g)
                 h = host[i]
-                if round == 2:
+                if round == 2 or packed:
                     ref.adam_step(h[0], h[1], gb, h[2], h[3], rcfg, t, tensor_id=i)     # whole tensor, in order
                 else:
                     ref_adam(h[0], h[1], gb, h[2], h[3], rcfg, t)
@@ -72,8 +77,11 @@ def _run_and_compare(key, steps, sampler, res_bits=0, round=0):
         idx = st.w32_samples[i][0]
         n = tv.spec.n
         got_hi = synth.bits16(st.hi[tv.off:tv.off + n][idx])
-        got_res = st.res[tv.off:tv.off + n][idx]
-        got_res = got_res.cpu().numpy().copy() if got_res.dtype == torch.uint8 else synth.bits16(got_res)
+        if packed:
+            got_res = st.res[st.res_off[i]:st.res_off[i] + mpo.mpo_res_bytes(n, res_bits, True)].cpu().numpy().copy()
+        else:
+            got_res = st.res[tv.off:tv.off + n][idx]
+            got_res = got_res.cpu().numpy().copy() if got_res.dtype == torch.uint8 else synth.bits16(got_res)
         got_m = st.m[tv.off:tv.off + n][idx].cpu().numpy()
         got_v = st.v[tv.off:tv.off + n][idx].cpu().numpy()
         name = "%s tensor %d (%s)" % (key, i, tv.spec.name)
@@ -135,6 +143,12 @@ def _whole_tensors(i, n):
 def test_c3_llama7b_nearest_per_layer_sampled():
     checked, wl = _run_and_compare("c3", 2, _blocks_sampler(seed=7), round=1)
     assert checked > 40_000_000
+
+
+def test_c3_llama7b_packed_12_bits_whole_tensors():
+    """The paper's Figure 1 example, 12 extra bits without padding: 3.5 B per weight, 25 B moved per Adam step."""
+    checked, wl = _run_and_compare("c3", 2, _whole_tensors, res_bits=12, packed=True)
+    assert checked > 100_000_000
 
 
 def test_c4_llama13b_fp16_stochastic_whole_tensors():
