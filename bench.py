@@ -103,7 +103,9 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     wl = synth.workload(a.workload)
-    steps = a.steps if a.steps is not None else wl.steps
+    # default: at least 20 steps (the configurations ask for 3-5; more steps only average the same step)
+    steps = a.steps if a.steps is not None else max(wl.steps, 20 if wl.per_layer else wl.steps)
+    props = torch.cuda.get_device_properties(0)
     t_setup = time.perf_counter()
     st = harness.ModelState(wl, dev, res_bits=a.res_bits, res_packed=a.res_packed,
                             round={"trunc": 0, "nearest": 1, "stochastic": 2}[a.round])
@@ -154,7 +156,9 @@ def main():
                                                                            15 if a.round == "stochastic" else 16),
                                                         "packed planes" if a.res_packed else "%d-bit residual" % (8 * st.res_bytes)), "optimizer": wl.optimizer if a.optimizer == "adam" else "sgd-momentum", "round": a.round, "loss_scale": wl.loss_scale,
                    "launches_per_step": launches // steps, "per_layer": wl.per_layer,
-                   "fresh_grads_in_loop": bool(a.fresh_grads), "resident_GB": st.resident_bytes / 1e9},
+                   "fresh_grads_in_loop": bool(a.fresh_grads), "resident_GB": st.resident_bytes / 1e9,
+                   "device": "%s (%d CUs) %s" % (props.name, props.multi_processor_count,
+                                                 getattr(props, "uuid", ""))},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                      "frac": achieved / PEAK_HBM_GBPS,
                      "traffic": (MEASURED_TRAFFIC_BYTES_PER_PARAM[wl.key] * P * steps / launches

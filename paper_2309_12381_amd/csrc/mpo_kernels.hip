@@ -3,27 +3,29 @@
  *
  * arXiv 2309.12381, Section 3.1: each weight is a 16-bit float plus the
  * significand bits an fp32 copy would have kept; the update runs in fp32 and
- * both parts are written back.  Here the whole step (merge, un-scale, decay,
- * moments, update, split) is ONE pass over memory: per parameter it reads
- * hi, res, grad (2 B each) and m, v (4 B each) and writes hi, res, m, v:
+ * both parts are written back.  Here the whole step (merge, un-scale, clamp,
+ * decay, moments, update, split) is ONE pass over memory: per parameter it
+ * reads hi, res, grad (2 B each) and m, v (4 B each) and writes hi, res, m, v:
  * 26 B for Adam, 18 B for SGD with momentum.  Nothing is a contraction, so
- * there is no MFMA; the work is bounded by HBM bandwidth and by plain VALU
- * issue (two IEEE divisions and a square root per parameter).
+ * there is no MFMA; the work is bounded by HBM bandwidth (replacing the
+ * arithmetic by a copy does not change the measured time).
  *
  * Mapping: one workgroup of 256 lanes (4 wavefronts of 64) per chunk of 4096
  * consecutive parameters of one tensor; the chunk table lets one launch cover
- * every tensor of a list (Section 3.1, "Fused" optimizer).  A lane owns 4
- * consecutive parameters per row: 64-bit accesses to the 16-bit arrays and
- * 128-bit accesses to the fp32 arrays, so EVERY load and store instruction of a
- * wavefront covers one dense span (512 B or 1 KiB) and no cache line is
- * touched by two instructions.  Each wavefront owns a contiguous quarter of the
- * chunk.  All rows of a chunk are loaded before any
- * arithmetic (4 rows x 5 streams = 20 requests per lane in flight), and all
- * accesses carry the non-temporal hint: the data is used once per step, and
- * streaming it past the caches measured 8-10 % faster than default policy
- * on MI355X (a lane owning 8 parameters, i.e. 128-bit accesses to the 16-bit
- * arrays and two strided 128-bit accesses to the fp32 arrays, measured
- * another 7 % slower, and much slower with the non-temporal hint).
+ * every tensor of a list (Section 3.1, "Fused" optimizer).
+ *   - A lane owns 4 consecutive parameters per row: 64-bit accesses to the
+ *     16-bit arrays and 128-bit accesses to the fp32 arrays, so EVERY load and
+ *     store instruction of a wavefront covers one dense span (512 B or 1 KiB)
+ *     and no cache line is touched by two instructions.  (8 parameters per lane,
+ *     i.e. 128-bit accesses to the 16-bit arrays and two 32-byte-strided
+ *     accesses to the fp32 arrays, measured 7 % slower on MI355X, and 25 %
+ *     slower once stores are non-temporal, because two instructions then write
+ *     halves of each line.)
+ *   - Each wavefront owns a contiguous quarter of the chunk and walks it in 4
+ *     rows (+5 % over rows interleaved across the wavefronts).
+ *   - All 4 rows are loaded before any arithmetic: 20 requests per lane in flight.
+ *   - All accesses carry the non-temporal hint: every byte is used once per step,
+ *     and streaming past the caches measured 6-8 % faster than the default policy.
  *
  * Built with -ffp-contract=off and correctly rounded division / square root:
  * every line of arithmetic below is one IEEE binary32 operation.
@@ -32,28 +34,12 @@
 
 #include "mpo_internal.h"
 
-/* Tuning knobs (defaults are the measured best; see the header comment). */
-#ifndef MPO_EPL
-#define MPO_EPL 4 /* parameters per lane per row: 4, or 8 (128-bit accesses to the 16-bit arrays) */
-#endif
-#ifndef MPO_BATCH
-#define MPO_BATCH (mpo::kChunkElems / (mpo::kBlock * MPO_EPL)) /* rows loaded together: all */
-#endif
-#ifndef MPO_NT_LOAD
-#define MPO_NT_LOAD 1
-#endif
-#ifndef MPO_NT_STORE
-#define MPO_NT_STORE 1
-#endif
-
 namespace mpo {
 namespace {
 
-constexpr int EPL = MPO_EPL;
-constexpr int ROWS = kChunkElems / (kBlock * EPL);
-constexpr int BATCH = MPO_BATCH;
-static_assert(EPL == 4 || EPL == 8, "a lane owns 4 or 8 parameters per row");
-static_assert(ROWS % BATCH == 0, "rows per chunk must be a multiple of the batch");
+constexpr int EPL = 4;                                /* parameters per lane per row   */
+constexpr int ROWS = kChunkElems / (kBlock * EPL);    /* rows per chunk, all in flight */
+static_assert(ROWS * kBlock * EPL == kChunkElems, "a chunk is a whole number of rows");
 
 /* Every parameter array lives in device (global) memory.  Saying so lets the
  * compiler emit global_load/global_store instead of flat accesses for pointers
@@ -61,89 +47,57 @@ static_assert(ROWS % BATCH == 0, "rows per chunk must be a multiple of the batch
 #define MPO_GLOBAL __attribute__((address_space(1)))
 typedef MPO_GLOBAL uint16_t *gu16p;
 typedef const MPO_GLOBAL uint16_t *gcu16p;
+typedef MPO_GLOBAL uint8_t *gu8p;
+typedef const MPO_GLOBAL uint8_t *gcu8p;
 typedef MPO_GLOBAL float *gf32p;
 typedef const MPO_GLOBAL float *gcf32p;
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-template <int NDW> struct DwVec;
-template <> struct DwVec<4> { typedef u32x4 T; };
-template <> struct DwVec<2> { typedef u32x2 T; };
+/* Vector accesses of the fast path: non-temporal (streaming) loads and stores. */
+template <typename T> __device__ __forceinline__ T ld_stream(const MPO_GLOBAL T *p) { return __builtin_nontemporal_load(p); }
+template <typename T> __device__ __forceinline__ void st_stream(MPO_GLOBAL T *p, T x) { __builtin_nontemporal_store(x, p); }
 
-/* EPL 16-bit values = EPL/2 dwords in one access. */
+/* 4 x 16 bit = 2 dwords in one access */
 __device__ __forceinline__ void load16(gcu16p p, uint32_t (&out)[EPL / 2])
 {
-    typedef DwVec<EPL / 2>::T T;
-    const MPO_GLOBAL T *q = reinterpret_cast<const MPO_GLOBAL T *>(p);
-    T x = MPO_NT_LOAD ? __builtin_nontemporal_load(q) : *q;
-#pragma unroll
-    for (int i = 0; i < EPL / 2; ++i) out[i] = x[i];
+    const u32x2 x = ld_stream(reinterpret_cast<const MPO_GLOBAL u32x2 *>(p));
+    out[0] = x[0];
+    out[1] = x[1];
 }
-
 __device__ __forceinline__ void store16(gu16p p, const uint32_t (&in)[EPL / 2])
 {
-    typedef DwVec<EPL / 2>::T T;
-    T x;
-#pragma unroll
-    for (int i = 0; i < EPL / 2; ++i) x[i] = in[i];
-    MPO_GLOBAL T *q = reinterpret_cast<MPO_GLOBAL T *>(p);
-    if (MPO_NT_STORE) __builtin_nontemporal_store(x, q); else *q = x;
+    u32x2 x;
+    x[0] = in[0];
+    x[1] = in[1];
+    st_stream(reinterpret_cast<MPO_GLOBAL u32x2 *>(p), x);
 }
 
-/* EPL bytes (8-bit residuals) = EPL/4 dwords in one access. */
-typedef const MPO_GLOBAL uint8_t *gcu8p;
-typedef MPO_GLOBAL uint8_t *gu8p;
-
+/* 4 x 8 bit (byte residuals) = 1 dword; the second register of the pair is unused */
 __device__ __forceinline__ void load8(gcu8p p, uint32_t (&out)[EPL / 2])
 {
-    if (EPL == 4) {
-        const MPO_GLOBAL uint32_t *q = reinterpret_cast<const MPO_GLOBAL uint32_t *>(p);
-        out[0] = MPO_NT_LOAD ? __builtin_nontemporal_load(q) : *q;
-    } else {
-        const MPO_GLOBAL u32x2 *q = reinterpret_cast<const MPO_GLOBAL u32x2 *>(p);
-        u32x2 x = MPO_NT_LOAD ? __builtin_nontemporal_load(q) : *q;
-        out[0] = x[0];
-        out[EPL / 2 - 1 > 0 ? 1 : 0] = x[1];
-    }
+    out[0] = ld_stream(reinterpret_cast<const MPO_GLOBAL uint32_t *>(p));
+    out[1] = 0u;
 }
-
 __device__ __forceinline__ void store8(gu8p p, const uint32_t (&in)[EPL / 2])
 {
-    if (EPL == 4) {
-        MPO_GLOBAL uint32_t *q = reinterpret_cast<MPO_GLOBAL uint32_t *>(p);
-        if (MPO_NT_STORE) __builtin_nontemporal_store(in[0], q); else *q = in[0];
-    } else {
-        u32x2 x;
-        x[0] = in[0];
-        x[1] = in[EPL / 2 - 1 > 0 ? 1 : 0];
-        MPO_GLOBAL u32x2 *q = reinterpret_cast<MPO_GLOBAL u32x2 *>(p);
-        if (MPO_NT_STORE) __builtin_nontemporal_store(x, q); else *q = x;
-    }
+    st_stream(reinterpret_cast<MPO_GLOBAL uint32_t *>(p), in[0]);
 }
 
+/* 4 x fp32 in one 128-bit access */
 __device__ __forceinline__ void load32(gcf32p p, float (&out)[EPL])
 {
-    const MPO_GLOBAL f32x4 *q = reinterpret_cast<const MPO_GLOBAL f32x4 *>(p);
+    const f32x4 x = ld_stream(reinterpret_cast<const MPO_GLOBAL f32x4 *>(p));
 #pragma unroll
-    for (int k = 0; k < EPL / 4; ++k) {
-        f32x4 x = MPO_NT_LOAD ? __builtin_nontemporal_load(q + k) : q[k];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) out[4 * k + i] = x[i];
-    }
+    for (int i = 0; i < 4; ++i) out[i] = x[i];
 }
-
 __device__ __forceinline__ void store32(gf32p p, const float (&in)[EPL])
 {
-    MPO_GLOBAL f32x4 *q = reinterpret_cast<MPO_GLOBAL f32x4 *>(p);
+    f32x4 x;
 #pragma unroll
-    for (int k = 0; k < EPL / 4; ++k) {
-        f32x4 x;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) x[i] = in[4 * k + i];
-        if (MPO_NT_STORE) __builtin_nontemporal_store(x, q + k); else q[k] = x;
-    }
+    for (int i = 0; i < 4; ++i) x[i] = in[i];
+    st_stream(reinterpret_cast<MPO_GLOBAL f32x4 *>(p), x);
 }
 
 /* ---- formats (Table 1; Section 3.1) --------------------------------------
@@ -629,19 +583,15 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
     const uint32_t t = threadIdx.x;
 
     if (aligned && len == kChunkElems) {
-        /* whole chunk: no bounds checks */
-#pragma unroll 1
-        for (int r0 = 0; r0 < ROWS; r0 += BATCH) {
-            Row x[BATCH];
+        /* whole chunk: no bounds checks; every row is requested before the first is used */
+        Row x[ROWS];
 #pragma unroll
-            for (int b = 0; b < BATCH; ++b)
-                load_row<OPT, MOM, RMODE>(x[b], hi, R, grad, m, v, row_elem(r0 + b, t));
+        for (int r = 0; r < ROWS; ++r) load_row<OPT, MOM, RMODE>(x[r], hi, R, grad, m, v, row_elem(r, t));
 #pragma unroll
-            for (int b = 0; b < BATCH; ++b) {
-                if (RND) compute_row_rounded<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x[b], s, kept, sh, rng, off + row_elem(r0 + b, t));
-                else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x[b], s, sh);
-                store_row<OPT, MOM, RMODE>(x[b], hi, R, m, v, row_elem(r0 + b, t));
-            }
+        for (int r = 0; r < ROWS; ++r) {
+            if (RND) compute_row_rounded<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x[r], s, kept, sh, rng, off + row_elem(r, t));
+            else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x[r], s, sh);
+            store_row<OPT, MOM, RMODE>(x[r], hi, R, m, v, row_elem(r, t));
         }
     } else if (RMODE == kResPlanes) {
         /* packed planes outside the fast path: every lane walks whole groups of EPL parameters */
