@@ -67,6 +67,68 @@ def cpu_baseline(wl, sample_params: int, steps: int):
                       "the tests, slice-parallel over %d host threads" % (n, steps, cores)}
 
 
+def layer_breakdown(st, cfg, stream, step_no, bpp):
+    """One more step with an event around every mpo_step_layer call: GB/s of the big launches
+    (transformer blocks, embedding, head) and the time of the small one (a norm vector)."""
+    import torch
+    from paper_2309_12381_amd import binding as mpo
+    rows = []
+    for layer in st.layers_backward:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        mpo.mpo_step_layer(st.plan, layer, cfg, step_no, stream=stream)
+        e1.record(stream)
+        rows.append((layer, sum(st.views[i].spec.n for i in st.by_layer[layer]), e0, e1))
+    torch.cuda.synchronize()
+    big, small = [], []
+    for layer, n, e0, e1 in rows:
+        ms = e0.elapsed_time(e1)
+        (big if n >= (1 << 24) else small).append((bpp * n / ms / 1e6, ms, n, layer))
+    big.sort()
+    out = {"what": "one extra step, an event pair around every per-layer launch (includes the gaps between launches)",
+           "big_launches": len(big), "big_GBps_min": big[0][0], "big_GBps_median": big[len(big) // 2][0],
+           "big_GBps_max": big[-1][0], "big_params_each": sorted({b[2] for b in big})}
+    if small:
+        out["small_launches"] = [{"layer": s[3], "params": s[2], "us": s[1] * 1e3} for s in small]
+    return out
+
+
+def traffic_ceiling(st, stream, with_v, bpp, steps):
+    """The same bytes over the same arrays in the same per-layer launches with the arithmetic
+    taken out (csrc/stream_probe.hip): what this access pattern reaches on this GPU.  Runs after
+    the timed region; it overwrites the state."""
+    import torch
+    from paper_2309_12381_amd import probe
+    if st.wl.per_layer:
+        spans = []
+        for layer in st.layers_backward:
+            ids = st.by_layer[layer]
+            assert ids == list(range(ids[0], ids[-1] + 1)), "a layer's tensors are adjacent in the flat arrays"
+            lo = st.views[ids[0]].off
+            up = st.views[ids[-1]].off + st.views[ids[-1]].spec.n
+            spans.append((lo, up - lo))
+    else:
+        spans = [(0, st.total)]
+
+    def once():
+        moved = 0
+        for lo, n in spans:
+            probe.stream_probe(st.hi[lo:], st.res[lo:], st.grad, st.m[lo:], st.v[lo:] if with_v else None, n, stream)
+            moved += n - n % 4096
+        return moved
+    once()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    moved = sum(once() for _ in range(steps))
+    e1.record(stream)
+    torch.cuda.synchronize()
+    gbps = bpp * moved / e0.elapsed_time(e1) / 1e6
+    return {"achieved": gbps, "unit": "GB/s", "frac_of_peak": gbps / PEAK_HBM_GBPS,
+            "what": "stream_probe: same arrays, same launches per step (%d), same bytes per parameter, no arithmetic; "
+                    "%d steps after the timed region" % (len(spans), steps)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -84,7 +146,12 @@ def main():
                     help="rounding of the 16-bit value: trunc is the method's base mode and the headline")
     ap.add_argument("--fresh-grads", action="store_true",
                     help="regenerate each layer's gradients inside the loop (adds generator kernels to the timing)")
+    ap.add_argument("--no-place", action="store_true",
+                    help="allocate the state arrays one after the other instead of dividing them between two "
+                         "HBM regions (paper_2309_12381_amd/placement.py)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-breakdown", action="store_true", help="skip the per-layer breakdown step")
+    ap.add_argument("--no-ceiling", action="store_true", help="skip the arithmetic-free traffic probe")
     ap.add_argument("--cpu-sample", type=int, default=1 << 26)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise kernel that reads 1 GiB and writes 1 GiB (known traffic, "
@@ -108,7 +175,7 @@ def main():
     props = torch.cuda.get_device_properties(0)
     t_setup = time.perf_counter()
     st = harness.ModelState(wl, dev, res_bits=a.res_bits, res_packed=a.res_packed,
-                            round={"trunc": 0, "nearest": 1, "stochastic": 2}[a.round])
+                            round={"trunc": 0, "nearest": 1, "stochastic": 2}[a.round], place=not a.no_place)
     if wl.per_layer:
         # the reused buffer holds one (largest) layer's worth of gradient values, read by every layer
         st.grad.normal_(0.0, wl.grad_std * wl.loss_scale, generator=synth.generator(7, dev))
@@ -129,17 +196,19 @@ def main():
         step_no += 1
         st.step(step_no, cfg, stream, fresh_grads=a.fresh_grads)
     torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    # one event after every step, on the stream the kernels are launched on
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     launches = 0
     t0 = time.perf_counter()
-    ev0.record(stream)
-    for _ in range(steps):
+    evs[0].record(stream)
+    for k in range(steps):
         step_no += 1
         launches += st.step(step_no, cfg, stream, fresh_grads=a.fresh_grads)
-    ev1.record(stream)
+        evs[k + 1].record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ev_ms = ev0.elapsed_time(ev1)
+    ev_ms = evs[0].elapsed_time(evs[-1])
+    step_ms = sorted(evs[k].elapsed_time(evs[k + 1]) for k in range(steps))
 
     P = wl.num_params
     value = P * steps / wall
@@ -157,6 +226,7 @@ def main():
                                                         "packed planes" if a.res_packed else "%d-bit residual" % (8 * st.res_bytes)), "optimizer": wl.optimizer if a.optimizer == "adam" else "sgd-momentum", "round": a.round, "loss_scale": wl.loss_scale,
                    "launches_per_step": launches // steps, "per_layer": wl.per_layer,
                    "fresh_grads_in_loop": bool(a.fresh_grads), "resident_GB": st.resident_bytes / 1e9,
+                   "placement": st.placement,
                    "device": "%s (%d CUs) %s" % (props.name, props.multi_processor_count,
                                                  getattr(props, "uuid", ""))},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
@@ -166,9 +236,16 @@ def main():
                                  and not a.res_packed else None),
                      "kernel": "step_kernel<%s,%s>" % (a.optimizer, wl.fmt), "bytes_per_param": bpp,
                      "bytes_per_launch": bytes_per_launch, "avg_launch_ms": ev_ms / launches,
-                     "event_ms": ev_ms, "launches": launches},
+                     "event_ms": ev_ms, "launches": launches,
+                     "step_ms_median": step_ms[len(step_ms) // 2], "step_ms_min": step_ms[0]},
         "setup_s": setup_s,
     }
+    if wl.per_layer and not a.no_breakdown:
+        res["breakdown"] = layer_breakdown(st, cfg, stream, step_no + 1, bpp)
+    if st.res_bytes == 2 and not a.res_packed and not a.no_ceiling:
+        ceil = traffic_ceiling(st, stream, a.optimizer == "adam", bpp, min(steps, 5))
+        ceil["step_kernel_frac_of_this"] = achieved / ceil["achieved"]
+        res["roofline"]["ceiling"] = ceil
     st.close()
     if a.calibrate_copy:
         src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)       # 1 GiB

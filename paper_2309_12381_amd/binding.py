@@ -10,6 +10,11 @@ import os
 from dataclasses import dataclass
 from typing import Optional, Sequence
 
+# PyTorch first: it brings the process's HIP runtime (its own copy of libamdhip64.so.7).  Loaded in
+# this order, libmpo.so binds to that same copy; loaded the other way round, the process would hold
+# two runtimes and the library's launches would go to one that never saw torch's streams and memory.
+import torch  # noqa: F401
+
 from . import build as _build
 
 MPO_OK = 0

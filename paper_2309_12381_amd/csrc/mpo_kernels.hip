@@ -801,6 +801,7 @@ hipError_t launch_step_t(const StepLaunch &L)
     uint64_t done = 0;
     while (done < L.num_chunks) {
         const uint64_t now = (L.num_chunks - done < kMaxGrid) ? (L.num_chunks - done) : kMaxGrid;
+        (void)hipGetLastError(); /* an error an earlier, unrelated runtime call left on this thread is not ours */
         step_kernel<OPT, WFMT, GFMT, DECAY, MOM, RMODE, RND><<<dim3((uint32_t)now), dim3(kBlock), 0, L.stream>>>(
             L.descs, L.chunks, L.first_chunk + done, L.s, L.ov);
         const hipError_t e = hipGetLastError();
@@ -856,6 +857,7 @@ hipError_t launch_split_t(const SplitMergeArgs &a)
     while (done < blocks) {
         const uint64_t now = (blocks - done < kMaxGrid) ? (blocks - done) : kMaxGrid;
         const uint64_t e0 = done * kChunkElems;
+        (void)hipGetLastError();
         split_kernel<FMT, RMODE, RND><<<dim3((uint32_t)now), dim3(kBlock), 0, a.stream>>>(
             a.w32_in, a.hi, a.res, a.n, e0, a.al, a.kept, a.sh, a.rs);
         const hipError_t e = hipGetLastError();
@@ -873,6 +875,7 @@ hipError_t launch_merge_t(const SplitMergeArgs &a)
     while (done < blocks) {
         const uint64_t now = (blocks - done < kMaxGrid) ? (blocks - done) : kMaxGrid;
         const uint64_t e0 = done * kChunkElems;
+        (void)hipGetLastError();
         merge_kernel<FMT, RMODE, RND><<<dim3((uint32_t)now), dim3(kBlock), 0, a.stream>>>(
             a.hi, a.res, a.w32_out, a.n, e0, a.al, a.kept, a.sh, a.rs.round);
         const hipError_t e = hipGetLastError();

@@ -10,6 +10,7 @@ from typing import Dict, List, Optional
 import torch
 
 from . import binding as mpo
+from . import placement
 from . import synth
 
 FMT = {"bf16": mpo.MPO_BF16, "fp16": mpo.MPO_FP16}
@@ -30,11 +31,13 @@ class ModelState:
     """hi, res, m, v for every tensor of a workload, each kind in ONE flat allocation (large
     blocks keep the driver on large page fragments), plus ONE gradient buffer sized for the
     largest layer and reused by every layer (Section 3.2: a gradient is consumed as soon as it
-    exists and never kept).  For workloads stepped in one launch the buffer holds all gradients."""
+    exists and never kept).  For workloads stepped in one launch the buffer holds all gradients.
+    With `place` (the default) a large state is laid out over two HBM regions: hi and m in one,
+    res, v and the gradient buffer in another (see placement.py); `self.placement` is the report."""
 
     def __init__(self, wl: synth.Workload, device="cuda:0", seed: int = 2309, keep_w32_samples=None,
                  res_bits: int = 0, round: int = mpo.MPO_ROUND_TRUNC, rng_seed: int = 0x2309_12381,
-                 res_packed: bool = False):
+                 res_packed: bool = False, place: bool = True):
         self.wl = wl
         self.res_packed = res_packed        # extra bits stored in packed planes (Section 3.1, Figure 1)
         self.round = round                  # how hi is rounded (Section 3.1, last paragraph)
@@ -56,21 +59,21 @@ class ModelState:
             off += _round_up(s.n, 8)
         self.total = off
         self.grad_len = max(layer_fill.values()) if wl.per_layer else off
-        self.hi = torch.empty(self.total, dtype=torch.int16, device=device)
         if res_packed:
             # one byte buffer; each tensor's planes start at a multiple of 16 bytes
             self.res_off, fill = [], 0
             for tv in self.views:
                 self.res_off.append(fill)
                 fill += mpo.mpo_res_bytes(tv.spec.n, res_bits, True)
-            self.res = torch.zeros(fill, dtype=torch.uint8, device=device)
+            res_spec = (fill, torch.uint8)
         else:
             self.res_off = [tv.off for tv in self.views]
-            self.res = torch.empty(self.total, dtype=torch.uint8 if self.res_bytes == 1 else torch.int16, device=device)
-        self.m = torch.zeros(self.total, dtype=torch.float32, device=device)
-        self.v = torch.zeros(self.total, dtype=torch.float32, device=device)
+            res_spec = (self.total, torch.uint8 if self.res_bytes == 1 else torch.int16)
         self.gdtype = torch.bfloat16 if wl.fmt == "bf16" else torch.float16
-        self.grad = torch.zeros(self.grad_len, dtype=self.gdtype, device=device)
+        arrays, self.placement = placement.allocate_state(self.total, res_spec, (self.grad_len, self.gdtype), device,
+                                                          zero_res=res_packed, place=place)
+        self.hi, self.m = arrays["hi"], arrays["m"]
+        self.res, self.v, self.grad = arrays["res"], arrays["v"], arrays["grad"]
         self.seed = seed
         self.w32_samples = {}
         # weights: fp32 ~ N(0, std^2), drawn per tensor on the device, then split by the library

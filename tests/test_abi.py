@@ -218,3 +218,22 @@ def test_plan_create_without_a_gpu_fails_loudly():
     with pytest.raises(mpo.MpoError) as e:
         mpo.Plan([T(0)])
     assert e.value.status == mpo.MPO_ERR_HIP and mpo.lib.mpo_last_hip_error() != 0
+
+
+@pytest.mark.parametrize("order", ["package, torch", "torch, package", "probe, torch"])
+def test_one_hip_runtime_whatever_the_import_order(order):
+    """The library and PyTorch must share ONE copy of the HIP runtime: with two, the library's
+    launches go to a runtime that knows nothing of torch's streams and allocations."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    first = {"package, torch": "import paper_2309_12381_amd, torch",
+             "torch, package": "import torch, paper_2309_12381_amd",
+             "probe, torch": "from paper_2309_12381_amd import probe; probe._load(); import torch, paper_2309_12381_amd"}[order]
+    code = (first + "\n"
+            "libs = sorted({l.split()[-1] for l in open('/proc/self/maps') if 'libamdhip64' in l})\n"
+            "print('\\n'.join(libs))\n")
+    out = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True, timeout=300)
+    assert out.returncode == 0, out.stderr
+    libs = [l for l in out.stdout.split("\n") if l]
+    assert len(libs) == 1, "more than one HIP runtime mapped: %s" % libs
