@@ -13,7 +13,8 @@ freed large blocks, the driver no longer hands memory out in order and large arr
 to be spread over the regions anyway.
 
 `allocate_state` allocates hi and m first, then up to `max_tries` candidates for
-(res, v, grad) one after the other, all kept until the choice is made.  Each candidate
+(res, v, grad) one after the other (at least 16 GiB apart, with filler blocks between
+small ones), all kept until the choice is made.  Each candidate
 is timed with the bandwidth probe (csrc/stream_probe.hip) on windows at several matching
 positions of the arrays, the way the step walks them; the search stops at the first
 candidate that shows the gain of a second region at every position; the fastest
@@ -30,7 +31,8 @@ GIB = 1 << 30
 _TEST_PARAMS = 1 << 26              # parameters per probe launch: 1.75 GB of traffic, about 0.3 ms
 _N2 = _TEST_PARAMS * 2              # bytes of a window of a 16-bit array
 _N4 = _TEST_PARAMS * 4              # bytes of a window of an fp32 array
-MIN_PARAMS = 1 << 30                # below this the state is not placed (windows must fit several times)
+MIN_PARAMS = 1 << 28                # below this the state is not placed (the windows must fit)
+_STRIDE = 16 * GIB                  # successive candidates start at least this far apart
 
 
 def _window(t: torch.Tensor, q: float, nbytes: int) -> torch.Tensor:
@@ -55,11 +57,11 @@ def _rate(hi, res, grad, m, v, stream) -> float:
 
 
 def allocate_state(n: int, res_spec: Tuple[int, torch.dtype], grad_spec: Tuple[int, torch.dtype], device="cuda:0",
-                   zero_res: bool = False, place: bool = True, threshold: float = 1.05, max_tries: int = 5,
+                   zero_res: bool = False, place: bool = True, threshold: float = 1.05, max_tries: int = 8,
                    positions: Sequence[float] = (0.0, 1.0 / 3, 2.0 / 3, 1.0)) -> Tuple[Dict[str, torch.Tensor], dict]:
     """Allocate hi (int16) and m, v (fp32, cleared) of n elements, res and grad as specified
     ((elements, dtype); grad cleared, res cleared if `zero_res`).  With `place`, and n at least
-    2^30, (res, v, grad) are placed in another HBM region than (hi, m) when the probe can find one.
+    2^28, (res, v, grad) are placed in another HBM region than (hi, m) when the probe can find one.
     Returns ({"hi","res","grad","m","v"}, report): report["split"] says whether the probe saw the
     gain of a second region at every tested position, with the rates it measured."""
     dev = torch.device(device)
@@ -99,13 +101,15 @@ def allocate_state(n: int, res_spec: Tuple[int, torch.dtype], grad_spec: Tuple[i
         return out
 
     need = res_bytes + 4 * n + grad_bytes
-    cands, rates = [], []
+    cands, rates, fillers = [], [], []
     found = False
     while len(cands) < max_tries:
         free, _ = torch.cuda.mem_get_info(dev)
-        if free < need + (4 << 30):
+        if free < max(need, _STRIDE) + (4 << 30):
             break
         # nothing is freed during the search: freed memory comes back in any order
+        if cands and need < _STRIDE:
+            fillers.append(torch.empty(_STRIDE - need, dtype=torch.uint8, device=dev))
         cands.append(second())
         rates.append(measure(cands[-1]))
         if all(s > threshold * p for s, p in zip(rates[-1], one_region)):
@@ -116,7 +120,7 @@ def allocate_state(n: int, res_spec: Tuple[int, torch.dtype], grad_spec: Tuple[i
         return finish(arrays, {"split": False, "why": "no memory to search with"})
     best = max(range(len(cands)), key=lambda i: sum(rates[i]))
     chosen = cands[best]
-    del cands
+    del cands, fillers
     torch.cuda.empty_cache()            # the candidates not chosen go back to the driver
     arrays.update(chosen)
     split = all(s > threshold * p for s, p in zip(rates[best], one_region))
