@@ -93,7 +93,7 @@ def layer_breakdown(st, cfg, stream, step_no, bpp):
     return out
 
 
-def traffic_ceiling(st, stream, with_v, bpp, steps):
+def traffic_probe(st, stream, with_v, bpp, steps):
     """The same bytes over the same arrays in the same per-layer launches with the arithmetic
     taken out (csrc/stream_probe.hip): what this access pattern reaches on this GPU.  Runs after
     the timed region; it overwrites the state."""
@@ -151,7 +151,7 @@ def main():
                          "HBM regions (paper_2309_12381_amd/placement.py)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true", help="skip the per-layer breakdown step")
-    ap.add_argument("--no-ceiling", action="store_true", help="skip the arithmetic-free traffic probe")
+    ap.add_argument("--no-probe", action="store_true", help="skip the arithmetic-free traffic probe")
     ap.add_argument("--cpu-sample", type=int, default=1 << 26)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise kernel that reads 1 GiB and writes 1 GiB (known traffic, "
@@ -242,10 +242,10 @@ def main():
     }
     if wl.per_layer and not a.no_breakdown:
         res["breakdown"] = layer_breakdown(st, cfg, stream, step_no + 1, bpp)
-    if st.res_bytes == 2 and not a.res_packed and not a.no_ceiling:
-        ceil = traffic_ceiling(st, stream, a.optimizer == "adam", bpp, min(steps, 5))
-        ceil["step_kernel_frac_of_this"] = achieved / ceil["achieved"]
-        res["roofline"]["ceiling"] = ceil
+    if st.res_bytes == 2 and not a.res_packed and not a.no_probe:
+        pr = traffic_probe(st, stream, a.optimizer == "adam", bpp, min(steps, 5))
+        pr["step_kernel_frac_of_this"] = achieved / pr["achieved"]
+        res["roofline"]["probe"] = pr
     st.close()
     if a.calibrate_copy:
         src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)       # 1 GiB
