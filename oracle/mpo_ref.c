@@ -134,6 +134,7 @@ typedef struct {
     int kept;      /* E: bits of them that are stored                    */
     int byte_slot; /* residual array is uint8_t                          */
     int packed;    /* residual stored in bit planes (Figure 1)           */
+    int stored;    /* packed: bits per value in the planes (E, plus the flag of STOCHASTIC) */
     uint64_t n;    /* number of values: fixes where each plane starts    */
     uint64_t seed;
     uint32_t tensor_id, step32;
@@ -141,7 +142,7 @@ typedef struct {
 
 static uint64_t round16(uint64_t x) { return (x + 15u) / 16u * 16u; }
 
-/* Packed storage: value i of a plane of width w (8, 4 or 2 bits) */
+/* Packed storage: value i of a plane of width w (8, 4, 2 or 1 bits) */
 static uint32_t plane_get(const uint8_t *plane, uint64_t i, int w)
 {
     uint64_t bit = i * (uint64_t)w;
@@ -155,27 +156,31 @@ static void plane_put(uint8_t *plane, uint64_t i, int w, uint32_t x)
     plane[bit / 8] = (uint8_t)((plane[bit / 8] & ~mask) | ((x << (bit % 8)) & mask));
 }
 
-/* The E kept bits of value i, assembled from / distributed to the planes: the 8-bit piece holds
- * the leading bits, then the 4-bit piece, then the 2-bit piece. */
-static uint16_t packed_get(const uint8_t *base, uint64_t n, uint64_t i, int E)
+/* The S stored bits of value i, assembled from / distributed to the planes: S is cut from the
+ * top into the pieces of 8, 4, 2 and 1 bits its binary form contains; the 8-bit piece holds the
+ * leading bits, then the 4-bit piece, the 2-bit piece, the 1-bit piece. */
+static uint16_t packed_get(const uint8_t *base, uint64_t n, uint64_t i, int S)
 {
     uint32_t r = 0;
     const uint8_t *plane = base;
-    if (E & 8) { r = (r << 8) | plane_get(plane, i, 8); plane += round16(n); }
-    if (E & 4) { r = (r << 4) | plane_get(plane, i, 4); plane += round16((n + 1) / 2); }
-    if (E & 2) { r = (r << 2) | plane_get(plane, i, 2); }
+    if (S & 8) { r = (r << 8) | plane_get(plane, i, 8); plane += round16(n); }
+    if (S & 4) { r = (r << 4) | plane_get(plane, i, 4); plane += round16((n + 1) / 2); }
+    if (S & 2) { r = (r << 2) | plane_get(plane, i, 2); plane += round16((n + 3) / 4); }
+    if (S & 1) { r = (r << 1) | plane_get(plane, i, 1); }
     return (uint16_t)r;
 }
 
-static void packed_put(uint8_t *base, uint64_t n, uint64_t i, int E, uint16_t r)
+static void packed_put(uint8_t *base, uint64_t n, uint64_t i, int S, uint16_t r)
 {
     uint8_t *plane = base;
-    int left = E;
-    if (E & 8) { left -= 8; plane_put(plane, i, 8, (r >> left) & 0xFFu); plane += round16(n); }
-    if (E & 4) { left -= 4; plane_put(plane, i, 4, (r >> left) & 0xFu); plane += round16((n + 1) / 2); }
-    if (E & 2) { left -= 2; plane_put(plane, i, 2, (r >> left) & 0x3u); }
+    int left = S;
+    if (S & 8) { left -= 8; plane_put(plane, i, 8, (r >> left) & 0xFFu); plane += round16(n); }
+    if (S & 4) { left -= 4; plane_put(plane, i, 4, (r >> left) & 0xFu); plane += round16((n + 1) / 2); }
+    if (S & 2) { left -= 2; plane_put(plane, i, 2, (r >> left) & 0x3u); plane += round16((n + 3) / 4); }
+    if (S & 1) { left -= 1; plane_put(plane, i, 1, (r >> left) & 0x1u); }
 }
 
+/* Packed: res_bits counts the bits stored per value (with STOCHASTIC one of them is the flag). */
 uint64_t mpo_ref_res_bytes(uint64_t n, int fmt, int res_bits, int res_packed)
 {
     (void)fmt;
@@ -184,6 +189,7 @@ uint64_t mpo_ref_res_bytes(uint64_t n, int fmt, int res_bits, int res_packed)
     if (res_bits & 8) b += round16(n);
     if (res_bits & 4) b += round16((n + 1) / 2);
     if (res_bits & 2) b += round16((n + 3) / 4);
+    if (res_bits & 1) b += round16((n + 7) / 8);
     return b;
 }
 
@@ -197,6 +203,9 @@ static res_layout make_layout(int fmt, int res_bits, int packed, uint64_t n, int
     L.round = round;
     L.full = fmt == MPO_REF_FP16 ? 13 : 16;
     L.kept = res_bits != 0 ? res_bits : (round == MPO_REF_STOCHASTIC && L.full == 16 ? 15 : L.full);
+    L.stored = res_bits;
+    /* in the planes the flag of STOCHASTIC is one of the res_bits stored bits, the leading one */
+    if (packed && round == MPO_REF_STOCHASTIC) L.kept = res_bits - 1;
     L.byte_slot = res_bits >= 1 && res_bits <= 8;
     L.seed = seed;
     L.tensor_id = tensor_id;
@@ -221,7 +230,7 @@ static uint32_t draw(const res_layout *L, uint64_t i)
 static void load_pair(const uint16_t *hi, const void *res, uint64_t i, const res_layout *L,
                       uint16_t *hi_trunc, uint16_t *res_full)
 {
-    uint16_t stored = L->packed ? packed_get((const uint8_t *)res, L->n, i, L->kept)
+    uint16_t stored = L->packed ? packed_get((const uint8_t *)res, L->n, i, L->stored)
                     : L->byte_slot ? ((const uint8_t *)res)[i] : ((const uint16_t *)res)[i];
     uint16_t kept = (uint16_t)(stored & ((1u << L->kept) - 1u));
     uint16_t full = (uint16_t)(kept << (L->full - L->kept));
@@ -246,7 +255,7 @@ static void store_pair(uint16_t *hi, void *res, uint64_t i, const res_layout *L,
     uint16_t kept = (uint16_t)(res_full >> (L->full - L->kept));
     if (L->round == MPO_REF_STOCHASTIC) kept = (uint16_t)(kept | (up << L->kept));
     hi[i] = (uint16_t)(hi_trunc + up);
-    if (L->packed) packed_put((uint8_t *)res, L->n, i, L->kept, kept);
+    if (L->packed) packed_put((uint8_t *)res, L->n, i, L->stored, kept);
     else if (L->byte_slot) ((uint8_t *)res)[i] = (uint8_t)kept;
     else ((uint16_t *)res)[i] = kept;
 }

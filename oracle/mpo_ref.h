@@ -60,13 +60,15 @@ enum { MPO_REF_BF16 = 0, MPO_REF_FP16 = 1 };
 enum { MPO_REF_TRUNC = 0, MPO_REF_NEAREST = 1, MPO_REF_STOCHASTIC = 2 };
 
 /* Packed storage (Section 3.1, Figure 1: the extra bits of many values packed without
- * padding).  With res_packed != 0 and an even E in 2..14 the residual is stored in bit planes
- * instead of one slot per value: the E kept bits are cut, from the top, into an 8-bit, a 4-bit
- * and a 2-bit piece (those that E contains: E = 8a + 4b + 2c); each piece has its own dense
- * array ("plane") in which value i occupies bits [w*i, w*i + w) (w = 8, 4, 2; little-endian
- * within a byte).  The planes follow each other in the residual buffer in that order, each
- * starting at a multiple of 16 bytes: sizes round16(n), round16(ceil(n/2)), round16(ceil(n/4)).
- * E bits per value, nothing wasted: 12 extra bits take 1.5 bytes. */
+ * padding).  With res_packed != 0 the residual is stored in bit planes instead of one slot per
+ * value, and res_bits = S in 1..15 is the number of bits stored per value: the E = S kept bits
+ * in TRUNC and NEAREST mode; in STOCHASTIC mode E = S - 1 kept bits below the flag, which is the
+ * leading stored bit.  The S bits are cut, from the top, into the pieces of 8, 4, 2 and 1 bits
+ * that the binary form of S contains; each piece has its own dense array ("plane") in which
+ * value i occupies bits [w*i, w*i + w) (w = 8, 4, 2, 1; little-endian within a byte).  The
+ * planes follow each other in the residual buffer in that order, each starting at a multiple
+ * of 16 bytes: sizes round16(n), round16(ceil(n/2)), round16(ceil(n/4)), round16(ceil(n/8)).
+ * S bits per value, nothing wasted: 12 extra bits take 1.5 bytes, the 13 of fp16 take 13 bits. */
 uint64_t mpo_ref_res_bytes(uint64_t n, int fmt, int res_bits, int res_packed);
 
 typedef struct {

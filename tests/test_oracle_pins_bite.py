@@ -95,8 +95,8 @@ MUTANTS = [
     ("partial bits: rounds up", "uint16_t kept = (uint16_t)(res_full >> (L->full - L->kept));",
      "uint16_t kept = (uint16_t)((res_full + (L->kept < L->full ? (1u << (L->full - L->kept - 1)) : 0u)) >> (L->full - L->kept));", 1),
     ("partial bits: fp16 uses the bf16 width", "L.full = fmt == MPO_REF_FP16 ? 13 : 16;", "L.full = 16;", 1),
-    ("packed: pieces in the wrong order", "    if (E & 8) { left -= 8; plane_put(plane, i, 8, (r >> left) & 0xFFu); plane += round16(n); }",
-     "    if (E & 8) { plane_put(plane, i, 8, r & 0xFFu); plane += round16(n); }", 1),
+    ("packed: pieces in the wrong order", "    if (S & 8) { left -= 8; plane_put(plane, i, 8, (r >> left) & 0xFFu); plane += round16(n); }",
+     "    if (S & 8) { plane_put(plane, i, 8, r & 0xFFu); plane += round16(n); }", 1),
     ("packed: planes not aligned", "static uint64_t round16(uint64_t x) { return (x + 15u) / 16u * 16u; }",
      "static uint64_t round16(uint64_t x) { return x; }", 1),
     ("packed: high nibble first", "    return (plane[bit / 8] >> (bit % 8)) & ((1u << w) - 1u);",
@@ -104,8 +104,12 @@ MUTANTS = [
     ("packed: put clobbers the neighbours", "    plane[bit / 8] = (uint8_t)((plane[bit / 8] & ~mask) | ((x << (bit % 8)) & mask));",
      "    plane[bit / 8] = (uint8_t)((x << (bit % 8)) & mask);", 1),
     ("packed: pieces read in another order than written",
-     "    if (E & 4) { r = (r << 4) | plane_get(plane, i, 4); plane += round16((n + 1) / 2); }\n    if (E & 2) { r = (r << 2) | plane_get(plane, i, 2); }",
-     "    if (E & 2) { r = (r << 2) | plane_get(plane, i, 2); }\n    if (E & 4) { r = (r << 4) | plane_get(plane, i, 4); }", 1),
+     "    if (S & 4) { r = (r << 4) | plane_get(plane, i, 4); plane += round16((n + 1) / 2); }\n    if (S & 2) { r = (r << 2) | plane_get(plane, i, 2); plane += round16((n + 3) / 4); }",
+     "    if (S & 2) { r = (r << 2) | plane_get(plane, i, 2); }\n    if (S & 4) { r = (r << 4) | plane_get(plane, i, 4); }", 1),
+    ("packed: the 1-bit plane starts inside the 2-bit plane", " plane += round16((n + 3) / 4); }", " }", 2),
+    ("packed: 1-bit piece not the last bit", "    if (S & 1) { left -= 1; plane_put(plane, i, 1, (r >> left) & 0x1u); }",
+     "    if (S & 1) { plane_put(plane, i, 1, (r >> (S - 1)) & 0x1u); }", 1),
+    ("packed: stochastic flag not among the stored bits", "    if (packed && round == MPO_REF_STOCHASTIC) L.kept = res_bits - 1;\n", "", 1),
     ("clip: lower bound missing", "            if (g < -CLIP) g = -CLIP;\n", "", 2),
     ("clip: applied to the scaled gradient", "        g = g * IS;\n        if (has_clip) {                    /* Sec. 4.1: element-wise clipping inside the step */\n            if (g > CLIP) g = CLIP;\n            if (g < -CLIP) g = -CLIP;\n        }\n",
      "        if (has_clip) {\n            if (g > CLIP) g = CLIP;\n            if (g < -CLIP) g = -CLIP;\n        }\n        g = g * IS;\n", 2),

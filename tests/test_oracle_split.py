@@ -317,13 +317,14 @@ def test_partial_bits_is_truncation(ref):
 # ---- packed storage of the extra bits (Section 3.1, Figure 1) -----------------------------------
 
 def unpack_planes(buf: np.ndarray, n: int, E: int) -> np.ndarray:
-    """Independent decoder of the packed layout, from its description: an 8-bit, a 4-bit and a
-    2-bit plane (those E contains), in that order, each starting at a multiple of 16 bytes, value i
-    at bits [w*i, w*i+w) of its plane, little-endian; the 8-bit piece holds the leading bits."""
+    """Independent decoder of the packed layout, from its description: an 8-, a 4-, a 2- and a
+    1-bit plane (those the binary form of E contains), in that order, each starting at a multiple of
+    16 bytes, value i at bits [w*i, w*i+w) of its plane, little-endian; the 8-bit piece holds the
+    leading bits."""
     bits = np.unpackbits(buf, bitorder="little")
     out = np.zeros(n, np.uint32)
     pos = 0                                             # byte offset of the current plane
-    for w in (8, 4, 2):
+    for w in (8, 4, 2, 1):
         if not E & w:
             continue
         plane = bits[8 * pos: 8 * pos + w * n].reshape(n, w)
@@ -339,20 +340,37 @@ def pins_packed_storage(ref):
     for fmt, full in ((ref.BF16, 16), (ref.FP16, 13)):
         for n in (1, 2, 3, 5, 16, 31, 33, 4099):
             x = (rng.standard_normal(n) * 0.02).astype(np.float32)
-            for E in (2, 4, 6, 8, 10, 12) + ((14,) if full == 16 else ()):
+            for E in range(1, min(full, 15) + 1):
                 hi_s, res_s = ref.split(x, fmt, E)                       # one slot per value
                 hi_p, buf = ref.split(x, fmt, E, packed=True)
                 assert buf.dtype == np.uint8 and buf.size == ref.res_bytes(n, fmt, E, True)
                 # E bits per value and nothing more (up to the 16-byte rounding of each plane)
-                assert buf.size <= (n * E + 7) // 8 + 3 * 16
+                assert buf.size <= (n * E + 7) // 8 + 4 * 16
                 assert np.array_equal(hi_p, hi_s)
                 assert np.array_equal(unpack_planes(buf, n, E), res_s.astype(np.uint32)), (fmt, n, E)
                 assert np.array_equal(ref.merge(hi_p, buf, fmt, E, packed=True).view(np.uint32),
                                       ref.merge(hi_s, res_s, fmt, E).view(np.uint32))
+    # rounded modes: NEAREST stores the same E bits; STOCHASTIC stores E + 1, the flag leading,
+    # which is exactly the content of the slot (kept bits, flag just above them)
+    for fmt, full in ((ref.BF16, 16), (ref.FP16, 13)):
+        for n in (1, 7, 64, 1001):
+            x = (rng.standard_normal(n) * 0.02).astype(np.float32)
+            for E in (1, 2, 6, 7, 12, 13):
+                hi_s, res_s = ref.split(x, fmt, E, ref.NEAREST)
+                hi_p, buf = ref.split(x, fmt, E, ref.NEAREST, packed=True)
+                assert np.array_equal(hi_p, hi_s) and np.array_equal(unpack_planes(buf, n, E), res_s.astype(np.uint32))
+                assert np.array_equal(ref.merge(hi_p, buf, fmt, E, ref.NEAREST, packed=True).view(np.uint32),
+                                      ref.merge(hi_s, res_s, fmt, E, ref.NEAREST).view(np.uint32))
+                hi_s, res_s = ref.split(x, fmt, E, ref.STOCHASTIC, 99, 3)
+                hi_p, buf = ref.split(x, fmt, E + 1, ref.STOCHASTIC, 99, 3, packed=True)
+                assert buf.size == ref.res_bytes(n, fmt, E + 1, True)
+                assert np.array_equal(hi_p, hi_s) and np.array_equal(unpack_planes(buf, n, E + 1), res_s.astype(np.uint32))
+                assert np.array_equal(ref.merge(hi_p, buf, fmt, E + 1, ref.STOCHASTIC, packed=True).view(np.uint32),
+                                      ref.merge(hi_s, res_s, fmt, E, ref.STOCHASTIC).view(np.uint32))
     # steps on packed storage hold the same values as steps on slots
     n = 1003
     x = (rng.standard_normal(n) * 0.02).astype(np.float32)
-    for E in (12, 4, 10):
+    for E in (12, 4, 10, 13, 7, 1):
         a_hi, a_res = ref.split(x, ref.BF16, E)
         b_hi, b_buf = ref.split(x, ref.BF16, E, packed=True)
         ma = np.zeros(n, np.float32); va = np.zeros(n, np.float32); mb = np.zeros(n, np.float32); vb = np.zeros(n, np.float32)
@@ -369,6 +387,17 @@ def pins_packed_storage(ref):
         assert np.array_equal(unpack_planes(b_buf, n, E), a_res.astype(np.uint32))
         assert np.array_equal(sa_hi, sb_hi) and np.array_equal(ba, bb)
         assert np.array_equal(unpack_planes(sb_buf, n, E), sa_res.astype(np.uint32))
+    for E, rnd in ((13, ref.STOCHASTIC), (6, ref.STOCHASTIC), (11, ref.NEAREST)):
+        S = E + (1 if rnd == ref.STOCHASTIC else 0)
+        a_hi, a_res = ref.split(x, ref.FP16, E, rnd, 5, 9)
+        b_hi, b_buf = ref.split(x, ref.FP16, S, rnd, 5, 9, packed=True)
+        ma = np.zeros(n, np.float32); va = np.zeros(n, np.float32); mb = np.zeros(n, np.float32); vb = np.zeros(n, np.float32)
+        for t in range(1, 5):
+            g = rng.integers(0x1400, 0x1800, n).astype(np.uint16)
+            ref.adam_step(a_hi, a_res, g, ma, va, ref.AdamCfg(weight_fmt=ref.FP16, grad_fmt=ref.FP16, res_bits=E, round=rnd, seed=5), t, tensor_id=9)
+            ref.adam_step(b_hi, b_buf, g, mb, vb, ref.AdamCfg(weight_fmt=ref.FP16, grad_fmt=ref.FP16, res_bits=S, res_packed=True, round=rnd, seed=5), t, tensor_id=9)
+        assert np.array_equal(a_hi, b_hi) and np.array_equal(ma, mb) and np.array_equal(va, vb)
+        assert np.array_equal(unpack_planes(b_buf, n, S), a_res.astype(np.uint32))
 
 
 def test_packed_storage(ref):
