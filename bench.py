@@ -141,7 +141,8 @@ def main():
                     help="extra bits kept per weight: 0 = all (the headline), 8 = the paper's bf16+8 / fp16+8 "
                          "(byte residual, 24 B per parameter for Adam)")
     ap.add_argument("--res-packed", action="store_true",
-                    help="store the extra bits in packed planes (even --res-bits from 2 to 14, e.g. 12: 1.5 B per weight)")
+                    help="store the extra bits in packed planes (--res-bits = bits stored per weight, 1 to 15, e.g. 12: 1.5 B "
+                         "per weight; with --round stochastic one of them is the flag)")
     ap.add_argument("--round", default="trunc", choices=["trunc", "nearest", "stochastic"],
                     help="rounding of the 16-bit value: trunc is the method's base mode and the headline")
     ap.add_argument("--fresh-grads", action="store_true",
@@ -221,9 +222,13 @@ def main():
         "ms_per_step": wall * 1e3 / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: %s" % (wl.key, wl.description), "params": P, "tensors": len(wl.tensors),
-                   "format": "%s+%d extra bits (%s)" % (wl.fmt, a.res_bits or (13 if wl.fmt == "fp16" else
-                                                                           15 if a.round == "stochastic" else 16),
-                                                        "packed planes" if a.res_packed else "%d-bit residual" % (8 * st.res_bytes)), "optimizer": wl.optimizer if a.optimizer == "adam" else "sgd-momentum", "round": a.round, "loss_scale": wl.loss_scale,
+                   "format": ("%s, %d bits stored per weight in packed planes%s"
+                              % (wl.fmt, a.res_bits, " (the leading one is the rounding flag)" if a.round == "stochastic" else "")
+                              if a.res_packed else
+                              "%s+%d extra bits (%d-bit residual)"
+                              % (wl.fmt, a.res_bits or (13 if wl.fmt == "fp16" else 15 if a.round == "stochastic" else 16),
+                                 8 * st.res_bytes)),
+                   "optimizer": wl.optimizer if a.optimizer == "adam" else "sgd-momentum", "round": a.round, "loss_scale": wl.loss_scale,
                    "launches_per_step": launches // steps, "per_layer": wl.per_layer,
                    "fresh_grads_in_loop": bool(a.fresh_grads), "resident_GB": st.resident_bytes / 1e9,
                    "placement": st.placement,

@@ -83,17 +83,22 @@ typedef enum { MPO_OPT_ADAM = 0, MPO_OPT_SGD = 1 } mpo_opt;
  * uint16_t; the E bits are right-aligned in it.  E above the format's full
  * count is MPO_ERR_INVALID_ARG.
  *
- * `res_packed` != 0 stores the E bits without padding (Section 3.1, Figure 1),
- * for even E from 2 to 14, truncation mode only (else MPO_ERR_INVALID_ARG /
- * MPO_ERR_UNSUPPORTED).  The layout is planar rather than one bit string, so
- * that every lane reads and writes whole bytes of its own: the E bits are
- * cut, from the top, into an 8-bit, a 4-bit and a 2-bit piece (those that E
- * contains: E = 8a + 4b + 2c); each piece has its own dense plane in which
- * value i occupies bits [w*i, w*i + w) (w = 8, 4, 2; little-endian in a byte);
- * the planes follow each other in `res` in that order, each starting at a
- * multiple of 16 bytes (sizes round16(n), round16(ceil(n/2)), round16(ceil(n/4))).
- * `res` must then be 16-byte aligned and hold mpo_res_bytes() bytes: 12 extra
- * bits take 1.5 bytes per parameter.
+ * `res_packed` != 0 stores the bits without padding (Section 3.1, Figure 1).
+ * `res_bits` = S, 1 to 15, is then the number of bits STORED per parameter:
+ * the E = S kept bits with MPO_ROUND_TRUNC and MPO_ROUND_NEAREST; with
+ * MPO_ROUND_STOCHASTIC the flag is the leading stored bit and E = S - 1 (so
+ * S >= 2).  E above the format's full count is MPO_ERR_INVALID_ARG (the 13
+ * extra bits of fp16 with the flag are S = 14).  The layout is planar rather
+ * than one bit string, so that lanes read and write whole bytes: the S bits
+ * are cut, from the top, into the pieces of 8, 4, 2 and 1 bits that the binary
+ * form of S contains; each piece has its own dense plane in which value i
+ * occupies bits [w*i, w*i + w) (w = 8, 4, 2, 1; little-endian in a byte); the
+ * planes follow each other in `res` in that order, each starting at a
+ * multiple of 16 bytes (sizes round16(n), round16(ceil(n/2)),
+ * round16(ceil(n/4)), round16(ceil(n/8))).  `res` must then be 16-byte
+ * aligned and hold mpo_res_bytes() bytes: 12 extra bits take 1.5 bytes per
+ * parameter.  Bits of the last bytes that belong to no parameter are written
+ * as zero by mpo_split and kept by the steps.
  */
 uint64_t mpo_res_bytes(uint64_t n, int32_t res_bits, int32_t res_packed);
 

@@ -47,8 +47,15 @@ inline uint32_t res_slot_bytes(int res_bits) { return (res_bits >= 1 && res_bits
 
 /* 0 means all; otherwise 1..full for the format.  Stochastic rounding stores one flag above
  * the kept bits: they must leave room for it in the slot. */
-/* Packed planes: even E from 2 to 14 (Figure 1 of the paper is E = 12). */
-inline bool valid_packed_bits(int res_bits) { return res_bits >= 2 && res_bits <= 14 && (res_bits & 1) == 0; }
+/* Packed planes: 1 to 15 stored bits per value (Figure 1 of the paper has 12). */
+inline bool valid_packed_bits(int res_bits) { return res_bits >= 1 && res_bits <= 15; }
+
+/* Packed planes with a format and a rounding mode: at least one kept bit, at most all of them. */
+inline bool valid_packed_mode(int res_bits, int fmt, int round)
+{
+    const int kept = kept_res_bits(fmt, res_bits, round, 1);
+    return valid_packed_bits(res_bits) && kept >= 1 && kept <= full_res_bits(fmt);
+}
 
 /* Kind of residual storage: 1 = bytes, 2 = 16-bit slots, 3 = packed planes. */
 inline uint32_t res_kind(int res_bits, int packed) { return packed ? 3u : res_slot_bytes(res_bits); }
@@ -57,7 +64,7 @@ inline bool valid_res_bits(int res_bits, int fmt, int round)
 {
     if (res_bits < 0 || res_bits > full_res_bits(fmt)) return false;
     if (round != MPO_ROUND_STOCHASTIC) return true;
-    return kept_res_bits(fmt, res_bits, round) + 1 <= 8 * (int)res_slot_bytes(res_bits);
+    return kept_res_bits(fmt, res_bits, round, 0) + 1 <= 8 * (int)res_slot_bytes(res_bits);
 }
 
 /* True if some written range overlaps any other range.  Read-only ranges
@@ -99,6 +106,7 @@ struct mpo_plan {
     bool all_have_grad = true, all_have_m = true, all_have_v = true;
     uint32_t res_slot = 0;       /* residual storage: 1 bytes, 2 16-bit slots, 3 packed planes; 0 = no elements yet */
     uint32_t max_res_bits = 0;   /* largest explicit res_bits in the list                       */
+    uint32_t min_res_bits = 16;  /* smallest explicit res_bits in the list                      */
     bool any_explicit_bits = false;
     bool on_device = false;
     int device = -1;
@@ -167,6 +175,7 @@ mpo_status build_plan(const mpo_tensor *tensors, uint64_t nt, mpo_plan **out)
             if (t.n && t.res_bits) {
                 p->any_explicit_bits = true;
                 p->max_res_bits = std::max(p->max_res_bits, (uint32_t)t.res_bits);
+                p->min_res_bits = std::min(p->min_res_bits, (uint32_t)t.res_bits);
             }
             if (aligned16(t.hi) && aligned16(t.res) && aligned16(t.m) && aligned16(t.v)) d.flags |= kStateAligned;
             if (t.grad && aligned16(t.grad)) d.flags |= kGradAligned;
@@ -293,9 +302,15 @@ mpo_status run(mpo_plan *p, StepLaunch &L, void *stream)
     const hipError_t de = hipGetDevice(&dev);
     if (de != hipSuccess) return hip_fail(de);
     if (dev != p->device) return MPO_ERR_INVALID_ARG;
-    if ((int)p->max_res_bits > full_res_bits(L.wfmt)) return MPO_ERR_INVALID_ARG;
-    if (L.s.round == MPO_ROUND_STOCHASTIC && p->max_res_bits > (p->res_slot == 1 ? 7u : 15u)) return MPO_ERR_INVALID_ARG;
-    if (p->res_slot == 3 && L.s.round != MPO_ROUND_TRUNC) return MPO_ERR_UNSUPPORTED;
+    if (p->res_slot == 3) {
+        /* packed planes: every tensor's stored bits must suit this format and rounding mode */
+        if (p->any_explicit_bits && (!valid_packed_mode((int)p->max_res_bits, L.wfmt, (int)L.s.round) ||
+                                     !valid_packed_mode((int)p->min_res_bits, L.wfmt, (int)L.s.round)))
+            return MPO_ERR_INVALID_ARG;
+    } else {
+        if ((int)p->max_res_bits > full_res_bits(L.wfmt)) return MPO_ERR_INVALID_ARG;
+        if (L.s.round == MPO_ROUND_STOCHASTIC && p->max_res_bits > (p->res_slot == 1 ? 7u : 15u)) return MPO_ERR_INVALID_ARG;
+    }
     L.rmode = p->res_slot == 3 ? kResPlanes : p->res_slot == 1 ? kResByte : (p->any_explicit_bits ? kResPartial : kResFull);
     L.descs = p->d_descs;
     L.chunks = p->d_chunks;
@@ -322,9 +337,7 @@ mpo_status mpo_split(const float *w32, uint16_t *hi, void *res, uint64_t n, mpo_
                      int32_t res_packed, mpo_round round, uint64_t seed, uint32_t tensor_id, void *hip_stream)
 {
     if (!valid_fmt(fmt) || check_round(round) != MPO_OK) return MPO_ERR_INVALID_ARG;
-    if (!valid_res_bits(res_bits, fmt, round)) return MPO_ERR_INVALID_ARG;
-    if (res_packed && !valid_packed_bits(res_bits)) return MPO_ERR_INVALID_ARG;
-    if (res_packed && round != MPO_ROUND_TRUNC) return MPO_ERR_UNSUPPORTED;
+    if (res_packed ? !valid_packed_mode(res_bits, fmt, round) : !valid_res_bits(res_bits, fmt, round)) return MPO_ERR_INVALID_ARG;
     if (res_packed && n > 0 && !aligned16(res)) return MPO_ERR_INVALID_ARG;
     if (n > kMaxElems) return MPO_ERR_INVALID_ARG;
     if (n == 0) return MPO_OK;
@@ -344,9 +357,7 @@ mpo_status mpo_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n
                      int32_t res_packed, mpo_round round, void *hip_stream)
 {
     if (!valid_fmt(fmt) || check_round(round) != MPO_OK) return MPO_ERR_INVALID_ARG;
-    if (!valid_res_bits(res_bits, fmt, round)) return MPO_ERR_INVALID_ARG;
-    if (res_packed && !valid_packed_bits(res_bits)) return MPO_ERR_INVALID_ARG;
-    if (res_packed && round != MPO_ROUND_TRUNC) return MPO_ERR_UNSUPPORTED;
+    if (res_packed ? !valid_packed_mode(res_bits, fmt, round) : !valid_res_bits(res_bits, fmt, round)) return MPO_ERR_INVALID_ARG;
     if (res_packed && n > 0 && !aligned16(res)) return MPO_ERR_INVALID_ARG;
     if (n > kMaxElems) return MPO_ERR_INVALID_ARG;
     if (n == 0) return MPO_OK;

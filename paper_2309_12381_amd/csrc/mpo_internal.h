@@ -80,6 +80,7 @@ inline uint64_t res_bytes(uint64_t n, int res_bits, int packed)
     if (res_bits & 8) b += round16(n);
     if (res_bits & 4) b += round16((n + 1) / 2);
     if (res_bits & 2) b += round16((n + 3) / 4);
+    if (res_bits & 1) b += round16((n + 7) / 8);
     return b;
 }
 
@@ -106,10 +107,12 @@ hipError_t launch_split(const float *w32, uint16_t *hi, void *res, uint64_t n, i
 hipError_t launch_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits, int packed,
                         int round, hipStream_t stream);
 
-/* Extra bits actually stored: an explicit count, else all of them; stochastic rounding of
- * bf16 keeps 15 so that the flag fits the 16-bit slot. */
-inline int kept_res_bits(int fmt, int res_bits, int round)
+/* Extra bits actually kept: an explicit count, else all of them; stochastic rounding of bf16
+ * keeps 15 so that the flag fits the 16-bit slot.  In packed planes res_bits counts the stored
+ * bits, and with stochastic rounding the leading one of them is the flag. */
+inline int kept_res_bits(int fmt, int res_bits, int round, int packed)
 {
+    if (packed) return res_bits - (round == MPO_ROUND_STOCHASTIC ? 1 : 0);
     if (res_bits) return res_bits;
     return (round == MPO_ROUND_STOCHASTIC && fmt == MPO_BF16) ? 15 : full_res_bits(fmt);
 }

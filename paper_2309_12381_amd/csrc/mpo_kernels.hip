@@ -235,34 +235,39 @@ template <int RMODE> struct ResElem { typedef uint16_t T; };
 template <> struct ResElem<kResByte> { typedef uint8_t T; };
 
 /* ---- packed planes (Section 3.1, Figure 1: extra bits stored without padding) --
- * The E kept bits are cut from the top into an 8-bit, a 4-bit and a 2-bit piece (those E
- * contains), each in a dense plane of its own, so that the EPL values of a lane occupy
- * whole bytes in every plane: no byte is shared between lanes, nothing has to be
- * exchanged or combined.  In registers the kept bits are held as in a cut 16-bit slot
- * (kResPartial), so the arithmetic path is shared. */
+ * The S stored bits (the kept bits, plus the flag of stochastic rounding) are cut from the
+ * top into the pieces of 8, 4, 2 and 1 bits that S contains, each in a dense plane of its
+ * own.  The EPL values of a lane occupy whole bytes of the 8-, 4- and 2-bit planes: no byte
+ * is shared between lanes.  In the 1-bit plane two neighbouring lanes share a byte: both
+ * load it, and on the way back the even lane fetches its neighbour's four bits with one
+ * cross-lane move and stores the byte.  Outside the fast path a lane walks groups of 8
+ * values and owns whole bytes of every plane.  In registers the stored bits are held as in
+ * a cut 16-bit slot (kResPartial), so the arithmetic path is shared. */
 constexpr int reg_mode(int rmode) { return rmode == kResPlanes ? kResPartial : rmode; }
 
 struct ResRef {
-    MPO_GLOBAL void *slots;           /* slot storage at the chunk's first parameter        */
-    MPO_GLOBAL uint8_t *p8, *p4, *p2; /* planes at the chunk's first parameter              */
-    uint32_t E;                       /* kept bits (planes)                                  */
+    MPO_GLOBAL void *slots;                /* slot storage at the chunk's first parameter  */
+    MPO_GLOBAL uint8_t *p8, *p4, *p2, *p1; /* planes at the chunk's first parameter        */
+    uint32_t S;                            /* bits stored per value (planes)               */
 };
 
 /* base: start of the tensor's residual buffer, n: its length, off: first parameter of the chunk */
 template <int RMODE>
-__device__ __forceinline__ ResRef res_ref(void *base, uint64_t n, uint64_t off, uint32_t E)
+__device__ __forceinline__ ResRef res_ref(void *base, uint64_t n, uint64_t off, uint32_t S)
 {
     ResRef R;
-    R.E = E;
+    R.S = S;
     R.slots = nullptr;
-    R.p8 = R.p4 = R.p2 = nullptr;
+    R.p8 = R.p4 = R.p2 = R.p1 = nullptr;
     if (RMODE == kResPlanes) {
         MPO_GLOBAL uint8_t *b = (MPO_GLOBAL uint8_t *)base;
         R.p8 = b + off;
-        if (E & 8u) b += (n + 15u) / 16u * 16u;
+        if (S & 8u) b += (n + 15u) / 16u * 16u;
         R.p4 = b + off / 2;
-        if (E & 4u) b += ((n + 1u) / 2u + 15u) / 16u * 16u;
+        if (S & 4u) b += ((n + 1u) / 2u + 15u) / 16u * 16u;
         R.p2 = b + off / 4;
+        if (S & 2u) b += ((n + 3u) / 4u + 15u) / 16u * 16u;
+        R.p1 = b + off / 8;
     } else {
         R.slots = (MPO_GLOBAL void *)(static_cast<char *>(base) + off * sizeof(typename ResElem<RMODE>::T));
     }
@@ -284,38 +289,64 @@ template <int NBYTES> __device__ __forceinline__ void st_bytes(MPO_GLOBAL uint8_
     else *reinterpret_cast<MPO_GLOBAL uint64_t *>(p) = x;
 }
 
-/* The EPL values that start at chunk-local parameter e (a multiple of EPL): planes -> 16-bit pairs. */
-__device__ __forceinline__ void planes_load(const ResRef &R, uint32_t e, uint32_t (&r)[EPL / 2])
+/* The EPL values that start at chunk-local parameter e (a multiple of EPL): the 8-, 4- and
+ * 2-bit planes plus `ones`, their EPL bits of the 1-bit plane -> 16-bit pairs. */
+__device__ __forceinline__ void planes_unpack(const ResRef &R, uint32_t e, uint32_t ones, uint32_t (&r)[EPL / 2])
 {
-    const uint64_t b8 = (R.E & 8u) ? ld_bytes<EPL>(R.p8 + e) : 0u;
-    const uint64_t b4 = (R.E & 4u) ? ld_bytes<EPL / 2>(R.p4 + e / 2) : 0u;
-    const uint64_t b2 = (R.E & 2u) ? ld_bytes<EPL / 4>(R.p2 + e / 4) : 0u;
+    const uint64_t b8 = (R.S & 8u) ? ld_bytes<EPL>(R.p8 + e) : 0u;
+    const uint64_t b4 = (R.S & 4u) ? ld_bytes<EPL / 2>(R.p4 + e / 2) : 0u;
+    const uint64_t b2 = (R.S & 2u) ? ld_bytes<EPL / 4>(R.p2 + e / 4) : 0u;
 #pragma unroll
     for (int j = 0; j < EPL / 2; ++j) r[j] = 0u;
 #pragma unroll
     for (int k = 0; k < EPL; ++k) {
         uint32_t x = 0u;
-        if (R.E & 8u) x = (uint32_t)(b8 >> (8 * k)) & 0xFFu;
-        if (R.E & 4u) x = (x << 4) | ((uint32_t)(b4 >> (4 * k)) & 0xFu);
-        if (R.E & 2u) x = (x << 2) | ((uint32_t)(b2 >> (2 * k)) & 0x3u);
+        if (R.S & 8u) x = (uint32_t)(b8 >> (8 * k)) & 0xFFu;
+        if (R.S & 4u) x = (x << 4) | ((uint32_t)(b4 >> (4 * k)) & 0xFu);
+        if (R.S & 2u) x = (x << 2) | ((uint32_t)(b2 >> (2 * k)) & 0x3u);
+        if (R.S & 1u) x = (x << 1) | ((ones >> k) & 1u);
         r[k / 2] |= x << (16 * (k & 1));
     }
 }
 
-__device__ __forceinline__ void planes_store(const ResRef &R, uint32_t e, const uint32_t (&r)[EPL / 2])
+/* The reverse: stores this lane's bytes of the 8-, 4- and 2-bit planes and returns its EPL
+ * bits of the 1-bit plane. */
+__device__ __forceinline__ uint32_t planes_pack(const ResRef &R, uint32_t e, const uint32_t (&r)[EPL / 2])
 {
     uint64_t b8 = 0u, b4 = 0u, b2 = 0u;
+    uint32_t ones = 0u;
 #pragma unroll
     for (int k = 0; k < EPL; ++k) {
         const uint32_t x = (r[k / 2] >> (16 * (k & 1))) & 0xFFFFu;
-        uint32_t left = R.E;
-        if (R.E & 8u) { left -= 8u; b8 |= (uint64_t)((x >> left) & 0xFFu) << (8 * k); }
-        if (R.E & 4u) { left -= 4u; b4 |= (uint64_t)((x >> left) & 0xFu) << (4 * k); }
-        if (R.E & 2u) { left -= 2u; b2 |= (uint64_t)((x >> left) & 0x3u) << (2 * k); }
+        uint32_t left = R.S;
+        if (R.S & 8u) { left -= 8u; b8 |= (uint64_t)((x >> left) & 0xFFu) << (8 * k); }
+        if (R.S & 4u) { left -= 4u; b4 |= (uint64_t)((x >> left) & 0xFu) << (4 * k); }
+        if (R.S & 2u) { left -= 2u; b2 |= (uint64_t)((x >> left) & 0x3u) << (2 * k); }
+        if (R.S & 1u) ones |= (x & 1u) << k;
     }
-    if (R.E & 8u) st_bytes<EPL>(R.p8 + e, b8);
-    if (R.E & 4u) st_bytes<EPL / 2>(R.p4 + e / 2, b4);
-    if (R.E & 2u) st_bytes<EPL / 4>(R.p2 + e / 4, b2);
+    if (R.S & 8u) st_bytes<EPL>(R.p8 + e, b8);
+    if (R.S & 4u) st_bytes<EPL / 2>(R.p4 + e / 2, b4);
+    if (R.S & 2u) st_bytes<EPL / 4>(R.p2 + e / 4, b2);
+    return ones;
+}
+
+static_assert(EPL == 4, "two lanes share a byte of the 1-bit plane");
+
+/* Fast path, every lane of the wavefront active, lane t at e = ... + 4 * (t % 64): the byte of
+ * the 1-bit plane is shared by lanes 2k and 2k+1. */
+__device__ __forceinline__ void planes_load(const ResRef &R, uint32_t e, uint32_t (&r)[EPL / 2])
+{
+    const uint32_t ones = (R.S & 1u) ? ((uint32_t)R.p1[e / 8] >> (e & 4u)) & 0xFu : 0u;
+    planes_unpack(R, e, ones, r);
+}
+
+__device__ __forceinline__ void planes_store(const ResRef &R, uint32_t e, const uint32_t (&r)[EPL / 2])
+{
+    const uint32_t ones = planes_pack(R, e, r);
+    if (R.S & 1u) {
+        const uint32_t other = (uint32_t)__shfl_xor((int)ones, 1);
+        if (!(e & 4u)) R.p1[e / 8] = (uint8_t)(ones | (other << 4));
+    }
 }
 
 template <int WFMT> struct FullBits { static constexpr uint32_t value = (WFMT == MPO_FP16) ? 13u : 16u; };
@@ -502,30 +533,47 @@ __device__ __forceinline__ void step_scalar(gu16p hi, MPO_GLOBAL void *res_, gcu
     if (Uses<OPT, MOM>::v) v[e] = vv;
 }
 
-/* Packed planes, up to EPL parameters starting at chunk-local parameter e (a multiple of EPL),
- * one at a time: ragged ends and tensors whose other arrays are not 16-byte aligned.  The lane
- * still owns whole bytes of every plane (the planes are padded to 16 bytes). */
-template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM>
+/* Packed planes outside the fast path: the (up to) 8 parameters that start at chunk-local
+ * parameter e (a multiple of 8), one at a time: ragged ends and tensors whose other arrays are
+ * not 16-byte aligned.  The lane owns whole bytes of every plane (the planes are padded to 16
+ * bytes); bits of positions past the end are written back as they were read. */
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, bool RND>
 __device__ __forceinline__ void step_group_planes(gu16p hi, const ResRef &R, gcu16p grad, gf32p m, gf32p v, uint32_t e,
-                                                  uint32_t count, const StepScalars &s, uint32_t sh)
+                                                  uint32_t len, const StepScalars &s, uint32_t kept, uint32_t sh,
+                                                  const Rng &g, uint64_t off)
 {
-    uint32_t r[EPL / 2];
-    planes_load(R, e, r);
+    uint32_t ones = (R.S & 1u) ? R.p1[e / 8] : 0u;
 #pragma unroll
-    for (int k = 0; k < EPL; ++k) {
-        if ((uint32_t)k < count) {
-            uint32_t h = hi[e + k];
-            uint32_t rr = ((r[k / 2] >> (16 * (k & 1))) & 0xFFFFu) << sh;
-            float mm = Uses<OPT, MOM>::m ? m[e + k] : 0.0f;
-            float vv = Uses<OPT, MOM>::v ? v[e + k] : 0.0f;
-            step_one<OPT, WFMT, GFMT, DECAY, MOM>(h, rr, grad[e + k], mm, vv, s);
-            hi[e + k] = (uint16_t)h;
-            if (Uses<OPT, MOM>::m) m[e + k] = mm;
-            if (Uses<OPT, MOM>::v) v[e + k] = vv;
-            r[k / 2] = (r[k / 2] & ~(0xFFFFu << (16 * (k & 1)))) | (((rr >> sh) & 0xFFFFu) << (16 * (k & 1)));
+    for (int half = 0; half < 2; ++half) {
+        const uint32_t eh = e + 4u * half;
+        if (eh < len) {
+            uint32_t r[EPL / 2];
+            planes_unpack(R, eh, (ones >> (4 * half)) & 0xFu, r);
+            uint32_t u[4] = {0u, 0u, 0u, 0u};
+            if (RND && s.round == MPO_ROUND_STOCHASTIC) draw4<FullBits<WFMT>::value>(g, (off + eh) / 4, u);
+#pragma unroll
+            for (int k = 0; k < EPL; ++k) {
+                if (eh + k < len) {
+                    uint32_t h = hi[eh + k], rr;
+                    uint32_t slot = (r[k / 2] >> (16 * (k & 1))) & 0xFFFFu;
+                    if (RND) unround<WFMT>(h, slot, rr, kept, sh, s.round);
+                    else rr = slot << sh;
+                    float mm = Uses<OPT, MOM>::m ? m[eh + k] : 0.0f;
+                    float vv = Uses<OPT, MOM>::v ? v[eh + k] : 0.0f;
+                    step_one<OPT, WFMT, GFMT, DECAY, MOM>(h, rr, grad[eh + k], mm, vv, s);
+                    if (RND) slot = reround<WFMT>(h, rr, kept, sh, s.round, u[k]);
+                    else slot = rr >> sh;
+                    hi[eh + k] = (uint16_t)h;
+                    if (Uses<OPT, MOM>::m) m[eh + k] = mm;
+                    if (Uses<OPT, MOM>::v) v[eh + k] = vv;
+                    r[k / 2] = (r[k / 2] & ~(0xFFFFu << (16 * (k & 1)))) | ((slot & 0xFFFFu) << (16 * (k & 1)));
+                }
+            }
+            const uint32_t out = planes_pack(R, eh, r);
+            ones = (ones & ~(0xFu << (4 * half))) | (out << (4 * half));
         }
     }
-    planes_store(R, e, r);
+    if (R.S & 1u) R.p1[e / 8] = (uint8_t)ones;
 }
 
 template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE>
@@ -569,12 +617,13 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
 
     /* cut bits of this tensor's residual (uniform); a full residual has none */
     const uint32_t all = (RND && s.round == MPO_ROUND_STOCHASTIC && WFMT == MPO_BF16) ? 15u : FullBits<WFMT>::value;
-    const uint32_t kept = d.res_bits ? d.res_bits : all;
+    const uint32_t stored = d.res_bits ? d.res_bits : all;
+    /* in the planes the flag of stochastic rounding is the leading one of the stored bits */
+    const uint32_t kept = (RMODE == kResPlanes && RND && s.round == MPO_ROUND_STOCHASTIC) ? stored - 1u : stored;
     const uint32_t sh = (RMODE == kResFull && !RND) ? 0u : FullBits<WFMT>::value - kept;
-    static_assert(!(RND && RMODE == kResPlanes), "packed planes are built for truncation mode only");
     const Rng rng = {s.seed_lo, s.seed_hi, s.step32, d.tensor_id};
     gu16p hi = (gu16p)(d.hi + off);
-    const ResRef R = res_ref<RMODE>(d.res, d.n, off, kept);
+    const ResRef R = res_ref<RMODE>(d.res, d.n, off, stored);
     MPO_GLOBAL void *res = R.slots;
     constexpr int RREG = reg_mode(RMODE);          /* how the kept bits sit in registers */
     gcu16p grad = (gcu16p)(gbase + off);
@@ -594,9 +643,9 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
             store_row<OPT, MOM, RMODE>(x[r], hi, R, m, v, row_elem(r, t));
         }
     } else if (RMODE == kResPlanes) {
-        /* packed planes outside the fast path: every lane walks whole groups of EPL parameters */
-        for (uint32_t e = t * EPL; e < len; e += kBlock * EPL)
-            step_group_planes<OPT, WFMT, GFMT, DECAY, MOM>(hi, R, grad, m, v, e, len - e < (uint32_t)EPL ? len - e : (uint32_t)EPL, s, sh);
+        /* packed planes outside the fast path: every lane walks whole groups of 8 parameters */
+        for (uint32_t e = t * 8u; e < len; e += kBlock * 8u)
+            step_group_planes<OPT, WFMT, GFMT, DECAY, MOM, RND>(hi, R, grad, m, v, e, len, s, kept, sh, rng, off);
     } else if (aligned) {
         /* last chunk of a tensor: full vectors, then one lane finishes the ragged end */
 #pragma unroll 1
@@ -645,7 +694,7 @@ __device__ __forceinline__ void split_store_one(float w, uint32_t &h, uint32_t &
 template <int FMT, int RMODE, bool RND>
 __global__ void __launch_bounds__(kBlock)
 split_kernel(const float *__restrict__ w32_, uint16_t *__restrict__ hi_, void *__restrict__ res_, uint64_t n,
-             uint64_t first, int aligned, uint32_t kept, uint32_t sh, RoundArgs rs)
+             uint64_t first, int aligned, uint32_t kept, uint32_t sh, uint32_t stored, RoundArgs rs)
 {
     typedef typename ResElem<RMODE>::T R;
     constexpr int RREG = reg_mode(RMODE);
@@ -654,7 +703,7 @@ split_kernel(const float *__restrict__ w32_, uint16_t *__restrict__ hi_, void *_
     const uint32_t len = left < kChunkElems ? (uint32_t)left : kChunkElems;
     gcf32p w32 = (gcf32p)(w32_ + off);
     gu16p hi = (gu16p)(hi_ + off);
-    const ResRef ref = res_ref<RMODE>(res_, n, off, kept);
+    const ResRef ref = res_ref<RMODE>(res_, n, off, stored);
     MPO_GLOBAL R *res = (MPO_GLOBAL R *)ref.slots;
     const Rng rng = {rs.seed_lo, rs.seed_hi, 0u, rs.tensor_id};
     const uint32_t t = threadIdx.x;
@@ -664,21 +713,30 @@ split_kernel(const float *__restrict__ w32_, uint16_t *__restrict__ hi_, void *_
         split_store_one<FMT, RREG, RND>(w32[i], h, slot, kept, sh, rs, u[(off + i) % 4]);
     };
     if (RMODE == kResPlanes && !(aligned && len == kChunkElems)) {
-        /* whole groups of EPL parameters per lane, one parameter at a time */
-        for (uint32_t e = t * EPL; e < len; e += kBlock * EPL) {
-            uint32_t q[EPL / 2];
+        /* whole groups of 8 parameters per lane, one parameter at a time; positions past the
+         * end are written as zero bits */
+        for (uint32_t e = t * 8u; e < len; e += kBlock * 8u) {
+            uint32_t ones = 0u;
 #pragma unroll
-            for (int j = 0; j < EPL / 2; ++j) q[j] = 0u;
+            for (int half = 0; half < 2; ++half) {
+                const uint32_t eh = e + 4u * half;
+                if (eh < len) {
+                    uint32_t q[EPL / 2];
 #pragma unroll
-            for (int k = 0; k < EPL; ++k) {
-                if (e + k < len) {
-                    uint32_t h, slot;
-                    one(e + k, h, slot);
-                    hi[e + k] = (uint16_t)h;
-                    q[k / 2] |= (slot & 0xFFFFu) << (16 * (k & 1));
+                    for (int j = 0; j < EPL / 2; ++j) q[j] = 0u;
+#pragma unroll
+                    for (int k = 0; k < EPL; ++k) {
+                        if (eh + k < len) {
+                            uint32_t h, slot;
+                            one(eh + k, h, slot);
+                            hi[eh + k] = (uint16_t)h;
+                            q[k / 2] |= (slot & 0xFFFFu) << (16 * (k & 1));
+                        }
+                    }
+                    ones |= planes_pack(ref, eh, q) << (4 * half);
                 }
             }
-            planes_store(ref, e, q);
+            if (ref.S & 1u) ref.p1[e / 8] = (uint8_t)ones;
         }
         return;
     }
@@ -742,7 +800,7 @@ __device__ __forceinline__ float merge_load_one(uint32_t h, uint32_t slot, uint3
 template <int FMT, int RMODE, bool RND>
 __global__ void __launch_bounds__(kBlock)
 merge_kernel(const uint16_t *__restrict__ hi_, const void *__restrict__ res_, float *__restrict__ w32_, uint64_t n,
-             uint64_t first, int aligned, uint32_t kept, uint32_t sh, uint32_t round)
+             uint64_t first, int aligned, uint32_t kept, uint32_t sh, uint32_t stored, uint32_t round)
 {
     typedef typename ResElem<RMODE>::T R;
     constexpr int RREG = reg_mode(RMODE);
@@ -751,16 +809,24 @@ merge_kernel(const uint16_t *__restrict__ hi_, const void *__restrict__ res_, fl
     const uint32_t len = left < kChunkElems ? (uint32_t)left : kChunkElems;
     gf32p w32 = (gf32p)(w32_ + off);
     gcu16p hi = (gcu16p)(hi_ + off);
-    const ResRef ref = res_ref<RMODE>(const_cast<void *>(res_), n, off, kept);
+    const ResRef ref = res_ref<RMODE>(const_cast<void *>(res_), n, off, stored);
     const MPO_GLOBAL R *res = (const MPO_GLOBAL R *)ref.slots;
     const uint32_t t = threadIdx.x;
     if (RMODE == kResPlanes && !(aligned && len == kChunkElems)) {
-        for (uint32_t e = t * EPL; e < len; e += kBlock * EPL) {
-            uint32_t q[EPL / 2];
-            planes_load(ref, e, q);
+        for (uint32_t e = t * 8u; e < len; e += kBlock * 8u) {
+            const uint32_t ones = (ref.S & 1u) ? ref.p1[e / 8] : 0u;
 #pragma unroll
-            for (int k = 0; k < EPL; ++k)
-                if (e + k < len) w32[e + k] = merge_load_one<FMT, RREG, RND>(hi[e + k], slot_get<RREG>(q, k), kept, sh, round);
+            for (int half = 0; half < 2; ++half) {
+                const uint32_t eh = e + 4u * half;
+                if (eh < len) {
+                    uint32_t q[EPL / 2];
+                    planes_unpack(ref, eh, (ones >> (4 * half)) & 0xFu, q);
+#pragma unroll
+                    for (int k = 0; k < EPL; ++k)
+                        if (eh + k < len)
+                            w32[eh + k] = merge_load_one<FMT, RREG, RND>(hi[eh + k], slot_get<RREG>(q, k), kept, sh, round);
+                }
+            }
         }
         return;
     }
@@ -816,8 +882,9 @@ hipError_t launch_step_res(const StepLaunch &L)
 {
     if (L.s.round != MPO_ROUND_TRUNC) {
         /* rounded modes always go through the general residual path */
-        return L.rmode == kResByte ? launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResByte, true>(L)
-                                   : launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResPartial, true>(L);
+        return L.rmode == kResByte     ? launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResByte, true>(L)
+               : L.rmode == kResPlanes ? launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResPlanes, true>(L)
+                                       : launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResPartial, true>(L);
     }
     switch (L.rmode) {
     case kResFull: return launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResFull, false>(L);
@@ -844,7 +911,7 @@ struct SplitMergeArgs {
     void *res;
     uint64_t n;
     int al;
-    uint32_t kept, sh;
+    uint32_t kept, sh, stored;
     RoundArgs rs;
     hipStream_t stream;
 };
@@ -859,7 +926,7 @@ hipError_t launch_split_t(const SplitMergeArgs &a)
         const uint64_t e0 = done * kChunkElems;
         (void)hipGetLastError();
         split_kernel<FMT, RMODE, RND><<<dim3((uint32_t)now), dim3(kBlock), 0, a.stream>>>(
-            a.w32_in, a.hi, a.res, a.n, e0, a.al, a.kept, a.sh, a.rs);
+            a.w32_in, a.hi, a.res, a.n, e0, a.al, a.kept, a.sh, a.stored, a.rs);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         done += now;
@@ -877,7 +944,7 @@ hipError_t launch_merge_t(const SplitMergeArgs &a)
         const uint64_t e0 = done * kChunkElems;
         (void)hipGetLastError();
         merge_kernel<FMT, RMODE, RND><<<dim3((uint32_t)now), dim3(kBlock), 0, a.stream>>>(
-            a.hi, a.res, a.w32_out, a.n, e0, a.al, a.kept, a.sh, a.rs.round);
+            a.hi, a.res, a.w32_out, a.n, e0, a.al, a.kept, a.sh, a.stored, a.rs.round);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         done += now;
@@ -891,7 +958,7 @@ hipError_t launch_sm(const SplitMergeArgs &a, int rmode)
     const bool rnd = a.rs.round != MPO_ROUND_TRUNC;
     if (rnd && rmode == kResFull) rmode = kResPartial;     /* rounded modes: general residual path */
 #define MPO_SM(RM, RN) (SPLIT ? launch_split_t<FMT, RM, RN>(a) : launch_merge_t<FMT, RM, RN>(a))
-    if (rnd) return rmode == kResByte ? MPO_SM(kResByte, true) : MPO_SM(kResPartial, true);
+    if (rnd) return rmode == kResByte ? MPO_SM(kResByte, true) : rmode == kResPlanes ? MPO_SM(kResPlanes, true) : MPO_SM(kResPartial, true);
     if (rmode == kResPlanes) return MPO_SM(kResPlanes, false);
     if (rmode == kResByte) return MPO_SM(kResByte, false);
     if (rmode == kResPartial) return MPO_SM(kResPartial, false);
@@ -902,12 +969,14 @@ hipError_t launch_sm(const SplitMergeArgs &a, int rmode)
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 /* Storage mode, kept bits and number of cut bits for a single-tensor call. */
-inline void res_layout(int fmt, int res_bits, int packed, int round, int &rmode, uint32_t &kept, uint32_t &sh)
+inline void res_layout(int fmt, int res_bits, int packed, int round, int &rmode, uint32_t &kept, uint32_t &sh,
+                       uint32_t &stored)
 {
     const int full = full_res_bits(fmt);
-    const int k = kept_res_bits(fmt, res_bits, round);
+    const int k = kept_res_bits(fmt, res_bits, round, packed);
     kept = (uint32_t)k;
     sh = (uint32_t)(full - k);
+    stored = packed ? (uint32_t)res_bits : kept;
     rmode = packed ? kResPlanes : (res_bits >= 1 && res_bits <= 8) ? kResByte : (k == full ? kResFull : kResPartial);
 }
 
@@ -937,7 +1006,7 @@ hipError_t launch_split(const float *w32, uint16_t *hi, void *res, uint64_t n, i
     a.w32_in = w32; a.w32_out = nullptr; a.hi = hi; a.res = res; a.n = n;
     a.al = aligned16(w32) && aligned16(hi) && aligned16(res);
     int rmode;
-    res_layout(fmt, res_bits, packed, round, rmode, a.kept, a.sh);
+    res_layout(fmt, res_bits, packed, round, rmode, a.kept, a.sh, a.stored);
     a.rs = RoundArgs{(uint32_t)round, (uint32_t)seed, (uint32_t)(seed >> 32), tensor_id};
     a.stream = stream;
     return fmt == MPO_BF16 ? launch_sm<MPO_BF16, true>(a, rmode) : launch_sm<MPO_FP16, true>(a, rmode);
@@ -950,7 +1019,7 @@ hipError_t launch_merge(const uint16_t *hi, const void *res, float *w32, uint64_
     a.w32_in = nullptr; a.w32_out = w32; a.hi = const_cast<uint16_t *>(hi); a.res = const_cast<void *>(res); a.n = n;
     a.al = aligned16(w32) && aligned16(hi) && aligned16(res);
     int rmode;
-    res_layout(fmt, res_bits, packed, round, rmode, a.kept, a.sh);
+    res_layout(fmt, res_bits, packed, round, rmode, a.kept, a.sh, a.stored);
     a.rs = RoundArgs{(uint32_t)round, 0u, 0u, 0u};
     a.stream = stream;
     return fmt == MPO_BF16 ? launch_sm<MPO_BF16, false>(a, rmode) : launch_sm<MPO_FP16, false>(a, rmode);

@@ -80,14 +80,19 @@ def test_split_merge_argument_validation():
     assert _status(mpo.mpo_merge, A, A + 0x1000, A + 0x2000, 10, fmt=mpo.MPO_FP16, res_bits=16) == mpo.MPO_ERR_INVALID_ARG
     # res [A+0x1000, +10 bytes) with 8 bits does not reach hi at A+0x100a; with 16 bits it does
     assert _status(mpo.mpo_split, A, A + 0x100a, A + 0x1000, 10, res_bits=9) == mpo.MPO_ERR_ALIAS
-    # packed planes: even E from 2 to 14, truncation only, 16-byte aligned buffer
-    assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, res_bits=12, res_packed=True,
-                   round=mpo.MPO_ROUND_NEAREST) == mpo.MPO_ERR_UNSUPPORTED
-    for bad in (0, 1, 3, 7, 16):
+    # packed planes: 1 to 15 stored bits, 16-byte aligned buffer
+    for bad in (0, 16, -2):
         assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, res_bits=bad, res_packed=True) == mpo.MPO_ERR_INVALID_ARG
     assert _status(mpo.mpo_merge, A, A + 0x1004, A + 0x2000, 10, res_bits=12, res_packed=True) == mpo.MPO_ERR_INVALID_ARG
+    # ... of which at least one and at most the format's are kept bits; with stochastic rounding one is the flag
     assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, fmt=mpo.MPO_FP16, res_bits=14, res_packed=True) \
         == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, fmt=mpo.MPO_FP16, res_bits=14, res_packed=True,
+                   round=mpo.MPO_ROUND_NEAREST) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_split, A, A + 0x1000, A + 0x2000, 10, fmt=mpo.MPO_FP16, res_bits=15, res_packed=True,
+                   round=mpo.MPO_ROUND_STOCHASTIC) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(mpo.mpo_merge, A, A + 0x1000, A + 0x2000, 10, res_bits=1, res_packed=True,
+                   round=mpo.MPO_ROUND_STOCHASTIC) == mpo.MPO_ERR_INVALID_ARG
     # zero elements: a legal no-op even with null pointers
     assert _status(mpo.mpo_split, 0, 0, 0, 0) == mpo.MPO_OK
     assert _status(mpo.mpo_merge, 0, 0, 0, 0, fmt=mpo.MPO_FP16) == mpo.MPO_OK
@@ -127,7 +132,9 @@ def test_res_bytes():
     assert _status(_host_plan, [a, T(1, res_bits=12, res_packed=True, hi=a.res + nb)]) == mpo.MPO_OK
     assert _status(_host_plan, [a, T(1, res_bits=12, res_packed=True, hi=a.res + nb - 2)]) == mpo.MPO_ERR_ALIAS
     assert _status(_host_plan, [a, T(1, res_bits=12)]) == mpo.MPO_ERR_UNSUPPORTED           # packed and slots mixed
-    assert _status(_host_plan, [T(0, res_bits=5, res_packed=True)]) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(_host_plan, [T(0, res_bits=0, res_packed=True)]) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(_host_plan, [T(0, res_bits=16, res_packed=True)]) == mpo.MPO_ERR_INVALID_ARG
+    assert _status(_host_plan, [T(0, res_bits=5, res_packed=True)]) == mpo.MPO_OK
     assert _status(_host_plan, [T(0, res_bits=12, res_packed=True, res=A + 0x100008)]) == mpo.MPO_ERR_INVALID_ARG
 
 

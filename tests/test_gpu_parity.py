@@ -753,15 +753,20 @@ def test_step_can_be_captured_in_a_hip_graph_and_replayed():
 
 # ---- packed planes: extra bits stored without padding (Section 3.1, Figure 1) ----------------------
 
-@pytest.mark.parametrize("fmt,res_bits", [("bf16", 12), ("bf16", 4), ("bf16", 2), ("bf16", 6), ("bf16", 10), ("bf16", 14),
-                                          ("bf16", 8), ("fp16", 12), ("fp16", 4), ("fp16", 10)])
+PACKED_SM = [("bf16", E, "trunc") for E in range(1, 16)] + [("fp16", E, "trunc") for E in (12, 4, 10, 13, 1, 7, 9)] + \
+            [("fp16", 14, "stochastic"), ("fp16", 13, "nearest"), ("bf16", 15, "stochastic"), ("bf16", 9, "stochastic"),
+             ("bf16", 2, "stochastic"), ("bf16", 11, "nearest"), ("fp16", 6, "nearest"), ("fp16", 8, "stochastic")]
+
+
+@pytest.mark.parametrize("fmt,res_bits,mode", PACKED_SM, ids=["%s-%d-%s" % c for c in PACKED_SM])
 @pytest.mark.parametrize("misalign", [0, 1])
-def test_split_merge_packed(fmt, res_bits, misalign):
+def test_split_merge_packed(fmt, res_bits, mode, misalign):
     """The packed buffer equals the oracle's byte for byte (planes, order within a byte, padding)."""
     gfmt, rfmt = FMT[fmt]
+    gmode, rmode = ROUND[mode]
     rng = np.random.default_rng(51)
-    for n in SIZES + [3, 5, 4 * CHUNK]:
-        say("packed split/merge fmt=%s res_bits=%d n=%d misalign=%d" % (fmt, res_bits, n, misalign))
+    for n in SIZES + [3, 5, 9, 4 * CHUNK]:
+        say("packed split/merge fmt=%s res_bits=%d mode=%s n=%d misalign=%d" % (fmt, res_bits, mode, n, misalign))
         x = interesting_f32(rng, n)
         w = torch.zeros(n + misalign + 8, dtype=torch.float32, device=DEV)[misalign:misalign + n]
         w.copy_(torch.from_numpy(x))
@@ -769,32 +774,38 @@ def test_split_merge_packed(fmt, res_bits, misalign):
         nb = mpo.mpo_res_bytes(n, res_bits, True)
         assert nb == ref.res_bytes(n, rfmt, res_bits, True)
         buf = torch.zeros(nb + 32, dtype=torch.uint8, device=DEV)
-        mpo.mpo_split(w, hi[misalign:], buf, n, fmt=gfmt, res_bits=res_bits, res_packed=True)
-        want_hi, want_buf = ref.split(x, rfmt, res_bits, packed=True)
+        mpo.mpo_split(w, hi[misalign:], buf, n, fmt=gfmt, res_bits=res_bits, res_packed=True, round=gmode, seed=77, tensor_id=3)
+        want_hi, want_buf = ref.split(x, rfmt, res_bits, rmode, 77, 3, packed=True)
         assert np.array_equal(host_u16(hi[misalign:misalign + n]), want_hi)
         got = buf.cpu().numpy()
         assert np.array_equal(got[:nb], want_buf) and not got[nb:].any()
         out = torch.full((n + misalign + 8,), -7.0, dtype=torch.float32, device=DEV)
-        mpo.mpo_merge(hi[misalign:], buf, out[misalign:], n, fmt=gfmt, res_bits=res_bits, res_packed=True)
-        want = ref.merge(want_hi, want_buf, rfmt, res_bits, packed=True)
+        mpo.mpo_merge(hi[misalign:], buf, out[misalign:], n, fmt=gfmt, res_bits=res_bits, res_packed=True, round=gmode)
+        want = ref.merge(want_hi, want_buf, rfmt, res_bits, rmode, packed=True)
         g = host_f32(out)
         assert np.array_equal(g[misalign:misalign + n].view(np.uint32), want.view(np.uint32))
         assert np.all(g[:misalign] == -7.0) and np.all(g[misalign + n:] == -7.0)
 
 
 PACKED_CASES = [
-    ("adam", "bf16", [12], dict(lr=1e-3, weight_decay=1e-2, decoupled_wd=True)),      # the paper's example: 12 extra bits
-    ("adam", "fp16", [12], dict(lr=1e-3, loss_scale=1024.0)),
-    ("adam", "bf16", [4, 12, 2, 14, 6, 10, 8], dict(lr=1e-3)),
-    ("sgd", "bf16", [12, 4], dict(lr=0.3, momentum=0.9, weight_decay=2e-4)),
-    ("sgd", "fp16", [10], dict(lr=0.1, momentum=0.0, loss_scale=128.0)),
+    ("adam", "bf16", [12], "trunc", dict(lr=1e-3, weight_decay=1e-2, decoupled_wd=True)),      # the paper's example: 12 extra bits
+    ("adam", "fp16", [12], "trunc", dict(lr=1e-3, loss_scale=1024.0)),
+    ("adam", "bf16", [4, 12, 2, 14, 6, 10, 8], "trunc", dict(lr=1e-3)),
+    ("adam", "bf16", [5, 13, 1, 15, 7, 11, 3, 9], "trunc", dict(lr=1e-3)),
+    ("adam", "fp16", [13], "trunc", dict(lr=1e-3, loss_scale=1024.0)),                         # all 13 bits of fp16 in 13
+    ("adam", "fp16", [14], "stochastic", dict(lr=1e-3, loss_scale=1024.0)),                    # the paper's fp16+13 with the flag
+    ("adam", "bf16", [9, 2, 12, 15, 6], "stochastic", dict(lr=1e-3, weight_decay=1e-2, decoupled_wd=True)),
+    ("adam", "bf16", [11, 4, 1], "nearest", dict(lr=1e-3)),
+    ("sgd", "bf16", [12, 4], "trunc", dict(lr=0.3, momentum=0.9, weight_decay=2e-4)),
+    ("sgd", "fp16", [10], "trunc", dict(lr=0.1, momentum=0.0, loss_scale=128.0)),
+    ("sgd", "fp16", [7, 14], "stochastic", dict(lr=0.1, momentum=0.9, loss_scale=128.0)),
 ]
 
 
-@pytest.mark.parametrize("kind,fmt,bits,kw", PACKED_CASES,
-                         ids=["%s-%s-%s" % (c[0], c[1], "_".join(map(str, c[2]))) for c in PACKED_CASES])
+@pytest.mark.parametrize("kind,fmt,bits,mode,kw", PACKED_CASES,
+                         ids=["%s-%s-%s-%s" % (c[0], c[1], "_".join(map(str, c[2])), c[3]) for c in PACKED_CASES])
 @pytest.mark.parametrize("misalign", [0, 1])
-def test_multi_tensor_list_packed(kind, fmt, bits, kw, misalign):
+def test_multi_tensor_list_packed(kind, fmt, bits, mode, kw, misalign):
     gfmt, rfmt = FMT[fmt]
     rng = np.random.default_rng(27 + misalign)
     sizes = _small_list(rng, count=21, total=600_000)
@@ -804,9 +815,10 @@ def test_multi_tensor_list_packed(kind, fmt, bits, kw, misalign):
     for i, n in enumerate(sizes):
         E = bits[i % len(bits)]
         w0 = synth.gen_weights(n, synth.seed_for(47, i), "cpu", 0.02).numpy()
-        devs.append(DevTensor(w0, gfmt, with_v=(kind == "adam"), layer=i % 4, misalign=misalign, res_bits=E, packed=True))
-        hosts.append(HostTensor(w0, rfmt, with_v=(kind == "adam"), res_bits=E, packed=True))
-        cfgs.append(cfg_pair(kind, fmt, res_bits=E, packed=True, **kw))
+        devs.append(DevTensor(w0, gfmt, with_v=(kind == "adam"), layer=i % 4, misalign=misalign, res_bits=E, packed=True,
+                              round=mode, seed=31, tensor_id=i))
+        hosts.append(HostTensor(w0, rfmt, with_v=(kind == "adam"), res_bits=E, packed=True, round=mode, seed=31, tensor_id=i))
+        cfgs.append(cfg_pair(kind, fmt, res_bits=E, packed=True, round=mode, seed=31, **kw))
     plan = mpo.Plan([d.spec() for d in devs])
     lib_cfg = cfgs[0][0]
     for t in range(1, 5):
@@ -814,9 +826,9 @@ def test_multi_tensor_list_packed(kind, fmt, bits, kw, misalign):
             g = synth.bits16(synth.gen_grads(d.n, synth.seed_for(53, i, t), "cpu", 1e-3, fmt, scale))
             d.grad.copy_(dev_u16(g))
             if kind == "adam":
-                ref.adam_step(h.hi, h.res, g, h.m, h.v, cfgs[i][1], t)
+                ref.adam_step(h.hi, h.res, g, h.m, h.v, cfgs[i][1], t, tensor_id=i)
             else:
-                ref.sgd_step(h.hi, h.res, g, h.m, cfgs[i][1], t)
+                ref.sgd_step(h.hi, h.res, g, h.m, cfgs[i][1], t, tensor_id=i)
         if t % 2:
             (mpo.mpo_adam_step if kind == "adam" else mpo.mpo_sgd_step)(plan, lib_cfg, t)
         else:
@@ -824,8 +836,16 @@ def test_multi_tensor_list_packed(kind, fmt, bits, kw, misalign):
                 mpo.mpo_step_layer(plan, ly, lib_cfg, t)
         for i, (d, h) in enumerate(zip(devs, hosts)):
             assert_state_equal(d, h, "tensor %d (n=%d, E=%d) step %d" % (i, d.n, d.res_bits, t))
-    with pytest.raises(mpo.MpoError) as e:                 # rounded modes are not built for packed planes
-        mpo.mpo_adam_step(plan, mpo.AdamCfg(round=mpo.MPO_ROUND_NEAREST), 9) if kind == "adam" else \
-            mpo.mpo_sgd_step(plan, mpo.SgdCfg(round=mpo.MPO_ROUND_NEAREST), 9)
-    assert e.value.status == mpo.MPO_ERR_UNSUPPORTED
+    # a mode the stored widths do not suit is refused before anything is launched
+    wrong = dict(weight_fmt=gfmt, grad_fmt=gfmt)
+    if fmt == "fp16" and max(bits) == 14:            # 14 stored bits of fp16 only make sense with the flag
+        wrong["round"] = mpo.MPO_ROUND_TRUNC
+    elif min(bits) == 1:                             # 1 stored bit leaves nothing below the flag
+        wrong["round"] = mpo.MPO_ROUND_STOCHASTIC
+    else:
+        wrong = None
+    if wrong is not None:
+        with pytest.raises(mpo.MpoError) as e:
+            mpo.mpo_adam_step(plan, mpo.AdamCfg(**wrong), 9) if kind == "adam" else mpo.mpo_sgd_step(plan, mpo.SgdCfg(**wrong), 9)
+        assert e.value.status == mpo.MPO_ERR_INVALID_ARG
     plan.destroy()
