@@ -57,7 +57,7 @@ __global__ __launch_bounds__(kLanes) void probe_kernel(void *hi, void *res, cons
     for (int k = 0; k < kRows; ++k) {
         const uint64_t e = chunk0 + (t / 64) * 1024 + k * 256 + (t % 64) * 4;
         st<u32x2>(hi, e * 2, h[k] ^ g[k]);
-        st<u32x2>(res, e * 2, r[k] + g[k]);
+        st<u32x2>(res, e * 2, ~(r[k] ^ g[k]));
         st<f32x4>(m, e * 4, a[k] + 1.0f);
         if (WITH_V) st<f32x4>(v, e * 4, b[k] + 2.0f);
     }

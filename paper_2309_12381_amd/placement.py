@@ -79,7 +79,7 @@ def allocate_state(n: int, res_spec: Tuple[int, torch.dtype], grad_spec: Tuple[i
     arrays = {"hi": torch.empty(n, dtype=torch.int16, device=dev), "m": torch.empty(n, dtype=torch.float32, device=dev)}
     res_bytes = res_spec[0] * torch.empty((), dtype=res_spec[1]).element_size()
     grad_bytes = grad_spec[0] * torch.empty((), dtype=grad_spec[1]).element_size()
-    if not place or n < MIN_PARAMS or res_bytes < 4 * _N2:
+    if not place or n < MIN_PARAMS or res_bytes < _N2:
         arrays.update(second())
         return finish(arrays, {"split": False, "why": "placement switched off" if not place else "state too small to place"})
 
