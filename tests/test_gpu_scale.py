@@ -44,7 +44,7 @@ def _run_and_compare(key, steps, sampler, res_bits=0, round=0, packed=False):
     host = {}
     for i, (idx, w) in st.w32_samples.items():
         if packed:
-            hi, res = ref.split(np.ascontiguousarray(w.numpy()), rf, res_bits, packed=True)
+            hi, res = ref.split(np.ascontiguousarray(w.numpy()), rf, res_bits, round, st.rng_seed, i, packed=True)
         elif round == 2:
             assert isinstance(idx, slice)
             hi, res = ref.split(np.ascontiguousarray(w.numpy()), rf, res_bits, round, st.rng_seed, i)
@@ -149,6 +149,21 @@ def test_c3_llama7b_packed_12_bits_whole_tensors():
     """The paper's Figure 1 example, 12 extra bits without padding: 3.5 B per weight, 25 B moved per Adam step."""
     checked, wl = _run_and_compare("c3", 2, _whole_tensors, res_bits=12, packed=True)
     assert checked > 100_000_000
+
+
+def test_c3_llama7b_packed_13_bits_whole_tensors():
+    """An odd width: 13 = 8 + 4 + 1 stored bits, so the 1-bit plane (two lanes per byte) is in play."""
+    checked, wl = _run_and_compare("c3", 2, _whole_tensors, res_bits=13, packed=True)
+    assert checked > 100_000_000
+
+
+def test_c4_llama13b_fp16_packed_14_bits_stochastic_whole_tensors():
+    """The paper's "fp16+13 rstoc" without padding: 13 extra bits and the un-round flag in 14 stored bits."""
+    free, total = torch.cuda.mem_get_info()
+    if total < 200e9:
+        pytest.skip("needs about 160 GB of device memory")
+    checked, wl = _run_and_compare("c4", 2, _whole_tensors, res_bits=14, round=2, packed=True)
+    assert checked > 200_000_000
 
 
 def test_c4_llama13b_fp16_stochastic_whole_tensors():
