@@ -26,7 +26,8 @@ class FusedBackwardOptimizer:
 
     params      bf16 or fp16 CUDA parameters (all of one dtype), contiguous.
     cfg         mpo.AdamCfg or mpo.SgdCfg; its weight_fmt / grad_fmt are set from the dtype.
-    res_bits    extra bits kept per weight (0 = all).
+    res_bits    extra bits kept per weight (0 = all); with res_packed the bits stored per weight.
+    res_packed  store the extra bits in packed planes (Section 3.1, Figure 1) instead of slots.
     init_fp32   optional fp32 tensors to start from (else the 16-bit values, residual 0).
     fused       True: step in the hook and free the gradient (Section 3.2).  False: keep gradients
                 and step them all in `step()`, the classical schedule, for comparison.
@@ -38,7 +39,7 @@ class FusedBackwardOptimizer:
 
     def __init__(self, params: Iterable[torch.nn.Parameter], cfg, res_bits: int = 0,
                  init_fp32: Optional[Sequence[torch.Tensor]] = None, fused: bool = True,
-                 observer: Optional[Callable] = None):
+                 observer: Optional[Callable] = None, res_packed: bool = False):
         self.params = [p for p in params if p.requires_grad]
         if not self.params:
             raise ValueError("no parameters")
@@ -52,6 +53,7 @@ class FusedBackwardOptimizer:
         self.cfg.weight_fmt = self.cfg.grad_fmt = _FMT[dtype]
         self.is_adam = isinstance(cfg, mpo.AdamCfg)
         self.res_bits = res_bits
+        self.res_packed = res_packed
         self.fused = fused
         self.observer = observer
         self.step_no = 0
@@ -60,8 +62,16 @@ class FusedBackwardOptimizer:
         for p in self.params:
             offs.append(total)
             total += _round_up(p.numel(), 8)
-        res_dtype = torch.uint8 if 1 <= res_bits <= 8 else torch.int16
-        self.res = torch.zeros(total, dtype=res_dtype, device=dev)
+        if res_packed:
+            # one byte buffer; each parameter's planes start at a multiple of 16 bytes
+            self.res_offs, fill = [], 0
+            for p in self.params:
+                self.res_offs.append(fill)
+                fill += mpo.mpo_res_bytes(p.numel(), res_bits, True)
+            self.res = torch.zeros(fill, dtype=torch.uint8, device=dev)
+        else:
+            self.res_offs = offs
+            self.res = torch.zeros(total, dtype=torch.uint8 if 1 <= res_bits <= 8 else torch.int16, device=dev)
         self.m = torch.zeros(total, dtype=torch.float32, device=dev)
         self.v = torch.zeros(total, dtype=torch.float32, device=dev) if self.is_adam else None
         self.offs = offs
@@ -70,10 +80,11 @@ class FusedBackwardOptimizer:
             n = p.numel()
             master = init_fp32[i].to(dev, torch.float32).reshape(-1).contiguous() if init_fp32 is not None \
                 else p.detach().float().reshape(-1)
-            mpo.mpo_split(master, p.data, self.res[off:], n, fmt=_FMT[dtype], res_bits=res_bits, round=cfg.round,
-                          seed=cfg.seed, tensor_id=i)
-            specs.append(mpo.Tensor(p.data, self.res[off:], None, self.m[off:],
-                                    self.v[off:] if self.is_adam else None, n, i, res_bits))
+            res = self.res[self.res_offs[i]:]
+            mpo.mpo_split(master, p.data, res, n, fmt=_FMT[dtype], res_bits=res_bits, round=cfg.round,
+                          seed=cfg.seed, tensor_id=i, res_packed=res_packed)
+            specs.append(mpo.Tensor(p.data, res, None, self.m[off:],
+                                    self.v[off:] if self.is_adam else None, n, i, res_bits, res_packed))
         torch.cuda.synchronize(dev)
         self.plan = mpo.Plan(specs)          # one layer id per parameter: the paper steps per parameter
         self._index = {id(p): i for i, p in enumerate(self.params)}
@@ -114,13 +125,14 @@ class FusedBackwardOptimizer:
         """The fp32 value of parameter i held by (hi, res)."""
         p = self.params[i]
         out = torch.empty(p.numel(), dtype=torch.float32, device=p.device)
-        mpo.mpo_merge(p.data, self.res[self.offs[i]:], out, p.numel(), fmt=_FMT[p.dtype], res_bits=self.res_bits,
-                      round=self.cfg.round)
+        mpo.mpo_merge(p.data, self.res[self.res_offs[i]:], out, p.numel(), fmt=_FMT[p.dtype], res_bits=self.res_bits,
+                      round=self.cfg.round, res_packed=self.res_packed)
         return out.view_as(p)
 
     def state_of(self, i: int):
-        n, off = self.params[i].numel(), self.offs[i]
-        return self.res[off:off + n], self.m[off:off + n], (self.v[off:off + n] if self.is_adam else None)
+        n, off, roff = self.params[i].numel(), self.offs[i], self.res_offs[i]
+        rlen = mpo.mpo_res_bytes(n, self.res_bits, True) if self.res_packed else n
+        return self.res[roff:roff + rlen], self.m[off:off + n], (self.v[off:off + n] if self.is_adam else None)
 
     def close(self):
         for h in self._handles:

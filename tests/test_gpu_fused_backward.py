@@ -30,10 +30,11 @@ def _model(dtype, width=384, depth=3, seed=0):
     (torch.float16, "adam", dict(lr=1e-3, loss_scale=256.0, grad_clip=0.01)),
     (torch.bfloat16, "sgd", dict(lr=1e-2, momentum=0.9, weight_decay=2e-4)),
 ], ids=["bf16-adamw", "bf16-adam-clip-stochastic", "fp16-adam-scaled-clip", "bf16-sgd"])
-@pytest.mark.parametrize("res_bits", [0, 7])
-def test_hooks_step_every_parameter_and_match_the_oracle(dtype, kind, kw, res_bits):
+@pytest.mark.parametrize("res_bits,packed", [(0, False), (7, False), (13, True), (6, True)],
+                         ids=["all", "7", "13-packed", "6-packed"])
+def test_hooks_step_every_parameter_and_match_the_oracle(dtype, kind, kw, res_bits, packed):
     fmt = "bf16" if dtype == torch.bfloat16 else "fp16"
-    say("fused backward dtype=%s kind=%s kw=%s res_bits=%d" % (fmt, kind, kw, res_bits))
+    say("fused backward dtype=%s kind=%s kw=%s res_bits=%d packed=%s" % (fmt, kind, kw, res_bits, packed))
     model = _model(dtype)
     params = [p for p in model.parameters()]
     w0 = [p.detach().float().cpu().numpy().reshape(-1).copy() for p in params]
@@ -43,7 +44,7 @@ def test_hooks_step_every_parameter_and_match_the_oracle(dtype, kind, kw, res_bi
 
     def observer(i, g):
         seen.append((i, synth.bits16(g.reshape(-1))))
-    opt = FusedBackwardOptimizer(params, cfg, res_bits=res_bits, observer=observer)
+    opt = FusedBackwardOptimizer(params, cfg, res_bits=res_bits, observer=observer, res_packed=packed)
     scale = kw.get("loss_scale", 1.0)
     g = torch.Generator(device=DEV)
     g.manual_seed(5)
@@ -67,9 +68,9 @@ def test_hooks_step_every_parameter_and_match_the_oracle(dtype, kind, kw, res_bi
     rf = FMT[fmt][1]
     rkw = dict(kw)
     rkw["round"] = {0: ref.TRUNC, 1: ref.NEAREST, 2: ref.STOCHASTIC}[kw.get("round", 0)]
-    rcfg = (ref.AdamCfg if kind == "adam" else ref.SgdCfg)(weight_fmt=rf, grad_fmt=rf, res_bits=res_bits, **rkw)
+    rcfg = (ref.AdamCfg if kind == "adam" else ref.SgdCfg)(weight_fmt=rf, grad_fmt=rf, res_bits=res_bits, res_packed=packed, **rkw)
     for i, p in enumerate(params):
-        hi, res = ref.split(w0[i], rf, res_bits, rcfg.round, rcfg.seed, i)
+        hi, res = ref.split(w0[i], rf, res_bits, rcfg.round, rcfg.seed, i, packed)
         m = np.zeros(hi.size, np.float32)
         v = np.zeros(hi.size, np.float32)
         for t in range(steps):
@@ -84,7 +85,7 @@ def test_hooks_step_every_parameter_and_match_the_oracle(dtype, kind, kw, res_bi
         assert np.array_equal(host_f32(gm).view(np.uint32), m.view(np.uint32)), "parameter %d: m differs" % i
         if kind == "adam":
             assert np.array_equal(host_f32(gv).view(np.uint32), v.view(np.uint32)), "parameter %d: v differs" % i
-        want32 = ref.merge(hi, res, rf, res_bits, rcfg.round)
+        want32 = ref.merge(hi, res, rf, res_bits, rcfg.round, packed)
         assert np.array_equal(host_f32(opt.master_fp32(i).reshape(-1)).view(np.uint32), want32.view(np.uint32))
     opt.close()
 
