@@ -17,7 +17,8 @@ def _load():
     global _lib
     if _lib is None:
         if not os.path.exists(LIB_PATH):
-            raise RuntimeError("libmpo_probe.so is not built: run `python -m paper_2309_12381_amd.build`")
+            from . import build as _build          # nothing built yet: build once (needs hipcc)
+            _build.build_probe()
         _lib = ctypes.CDLL(LIB_PATH)
         _lib.mpo_probe_stream.restype = ctypes.c_int
         _lib.mpo_probe_stream.argtypes = [ctypes.c_void_p] * 5 + [ctypes.c_longlong, ctypes.c_void_p]
