@@ -10,9 +10,15 @@
 
 namespace mpo {
 
-/* One workgroup (256 lanes = 4 wavefronts of 64) owns one chunk. */
+/* One workgroup (256 lanes = 4 wavefronts of 64) owns one chunk.  The chunk length can be set at
+ * build time (a multiple of 1024) for measurements: 1024, 2048 and 4096 give the same throughput on
+ * the large parameter sets; 4096 keeps the chunk table smallest. */
 constexpr uint32_t kBlock = 256;
-constexpr uint32_t kChunkElems = 4096;
+#ifndef MPO_CHUNK_ELEMS
+#define MPO_CHUNK_ELEMS 4096
+#endif
+constexpr uint32_t kChunkElems = MPO_CHUNK_ELEMS;
+static_assert(kChunkElems % 1024 == 0 && kChunkElems >= 1024, "a chunk is a whole number of rows of 4 wavefronts");
 
 /* Bits of TensorDesc::flags. */
 constexpr uint32_t kStateAligned = 1u; /* hi, res, m, v all 16-byte aligned          */
