@@ -206,6 +206,74 @@ def test_sgd_single_tensor_config0(fmt, momentum, wd):
     plan.destroy()
 
 
+def _same_or_both_nan(got: np.ndarray, want: np.ndarray, what: str):
+    """Bit equality of fp32 arrays, except that where the oracle has a NaN any NaN will do: which NaN
+    an invalid operation produces (sign, payload) is the processor's choice, not the method's."""
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan), what + ": NaNs in other places"
+    bad = np.flatnonzero((got.view(np.uint32) != want.view(np.uint32)) & ~nan)
+    assert bad.size == 0, "%s: %d differ, first at %d: gpu %08x oracle %08x" % (
+        what, bad.size, bad[0], got.view(np.uint32)[bad[0]], want.view(np.uint32)[bad[0]])
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "fp16"])
+@pytest.mark.parametrize("kind,kw", [("adam", dict(lr=1e-3, weight_decay=0.1, decoupled_wd=True)),
+                                     ("adam", dict(lr=0.5, weight_decay=0.01, decoupled_wd=False, eps=1e-30)),
+                                     ("adam", dict(lr=1e-3, loss_scale=65536.0, grad_clip=1.0)),
+                                     ("sgd", dict(lr=0.1, momentum=0.9, weight_decay=1e-3)),
+                                     ("sgd", dict(lr=1e30, momentum=0.5))],
+                         ids=["adamw", "adam-l2-tiny-eps", "adam-scaled-clip", "sgd", "sgd-huge-lr"])
+def test_steps_on_arbitrary_bit_patterns(fmt, kind, kw):
+    """State and gradients drawn as raw bit patterns over ALL exponents (denormals, huge values,
+    infinite and NaN gradients, v = 0): every division, square root, product and sum of the step,
+    with overflow and gradual underflow, has to round as IEEE binary32 on both sides."""
+    gfmt, rfmt = FMT[fmt]
+    rng = np.random.default_rng(303)
+    n = 3 * CHUNK + 777
+    say("arbitrary bit patterns fmt=%s kind=%s kw=%s" % (fmt, kind, kw))
+    lib_cfg, ref_cfg = cfg_pair(kind, fmt, **kw)
+    d = DevTensor(np.zeros(n, np.float32), gfmt, with_v=(kind == "adam"))
+    h = HostTensor(np.zeros(n, np.float32), rfmt, with_v=(kind == "adam"))
+    # finite weights of every magnitude: any 16-bit pattern whose exponent field is not all ones
+    hi = rng.integers(0, 1 << 16, n).astype(np.uint16)
+    expo = (hi >> 7) & 0xFF if fmt == "bf16" else (hi >> 10) & 0x1F
+    hi[expo == (0xFF if fmt == "bf16" else 0x1F)] &= 0x8000
+    res = rng.integers(0, 1 << (16 if fmt == "bf16" else 13), n).astype(np.uint16)
+    m = rng.integers(0, 1 << 32, n, dtype=np.uint64).astype(np.uint32)
+    m[(m >> 23) & 0xFF == 0xFF] &= 0x807FFFFF                      # finite first moments, denormals included
+    v = rng.integers(0, 1 << 31, n, dtype=np.uint64).astype(np.uint32)   # non-negative second moments
+    v[(v >> 23) & 0xFF == 0xFF] &= 0x007FFFFF
+    v[:64] = 0
+    g = rng.integers(0, 1 << 16, n).astype(np.uint16)              # every kind of gradient, inf and NaN too
+    h.hi[:], h.res[:], h.m[:] = hi, res, m.view(np.float32)
+    d.hi.copy_(dev_u16(hi)); d.res.copy_(dev_u16(res)); d.m.copy_(dev_f32(m.view(np.float32))); d.grad.copy_(dev_u16(g))
+    if kind == "adam":
+        h.v[:] = v.view(np.float32)
+        d.v.copy_(dev_f32(v.view(np.float32)))
+    plan = mpo.Plan([d.spec()])
+    for t in (1, 2):
+        if kind == "adam":
+            mpo.mpo_adam_step(plan, lib_cfg, t)
+            ref.adam_step(h.hi, h.res, g, h.m, h.v, ref_cfg, t)
+        else:
+            mpo.mpo_sgd_step(plan, lib_cfg, t)
+            ref.sgd_step(h.hi, h.res, g, h.m, ref_cfg, t)
+        torch.cuda.synchronize()
+        want_w = ref.merge(h.hi, h.res, rfmt)
+        got_w = ref.merge(host_u16(d.hi), host_u16(d.res), rfmt)
+        _same_or_both_nan(got_w, want_w, "step %d weights" % t)
+        ok = ~np.isnan(want_w)
+        assert np.array_equal(host_u16(d.hi)[ok], h.hi[ok]) and np.array_equal(host_u16(d.res)[ok], h.res[ok])
+        _same_or_both_nan(host_f32(d.m), h.m, "step %d m" % t)
+        if kind == "adam":
+            _same_or_both_nan(host_f32(d.v), h.v, "step %d v" % t)
+        # continue from the oracle's state, so that the second step also starts from identical bits
+        d.hi.copy_(dev_u16(h.hi)); d.res.copy_(dev_u16(h.res)); d.m.copy_(dev_f32(h.m))
+        if kind == "adam":
+            d.v.copy_(dev_f32(h.v))
+    plan.destroy()
+
+
 def test_all_fp16_gradient_patterns_convert_exactly():
     """After one momentum step from a zero buffer the buffer equals the gradient: every finite
     fp16 and bf16 pattern must come out as the library cast reads it."""
