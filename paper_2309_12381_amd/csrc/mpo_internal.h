@@ -73,7 +73,7 @@ enum ResMode {
     kResFull = 0,    /* uint16_t, every extra bit kept: no shifting                  */
     kResPartial = 1, /* uint16_t, some tensor keeps fewer bits: shift per descriptor  */
     kResByte = 2,    /* uint8_t (1..8 bits kept)                                      */
-    kResPlanes = 3   /* packed bit planes of 8, 4 and 2 bits (even E, Figure 1)        */
+    kResPlanes = 3   /* packed bit planes of 8, 4, 2 and 1 bits (Figure 1)             */
 };
 
 inline uint64_t round16(uint64_t x) { return (x + 15u) / 16u * 16u; }
