@@ -133,6 +133,10 @@ mpo_status mpo_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n
  * residual storage, else MPO_ERR_UNSUPPORTED.
  * Gradient buffers may overlap each other (one reused buffer for all layers);
  * nothing may overlap hi, res, m or v.
+ * Alignment: arrays that are all 16-byte aligned take the vector path (any
+ * alignment gives the same results, more slowly).  For full speed start every
+ * array on a 128-byte boundary: rows of a tensor that starts inside a memory
+ * line straddle lines, which costs about 14 % on lists of many small tensors.
  */
 typedef struct {
     uint16_t *hi;

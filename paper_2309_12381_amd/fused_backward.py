@@ -61,7 +61,7 @@ class FusedBackwardOptimizer:
         offs, total = [], 0
         for p in self.params:
             offs.append(total)
-            total += _round_up(p.numel(), 8)
+            total += _round_up(p.numel(), 64)       # every parameter's state starts on a 128-byte line
         if res_packed:
             # one byte buffer; each parameter's planes start at a multiple of 16 bytes
             self.res_offs, fill = [], 0
