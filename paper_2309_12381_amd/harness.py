@@ -5,7 +5,7 @@ step of the method is a call into the library.  Shared by bench.py, the smoke
 check and the full-size GPU tests.
 """
 from dataclasses import dataclass
-from typing import Dict, List, Optional
+from typing import Dict, List
 
 import torch
 

@@ -10,7 +10,7 @@ from paper_2309_12381_amd.fused_backward import FusedBackwardOptimizer
 from paper_2309_12381_amd import synth
 from oracle import ref
 
-from gpu_util import DEV, FMT, ROUND, host_f32, host_res, host_u16, say
+from gpu_util import DEV, FMT, host_f32, host_res, say
 
 pytestmark = pytest.mark.gpu
 

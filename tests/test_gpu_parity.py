@@ -15,7 +15,7 @@ import paper_2309_12381_amd as mpo
 from paper_2309_12381_amd import synth
 from oracle import ref
 
-from gpu_util import (DEV, FMT, ROUND, DevTensor, HostTensor, assert_state_equal, cfg_pair, dev_f32, dev_res, dev_u16,
+from gpu_util import (DEV, FMT, ROUND, DevTensor, HostTensor, assert_state_equal, cfg_pair, dev_f32, dev_u16,
                       host_f32, host_res, host_u16, parallel_slices, ref_adam, ref_sgd, ref_split, res_torch_dtype, say)
 
 pytestmark = pytest.mark.gpu

@@ -15,7 +15,7 @@ import paper_2309_12381_amd as mpo
 from paper_2309_12381_amd import harness, synth
 from oracle import ref
 
-from gpu_util import DEV, FMT, parallel_slices, ref_adam, ref_split, say
+from gpu_util import DEV, ref_adam, ref_split, say
 
 pytestmark = pytest.mark.gpu
 

@@ -9,7 +9,6 @@ into a scratch library on the CPU, and checks that at least one pin from
 test_oracle_split.py / test_oracle_steps.py fails on it, while all of them
 pass on the untouched source built the same way.
 """
-import os
 import subprocess
 
 import pytest

@@ -15,7 +15,6 @@ What pins them:
 `pins_*` take the oracle as argument (tests/test_oracle_pins_bite.py runs them on broken builds).
 """
 import numpy as np
-import pytest
 import torch
 
 from test_oracle_steps import bf16_to_f32, fp16_to_f32, make_state, to_bf16_bits, to_fp16_bits
