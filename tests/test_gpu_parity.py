@@ -5,8 +5,6 @@ split, merge and SGD bit-exact; Adam: stored weights within 1 fp32 ulp of the or
 m and v within 1e-6 relative.  Both sides do one IEEE binary32 operation at a time in the
 same order, so these tests hold the stronger bar: every output bit-identical.
 """
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -78,8 +76,8 @@ def _structured_patterns():
 @pytest.mark.parametrize("fmt", ["bf16", "fp16"])
 def test_split_merge_structured_and_random_patterns(fmt):
     """2^25 structured plus 2^25 random fp32 patterns through mpo_split and back through
-    mpo_merge, against the oracle (which is itself checked on all 2^32 patterns on the CPU).
-    MPO_EXHAUSTIVE=1 runs all 2^32 patterns on the GPU as well."""
+    mpo_merge, against the oracle (which is itself checked on all 2^32 patterns on the CPU);
+    the next test runs all 2^32 patterns on the GPU as well."""
     gfmt, rfmt = FMT[fmt]
     rng = np.random.default_rng(2)
     pats = np.concatenate([_structured_patterns(),
@@ -100,10 +98,10 @@ def test_split_merge_structured_and_random_patterns(fmt):
     assert np.array_equal(host_f32(back).view(np.uint32), want.view(np.uint32))
 
 
-@pytest.mark.skipif(os.environ.get("MPO_EXHAUSTIVE") != "1", reason="set MPO_EXHAUSTIVE=1 (several minutes)")
 @pytest.mark.parametrize("fmt", ["bf16", "fp16"])
 def test_split_merge_every_fp32_pattern(fmt):
-    """All 2^32 fp32 patterns through mpo_split and back through mpo_merge, against the oracle."""
+    """All 2^32 fp32 patterns through mpo_split and back through mpo_merge, against the oracle
+    (about 20 s per format, most of it the oracle on the host)."""
     gfmt, rfmt = FMT[fmt]
     n = 1 << 26
     w = torch.empty(n, dtype=torch.int32, device=DEV)
