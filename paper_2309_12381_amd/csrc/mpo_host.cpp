@@ -45,8 +45,6 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 /* Section 3.1, partial extra bits: at most 8 kept bits live in a byte, more in 16 bits. */
 inline uint32_t res_slot_bytes(int res_bits) { return (res_bits >= 1 && res_bits <= 8) ? 1u : 2u; }
 
-/* 0 means all; otherwise 1..full for the format.  Stochastic rounding stores one flag above
- * the kept bits: they must leave room for it in the slot. */
 /* Packed planes: 1 to 15 stored bits per value (Figure 1 of the paper has 12). */
 inline bool valid_packed_bits(int res_bits) { return res_bits >= 1 && res_bits <= 15; }
 
@@ -60,6 +58,8 @@ inline bool valid_packed_mode(int res_bits, int fmt, int round)
 /* Kind of residual storage: 1 = bytes, 2 = 16-bit slots, 3 = packed planes. */
 inline uint32_t res_kind(int res_bits, int packed) { return packed ? 3u : res_slot_bytes(res_bits); }
 
+/* Slots: 0 means all; otherwise 1..full for the format.  Stochastic rounding stores one flag
+ * above the kept bits: they must leave room for it in the slot. */
 inline bool valid_res_bits(int res_bits, int fmt, int round)
 {
     if (res_bits < 0 || res_bits > full_res_bits(fmt)) return false;
