@@ -129,6 +129,73 @@ def traffic_probe(st, stream, with_v, bpp, steps):
                     "%d steps after the timed region" % (len(spans), steps)}
 
 
+def fused_backward_run(a):
+    """Section 3.2 on a real PyTorch backward: a stack of residual MLP blocks (bf16, synthetic data)
+    trained with the split-precision Adam step, once with the step fused into backward (each
+    parameter stepped in its post-accumulate-grad hook, gradient freed there) and once with the
+    classical schedule (all gradients kept, stepped after backward).  Prints one JSON line with
+    the time per iteration and the peak device memory of both."""
+    import torch
+    import paper_2309_12381_amd as mpo
+    from paper_2309_12381_amd.fused_backward import FusedBackwardOptimizer
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    d, depth, tokens = a.width, a.depth, a.tokens
+
+    class Block(torch.nn.Module):
+        def __init__(self):
+            super().__init__()
+            self.norm = torch.nn.LayerNorm(d)
+            self.up = torch.nn.Linear(d, 4 * d, bias=False)
+            self.down = torch.nn.Linear(4 * d, d, bias=False)
+
+        def forward(self, x):
+            return x + self.down(torch.nn.functional.gelu(self.up(self.norm(x))))
+
+    def run(fused):
+        torch.manual_seed(0)
+        model = torch.nn.Sequential(*[Block() for _ in range(depth)]).to(dev).to(torch.bfloat16)
+        params = sum(p.numel() for p in model.parameters())
+        opt = FusedBackwardOptimizer(model.parameters(), mpo.AdamCfg(lr=1e-4, weight_decay=0.01), fused=fused)
+        x = torch.randn(tokens, d, device=dev, dtype=torch.bfloat16)
+        y = torch.randn(tokens, d, device=dev, dtype=torch.bfloat16)
+
+        def iteration():
+            opt.start_step()
+            loss = torch.nn.functional.mse_loss(model(x).float(), y.float())
+            loss.backward()
+            if not fused:
+                opt.step()
+        for _ in range(a.warmup):
+            iteration()
+        torch.cuda.synchronize()
+        resident = torch.cuda.memory_allocated()
+        torch.cuda.reset_peak_memory_stats()
+        steps = a.steps or 5
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            iteration()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        peak = torch.cuda.max_memory_allocated()
+        opt.close()
+        del model, opt, x, y
+        torch.cuda.empty_cache()
+        return {"ms_per_iteration": dt * 1e3, "peak_GB": peak / 1e9, "resident_GB": resident / 1e9}, params
+
+    fused, params = run(True)
+    classical, _ = run(False)
+    print(json.dumps({
+        "metric": "training iteration with the split-precision Adam step fused into backward vs stepped after it",
+        "n_gpus": 1, "data": "synthetic", "dtype": "bf16 forward/backward, f32 update",
+        "config": {"workload": "%d residual MLP blocks of width %d (%.2f B parameters), %d tokens per iteration"
+                               % (depth, d, params / 1e9, tokens), "optimizer": "adamw"},
+        "fused": fused, "classical": classical,
+        "gradient_bytes_GB": params * 2 / 1e9,
+        "peak_saved_GB": classical["peak_GB"] - fused["peak_GB"],
+    }), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -150,6 +217,12 @@ def main():
     ap.add_argument("--no-place", action="store_true",
                     help="allocate the state arrays one after the other instead of dividing them between two "
                          "HBM regions (paper_2309_12381_amd/placement.py)")
+    ap.add_argument("--fused-backward", action="store_true",
+                    help="instead of the optimizer-only benchmark: a real PyTorch backward with the step fused into "
+                         "it (Section 3.2) against the classical schedule; see --width, --depth, --tokens")
+    ap.add_argument("--width", type=int, default=4096)
+    ap.add_argument("--depth", type=int, default=16)
+    ap.add_argument("--tokens", type=int, default=1024)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true", help="skip the per-layer breakdown step")
     ap.add_argument("--no-probe", action="store_true", help="skip the arithmetic-free traffic probe")
@@ -168,6 +241,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if a.fused_backward:
+        fused_backward_run(a)
+        return
     dev = "cuda:0"
     torch.cuda.set_device(0)
     wl = synth.workload(a.workload)
