@@ -272,6 +272,27 @@ def test_steps_on_arbitrary_bit_patterns(fmt, kind, kw):
     plan.destroy()
 
 
+@pytest.mark.parametrize("mode", ["trunc", "stochastic"])
+def test_step_numbers_far_apart(mode):
+    """The step number enters through the bias corrections (formed in double on the host) and, with
+    stochastic rounding, through the counter of the random stream (its low 32 bits)."""
+    rng = np.random.default_rng(404)
+    n = CHUNK + 100
+    w0 = synth.gen_weights(n, 77, "cpu", 0.02).numpy()
+    lib_cfg, ref_cfg = cfg_pair("adam", "bf16", lr=1e-3, weight_decay=0.01, decoupled_wd=True, round=mode, seed=12)
+    d = DevTensor(w0, mpo.MPO_BF16, round=mode, seed=12, tensor_id=0)
+    h = HostTensor(w0, ref.BF16, round=mode, seed=12, tensor_id=0)
+    plan = mpo.Plan([d.spec()])
+    for t in (1, 2, 3, 1000, 10 ** 6, 2 ** 32 - 1, 2 ** 32, 2 ** 32 + 5, 2 ** 40 + 1, 2 ** 63):
+        say("step number %d mode=%s" % (t, mode))
+        g = synth.bits16(synth.gen_grads(n, int(rng.integers(1 << 30)), "cpu", 1e-3, "bf16", 1.0))
+        d.grad.copy_(dev_u16(g))
+        mpo.mpo_adam_step(plan, lib_cfg, t)
+        ref.adam_step(h.hi, h.res, g, h.m, h.v, ref_cfg, t, tensor_id=0)
+        assert_state_equal(d, h, "step number %d" % t)
+    plan.destroy()
+
+
 def test_all_fp16_gradient_patterns_convert_exactly():
     """After one momentum step from a zero buffer the buffer equals the gradient: every finite
     fp16 and bf16 pattern must come out as the library cast reads it."""
