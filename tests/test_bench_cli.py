@@ -1,0 +1,49 @@
+"""bench.py's command line: what can be checked without a GPU, and the JSON line on one."""
+import json
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _run(*args, timeout=600):
+    return subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), *args], cwd=ROOT, capture_output=True,
+                          text=True, timeout=timeout)
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    out = _run("--gpus", "2")
+    assert out.returncode == 2 and "ONE GPU" in out.stderr and out.stdout == ""
+
+
+def test_without_a_gpu_it_fails_loudly():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    out = _run("--workload", "c0")
+    assert out.returncode == 1 and "no GPU" in out.stderr and out.stdout == ""
+
+
+@pytest.mark.gpu
+def test_json_line_on_the_small_workload():
+    """One JSON line with the fields the contract names, the roofline object and the CPU baseline."""
+    out = _run("--workload", "c0", "--steps", "3", "--warmup", "1", "--cpu-sample", str(1 << 20))
+    assert out.returncode == 0, out.stderr
+    lines = [l for l in out.stdout.split("\n") if l.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in d, key
+    assert d["unit"] == "params/s" and d["n_gpus"] == 1 and d["steps"] == 3 and d["warmup"] == 1
+    assert d["vs_baseline"] is None and d["data"] == "synthetic" and d["higher_is_better"] is True
+    assert d["config"]["workload"].startswith("c0") and "model" not in d["config"]
+    r = d["roofline"]
+    assert r["bound"] == "hbm" and r["peak"] == 8000.0 and r["unit"] == "GB/s"
+    assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-12 and r["achieved"] > 0
+    assert abs(d["value"] - d["config"]["params"] / (d["ms_per_step"] * 1e-3)) < 1e-6 * d["value"]
+    c = d["cpu_baseline"]
+    assert c["kind"] == "oracle" and c["unit"] == "params/s" and c["cores"] >= 1 and c["value"] > 0
