@@ -936,3 +936,65 @@ def test_multi_tensor_list_packed(kind, fmt, bits, mode, kw, misalign):
             mpo.mpo_adam_step(plan, mpo.AdamCfg(**wrong), 9) if kind == "adam" else mpo.mpo_sgd_step(plan, mpo.SgdCfg(**wrong), 9)
         assert e.value.status == mpo.MPO_ERR_INVALID_ARG
     plan.destroy()
+
+
+# ---- seeded random configurations: combinations no hand-written case above happens to use -------------
+
+def _random_case(rng):
+    kind = "adam" if rng.random() < 0.65 else "sgd"
+    fmt = "bf16" if rng.random() < 0.5 else "fp16"
+    gfmt = fmt if rng.random() < 0.7 else ("fp16" if fmt == "bf16" else "bf16")
+    full = 16 if fmt == "bf16" else 13
+    mode = ["trunc", "nearest", "stochastic"][int(rng.integers(3))]
+    packed = bool(rng.random() < 0.4)
+    flag = 1 if mode == "stochastic" else 0
+    if packed:
+        bits = int(rng.integers(1 + flag, min(15, full + flag) + 1))          # stored bits
+    else:
+        choices = [0] + list(range(1, 8 - flag + 1)) + list(range(9, min(full, 16 - flag) + 1))
+        bits = int(choices[int(rng.integers(len(choices)))])
+    kw = dict(lr=float(10.0 ** rng.uniform(-5, -1)), loss_scale=float(2.0 ** int(rng.integers(0, 12))))
+    if rng.random() < 0.4:
+        kw["grad_clip"] = float(10.0 ** rng.uniform(-4, -1))
+    if kind == "adam":
+        kw.update(beta1=float(rng.choice([0.0, 0.5, 0.9, 0.99])), beta2=float(rng.choice([0.0, 0.9, 0.999, 0.9999])),
+                  eps=float(10.0 ** rng.uniform(-12, -4)), weight_decay=float(rng.choice([0.0, 1e-4, 0.1])),
+                  decoupled_wd=bool(rng.random() < 0.5))
+    else:
+        kw.update(momentum=float(rng.choice([0.0, 0.5, 0.9])), weight_decay=float(rng.choice([0.0, 1e-4, 0.01])))
+    return kind, fmt, gfmt, mode, packed, bits, kw
+
+
+@pytest.mark.parametrize("case", range(48))
+def test_random_configurations(case):
+    rng = np.random.default_rng(9000 + case)
+    kind, fmt, gfmt, mode, packed, bits, kw = _random_case(rng)
+    misalign = int(rng.integers(0, 4)) if rng.random() < 0.4 else 0
+    sizes = [int(x) for x in rng.choice([1, 5, 64, 1000, CHUNK - 3, CHUNK, 2 * CHUNK + 9, 5 * CHUNK + 1], size=4)]
+    say("random configuration %d: %s w=%s g=%s mode=%s packed=%s bits=%d misalign=%d sizes=%s kw=%s"
+        % (case, kind, fmt, gfmt, mode, packed, bits, misalign, sizes, kw))
+    lib_cfg, ref_cfg = cfg_pair(kind, fmt, gfmt=gfmt, res_bits=bits, round=mode, seed=1000 + case, packed=packed, **kw)
+    devs, hosts = [], []
+    for i, n in enumerate(sizes):
+        w0 = synth.gen_weights(n, synth.seed_for(61, case, i), "cpu", 0.02).numpy()
+        devs.append(DevTensor(w0, FMT[fmt][0], with_v=(kind == "adam"), layer=i % 2, misalign=misalign, res_bits=bits,
+                              round=mode, seed=1000 + case, tensor_id=i, packed=packed))
+        hosts.append(HostTensor(w0, FMT[fmt][1], with_v=(kind == "adam"), res_bits=bits, round=mode, seed=1000 + case,
+                                tensor_id=i, packed=packed))
+    plan = mpo.Plan([d.spec() for d in devs])
+    for t in (1, 2, 3):
+        for i, (d, h) in enumerate(zip(devs, hosts)):
+            g = synth.bits16(synth.gen_grads(d.n, synth.seed_for(67, case, i, t), "cpu", 1e-3, gfmt, kw["loss_scale"]))
+            d.grad.copy_(dev_u16(g))
+            if kind == "adam":
+                ref.adam_step(h.hi, h.res, g, h.m, h.v, ref_cfg, t, tensor_id=i)
+            else:
+                ref.sgd_step(h.hi, h.res, g, h.m, ref_cfg, t, tensor_id=i)
+        if t == 2:
+            for ly in (1, 0):
+                mpo.mpo_step_layer(plan, ly, lib_cfg, t)
+        else:
+            (mpo.mpo_adam_step if kind == "adam" else mpo.mpo_sgd_step)(plan, lib_cfg, t)
+        for i, (d, h) in enumerate(zip(devs, hosts)):
+            assert_state_equal(d, h, "case %d tensor %d step %d" % (case, i, t))
+    plan.destroy()
