@@ -163,7 +163,8 @@ class Oracle:
 
     def split(self, w32, fmt=BF16, res_bits=0, round=TRUNC, seed=0, tensor_id=0, packed=False):
         """fp32 array -> (hi uint16, res) arrays; res is uint16 or uint8 per value, or with
-        packed=True the bit planes as one uint8 array."""
+        packed=True the bit planes as one uint8 array (res_bits then counts the bits stored per
+        value: with STOCHASTIC the leading one is the flag)."""
         _chk(w32, np.float32)
         n = w32.shape[0]
         hi = np.empty(n, np.uint16)
