@@ -33,7 +33,7 @@ extern "C" {
 
 enum { MPO_REF_BF16 = 0, MPO_REF_FP16 = 1 };
 
-/* Section 3.1 also keeps "only part of those bits": res_bits = E keeps the E
+/* Section 3.1 also allows keeping only some of those bits: res_bits = E keeps the E
  * leading bits of the dropped significand bits (E = 8 is the paper's fp16+8 /
  * bf16+8).  0 means all of them (16 for bf16, 13 for fp16).  The residual array
  * has one uint8_t per element when 1 <= E <= 8, else one uint16_t; the E bits
@@ -102,10 +102,10 @@ void mpo_ref_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fm
 void mpo_ref_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits, int res_packed,
                    int round);
 
-/* Section 3.1 "classic optimizers": bias-corrected Adam / AdamW on one tensor. */
+/* Section 3.1 (the usual optimizers): bias-corrected Adam / AdamW on one tensor. */
 void mpo_ref_adam_step(uint16_t *hi, void *res, const uint16_t *grad, float *m, float *v,
                        uint64_t n, const mpo_ref_adam_cfg *cfg, uint64_t step, uint32_t tensor_id);
-/* Section 3.1 "classic optimizers": SGD with momentum (dampening 0, no Nesterov).
+/* Section 3.1 (the usual optimizers): SGD with momentum (dampening 0, no Nesterov).
  * momentum == 0 leaves buf untouched (it may then be NULL). */
 void mpo_ref_sgd_step(uint16_t *hi, void *res, const uint16_t *grad, float *buf,
                       uint64_t n, const mpo_ref_sgd_cfg *cfg, uint64_t step, uint32_t tensor_id);

@@ -240,7 +240,7 @@ def test_cvt16_matches_library_cast(ref, fmt):
         assert ref.cvt16(p, f) == float(lib[p])
 
 
-# ---- keeping only E of the extra bits (Section 3.1: "keeping only part of those bits") ----
+# ---- keeping only E of the extra bits (Section 3.1 allows keeping only some of them) ----
 
 FULL = {"bf16": 16, "fp16": 13}
 

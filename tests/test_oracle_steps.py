@@ -5,7 +5,7 @@ as an fp32 training; Section 4.1: gradient scaling happens inside the step).
 Pins used, each against something other than the oracle itself:
   * torch.optim.Adam / AdamW / SGD on fp32 master weights (library routine);
   * an ordinary fp32-master optimizer whose 16-bit copy is the truncation of
-    the master (Section 3.1: "as precise as fp32"), in numpy float32;
+    the master (Section 3.1: the stored value is as precise as in fp32 training), in numpy float32;
   * an exact-rational model of binary32 arithmetic (tests/exact_fp32.py);
   * closed forms in real arithmetic: first Adam step, constant-gradient Adam,
     momentum as a geometric series, decay-only steps;
