@@ -274,36 +274,36 @@ __device__ __forceinline__ ResRef res_ref(void *base, uint64_t n, uint64_t off, 
     return R;
 }
 
-template <int NBYTES> __device__ __forceinline__ uint64_t ld_bytes(const MPO_GLOBAL uint8_t *p)
+/* 1, 2 or 4 bytes of a plane: everything a lane owns of one plane fits a dword */
+template <int NBYTES> __device__ __forceinline__ uint32_t ld_bytes(const MPO_GLOBAL uint8_t *p)
 {
+    static_assert(NBYTES == 1 || NBYTES == 2 || NBYTES == 4, "a lane owns 4, 2 or 1 bytes of a plane");
     if (NBYTES == 1) return *p;
     if (NBYTES == 2) return *reinterpret_cast<const MPO_GLOBAL uint16_t *>(p);
-    if (NBYTES == 4) return *reinterpret_cast<const MPO_GLOBAL uint32_t *>(p);
-    return *reinterpret_cast<const MPO_GLOBAL uint64_t *>(p);
+    return *reinterpret_cast<const MPO_GLOBAL uint32_t *>(p);
 }
-template <int NBYTES> __device__ __forceinline__ void st_bytes(MPO_GLOBAL uint8_t *p, uint64_t x)
+template <int NBYTES> __device__ __forceinline__ void st_bytes(MPO_GLOBAL uint8_t *p, uint32_t x)
 {
     if (NBYTES == 1) *p = (uint8_t)x;
     else if (NBYTES == 2) *reinterpret_cast<MPO_GLOBAL uint16_t *>(p) = (uint16_t)x;
-    else if (NBYTES == 4) *reinterpret_cast<MPO_GLOBAL uint32_t *>(p) = (uint32_t)x;
-    else *reinterpret_cast<MPO_GLOBAL uint64_t *>(p) = x;
+    else *reinterpret_cast<MPO_GLOBAL uint32_t *>(p) = x;
 }
 
 /* The EPL values that start at chunk-local parameter e (a multiple of EPL): the 8-, 4- and
  * 2-bit planes plus `ones`, their EPL bits of the 1-bit plane -> 16-bit pairs. */
 __device__ __forceinline__ void planes_unpack(const ResRef &R, uint32_t e, uint32_t ones, uint32_t (&r)[EPL / 2])
 {
-    const uint64_t b8 = (R.S & 8u) ? ld_bytes<EPL>(R.p8 + e) : 0u;
-    const uint64_t b4 = (R.S & 4u) ? ld_bytes<EPL / 2>(R.p4 + e / 2) : 0u;
-    const uint64_t b2 = (R.S & 2u) ? ld_bytes<EPL / 4>(R.p2 + e / 4) : 0u;
+    const uint32_t b8 = (R.S & 8u) ? ld_bytes<EPL>(R.p8 + e) : 0u;
+    const uint32_t b4 = (R.S & 4u) ? ld_bytes<EPL / 2>(R.p4 + e / 2) : 0u;
+    const uint32_t b2 = (R.S & 2u) ? ld_bytes<EPL / 4>(R.p2 + e / 4) : 0u;
 #pragma unroll
     for (int j = 0; j < EPL / 2; ++j) r[j] = 0u;
 #pragma unroll
     for (int k = 0; k < EPL; ++k) {
         uint32_t x = 0u;
-        if (R.S & 8u) x = (uint32_t)(b8 >> (8 * k)) & 0xFFu;
-        if (R.S & 4u) x = (x << 4) | ((uint32_t)(b4 >> (4 * k)) & 0xFu);
-        if (R.S & 2u) x = (x << 2) | ((uint32_t)(b2 >> (2 * k)) & 0x3u);
+        if (R.S & 8u) x = (b8 >> (8 * k)) & 0xFFu;
+        if (R.S & 4u) x = (x << 4) | ((b4 >> (4 * k)) & 0xFu);
+        if (R.S & 2u) x = (x << 2) | ((b2 >> (2 * k)) & 0x3u);
         if (R.S & 1u) x = (x << 1) | ((ones >> k) & 1u);
         r[k / 2] |= x << (16 * (k & 1));
     }
@@ -313,15 +313,14 @@ __device__ __forceinline__ void planes_unpack(const ResRef &R, uint32_t e, uint3
  * bits of the 1-bit plane. */
 __device__ __forceinline__ uint32_t planes_pack(const ResRef &R, uint32_t e, const uint32_t (&r)[EPL / 2])
 {
-    uint64_t b8 = 0u, b4 = 0u, b2 = 0u;
-    uint32_t ones = 0u;
+    uint32_t b8 = 0u, b4 = 0u, b2 = 0u, ones = 0u;
 #pragma unroll
     for (int k = 0; k < EPL; ++k) {
         const uint32_t x = (r[k / 2] >> (16 * (k & 1))) & 0xFFFFu;
         uint32_t left = R.S;
-        if (R.S & 8u) { left -= 8u; b8 |= (uint64_t)((x >> left) & 0xFFu) << (8 * k); }
-        if (R.S & 4u) { left -= 4u; b4 |= (uint64_t)((x >> left) & 0xFu) << (4 * k); }
-        if (R.S & 2u) { left -= 2u; b2 |= (uint64_t)((x >> left) & 0x3u) << (2 * k); }
+        if (R.S & 8u) { left -= 8u; b8 |= ((x >> left) & 0xFFu) << (8 * k); }
+        if (R.S & 4u) { left -= 4u; b4 |= ((x >> left) & 0xFu) << (4 * k); }
+        if (R.S & 2u) { left -= 2u; b2 |= ((x >> left) & 0x3u) << (2 * k); }
         if (R.S & 1u) ones |= (x & 1u) << k;
     }
     if (R.S & 8u) st_bytes<EPL>(R.p8 + e, b8);
