@@ -226,7 +226,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true", help="skip the per-layer breakdown step")
     ap.add_argument("--no-probe", action="store_true", help="skip the arithmetic-free traffic probe")
-    ap.add_argument("--cpu-sample", type=int, default=1 << 27)
+    ap.add_argument("--cpu-sample", type=int, default=202_383_360,
+                    help="parameters of the CPU baseline's sample (default: one transformer layer of the 7B-shaped set)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise kernel that reads 1 GiB and writes 1 GiB (known traffic, "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -336,7 +337,7 @@ def main():
         torch.cuda.synchronize()
         res["calibration"] = "3 x torch.add(src, 1.0, out=dst) on 2^28 fp32: 1 GiB read + 1 GiB written each"
     if not a.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(wl, a.cpu_sample, 8)
+        res["cpu_baseline"] = cpu_baseline(wl, a.cpu_sample, 5)
     print(json.dumps(res), flush=True)
 
 
