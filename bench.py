@@ -62,7 +62,7 @@ def cpu_baseline(wl, sample_params: int, steps: int):
             dt = time.perf_counter() - t0
         out[label] = n * steps / dt
     return {"value": out["all"], "unit": "params/s", "cores": cores, "kind": "oracle",
-            "value_1core": out["1"],
+            "value_1core": out["1"], "host_GBps": out["all"] * ADAM_BYTES_PER_PARAM / 1e9,
             "sample": "%d params of the same value distributions, %d Adam steps, oracle/mpo_ref.c as built for "
                       "the tests, slice-parallel over %d host threads" % (n, steps, cores)}
 
