@@ -248,8 +248,9 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     wl = synth.workload(a.workload)
-    # default: at least 20 steps (the configurations ask for 3-5; more steps only average the same step)
-    steps = a.steps if a.steps is not None else max(wl.steps, 20 if wl.per_layer else wl.steps)
+    # default: 100 steps for the per-layer sets (the configurations ask for 3-5; more steps only average the
+    # same step, and a few seconds of sustained work read 0.5 % higher than half a second)
+    steps = a.steps if a.steps is not None else max(wl.steps, 100 if wl.per_layer else wl.steps)
     props = torch.cuda.get_device_properties(0)
     t_setup = time.perf_counter()
     st = harness.ModelState(wl, dev, res_bits=a.res_bits, res_packed=a.res_packed,
