@@ -181,3 +181,55 @@ def test_c4_llama13b_fp16_per_layer_sampled():
         pytest.skip("needs about 160 GB of device memory")
     checked, wl = _run_and_compare("c4", 1, _blocks_sampler(whole_every=131))
     assert wl.num_params == 13_015_864_320 and checked > 40_000_000
+
+
+def test_one_tensor_longer_than_2_to_32():
+    """Element offsets beyond 32 bits: one tensor of 2^32 + 3 chunks + 5 parameters (60 GB of state)
+    through split, two Adam steps and merge; blocks at the start, across the 2^32 boundary, at the
+    ragged end and at random places are replayed by the oracle."""
+    torch.cuda.empty_cache()
+    free, total = torch.cuda.mem_get_info()
+    if free < 100e9:
+        pytest.skip("needs about 80 GB of device memory")
+    n = (1 << 32) + 3 * BLOCK + 5
+    say("one tensor of %d parameters" % n)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(11)
+    w = torch.empty(n, dtype=torch.float32, device=DEV)
+    w.normal_(0.0, 0.02, generator=g)
+    hi = torch.empty(n, dtype=torch.int16, device=DEV)
+    res = torch.empty(n, dtype=torch.int16, device=DEV)
+    m = torch.zeros(n, dtype=torch.float32, device=DEV)
+    v = torch.zeros(n, dtype=torch.float32, device=DEV)
+    grad = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    rng = np.random.default_rng(12)
+    spans = [(0, 2 * BLOCK), ((1 << 32) - 2 * BLOCK, (1 << 32) + 2 * BLOCK), (n - BLOCK - 9, n)]
+    spans += [(int(b) * BLOCK, int(b) * BLOCK + BLOCK) for b in rng.integers(0, n // BLOCK, size=12)]
+    host = []
+    for lo, up in spans:
+        h, r = ref.split(np.ascontiguousarray(w[lo:up].cpu().numpy()), ref.BF16)
+        host.append([h, r, np.zeros(up - lo, np.float32), np.zeros(up - lo, np.float32)])
+    mpo.mpo_split(w, hi, res, n, fmt=mpo.MPO_BF16)
+    del w
+    plan = mpo.Plan([mpo.Tensor(hi, res, grad, m, v, n, 0)])
+    assert plan.num_params == n and plan.num_chunks == (n + BLOCK - 1) // BLOCK
+    cfg = mpo.AdamCfg(lr=1e-3, weight_decay=0.01)
+    rcfg = ref.AdamCfg(lr=1e-3, weight_decay=0.01)
+    for t in (1, 2):
+        grad.normal_(0.0, 1e-3, generator=g)
+        for (lo, up), h in zip(spans, host):
+            ref.adam_step(h[0], h[1], synth.bits16(grad[lo:up]), h[2], h[3], rcfg, t)
+        if t == 1:
+            mpo.mpo_adam_step(plan, cfg, t)
+        else:
+            mpo.mpo_step_layer(plan, 0, cfg, t)
+    out = torch.empty(n, dtype=torch.float32, device=DEV)
+    mpo.mpo_merge(hi, res, out, n, fmt=mpo.MPO_BF16)
+    torch.cuda.synchronize()
+    for (lo, up), h in zip(spans, host):
+        what = "parameters [%d, %d)" % (lo, up)
+        assert np.array_equal(synth.bits16(hi[lo:up]), h[0]) and np.array_equal(synth.bits16(res[lo:up]), h[1]), what
+        assert np.array_equal(m[lo:up].cpu().numpy().view(np.uint32), h[2].view(np.uint32)), what + ": m"
+        assert np.array_equal(v[lo:up].cpu().numpy().view(np.uint32), h[3].view(np.uint32)), what + ": v"
+        assert np.array_equal(out[lo:up].cpu().numpy().view(np.uint32), ref.merge(h[0], h[1], ref.BF16).view(np.uint32)), what
+    plan.destroy()
