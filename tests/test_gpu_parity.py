@@ -938,6 +938,51 @@ def test_multi_tensor_list_packed(kind, fmt, bits, mode, kw, misalign):
     plan.destroy()
 
 
+def test_two_lists_stepped_concurrently_on_two_streams():
+    """The library keeps no state outside a plan: two plans stepped at the same time on two streams give
+    what each gives alone."""
+    n = 6 * CHUNK + 11
+    lib_cfg, ref_cfg = cfg_pair("adam", "bf16", lr=1e-3, weight_decay=0.01, decoupled_wd=True)
+    streams = [torch.cuda.Stream(device=DEV), torch.cuda.Stream(device=DEV)]
+    devs, hosts, plans = [], [], []
+    for k in range(2):
+        w0 = synth.gen_weights(n, 500 + k, "cpu", 0.02).numpy()
+        devs.append(DevTensor(w0, mpo.MPO_BF16))
+        hosts.append(HostTensor(w0, ref.BF16))
+        plans.append(mpo.Plan([devs[k].spec()]))
+    say("two plans on two streams")
+    torch.cuda.synchronize()
+    for t in range(1, 6):
+        for k in range(2):
+            g = synth.bits16(synth.gen_grads(n, synth.seed_for(71, k, t), "cpu", 1e-3, "bf16", 1.0))
+            devs[k].grad.copy_(dev_u16(g))
+            ref.adam_step(hosts[k].hi, hosts[k].res, g, hosts[k].m, hosts[k].v, ref_cfg, t)
+        torch.cuda.synchronize()
+        for k in range(2):
+            mpo.mpo_adam_step(plans[k], lib_cfg, t, stream=streams[k])
+        for s_ in streams:
+            s_.synchronize()
+    for k in range(2):
+        assert_state_equal(devs[k], hosts[k], "plan %d" % k)
+        plans[k].destroy()
+
+
+def test_plans_give_their_device_memory_back():
+    """mpo_plan_create allocates the chunk table and the descriptors; mpo_plan_destroy frees them."""
+    n = 64 * CHUNK
+    d = DevTensor(np.zeros(n, np.float32), mpo.MPO_BF16)
+    torch.cuda.synchronize()
+    mpo.Plan([d.spec()]).destroy()                      # whatever the runtime sets up on first use
+    free0, _ = torch.cuda.mem_get_info()
+    for _ in range(200):
+        mpo.Plan([d.spec()] ).destroy()
+    kept = [mpo.Plan([d.spec()]) for _ in range(8)]
+    for p in kept:
+        p.destroy()
+    free1, _ = torch.cuda.mem_get_info()
+    assert free0 - free1 < (8 << 20)
+
+
 # ---- seeded random configurations: combinations no hand-written case above happens to use -------------
 
 def _random_case(rng):
