@@ -233,3 +233,46 @@ def test_one_tensor_longer_than_2_to_32():
         assert np.array_equal(v[lo:up].cpu().numpy().view(np.uint32), h[3].view(np.uint32)), what + ": v"
         assert np.array_equal(out[lo:up].cpu().numpy().view(np.uint32), ref.merge(h[0], h[1], ref.BF16).view(np.uint32)), what
     plan.destroy()
+
+
+def test_stochastic_split_beyond_2_to_34_elements():
+    """The random stream is indexed by (element / 4) as a 64-bit counter: with more than 2^34 elements
+    its high word is in use.  Sampled elements are rebuilt from the oracle's own pieces: the truncated
+    pair of the value, and the Philox block of the element's counter."""
+    torch.cuda.empty_cache()
+    free, total = torch.cuda.mem_get_info()
+    if free < 230e9:
+        pytest.skip("needs about 210 GB of device memory")
+    n = (1 << 34) + BLOCK + 3
+    seed, tid = 0x1234_5678_9ABC, 5
+    say("stochastic split of %d parameters" % n)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(13)
+    w = torch.empty(n, dtype=torch.float32, device=DEV)
+    w.normal_(0.0, 0.02, generator=g)
+    hi = torch.empty(n, dtype=torch.int16, device=DEV)
+    res = torch.empty(n, dtype=torch.int16, device=DEV)
+    mpo.mpo_split(w, hi, res, n, fmt=mpo.MPO_BF16, round=mpo.MPO_ROUND_STOCHASTIC, seed=seed, tensor_id=tid)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(14)
+    idx = np.concatenate([np.arange(0, 8), np.arange((1 << 34) - 8, (1 << 34) + 8), np.arange(n - 8, n),
+                          rng.integers(1 << 34, n, size=200), rng.integers(0, n, size=200)]).astype(np.int64)
+    ti = torch.from_numpy(idx).to(DEV)
+    x = w[ti].cpu().numpy()
+    got_hi, got_res = synth.bits16(hi[ti]), synth.bits16(res[ti])
+    t_hi, t_res = ref.split(np.ascontiguousarray(x), ref.BF16)              # truncation: hi and all 16 dropped bits
+    ups = 0
+    for k, i in enumerate(idx):
+        block = int(i) // 4
+        u = ref.philox([block & 0xFFFFFFFF, block >> 32, 0, tid], [seed & 0xFFFFFFFF, seed >> 32])[int(i) % 4] >> 16
+        up = int((int(t_hi[k]) & 0x7FFF) < 0x7F7F and u < int(t_res[k]))
+        ups += up
+        assert int(got_hi[k]) == (int(t_hi[k]) + up) & 0xFFFF, "element %d: hi" % i
+        assert int(got_res[k]) == (int(t_res[k]) >> 1) | (up << 15), "element %d: 15 kept bits and the flag" % i
+    assert 0.3 * idx.size < ups < 0.7 * idx.size                            # about half of them round up
+    out = torch.empty(n, dtype=torch.float32, device=DEV)
+    del ti
+    mpo.mpo_merge(hi, res, out, n, fmt=mpo.MPO_BF16, round=mpo.MPO_ROUND_STOCHASTIC)
+    # merge undoes the rounding: the value cut to 16 + 15 bits
+    w.view(torch.int32).bitwise_and_(-2)                                   # in place: no third 69 GB array
+    assert torch.equal(out.view(torch.int32), w.view(torch.int32))
