@@ -32,14 +32,22 @@ class FusedBackwardOptimizer:
     fused       True: step in the hook and free the gradient (Section 3.2).  False: keep gradients
                 and step them all in `step()`, the classical schedule, for comparison.
     observer    optional callable(index, grad) invoked just before a parameter is stepped.
+    overlap     run the steps on a stream of their own, so that a layer's (memory-bound) step runs
+                while backward computes the layers below it; each step waits for everything
+                backward had enqueued when its gradient arrived, and `start_step()` makes the
+                next forward wait for the last steps.  Results are the same; a gradient lives
+                until its step has run instead of until it is enqueued.  (Measured on MI355X with
+                2 B parameters: no gain, 22.8 against 23.0 ms per iteration; both the step and the
+                matrix products of backward fill every compute unit, so they take turns anyway.)
 
     Call `start_step()` before every backward: all parameters stepped during one backward share
-    the step count.
+    the step count.  With `overlap`, call `synchronize()` before reading parameters or state from
+    another stream than the one `start_step()` is called on.
     """
 
     def __init__(self, params: Iterable[torch.nn.Parameter], cfg, res_bits: int = 0,
                  init_fp32: Optional[Sequence[torch.Tensor]] = None, fused: bool = True,
-                 observer: Optional[Callable] = None, res_packed: bool = False):
+                 observer: Optional[Callable] = None, res_packed: bool = False, overlap: bool = False):
         self.params = [p for p in params if p.requires_grad]
         if not self.params:
             raise ValueError("no parameters")
@@ -57,6 +65,7 @@ class FusedBackwardOptimizer:
         self.fused = fused
         self.observer = observer
         self.step_no = 0
+        self.side = torch.cuda.Stream(device=self.params[0].device) if (overlap and fused) else None
         dev = self.params[0].device
         offs, total = [], 0
         for p in self.params:
@@ -94,7 +103,13 @@ class FusedBackwardOptimizer:
                 self._handles.append(p.register_post_accumulate_grad_hook(self._on_grad))
 
     def start_step(self):
+        self.synchronize()
         self.step_no += 1
+
+    def synchronize(self):
+        """Make the current stream wait for the steps enqueued so far (a no-op without `overlap`)."""
+        if self.side is not None:
+            torch.cuda.current_stream(self.params[0].device).wait_stream(self.side)
 
     def _step_param(self, i: int, p: torch.nn.Parameter):
         g = p.grad
@@ -104,7 +119,14 @@ class FusedBackwardOptimizer:
             g = g.contiguous()
         if self.observer is not None:
             self.observer(i, g)
-        mpo.mpo_step_layer(self.plan, i, self.cfg, self.step_no, grads=[g], stream=torch.cuda.current_stream(p.device))
+        stream = torch.cuda.current_stream(p.device)
+        if self.side is not None:
+            # after everything backward has enqueued so far (the kernels that read this weight and
+            # wrote this gradient among it), and keep the gradient's memory until the step has run
+            self.side.wait_stream(stream)
+            g.record_stream(self.side)
+            stream = self.side
+        mpo.mpo_step_layer(self.plan, i, self.cfg, self.step_no, grads=[g], stream=stream)
 
     def _on_grad(self, p: torch.nn.Parameter):
         if self.step_no == 0:
@@ -123,6 +145,7 @@ class FusedBackwardOptimizer:
 
     def master_fp32(self, i: int) -> torch.Tensor:
         """The fp32 value of parameter i held by (hi, res)."""
+        self.synchronize()
         p = self.params[i]
         out = torch.empty(p.numel(), dtype=torch.float32, device=p.device)
         mpo.mpo_merge(p.data, self.res[self.res_offs[i]:], out, p.numel(), fmt=_FMT[p.dtype], res_bits=self.res_bits,
@@ -130,11 +153,13 @@ class FusedBackwardOptimizer:
         return out.view_as(p)
 
     def state_of(self, i: int):
+        self.synchronize()
         n, off, roff = self.params[i].numel(), self.offs[i], self.res_offs[i]
         rlen = mpo.mpo_res_bytes(n, self.res_bits, True) if self.res_packed else n
         return self.res[roff:roff + rlen], self.m[off:off + n], (self.v[off:off + n] if self.is_adam else None)
 
     def close(self):
+        self.synchronize()
         for h in self._handles:
             h.remove()
         self._handles = []

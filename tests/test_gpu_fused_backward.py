@@ -30,9 +30,10 @@ def _model(dtype, width=384, depth=3, seed=0):
     (torch.float16, "adam", dict(lr=1e-3, loss_scale=256.0, grad_clip=0.01)),
     (torch.bfloat16, "sgd", dict(lr=1e-2, momentum=0.9, weight_decay=2e-4)),
 ], ids=["bf16-adamw", "bf16-adam-clip-stochastic", "fp16-adam-scaled-clip", "bf16-sgd"])
-@pytest.mark.parametrize("res_bits,packed", [(0, False), (7, False), (13, True), (6, True)],
-                         ids=["all", "7", "13-packed", "6-packed"])
-def test_hooks_step_every_parameter_and_match_the_oracle(dtype, kind, kw, res_bits, packed):
+@pytest.mark.parametrize("res_bits,packed,overlap", [(0, False, False), (7, False, False), (13, True, False),
+                                                     (6, True, False), (0, False, True), (13, True, True)],
+                         ids=["all", "7", "13-packed", "6-packed", "all-overlapped", "13-packed-overlapped"])
+def test_hooks_step_every_parameter_and_match_the_oracle(dtype, kind, kw, res_bits, packed, overlap):
     fmt = "bf16" if dtype == torch.bfloat16 else "fp16"
     say("fused backward dtype=%s kind=%s kw=%s res_bits=%d packed=%s" % (fmt, kind, kw, res_bits, packed))
     model = _model(dtype)
@@ -44,7 +45,7 @@ def test_hooks_step_every_parameter_and_match_the_oracle(dtype, kind, kw, res_bi
 
     def observer(i, g):
         seen.append((i, synth.bits16(g.reshape(-1))))
-    opt = FusedBackwardOptimizer(params, cfg, res_bits=res_bits, observer=observer, res_packed=packed)
+    opt = FusedBackwardOptimizer(params, cfg, res_bits=res_bits, observer=observer, res_packed=packed, overlap=overlap)
     scale = kw.get("loss_scale", 1.0)
     g = torch.Generator(device=DEV)
     g.manual_seed(5)
@@ -57,6 +58,7 @@ def test_hooks_step_every_parameter_and_match_the_oracle(dtype, kind, kw, res_bi
         seen.clear()
         loss = torch.nn.functional.mse_loss(model(x).float(), y.float()) * scale
         loss.backward()
+        opt.synchronize()
         torch.cuda.synchronize()
         assert all(p.grad is None for p in params), "a gradient outlived backward"
         assert sorted(i for i, _ in seen) == list(range(len(params))), "every parameter is stepped exactly once"
