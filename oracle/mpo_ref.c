@@ -7,6 +7,7 @@
 #include "mpo_ref.h"
 
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 
 /* ---- bit views ---------------------------------------------------------- */
@@ -136,6 +137,7 @@ typedef struct {
     int packed;    /* residual stored in bit planes (Figure 1)           */
     int stored;    /* packed: bits per value in the planes (E, plus the flag of STOCHASTIC) */
     uint64_t n;    /* number of values: fixes where each plane starts    */
+    uint64_t first; /* index, within its tensor, of element 0 of the arrays given */
     uint64_t seed;
     uint32_t tensor_id, step32;
 } res_layout;
@@ -194,11 +196,15 @@ uint64_t mpo_ref_res_bytes(uint64_t n, int fmt, int res_bits, int res_packed)
 }
 
 static res_layout make_layout(int fmt, int res_bits, int packed, uint64_t n, int round, uint64_t seed,
-                              uint32_t tensor_id, uint64_t step)
+                              uint32_t tensor_id, uint64_t step, uint64_t first_index)
 {
     res_layout L;
+    /* the planes of a packed residual start at places fixed by the tensor's length: a slice of
+     * such a tensor cannot be handled on its own */
+    if (packed && first_index != 0) abort();
     L.packed = packed;
     L.n = n;
+    L.first = first_index;
     L.fmt = fmt;
     L.round = round;
     L.full = fmt == MPO_REF_FP16 ? 13 : 16;
@@ -215,9 +221,14 @@ static res_layout make_layout(int fmt, int res_bits, int packed, uint64_t n, int
 
 static uint16_t max_finite_hi(int fmt) { return fmt == MPO_REF_FP16 ? 0x7BFFu : 0x7F7Fu; }
 
-/* Uniform integer in [0, 2^full) for element i of this tensor at this step. */
+/* A 16-bit pattern above that of infinity (sign aside) is a NaN. */
+static int is_nan16(uint16_t h, int fmt) { return (uint16_t)(h & 0x7FFFu) > (fmt == MPO_REF_FP16 ? 0x7C00u : 0x7F80u); }
+
+/* Uniform integer in [0, 2^full) for element i of the arrays at this step: the stream is
+ * indexed by the element's position in its tensor. */
 static uint32_t draw(const res_layout *L, uint64_t i)
 {
+    i += L->first;
     uint64_t block = i / 4;
     uint32_t counter[4] = { (uint32_t)block, (uint32_t)(block >> 32), L->step32, L->tensor_id };
     uint32_t key[2] = { (uint32_t)L->seed, (uint32_t)(L->seed >> 32) };
@@ -236,7 +247,8 @@ static void load_pair(const uint16_t *hi, const void *res, uint64_t i, const res
     uint16_t full = (uint16_t)(kept << (L->full - L->kept));
     int was_rounded_up = 0;
     if (L->round == MPO_REF_STOCHASTIC) was_rounded_up = (stored >> L->kept) & 1;
-    if (L->round == MPO_REF_NEAREST) was_rounded_up = (full >> (L->full - 1)) & 1;
+    /* NEAREST leaves NaN patterns alone (see store_pair), so there is nothing to undo on one */
+    if (L->round == MPO_REF_NEAREST) was_rounded_up = !is_nan16(hi[i], L->fmt) && ((full >> (L->full - 1)) & 1);
     *hi_trunc = (uint16_t)(hi[i] - was_rounded_up);     /* un-round */
     *res_full = full;
 }
@@ -245,9 +257,11 @@ static void load_pair(const uint16_t *hi, const void *res, uint64_t i, const res
 static void store_pair(uint16_t *hi, void *res, uint64_t i, const res_layout *L, uint16_t hi_trunc, uint16_t res_full)
 {
     int up = 0;
-    /* NEAREST: the leading dropped bit decides, always (it is also what tells merge to undo it);
-     * like IEEE rounding, a value within half a unit of overflow becomes infinity. */
-    if (L->round == MPO_REF_NEAREST) up = (res_full >> (L->full - 1)) & 1;
+    /* NEAREST: the leading dropped bit decides (it is also what tells merge to undo it); like
+     * IEEE rounding, a value within half a unit of overflow becomes infinity.  A NaN pattern is
+     * never rounded: adding one to the all-ones pattern would wrap around to a zero, and the
+     * 16-bit weight must stay a NaN when the fp32 value is one. */
+    if (L->round == MPO_REF_NEAREST) up = !is_nan16(hi_trunc, L->fmt) && ((res_full >> (L->full - 1)) & 1);
     /* STOCHASTIC: up with probability res_full / 2^full, but never out of the finite range
      * (the stored flag keeps this invertible) */
     if (L->round == MPO_REF_STOCHASTIC)
@@ -267,9 +281,9 @@ float mpo_ref_cvt16(uint16_t x, int fmt)
 }
 
 void mpo_ref_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits, int res_packed,
-                   int round, uint64_t seed, uint32_t tensor_id)
+                   int round, uint64_t seed, uint32_t tensor_id, uint64_t first_index)
 {
-    res_layout L = make_layout(fmt, res_bits, res_packed, n, round, seed, tensor_id, 0);
+    res_layout L = make_layout(fmt, res_bits, res_packed, n, round, seed, tensor_id, 0, first_index);
     for (uint64_t i = 0; i < n; ++i) {
         uint16_t h, full;
         split_one(w32[i], &h, &full, fmt);
@@ -280,7 +294,7 @@ void mpo_ref_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fm
 void mpo_ref_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits, int res_packed,
                    int round)
 {
-    res_layout L = make_layout(fmt, res_bits, res_packed, n, round, 0, 0, 0);
+    res_layout L = make_layout(fmt, res_bits, res_packed, n, round, 0, 0, 0, 0);
     for (uint64_t i = 0; i < n; ++i) {
         uint16_t h, full;
         load_pair(hi, res, i, &L, &h, &full);
@@ -297,9 +311,10 @@ void mpo_ref_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, 
  * line below is one rounded fp32 operation.
  */
 void mpo_ref_adam_step(uint16_t *hi, void *res, const uint16_t *grad, float *m, float *v,
-                       uint64_t n, const mpo_ref_adam_cfg *cfg, uint64_t step, uint32_t tensor_id)
+                       uint64_t n, const mpo_ref_adam_cfg *cfg, uint64_t step, uint32_t tensor_id, uint64_t first_index)
 {
-    const res_layout L = make_layout(cfg->weight_fmt, cfg->res_bits, cfg->res_packed, n, cfg->round, cfg->seed, tensor_id, step);
+    const res_layout L = make_layout(cfg->weight_fmt, cfg->res_bits, cfg->res_packed, n, cfg->round, cfg->seed, tensor_id, step,
+                                     first_index);
     const double t = (double)step;
     const float B1 = (float)cfg->beta1;
     const float B2 = (float)cfg->beta2;
@@ -355,10 +370,11 @@ void mpo_ref_adam_step(uint16_t *hi, void *res, const uint16_t *grad, float *m, 
 
 /* ---- SGD with momentum (Sec. 3.1; appendix: SGD with momentum, weight decay) */
 void mpo_ref_sgd_step(uint16_t *hi, void *res, const uint16_t *grad, float *buf,
-                      uint64_t n, const mpo_ref_sgd_cfg *cfg, uint64_t step, uint32_t tensor_id)
+                      uint64_t n, const mpo_ref_sgd_cfg *cfg, uint64_t step, uint32_t tensor_id, uint64_t first_index)
 {
     /* momentum buffers start at zero, so step 1 needs no special case */
-    const res_layout L = make_layout(cfg->weight_fmt, cfg->res_bits, cfg->res_packed, n, cfg->round, cfg->seed, tensor_id, step);
+    const res_layout L = make_layout(cfg->weight_fmt, cfg->res_bits, cfg->res_packed, n, cfg->round, cfg->seed, tensor_id, step,
+                                     first_index);
     const float LR = (float)cfg->lr;
     const float MU = (float)cfg->momentum;
     const float WD = (float)cfg->weight_decay;

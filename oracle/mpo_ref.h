@@ -50,7 +50,9 @@ enum { MPO_REF_BF16 = 0, MPO_REF_FP16 = 1 };
  * In every mode merge gives back the same fp32 value as TRUNC would: only the
  * 16-bit value seen by forward / backward differs.  STOCHASTIC never rounds a
  * value up out of the finite range; NEAREST, like IEEE rounding, turns a value
- * within half a unit of overflow into infinity (merge still undoes it).
+ * within half a unit of overflow into infinity (merge still undoes it), and never
+ * touches a NaN pattern (a NaN stays a NaN in hi; its payload is not preserved
+ * when the fp32 NaN has its payload in the dropped bits only).
  * In STOCHASTIC mode res_bits = 0 means 15 kept bits
  * for bf16 (15 + 1 flag fill the 16-bit slot) and 13 for fp16; at most 7 kept
  * bits fit a byte slot and 15 a 16-bit slot.
@@ -95,20 +97,28 @@ typedef struct {
     double grad_clip;
 } mpo_ref_sgd_cfg;
 
+/* `first_index` (split and the steps): the arrays given hold elements first_index ..
+ * first_index + n - 1 of their tensor.  It matters to STOCHASTIC rounding only, whose random
+ * stream is indexed by an element's position in its tensor: a slice of a tensor handled with its
+ * first_index gives the same bits as the same elements handled as part of the whole tensor.
+ * Must be 0 with res_packed (where a plane starts depends on the tensor's length). */
+
 /* Section 3.1, Table 1: fp32 -> (16-bit float, extra bits), truncation. */
 void mpo_ref_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits, int res_packed,
-                   int round, uint64_t seed, uint32_t tensor_id);
+                   int round, uint64_t seed, uint32_t tensor_id, uint64_t first_index);
 /* Section 3.1: (16-bit float, extra bits) -> fp32. */
 void mpo_ref_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits, int res_packed,
                    int round);
 
 /* Section 3.1 (the usual optimizers): bias-corrected Adam / AdamW on one tensor. */
 void mpo_ref_adam_step(uint16_t *hi, void *res, const uint16_t *grad, float *m, float *v,
-                       uint64_t n, const mpo_ref_adam_cfg *cfg, uint64_t step, uint32_t tensor_id);
+                       uint64_t n, const mpo_ref_adam_cfg *cfg, uint64_t step, uint32_t tensor_id,
+                       uint64_t first_index);
 /* Section 3.1 (the usual optimizers): SGD with momentum (dampening 0, no Nesterov).
  * momentum == 0 leaves buf untouched (it may then be NULL). */
 void mpo_ref_sgd_step(uint16_t *hi, void *res, const uint16_t *grad, float *buf,
-                      uint64_t n, const mpo_ref_sgd_cfg *cfg, uint64_t step, uint32_t tensor_id);
+                      uint64_t n, const mpo_ref_sgd_cfg *cfg, uint64_t step, uint32_t tensor_id,
+                      uint64_t first_index);
 
 /* One Philox4x32-10 block: out = philox(counter, key). */
 void mpo_ref_philox4x32_10(const uint32_t counter[4], const uint32_t key[2], uint32_t out[4]);

@@ -125,7 +125,7 @@ class Oracle:
     def __init__(self, path):
         lib = ctypes.CDLL(path)
         lib.mpo_ref_split.argtypes = [_f32p, _u16p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int, ctypes.c_int,
-                                      ctypes.c_int, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32]
+                                      ctypes.c_int, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64]
         lib.mpo_ref_res_bytes.argtypes = [ctypes.c_uint64, ctypes.c_int, ctypes.c_int, ctypes.c_int]
         lib.mpo_ref_res_bytes.restype = ctypes.c_uint64
         lib.mpo_ref_split.restype = None
@@ -133,10 +133,10 @@ class Oracle:
                                       ctypes.c_int, ctypes.c_int]
         lib.mpo_ref_merge.restype = None
         lib.mpo_ref_adam_step.argtypes = [_u16p, ctypes.c_void_p, _u16p, _f32p, _f32p, ctypes.c_uint64,
-                                          ctypes.POINTER(_AdamCfg), ctypes.c_uint64, ctypes.c_uint32]
+                                          ctypes.POINTER(_AdamCfg), ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64]
         lib.mpo_ref_adam_step.restype = None
         lib.mpo_ref_sgd_step.argtypes = [_u16p, ctypes.c_void_p, _u16p, _f32p, ctypes.c_uint64,
-                                         ctypes.POINTER(_SgdCfg), ctypes.c_uint64, ctypes.c_uint32]
+                                         ctypes.POINTER(_SgdCfg), ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64]
         lib.mpo_ref_sgd_step.restype = None
         lib.mpo_ref_cvt16.argtypes = [ctypes.c_uint16, ctypes.c_int]
         lib.mpo_ref_cvt16.restype = ctypes.c_float
@@ -161,15 +161,17 @@ class Oracle:
         else:
             _chk(res, res_dtype(res_bits), n)
 
-    def split(self, w32, fmt=BF16, res_bits=0, round=TRUNC, seed=0, tensor_id=0, packed=False):
+    def split(self, w32, fmt=BF16, res_bits=0, round=TRUNC, seed=0, tensor_id=0, packed=False, first_index=0):
         """fp32 array -> (hi uint16, res) arrays; res is uint16 or uint8 per value, or with
         packed=True the bit planes as one uint8 array (res_bits then counts the bits stored per
-        value: with STOCHASTIC the leading one is the flag)."""
+        value: with STOCHASTIC the leading one is the flag).  first_index: position, in its tensor,
+        of the array's first element (selects the random numbers of STOCHASTIC; 0 when packed)."""
         _chk(w32, np.float32)
         n = w32.shape[0]
         hi = np.empty(n, np.uint16)
         res = np.zeros(self.res_bytes(n, fmt, res_bits, True), np.uint8) if packed else np.empty(n, res_dtype(res_bits))
-        self._lib.mpo_ref_split(_p32(w32), _p16(hi), _pv(res), n, fmt, res_bits, int(packed), round, seed, tensor_id)
+        self._lib.mpo_ref_split(_p32(w32), _p16(hi), _pv(res), n, fmt, res_bits, int(packed), round, seed, tensor_id,
+                                first_index)
         return hi, res
 
     def merge(self, hi, res, fmt=BF16, res_bits=0, round=TRUNC, packed=False):
@@ -180,8 +182,9 @@ class Oracle:
         self._lib.mpo_ref_merge(_p16(hi), _pv(res), _p32(w32), n, fmt, res_bits, int(packed), round)
         return w32
 
-    def adam_step(self, hi, res, grad, m, v, cfg: AdamCfg, step: int, tensor_id: int = 0):
-        """One Adam step on one tensor, in place on hi, res, m, v."""
+    def adam_step(self, hi, res, grad, m, v, cfg: AdamCfg, step: int, tensor_id: int = 0, first_index: int = 0):
+        """One Adam step on one tensor (or on the slice of it that starts at first_index), in place
+        on hi, res, m, v."""
         n = _chk(hi, np.uint16).shape[0]
         self._res_ok(res, n, cfg.weight_fmt, cfg.res_bits, cfg.res_packed)
         _chk(grad, np.uint16, n)
@@ -191,10 +194,11 @@ class Oracle:
             raise ValueError("step counts from 1")
         c = cfg._c()
         self._lib.mpo_ref_adam_step(_p16(hi), _pv(res), _p16(grad), _p32(m), _p32(v), n,
-                                    ctypes.byref(c), step, tensor_id)
+                                    ctypes.byref(c), step, tensor_id, first_index)
 
-    def sgd_step(self, hi, res, grad, buf, cfg: SgdCfg, step: int, tensor_id: int = 0):
-        """One SGD(-momentum) step on one tensor, in place on hi, res, buf."""
+    def sgd_step(self, hi, res, grad, buf, cfg: SgdCfg, step: int, tensor_id: int = 0, first_index: int = 0):
+        """One SGD(-momentum) step on one tensor (or on the slice of it that starts at first_index),
+        in place on hi, res, buf."""
         n = _chk(hi, np.uint16).shape[0]
         self._res_ok(res, n, cfg.weight_fmt, cfg.res_bits, cfg.res_packed)
         _chk(grad, np.uint16, n)
@@ -204,7 +208,8 @@ class Oracle:
             raise ValueError("step counts from 1")
         c = cfg._c()
         bp = _p32(buf) if buf is not None else ctypes.cast(None, _f32p)
-        self._lib.mpo_ref_sgd_step(_p16(hi), _pv(res), _p16(grad), bp, n, ctypes.byref(c), step, tensor_id)
+        self._lib.mpo_ref_sgd_step(_p16(hi), _pv(res), _p16(grad), bp, n, ctypes.byref(c), step, tensor_id,
+                                   first_index)
 
     def cvt16(self, x: int, fmt=BF16) -> float:
         """One 16-bit float pattern read as fp32."""

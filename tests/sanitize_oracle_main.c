@@ -29,16 +29,16 @@ static int run(uint64_t n, int fmt, int res_bits, int packed, int round)
         memcpy(&w[i], &bits, 4);
         g[i] = (uint16_t)(lcg(&s) >> 16);
     }
-    mpo_ref_split(w, hi, res, n, fmt, res_bits, packed, round, 99, 3);
+    mpo_ref_split(w, hi, res, n, fmt, res_bits, packed, round, 99, 3, 0);
     mpo_ref_merge(hi, res, back, n, fmt, res_bits, packed, round);
     mpo_ref_adam_cfg a = {1e-3, 0.9, 0.999, 1e-8, 0.01, 1, 1.0, fmt, fmt, res_bits, packed, round, 99, 0.5};
     mpo_ref_sgd_cfg q = {1e-2, 0.9, 1e-4, 128.0, fmt, fmt, res_bits, packed, round, 99, 0.0};
     for (uint64_t t = 1; t <= 2; ++t) {
-        mpo_ref_adam_step(hi, res, g, m, v, n, &a, t, 3);
-        mpo_ref_sgd_step(hi, res, g, m, n, &q, t, 3);
+        mpo_ref_adam_step(hi, res, g, m, v, n, &a, t, 3, 0);
+        mpo_ref_sgd_step(hi, res, g, m, n, &q, t, 3, 0);
     }
     q.momentum = 0.0;
-    mpo_ref_sgd_step(hi, res, g, NULL, n, &q, 3, 3);
+    mpo_ref_sgd_step(hi, res, g, NULL, n, &q, 3, 3, 0);
     mpo_ref_merge(hi, res, back, n, fmt, res_bits, packed, round);
     free(w); free(back); free(m); free(v); free(hi); free(g); free(res);
     return 1;

@@ -51,6 +51,8 @@ PINS = [
     tr.pins_stochastic_statistics,
     tr.pins_stochastic_stream,
     tr.pins_trajectory_is_mode_independent,
+    tr.pins_first_index,
+    tr.pins_nearest_keeps_nan,
 ]
 
 # (name, text in mpo_ref.c, what it is replaced with, occurrences expected)
@@ -119,8 +121,16 @@ MUTANTS = [
     ("rounding: tensor not in the counter", "(uint32_t)(block >> 32), L->step32, L->tensor_id", "(uint32_t)(block >> 32), L->step32, 0u", 1),
     ("rounding: one draw per block of four", "return out[i % 4] >> (32 - L->full);", "return out[0] >> (32 - L->full);", 1),
     ("rounding: low bits of the draw", "return out[i % 4] >> (32 - L->full);", "return out[i % 4] & ((1u << L->full) - 1u);", 1),
-    ("rounding: nearest at a quarter", "if (L->round == MPO_REF_NEAREST) up = (res_full >> (L->full - 1)) & 1;",
-     "if (L->round == MPO_REF_NEAREST) up = (res_full >> (L->full - 2)) != 0;", 1),
+    ("rounding: nearest at a quarter", "up = !is_nan16(hi_trunc, L->fmt) && ((res_full >> (L->full - 1)) & 1);",
+     "up = !is_nan16(hi_trunc, L->fmt) && ((res_full >> (L->full - 2)) != 0);", 1),
+    ("rounding: nearest rounds a NaN pattern up", "up = !is_nan16(hi_trunc, L->fmt) && ((res_full >> (L->full - 1)) & 1);",
+     "up = (res_full >> (L->full - 1)) & 1;", 1),
+    ("rounding: nearest un-rounds a NaN pattern", "was_rounded_up = !is_nan16(hi[i], L->fmt) && ((full >> (L->full - 1)) & 1);",
+     "was_rounded_up = (full >> (L->full - 1)) & 1;", 1),
+    ("rounding: infinity counted as a NaN", "(uint16_t)(h & 0x7FFFu) > (fmt == MPO_REF_FP16 ? 0x7C00u : 0x7F80u)",
+     "(uint16_t)(h & 0x7FFFu) >= (fmt == MPO_REF_FP16 ? 0x7C00u : 0x7F80u)", 1),
+    ("rounding: position of the slice ignored", "    i += L->first;\n", "", 1),
+    ("rounding: position of the slice counted in blocks", "    i += L->first;\n", "    i += 4 * L->first;\n", 1),
     ("rounding: stochastic may overflow", "(uint16_t)(hi_trunc & 0x7FFFu) < max_finite_hi(L->fmt) && draw(L, i) < res_full;",
      "draw(L, i) < res_full;", 1),
     ("rounding: philox multiplier", "(uint64_t)0xCD9E8D57u * c2", "(uint64_t)0xCD9E8D57u * c0", 1),

@@ -11,6 +11,8 @@ What pins them:
   * STOCHASTIC: hi is one of the two neighbours, P(up) = dropped bits / 2^full (binomial bound),
     the mean of hi is x, never up from an exact value or out of the finite range, the flag sits
     just above the kept bits, draws depend on seed, step, tensor and element exactly as stated;
+  * a slice handled with `first_index` draws what the stated stream gives at those positions;
+  * NEAREST never turns a NaN into something else (the all-ones pattern does not wrap to zero);
   * steps: the fp32 trajectory (merged weights, m, v) does not depend on the rounding mode.
 `pins_*` take the oracle as argument (tests/test_oracle_pins_bite.py runs them on broken builds).
 """
@@ -172,16 +174,17 @@ def test_stochastic_statistics(ref):
     pins_stochastic_statistics(ref)
 
 
-def _expected_up(x_res_full, full, seed, step, tensor, n):
+def _expected_up(x_res_full, full, seed, step, tensor, n, first=0):
     """Which elements round up, from the stated stream: Philox4x32-10 with key = seed and counter
-    = (i/4 low, i/4 high, step low 32 bits, tensor); element i takes word i%4, its top bits."""
+    = (i/4 low, i/4 high, step low 32 bits, tensor); element i takes word i%4, its top bits.
+    `first`: position in the tensor of element 0 of the array."""
     key = [seed & 0xFFFFFFFF, seed >> 32]
     out = np.zeros(n, bool)
-    for b in range((n + 3) // 4):
+    for b in range(first // 4, (first + n + 3) // 4):
         w = philox_py([b & 0xFFFFFFFF, b >> 32, step & 0xFFFFFFFF, tensor], key)
         for j in range(4):
-            i = 4 * b + j
-            if i < n:
+            i = 4 * b + j - first
+            if 0 <= i < n:
                 out[i] = (w[j] >> (32 - full)) < int(x_res_full[i])
     return out
 
@@ -216,6 +219,93 @@ def pins_stochastic_stream(ref):
 
 def test_stochastic_stream(ref):
     pins_stochastic_stream(ref)
+
+
+def pins_first_index(ref):
+    """A slice of a tensor, handled with the position of its first element, gets the draws of
+    those positions: checked against the stated stream (second Philox implementation) for starts
+    of every residue modulo 4 and beyond 2^34 elements, where the counter's second word is in
+    use, and against the same elements handled as part of a whole array."""
+    rng = np.random.default_rng(17)
+    n = 203
+    x = (0.5 + rng.random(n)).astype(np.float32)
+    for fmt in (ref.BF16, ref.FP16):
+        full = FULL[fmt]
+        ht, rfull = ref.split(x, fmt, 0, ref.TRUNC)
+        whole_hi, whole_res = ref.split(x, fmt, 0, ref.STOCHASTIC, seed=5, tensor_id=2)
+        for first in (0, 1, 2, 3, 4, 77, (1 << 34) - 2, (1 << 34) + 5, (3 << 34) + 1):
+            hi, res = ref.split(x, fmt, 0, ref.STOCHASTIC, seed=5, tensor_id=2, first_index=first)
+            assert np.array_equal(hi != ht, _expected_up(rfull, full, 5, 0, 2, n, first)), (fmt, first)
+            if first < n:           # the tail of the whole array is the slice that starts there
+                h2, r2 = ref.split(x[first:].copy(), fmt, 0, ref.STOCHASTIC, seed=5, tensor_id=2, first_index=first)
+                assert np.array_equal(h2, whole_hi[first:]) and np.array_equal(r2, whole_res[first:])
+        # the steps take it the same way (lr = 0: the value is only re-rounded with this step's draws)
+        keep = 15 if fmt == ref.BF16 else 13
+        _, rk = ref.split(x, fmt, keep, ref.TRUNC)
+        rf = rk.astype(np.uint32) << (full - keep)
+        for first in (0, 3, (1 << 34) + 6):
+            hi, res = ref.split(x, fmt, 0, ref.STOCHASTIC, seed=5, tensor_id=2, first_index=first)
+            cfg = ref.SgdCfg(lr=0.0, momentum=0.0, weight_fmt=fmt, round=ref.STOCHASTIC, seed=5)
+            ref.sgd_step(hi, res, np.zeros(n, np.uint16), None, cfg, 3, tensor_id=2, first_index=first)
+            assert np.array_equal(hi != ht, _expected_up(rf, full, 5, 3, 2, n, first)), (fmt, first)
+            hi, res = ref.split(x, fmt, 0, ref.STOCHASTIC, seed=5, tensor_id=2, first_index=first)
+            acfg = ref.AdamCfg(lr=0.0, weight_fmt=fmt, grad_fmt=fmt, round=ref.STOCHASTIC, seed=5)
+            ref.adam_step(hi, res, np.zeros(n, np.uint16), np.zeros(n, np.float32), np.zeros(n, np.float32), acfg, 3,
+                          tensor_id=2, first_index=first)
+            assert np.array_equal(hi != ht, _expected_up(rf, full, 5, 3, 2, n, first)), (fmt, first)
+
+
+def test_first_index(ref):
+    pins_first_index(ref)
+
+
+def pins_nearest_keeps_nan(ref):
+    """Round-to-nearest adds one to the 16-bit pattern; on a NaN pattern that could wrap around to a
+    zero.  A NaN must stay a NaN in hi and in the merged value, in split and through a step, and
+    every pattern that is not a NaN must still come back bit for bit."""
+    for fmt, tof32, inf in ((ref.BF16, bf16_to_f32, 0x7F80), (ref.FP16, fp16_to_f32, 0x7C00)):
+        full = FULL[fmt]
+        # every fp32 NaN whose 16-bit part is all ones, with the leading dropped bit set or not, both signs
+        if fmt == ref.BF16:
+            nan_bits = np.array([0x7FFF8000, 0x7FFFFFFF, 0xFFFF8000, 0xFFFFFFFF, 0x7FFF0001, 0x7F808000, 0x7FC08000,
+                                 0x7F800001, 0xFF80FFFF], np.uint32)
+        else:
+            nan_bits = np.array([0x7FFFF000, 0x7FFFFFFF, 0xFFFFF000, 0x7FC01000, 0xFF801000, 0x7F800001], np.uint32)
+        x = nan_bits.view(np.float32)
+        hi, res = ref.split(x, fmt, 0, ref.NEAREST)
+        assert np.all((hi & 0x7FFF) >= inf), [hex(h) for h in hi]
+        back = ref.merge(hi, res, fmt, 0, ref.NEAREST)
+        assert np.all(np.isnan(back)), back
+        # what forward sees is a NaN whenever the 16-bit pattern of the truncated value is one
+        ht, _ = ref.split(x, fmt, 0, ref.TRUNC)
+        was_nan16 = (ht & 0x7FFF) > inf
+        assert np.all(np.isnan(tof32(hi))[was_nan16])
+        # such a pattern is left alone in both directions: it comes back as TRUNC would give it
+        t_back = ref.merge(*ref.split(x, fmt, 0, ref.TRUNC), fmt, 0, ref.TRUNC)
+        assert np.array_equal(back.view(np.uint32)[was_nan16], t_back.view(np.uint32)[was_nan16])
+        assert np.array_equal(hi[was_nan16], ht[was_nan16])
+        # through a step: a NaN gradient makes the weight a NaN and it stays one
+        w = np.full(8, 0.5, np.float32)
+        hi, res = ref.split(w, fmt, 0, ref.NEAREST)
+        g = np.full(8, 0x7FFF, np.uint16)
+        cfg = ref.SgdCfg(lr=0.1, momentum=0.0, weight_fmt=fmt, grad_fmt=fmt, round=ref.NEAREST)
+        for t in (1, 2, 3):
+            ref.sgd_step(hi, res, g if t == 1 else np.zeros(8, np.uint16), None, cfg, t)
+            assert np.all(np.isnan(tof32(hi))) and np.all(np.isnan(ref.merge(hi, res, fmt, 0, ref.NEAREST)))
+        # everything that is not a NaN still round-trips exactly (all 16-bit values x a few residuals)
+        h_all = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16)
+        h_all = h_all[(h_all & 0x7FFF) <= inf]
+        for r in (0, 1, (1 << (full - 1)) - 1, 1 << (full - 1), (1 << full) - 1):
+            rr = np.full(h_all.size, r, np.uint16)
+            val = ref.merge(h_all, rr, fmt, 0, ref.TRUNC)
+            keep = ~np.isnan(val)
+            h1, r1 = ref.split(val[keep], fmt, 0, ref.NEAREST)
+            again = ref.merge(h1, r1, fmt, 0, ref.NEAREST)
+            assert np.array_equal(again.view(np.uint32), val[keep].view(np.uint32)), (fmt, r)
+
+
+def test_nearest_keeps_nan(ref):
+    pins_nearest_keeps_nan(ref)
 
 
 # ---- steps: the fp32 trajectory does not depend on how hi is rounded ---------------------------
