@@ -17,7 +17,9 @@
  *     is uint16_t or, with at most 8 extra bits kept, uint8_t (see res_bits).
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = default stream).
  *     Calls only enqueue work on that stream and return; they never wait for
- *     the device.  The step entry points allocate nothing.
+ *     the device.  Only mpo_plan_create allocates (host and device memory, freed
+ *     by mpo_plan_destroy); split, merge and the step entry points allocate
+ *     nothing, on the host or on the device.
  *   - Pointers need no particular alignment: 16-byte aligned tensors take the
  *     128-bit path, others a slower element-wise path with identical results.
  *   - Errors are reported by return code only and nothing is enqueued when a
@@ -60,7 +62,8 @@ typedef enum { MPO_BF16 = 0, MPO_FP16 = 1 } mpo_fmt;
  *                         MPO_ERR_INVALID_ARG.
  *   MPO_ROUND_NEAREST     the deterministic counterpart: up when the dropped bits are at least
  *                         half a unit (ties away from zero; like IEEE rounding a value within
- *                         half a unit of overflow becomes infinity).  The leading dropped bit
+ *                         half a unit of overflow becomes infinity; a NaN pattern is left as
+ *                         it is, so a NaN weight stays a NaN in hi).  The leading dropped bit
  *                         tells the step to undo it; nothing extra is stored.
  * In every mode the fp32 value held by (hi, res), and therefore the whole fp32 trajectory of a
  * training run, is the same as with MPO_ROUND_TRUNC; only the 16-bit value that forward and
@@ -208,16 +211,35 @@ mpo_status mpo_plan_destroy(mpo_plan *plan);
  * on such a plan return MPO_ERR_INVALID_ARG. */
 mpo_status mpo_plan_create_host(const mpo_tensor *tensors, uint64_t nt, mpo_plan **out);
 
-/* Layout queries (host side, no HIP call).  Chunks are numbered in launch
- * order; chunk i covers elements [index*chunk_elems, min(n, (index+1)*chunk_elems))
- * of tensor `tensor` (an index into the list given at creation). */
+/* mpo_plan_create with options; opts == NULL or a zero field means the default.
+ *   small_layer_params  layers with fewer parameters than this are cut into chunks of 1024
+ *                       parameters instead of 4096 (default 2^26; 1 = long chunks everywhere,
+ *                       UINT64_MAX = short chunks everywhere).  A tuning knob: results do not
+ *                       depend on it.
+ *   host_only           != 0: as mpo_plan_create_host. */
+typedef struct {
+    uint64_t small_layer_params;
+    int32_t host_only;
+} mpo_plan_opts;
+mpo_status mpo_plan_create_opts(const mpo_tensor *tensors, uint64_t nt, const mpo_plan_opts *opts, mpo_plan **out);
+
+/* Layout queries (host side, no HIP call).  One workgroup handles one chunk.  All
+ * chunks of a layer have the same length: 4096 parameters (what mpo_plan_chunk_elems
+ * returns, the longest), or 1024 in layers of fewer than 2^26 parameters, which fill
+ * the GPU better with more, shorter chunks.  Chunks are numbered in launch order:
+ * layer by layer; within a layer first every tensor's last, shorter chunk (if its
+ * length is not a multiple of the chunk length), then the full chunks tensor by
+ * tensor.  Chunk i covers `count` elements from element `first` of tensor `tensor`
+ * (an index into the list given at creation). */
 uint64_t mpo_plan_chunk_elems(const mpo_plan *plan);
 uint64_t mpo_plan_num_chunks(const mpo_plan *plan);
 uint64_t mpo_plan_num_params(const mpo_plan *plan);
-mpo_status mpo_plan_get_chunk(const mpo_plan *plan, uint64_t i, uint64_t *tensor, uint64_t *index);
-/* Chunk range and parameter count of one layer; an unknown layer is MPO_ERR_INVALID_ARG. */
+mpo_status mpo_plan_get_chunk(const mpo_plan *plan, uint64_t i, uint64_t *tensor, uint64_t *first, uint64_t *count);
+/* Chunk range, tensor and parameter count and chunk length of one layer (any output may be
+ * NULL); an unknown layer is MPO_ERR_INVALID_ARG. */
 mpo_status mpo_plan_layer_info(const mpo_plan *plan, int32_t layer, uint64_t *first_chunk,
-                               uint64_t *num_chunks, uint64_t *num_tensors, uint64_t *num_params);
+                               uint64_t *num_chunks, uint64_t *num_tensors, uint64_t *num_params,
+                               uint64_t *chunk_elems);
 
 /* One optimizer step over every tensor of the plan in ONE kernel launch
  * (Section 3.1).  `step` counts from 1 and is shared by all tensors.  Every

@@ -43,6 +43,10 @@ class mpo_tensor(ctypes.Structure):
                 ("layer", ctypes.c_int32), ("res_bits", ctypes.c_int32), ("res_packed", ctypes.c_int32)]
 
 
+class mpo_plan_opts(ctypes.Structure):
+    _fields_ = [("small_layer_params", ctypes.c_uint64), ("host_only", ctypes.c_int32)]
+
+
 class mpo_adam_cfg(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
                 ("eps", ctypes.c_double), ("weight_decay", ctypes.c_double),
@@ -68,13 +72,14 @@ EXPORTS = {
     "mpo_plan_create": ([ctypes.POINTER(mpo_tensor), ctypes.c_uint64, ctypes.POINTER(ctypes.c_void_p)], ctypes.c_int),
     "mpo_plan_create_host": ([ctypes.POINTER(mpo_tensor), ctypes.c_uint64, ctypes.POINTER(ctypes.c_void_p)],
                              ctypes.c_int),
+    "mpo_plan_create_opts": ([ctypes.POINTER(mpo_tensor), ctypes.c_uint64, ctypes.POINTER(mpo_plan_opts),
+                              ctypes.POINTER(ctypes.c_void_p)], ctypes.c_int),
     "mpo_plan_destroy": ([ctypes.c_void_p], ctypes.c_int),
     "mpo_plan_chunk_elems": ([ctypes.c_void_p], ctypes.c_uint64),
     "mpo_plan_num_chunks": ([ctypes.c_void_p], ctypes.c_uint64),
     "mpo_plan_num_params": ([ctypes.c_void_p], ctypes.c_uint64),
-    "mpo_plan_get_chunk": ([ctypes.c_void_p, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint64),
-                            ctypes.POINTER(ctypes.c_uint64)], ctypes.c_int),
-    "mpo_plan_layer_info": ([ctypes.c_void_p, ctypes.c_int32] + [ctypes.POINTER(ctypes.c_uint64)] * 4, ctypes.c_int),
+    "mpo_plan_get_chunk": ([ctypes.c_void_p, ctypes.c_uint64] + [ctypes.POINTER(ctypes.c_uint64)] * 3, ctypes.c_int),
+    "mpo_plan_layer_info": ([ctypes.c_void_p, ctypes.c_int32] + [ctypes.POINTER(ctypes.c_uint64)] * 5, ctypes.c_int),
     "mpo_adam_step": ([ctypes.c_void_p, ctypes.POINTER(mpo_adam_cfg), ctypes.c_uint64, ctypes.c_void_p], ctypes.c_int),
     "mpo_sgd_step": ([ctypes.c_void_p, ctypes.POINTER(mpo_sgd_cfg), ctypes.c_uint64, ctypes.c_void_p], ctypes.c_int),
     "mpo_step_layer": ([ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint64,
@@ -86,8 +91,9 @@ EXPORTS = {
 
 def _load():
     path = _build.LIB
-    if not os.path.exists(path):
-        # nothing built yet: build once (needs hipcc); never fall back to another implementation
+    if not os.path.exists(path) or (_build.needs_build() and os.path.exists(_build.HIPCC)):
+        # nothing built yet, or the sources are newer than the library (and there is a compiler):
+        # build (a no-op when fresh); never fall back to another implementation
         path = _build.build()
     lib = ctypes.CDLL(path)
     for name, (argtypes, restype) in EXPORTS.items():
@@ -199,18 +205,30 @@ class Tensor:
     res_packed: bool = False
 
 
-class Plan:
-    """Owns an mpo_plan*.  Keeps references to torch tensors so their memory outlives the plan."""
+def _tensor_array(tensors: Sequence[Tensor]):
+    arr = (mpo_tensor * max(len(tensors), 1))()
+    for i, t in enumerate(tensors):
+        arr[i] = mpo_tensor(_ptr(t.hi), _ptr(t.res), _ptr(t.grad), _ptr(t.m), _ptr(t.v), t.n, t.layer, t.res_bits,
+                            int(t.res_packed))
+    return arr
 
-    def __init__(self, tensors: Sequence[Tensor], host_only: bool = False):
+
+# mpo_plan_opts.small_layer_params of plans made without an explicit value (0 = the library's default);
+# the GPU tests set it to run the same cases with short and with long chunks
+default_small_layer_params = 0
+
+
+class Plan:
+    """Owns an mpo_plan*.  Keeps references to torch tensors so their memory outlives the plan.
+    small_layer_params: see mpo_plan_opts in include/mpo.h (a tuning knob; None = the default)."""
+
+    def __init__(self, tensors: Sequence[Tensor], host_only: bool = False, small_layer_params: Optional[int] = None):
         self._keep = list(tensors)
-        arr = (mpo_tensor * max(len(tensors), 1))()
-        for i, t in enumerate(tensors):
-            arr[i] = mpo_tensor(_ptr(t.hi), _ptr(t.res), _ptr(t.grad), _ptr(t.m), _ptr(t.v), t.n, t.layer, t.res_bits,
-                                int(t.res_packed))
+        arr = _tensor_array(tensors)
         handle = ctypes.c_void_p()
-        create = lib.mpo_plan_create_host if host_only else lib.mpo_plan_create
-        _check(create(arr, len(tensors), ctypes.byref(handle)), "mpo_plan_create")
+        opts = mpo_plan_opts(default_small_layer_params if small_layer_params is None else small_layer_params,
+                             int(host_only))
+        _check(lib.mpo_plan_create_opts(arr, len(tensors), ctypes.byref(opts), ctypes.byref(handle)), "mpo_plan_create")
         self._h = handle
 
     def destroy(self):
@@ -238,15 +256,18 @@ class Plan:
         return lib.mpo_plan_num_params(self._h)
 
     def chunk(self, i: int):
-        t, k = ctypes.c_uint64(), ctypes.c_uint64()
-        _check(lib.mpo_plan_get_chunk(self._h, i, ctypes.byref(t), ctypes.byref(k)), "mpo_plan_get_chunk")
-        return t.value, k.value
+        """(tensor, first element, number of elements) of chunk i, in launch order."""
+        t, f, c = ctypes.c_uint64(), ctypes.c_uint64(), ctypes.c_uint64()
+        _check(lib.mpo_plan_get_chunk(self._h, i, ctypes.byref(t), ctypes.byref(f), ctypes.byref(c)),
+               "mpo_plan_get_chunk")
+        return t.value, f.value, c.value
 
     def layer_info(self, layer: int):
-        a, b, c, d = (ctypes.c_uint64() for _ in range(4))
+        a, b, c, d, e = (ctypes.c_uint64() for _ in range(5))
         _check(lib.mpo_plan_layer_info(self._h, layer, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c),
-                                       ctypes.byref(d)), "mpo_plan_layer_info")
-        return {"first_chunk": a.value, "num_chunks": b.value, "num_tensors": c.value, "num_params": d.value}
+                                       ctypes.byref(d), ctypes.byref(e)), "mpo_plan_layer_info")
+        return {"first_chunk": a.value, "num_chunks": b.value, "num_tensors": c.value, "num_params": d.value,
+                "chunk_elems": e.value}
 
 
 def mpo_adam_step(plan: Plan, cfg: AdamCfg, step: int, stream=None):

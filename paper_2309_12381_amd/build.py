@@ -8,8 +8,13 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmpo.so")
-SOURCES = [os.path.join(CSRC, "mpo_host.cpp"), os.path.join(CSRC, "mpo_kernels.hip")]
-HEADERS = [os.path.join(CSRC, "mpo_internal.h"), os.path.join(ROOT, "include", "mpo.h")]
+# (source, extra flags): the step kernels are one source compiled in four parts (Adam / SGD, gradient
+# pointers from the plan / per call) so that the parts build side by side
+PARTS = [("mpo_host.cpp", ()), ("mpo_split_merge.hip", ()),
+         ("mpo_step.hip", ("-DMPO_PART_OPT=0", "-DMPO_PART_OV=0")), ("mpo_step.hip", ("-DMPO_PART_OPT=0", "-DMPO_PART_OV=1")),
+         ("mpo_step.hip", ("-DMPO_PART_OPT=1", "-DMPO_PART_OV=0")), ("mpo_step.hip", ("-DMPO_PART_OPT=1", "-DMPO_PART_OV=1"))]
+SOURCES = sorted({os.path.join(CSRC, src) for src, _ in PARTS})
+HEADERS = [os.path.join(CSRC, "mpo_internal.h"), os.path.join(CSRC, "mpo_device.h"), os.path.join(ROOT, "include", "mpo.h")]
 PROBE_LIB = os.path.join(HERE, "libmpo_probe.so")
 PROBE_SOURCES = [os.path.join(CSRC, "stream_probe.hip")]
 
@@ -19,7 +24,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # division and square root, denormals kept; no fast-math anywhere.  Packed fp32 VALU forms are
 # switched off (the compiler would otherwise pair independent fp32 operations).
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt", "-fno-fast-math",
     "-fno-gpu-flush-denormals-to-zero",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -41,16 +46,30 @@ def needs_build() -> bool:
 
 def _compile(sources, out, extra=()):
     tmp = out + ".tmp.%d" % os.getpid()
-    subprocess.check_call([HIPCC, *FLAGS, *extra, "-x", "hip", *sources, "-o", tmp])
+    subprocess.check_call([HIPCC, *FLAGS, "-shared", *extra, "-x", "hip", *sources, "-o", tmp])
     os.replace(tmp, out)
     return out
 
 
 def build(force: bool = False, extra=(), out: str = LIB) -> str:
-    """Compile the library.  `extra` adds compiler flags for experiments."""
+    """Compile the library: every part to an object file (in parallel), then one link.
+    `extra` adds compiler flags for experiments."""
     if not force and out == LIB and not needs_build():
         return out
-    return _compile(SOURCES, out, extra)
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+    with tempfile.TemporaryDirectory(prefix="mpo_build_") as tmpdir:
+        def one(i):
+            src, defs = PARTS[i]
+            obj = os.path.join(tmpdir, "part%d.o" % i)
+            subprocess.check_call([HIPCC, *FLAGS, *extra, *defs, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj])
+            return obj
+        with ThreadPoolExecutor(min(len(PARTS), os.cpu_count() or 1)) as ex:
+            objs = list(ex.map(one, range(len(PARTS))))
+        tmp = out + ".tmp.%d" % os.getpid()
+        subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-fPIC", "-shared", *objs, "-o", tmp])
+        os.replace(tmp, out)
+    return out
 
 
 def build_probe(force: bool = False) -> str:

@@ -1,5 +1,6 @@
 /*
- * mpo kernels for gfx950 (MI355X): split, merge and the fused optimizer step.
+ * mpo device code for gfx950 (MI355X), shared by the kernel files (mpo_step.hip,
+ * mpo_split_merge.hip): formats, residual storage, rounding and the fused optimizer step.
  *
  * arXiv 2309.12381, Section 3.1: each weight is a 16-bit float plus the
  * significand bits an fp32 copy would have kept; the update runs in fp32 and
@@ -11,8 +12,8 @@
  * arithmetic by a copy does not change the measured time).
  *
  * Mapping: one workgroup of 256 lanes (4 wavefronts of 64) per chunk of 4096
- * consecutive parameters of one tensor; the chunk table lets one launch cover
- * every tensor of a list (Section 3.1, "Fused" optimizer).
+ * (in small layers 1024) consecutive parameters of one tensor; the chunk table
+ * lets one launch cover every tensor of a list (Section 3.1, "Fused" optimizer).
  *   - A lane owns 4 consecutive parameters per row: 64-bit accesses to the
  *     16-bit arrays and 128-bit accesses to the fp32 arrays, so EVERY load and
  *     store instruction of a wavefront covers one dense span (512 B or 1 KiB)
@@ -30,6 +31,8 @@
  * Built with -ffp-contract=off and correctly rounded division / square root:
  * every line of arithmetic below is one IEEE binary32 operation.
  */
+#ifndef MPO_DEVICE_H
+#define MPO_DEVICE_H
 #include <hip/hip_runtime.h>
 
 #include "mpo_internal.h"
@@ -38,8 +41,9 @@ namespace mpo {
 namespace {
 
 constexpr int EPL = 4;                                /* parameters per lane per row   */
-constexpr int ROWS = kChunkElems / (kBlock * EPL);    /* rows per chunk, all in flight */
+constexpr int ROWS = kChunkElems / (kBlock * EPL);    /* rows of the longest chunk, all in flight */
 static_assert(ROWS * kBlock * EPL == kChunkElems, "a chunk is a whole number of rows");
+static_assert(kBlock * EPL == kRowElems, "a row is one access of every lane of the workgroup");
 
 /* Every parameter array lives in device (global) memory.  Saying so lets the
  * compiler emit global_load/global_store instead of flat accesses for pointers
@@ -349,6 +353,8 @@ __device__ __forceinline__ void planes_store(const ResRef &R, uint32_t e, const 
 }
 
 template <int WFMT> struct FullBits { static constexpr uint32_t value = (WFMT == MPO_FP16) ? 13u : 16u; };
+/* 16-bit pattern of infinity without the sign: everything above it is a NaN */
+template <int WFMT> struct InfBits { static constexpr uint32_t value = (WFMT == MPO_FP16) ? 0x7C00u : 0x7F80u; };
 
 /* ---- rounding of the 16-bit value (Section 3.1, last paragraph) -------------
  * Philox4x32-10 (Salmon et al., SC'11): counter-based, so every lane computes
@@ -390,8 +396,10 @@ __device__ __forceinline__ void unround(uint32_t &hi, uint32_t slot, uint32_t &r
 {
     constexpr uint32_t FULL = FullBits<WFMT>::value;
     res_full = (slot & ((1u << kept) - 1u)) << sh;
+    /* round-to-nearest never touches a NaN pattern: a NaN stays a NaN in what forward sees */
+    const uint32_t is_nan = ((hi & 0x7FFFu) > InfBits<WFMT>::value) ? 1u : 0u;
     const uint32_t flag = (round == MPO_ROUND_STOCHASTIC) ? ((slot >> kept) & 1u)
-                        : (round == MPO_ROUND_NEAREST)    ? ((res_full >> (FULL - 1u)) & 1u) : 0u;
+                        : (round == MPO_ROUND_NEAREST)    ? (((res_full >> (FULL - 1u)) & 1u) & ~is_nan) : 0u;
     hi = (hi - flag) & 0xFFFFu;
 }
 
@@ -403,7 +411,7 @@ __device__ __forceinline__ uint32_t reround(uint32_t &hi, uint32_t res_full, uin
     constexpr uint32_t FULL = FullBits<WFMT>::value;
     constexpr uint32_t MAXFIN = (WFMT == MPO_FP16) ? 0x7BFFu : 0x7F7Fu;
     uint32_t up = 0u;
-    if (round == MPO_ROUND_NEAREST) up = (res_full >> (FULL - 1u)) & 1u;
+    if (round == MPO_ROUND_NEAREST) up = ((hi & 0x7FFFu) > InfBits<WFMT>::value) ? 0u : ((res_full >> (FULL - 1u)) & 1u);
     if (round == MPO_ROUND_STOCHASTIC) up = ((hi & 0x7FFFu) < MAXFIN && u < res_full) ? 1u : 0u;
     hi = (hi + up) & 0xFFFFu;
     uint32_t slot = res_full >> sh;
@@ -432,10 +440,10 @@ template <int OPT, bool MOM> struct Uses {
  * contiguous quarter of the chunk and walks it row by row, so the rows one wavefront
  * requests from a stream are adjacent in memory (measured ~5 % faster than rows
  * interleaved across the four wavefronts). */
-__device__ __forceinline__ uint32_t row_elem(uint32_t r, uint32_t t)
+__device__ __forceinline__ uint32_t row_elem(uint32_t r, uint32_t t, uint32_t span = kChunkElems / (kBlock / 64))
 {
-    constexpr uint32_t kWaves = kBlock / 64;
-    return (t / 64) * (kChunkElems / kWaves) + r * (64 * EPL) + (t % 64) * EPL;
+    /* span: the wavefront's share of the chunk (a quarter of its length) */
+    return (t / 64) * span + r * (64 * EPL) + (t % 64) * EPL;
 }
 
 struct Row {
@@ -595,24 +603,32 @@ __device__ __forceinline__ void step_scalar_rounded(gu16p hi, MPO_GLOBAL void *r
     if (Uses<OPT, MOM>::v) v[e] = vv;
 }
 
-template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE, bool RND>
+/* How a launch gets its gradient pointers: from the descriptors, or (Section 3.2, per-call
+ * pointers of one layer) from the kernel arguments. */
+template <bool OV> struct OvArg { typedef NoOverride T; };
+template <> struct OvArg<true> { typedef GradOverride T; };
+
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE, bool RND, bool OV>
 __global__ void __launch_bounds__(kBlock)
 step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chunks, uint64_t first_chunk,
-            StepScalars s, GradOverride ov)
+            StepScalars s, typename OvArg<OV>::T ov)
 {
     /* Uniform per workgroup: scalar loads. */
     const Chunk c = chunks[first_chunk + blockIdx.x];
     const TensorDesc d = descs[c.tensor];
     const uint16_t *gbase = d.grad;
     bool aligned = (d.flags & (kStateAligned | kGradAligned)) == (kStateAligned | kGradAligned);
-    if (ov.enabled) {
+    if constexpr (OV) {
         const uint32_t k = c.tensor - ov.first;
         gbase = ov.ptr[k];
         aligned = (d.flags & kStateAligned) && !((ov.misaligned >> k) & 1ull);
     }
-    const uint64_t off = (uint64_t)c.index * kChunkElems;
+    const uint32_t rows = 1u << (c.where >> kChunkStartBits);      /* 1, 2 or 4 */
+    const uint32_t celems = rows * kRowElems;
+    const uint32_t span = celems / (kBlock / 64);                  /* a wavefront's contiguous share */
+    const uint64_t off = (uint64_t)(c.where & kChunkStartMask) * kRowElems;
     const uint64_t left = d.n - off;
-    const uint32_t len = left < kChunkElems ? (uint32_t)left : kChunkElems;
+    const uint32_t len = left < celems ? (uint32_t)left : celems;
 
     /* cut bits of this tensor's residual (uniform); a full residual has none */
     const uint32_t all = (RND && s.round == MPO_ROUND_STOCHASTIC && WFMT == MPO_BF16) ? 15u : FullBits<WFMT>::value;
@@ -631,7 +647,7 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
     const uint32_t t = threadIdx.x;
 
     if (aligned && len == kChunkElems) {
-        /* whole chunk: no bounds checks; every row is requested before the first is used */
+        /* whole 4-row chunk: no bounds checks; every row is requested before the first is used */
         Row x[ROWS];
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) load_row<OPT, MOM, RMODE>(x[r], hi, R, grad, m, v, row_elem(r, t));
@@ -641,6 +657,17 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
             else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x[r], s, sh);
             store_row<OPT, MOM, RMODE>(x[r], hi, R, m, v, row_elem(r, t));
         }
+    } else if (aligned && len == celems) {
+        /* whole shorter chunk (small layers): row by row, every lane active, no bounds checks */
+#pragma unroll 1
+        for (uint32_t r = 0; r < rows; ++r) {
+            const uint32_t e = row_elem(r, t, span);
+            Row x;
+            load_row<OPT, MOM, RMODE>(x, hi, R, grad, m, v, e);
+            if (RND) compute_row_rounded<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x, s, kept, sh, rng, off + e);
+            else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x, s, sh);
+            store_row<OPT, MOM, RMODE>(x, hi, R, m, v, e);
+        }
     } else if (RMODE == kResPlanes) {
         /* packed planes outside the fast path: every lane walks whole groups of 8 parameters */
         for (uint32_t e = t * 8u; e < len; e += kBlock * 8u)
@@ -648,8 +675,8 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
     } else if (aligned) {
         /* last chunk of a tensor: full vectors, then one lane finishes the ragged end */
 #pragma unroll 1
-        for (int r = 0; r < ROWS; ++r) {
-            const uint32_t e = row_elem(r, t);
+        for (uint32_t r = 0; r < rows; ++r) {
+            const uint32_t e = row_elem(r, t, span);
             if (e + EPL <= len) {
                 Row x;
                 load_row<OPT, MOM, RMODE>(x, hi, R, grad, m, v, e);
@@ -671,357 +698,11 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
     }
 }
 
-/* ---- split / merge: 8 B per parameter (7 B with byte residuals) ------------
- * RND: the 16-bit value is rounded to nearest or stochastically (split) and
- * un-rounded (merge); `rs` carries mode, seed and tensor id, step32 is 0. */
-
-struct RoundArgs {
-    uint32_t round, seed_lo, seed_hi, tensor_id;
-};
-
-template <int FMT, int RMODE, bool RND>
-__device__ __forceinline__ void split_store_one(float w, uint32_t &h, uint32_t &slot, uint32_t kept, uint32_t sh,
-                                                const RoundArgs &rs, uint32_t u)
-{
-    uint32_t r;
-    split32<FMT>(w, h, r);
-    if (RND) slot = reround<FMT>(h, r, kept, sh, rs.round, u);
-    else slot = r >> sh;
-}
-
-/* w32, hi, res point at the tensor's first parameter; this launch covers chunks from `first`. */
-template <int FMT, int RMODE, bool RND>
-__global__ void __launch_bounds__(kBlock)
-split_kernel(const float *__restrict__ w32_, uint16_t *__restrict__ hi_, void *__restrict__ res_, uint64_t n,
-             uint64_t first, int aligned, uint32_t kept, uint32_t sh, uint32_t stored, RoundArgs rs)
-{
-    typedef typename ResElem<RMODE>::T R;
-    constexpr int RREG = reg_mode(RMODE);
-    const uint64_t off = first + (uint64_t)blockIdx.x * kChunkElems;   /* tensor-relative */
-    const uint64_t left = n - off;
-    const uint32_t len = left < kChunkElems ? (uint32_t)left : kChunkElems;
-    gcf32p w32 = (gcf32p)(w32_ + off);
-    gu16p hi = (gu16p)(hi_ + off);
-    const ResRef ref = res_ref<RMODE>(res_, n, off, stored);
-    MPO_GLOBAL R *res = (MPO_GLOBAL R *)ref.slots;
-    const Rng rng = {rs.seed_lo, rs.seed_hi, 0u, rs.tensor_id};
-    const uint32_t t = threadIdx.x;
-    auto one = [&](uint32_t i, uint32_t &h, uint32_t &slot) {
-        uint32_t u[4] = {0u, 0u, 0u, 0u};
-        if (RND && rs.round == MPO_ROUND_STOCHASTIC) draw4<FullBits<FMT>::value>(rng, (off + i) / 4, u);
-        split_store_one<FMT, RREG, RND>(w32[i], h, slot, kept, sh, rs, u[(off + i) % 4]);
-    };
-    if (RMODE == kResPlanes && !(aligned && len == kChunkElems)) {
-        /* whole groups of 8 parameters per lane, one parameter at a time; positions past the
-         * end are written as zero bits */
-        for (uint32_t e = t * 8u; e < len; e += kBlock * 8u) {
-            uint32_t ones = 0u;
-#pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                const uint32_t eh = e + 4u * half;
-                if (eh < len) {
-                    uint32_t q[EPL / 2];
-#pragma unroll
-                    for (int j = 0; j < EPL / 2; ++j) q[j] = 0u;
-#pragma unroll
-                    for (int k = 0; k < EPL; ++k) {
-                        if (eh + k < len) {
-                            uint32_t h, slot;
-                            one(eh + k, h, slot);
-                            hi[eh + k] = (uint16_t)h;
-                            q[k / 2] |= (slot & 0xFFFFu) << (16 * (k & 1));
-                        }
-                    }
-                    ones |= planes_pack(ref, eh, q) << (4 * half);
-                }
-            }
-            if (ref.S & 1u) ref.p1[e / 8] = (uint8_t)ones;
-        }
-        return;
-    }
-    if (!aligned) {
-        for (uint32_t i = t; i < len; i += kBlock) {
-            uint32_t h, slot;
-            one(i, h, slot);
-            hi[i] = (uint16_t)h;
-            res[i] = (R)slot;
-        }
-        return;
-    }
-#pragma unroll
-    for (int r = 0; r < ROWS; ++r) {
-        const uint32_t e = row_elem(r, t);
-        if (e + EPL <= len) {
-            float w[EPL];
-            uint32_t h[EPL / 2], q[EPL / 2];
-            load32(w32 + e, w);
-#pragma unroll
-            for (int j = 0; j < EPL / 2; ++j) q[j] = 0u;
-#pragma unroll
-            for (int g4 = 0; g4 < EPL / 4; ++g4) {
-                uint32_t u[4] = {0u, 0u, 0u, 0u};
-                if (RND && rs.round == MPO_ROUND_STOCHASTIC) draw4<FullBits<FMT>::value>(rng, (off + e) / 4 + g4, u);
-#pragma unroll
-                for (int jj = 0; jj < 2; ++jj) {
-                    const int j = 2 * g4 + jj;
-                    uint32_t h0, s0, h1, s1;
-                    split_store_one<FMT, RREG, RND>(w[2 * j], h0, s0, kept, sh, rs, u[2 * jj]);
-                    split_store_one<FMT, RREG, RND>(w[2 * j + 1], h1, s1, kept, sh, rs, u[2 * jj + 1]);
-                    h[j] = h0 | (h1 << 16);
-                    slot_put<RREG>(q, 2 * j, s0);
-                    slot_put<RREG>(q, 2 * j + 1, s1);
-                }
-            }
-            store16(hi + e, h);
-            if (RMODE == kResPlanes) planes_store(ref, e, q);
-            else if (RMODE == kResByte) store8((gu8p)res + e, q);
-            else store16((gu16p)res + e, q);
-        } else if (e < len) {
-            for (uint32_t i = e; i < len; ++i) {
-                uint32_t h, slot;
-                one(i, h, slot);
-                hi[i] = (uint16_t)h;
-                res[i] = (R)slot;
-            }
-        }
-    }
-}
-
-template <int FMT, int RMODE, bool RND>
-__device__ __forceinline__ float merge_load_one(uint32_t h, uint32_t slot, uint32_t kept, uint32_t sh, uint32_t round)
-{
-    uint32_t r;
-    if (RND) unround<FMT>(h, slot, r, kept, sh, round);
-    else r = slot << sh;
-    return merge16<FMT>(h, r);
-}
-
-template <int FMT, int RMODE, bool RND>
-__global__ void __launch_bounds__(kBlock)
-merge_kernel(const uint16_t *__restrict__ hi_, const void *__restrict__ res_, float *__restrict__ w32_, uint64_t n,
-             uint64_t first, int aligned, uint32_t kept, uint32_t sh, uint32_t stored, uint32_t round)
-{
-    typedef typename ResElem<RMODE>::T R;
-    constexpr int RREG = reg_mode(RMODE);
-    const uint64_t off = first + (uint64_t)blockIdx.x * kChunkElems;
-    const uint64_t left = n - off;
-    const uint32_t len = left < kChunkElems ? (uint32_t)left : kChunkElems;
-    gf32p w32 = (gf32p)(w32_ + off);
-    gcu16p hi = (gcu16p)(hi_ + off);
-    const ResRef ref = res_ref<RMODE>(const_cast<void *>(res_), n, off, stored);
-    const MPO_GLOBAL R *res = (const MPO_GLOBAL R *)ref.slots;
-    const uint32_t t = threadIdx.x;
-    if (RMODE == kResPlanes && !(aligned && len == kChunkElems)) {
-        for (uint32_t e = t * 8u; e < len; e += kBlock * 8u) {
-            const uint32_t ones = (ref.S & 1u) ? ref.p1[e / 8] : 0u;
-#pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                const uint32_t eh = e + 4u * half;
-                if (eh < len) {
-                    uint32_t q[EPL / 2];
-                    planes_unpack(ref, eh, (ones >> (4 * half)) & 0xFu, q);
-#pragma unroll
-                    for (int k = 0; k < EPL; ++k)
-                        if (eh + k < len)
-                            w32[eh + k] = merge_load_one<FMT, RREG, RND>(hi[eh + k], slot_get<RREG>(q, k), kept, sh, round);
-                }
-            }
-        }
-        return;
-    }
-    if (!aligned) {
-        for (uint32_t i = t; i < len; i += kBlock)
-            w32[i] = merge_load_one<FMT, RREG, RND>(hi[i], (uint32_t)res[i], kept, sh, round);
-        return;
-    }
-#pragma unroll
-    for (int r = 0; r < ROWS; ++r) {
-        const uint32_t e = row_elem(r, t);
-        if (e + EPL <= len) {
-            float w[EPL];
-            uint32_t h[EPL / 2], q[EPL / 2];
-            load16(hi + e, h);
-            if (RMODE == kResPlanes) planes_load(ref, e, q);
-            else if (RMODE == kResByte) load8((gcu8p)res + e, q);
-            else load16((gcu16p)res + e, q);
-#pragma unroll
-            for (int j = 0; j < EPL / 2; ++j) {
-                w[2 * j] = merge_load_one<FMT, RREG, RND>(h[j] & 0xFFFFu, slot_get<RREG>(q, 2 * j), kept, sh, round);
-                w[2 * j + 1] = merge_load_one<FMT, RREG, RND>(h[j] >> 16, slot_get<RREG>(q, 2 * j + 1), kept, sh, round);
-            }
-            store32(w32 + e, w);
-        } else if (e < len) {
-            for (uint32_t i = e; i < len; ++i)
-                w32[i] = merge_load_one<FMT, RREG, RND>(hi[i], (uint32_t)res[i], kept, sh, round);
-        }
-    }
-}
-
 /* Grids are limited to 2^31-1 workgroups: longer lists go out in slices. */
 constexpr uint64_t kMaxGrid = 0x7FFFFFFFull;
 
-template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE, bool RND>
-hipError_t launch_step_t(const StepLaunch &L)
-{
-    uint64_t done = 0;
-    while (done < L.num_chunks) {
-        const uint64_t now = (L.num_chunks - done < kMaxGrid) ? (L.num_chunks - done) : kMaxGrid;
-        (void)hipGetLastError(); /* an error an earlier, unrelated runtime call left on this thread is not ours */
-        step_kernel<OPT, WFMT, GFMT, DECAY, MOM, RMODE, RND><<<dim3((uint32_t)now), dim3(kBlock), 0, L.stream>>>(
-            L.descs, L.chunks, L.first_chunk + done, L.s, L.ov);
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        done += now;
-    }
-    return hipSuccess;
-}
-
-template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM>
-hipError_t launch_step_res(const StepLaunch &L)
-{
-    if (L.s.round != MPO_ROUND_TRUNC) {
-        /* rounded modes always go through the general residual path */
-        return L.rmode == kResByte     ? launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResByte, true>(L)
-               : L.rmode == kResPlanes ? launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResPlanes, true>(L)
-                                       : launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResPartial, true>(L);
-    }
-    switch (L.rmode) {
-    case kResFull: return launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResFull, false>(L);
-    case kResPartial: return launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResPartial, false>(L);
-    case kResPlanes: return launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResPlanes, false>(L);
-    default: return launch_step_t<OPT, WFMT, GFMT, DECAY, MOM, kResByte, false>(L);
-    }
-}
-
-template <int OPT, int DECAY, bool MOM>
-hipError_t launch_step_fmt(const StepLaunch &L)
-{
-    if (L.wfmt == MPO_BF16)
-        return L.gfmt == MPO_BF16 ? launch_step_res<OPT, MPO_BF16, MPO_BF16, DECAY, MOM>(L)
-                                  : launch_step_res<OPT, MPO_BF16, MPO_FP16, DECAY, MOM>(L);
-    return L.gfmt == MPO_BF16 ? launch_step_res<OPT, MPO_FP16, MPO_BF16, DECAY, MOM>(L)
-                              : launch_step_res<OPT, MPO_FP16, MPO_FP16, DECAY, MOM>(L);
-}
-
-struct SplitMergeArgs {
-    const float *w32_in;
-    float *w32_out;
-    uint16_t *hi;
-    void *res;
-    uint64_t n;
-    int al;
-    uint32_t kept, sh, stored;
-    RoundArgs rs;
-    hipStream_t stream;
-};
-
-template <int FMT, int RMODE, bool RND>
-hipError_t launch_split_t(const SplitMergeArgs &a)
-{
-    uint64_t done = 0;
-    const uint64_t blocks = (a.n + kChunkElems - 1) / kChunkElems;
-    while (done < blocks) {
-        const uint64_t now = (blocks - done < kMaxGrid) ? (blocks - done) : kMaxGrid;
-        const uint64_t e0 = done * kChunkElems;
-        (void)hipGetLastError();
-        split_kernel<FMT, RMODE, RND><<<dim3((uint32_t)now), dim3(kBlock), 0, a.stream>>>(
-            a.w32_in, a.hi, a.res, a.n, e0, a.al, a.kept, a.sh, a.stored, a.rs);
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        done += now;
-    }
-    return hipSuccess;
-}
-
-template <int FMT, int RMODE, bool RND>
-hipError_t launch_merge_t(const SplitMergeArgs &a)
-{
-    uint64_t done = 0;
-    const uint64_t blocks = (a.n + kChunkElems - 1) / kChunkElems;
-    while (done < blocks) {
-        const uint64_t now = (blocks - done < kMaxGrid) ? (blocks - done) : kMaxGrid;
-        const uint64_t e0 = done * kChunkElems;
-        (void)hipGetLastError();
-        merge_kernel<FMT, RMODE, RND><<<dim3((uint32_t)now), dim3(kBlock), 0, a.stream>>>(
-            a.hi, a.res, a.w32_out, a.n, e0, a.al, a.kept, a.sh, a.stored, a.rs.round);
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        done += now;
-    }
-    return hipSuccess;
-}
-
-template <int FMT, bool SPLIT>
-hipError_t launch_sm(const SplitMergeArgs &a, int rmode)
-{
-    const bool rnd = a.rs.round != MPO_ROUND_TRUNC;
-    if (rnd && rmode == kResFull) rmode = kResPartial;     /* rounded modes: general residual path */
-#define MPO_SM(RM, RN) (SPLIT ? launch_split_t<FMT, RM, RN>(a) : launch_merge_t<FMT, RM, RN>(a))
-    if (rnd) return rmode == kResByte ? MPO_SM(kResByte, true) : rmode == kResPlanes ? MPO_SM(kResPlanes, true) : MPO_SM(kResPartial, true);
-    if (rmode == kResPlanes) return MPO_SM(kResPlanes, false);
-    if (rmode == kResByte) return MPO_SM(kResByte, false);
-    if (rmode == kResPartial) return MPO_SM(kResPartial, false);
-    return MPO_SM(kResFull, false);
-#undef MPO_SM
-}
-
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-/* Storage mode, kept bits and number of cut bits for a single-tensor call. */
-inline void res_layout(int fmt, int res_bits, int packed, int round, int &rmode, uint32_t &kept, uint32_t &sh,
-                       uint32_t &stored)
-{
-    const int full = full_res_bits(fmt);
-    const int k = kept_res_bits(fmt, res_bits, round, packed);
-    kept = (uint32_t)k;
-    sh = (uint32_t)(full - k);
-    stored = packed ? (uint32_t)res_bits : kept;
-    rmode = packed ? kResPlanes : (res_bits >= 1 && res_bits <= 8) ? kResByte : (k == full ? kResFull : kResPartial);
-}
-
 } // namespace
-
-hipError_t launch_step(const StepLaunch &L)
-{
-    if (L.num_chunks == 0) return hipSuccess;
-    if (L.opt == MPO_OPT_ADAM) {
-        switch (L.decay) {
-        case kNoDecay: return launch_step_fmt<MPO_OPT_ADAM, kNoDecay, true>(L);
-        case kDecoupled: return launch_step_fmt<MPO_OPT_ADAM, kDecoupled, true>(L);
-        default: return launch_step_fmt<MPO_OPT_ADAM, kL2, true>(L);
-        }
-    }
-    if (L.momentum)
-        return L.decay == kL2 ? launch_step_fmt<MPO_OPT_SGD, kL2, true>(L)
-                              : launch_step_fmt<MPO_OPT_SGD, kNoDecay, true>(L);
-    return L.decay == kL2 ? launch_step_fmt<MPO_OPT_SGD, kL2, false>(L)
-                          : launch_step_fmt<MPO_OPT_SGD, kNoDecay, false>(L);
-}
-
-hipError_t launch_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits, int packed,
-                        int round, uint64_t seed, uint32_t tensor_id, hipStream_t stream)
-{
-    SplitMergeArgs a;
-    a.w32_in = w32; a.w32_out = nullptr; a.hi = hi; a.res = res; a.n = n;
-    a.al = aligned16(w32) && aligned16(hi) && aligned16(res);
-    int rmode;
-    res_layout(fmt, res_bits, packed, round, rmode, a.kept, a.sh, a.stored);
-    a.rs = RoundArgs{(uint32_t)round, (uint32_t)seed, (uint32_t)(seed >> 32), tensor_id};
-    a.stream = stream;
-    return fmt == MPO_BF16 ? launch_sm<MPO_BF16, true>(a, rmode) : launch_sm<MPO_FP16, true>(a, rmode);
-}
-
-hipError_t launch_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits, int packed,
-                        int round, hipStream_t stream)
-{
-    SplitMergeArgs a;
-    a.w32_in = nullptr; a.w32_out = w32; a.hi = const_cast<uint16_t *>(hi); a.res = const_cast<void *>(res); a.n = n;
-    a.al = aligned16(w32) && aligned16(hi) && aligned16(res);
-    int rmode;
-    res_layout(fmt, res_bits, packed, round, rmode, a.kept, a.sh, a.stored);
-    a.rs = RoundArgs{(uint32_t)round, 0u, 0u, 0u};
-    a.stream = stream;
-    return fmt == MPO_BF16 ? launch_sm<MPO_BF16, false>(a, rmode) : launch_sm<MPO_FP16, false>(a, rmode);
-}
-
 } // namespace mpo
+#endif /* MPO_DEVICE_H */

@@ -10,15 +10,14 @@
 
 namespace mpo {
 
-/* One workgroup (256 lanes = 4 wavefronts of 64) owns one chunk.  The chunk length can be set at
- * build time (a multiple of 1024) for measurements: 1024, 2048 and 4096 give the same throughput on
- * the large parameter sets; 4096 keeps the chunk table smallest. */
+/* One workgroup (256 lanes = 4 wavefronts of 64) owns one chunk.  A chunk is 1, 2 or 4 "rows" of
+ * 1024 consecutive parameters (4 per lane).  On the large parameter sets 1024 and 4096 give the
+ * same throughput and 4096 keeps the chunk table smallest; a small layer fills the GPU better with
+ * more, shorter chunks (a list of 25.6 M parameters: +5 %), so the length is chosen per layer. */
 constexpr uint32_t kBlock = 256;
-#ifndef MPO_CHUNK_ELEMS
-#define MPO_CHUNK_ELEMS 4096
-#endif
-constexpr uint32_t kChunkElems = MPO_CHUNK_ELEMS;
-static_assert(kChunkElems % 1024 == 0 && kChunkElems >= 1024, "a chunk is a whole number of rows of 4 wavefronts");
+constexpr uint32_t kRowElems = 1024;                 /* kBlock lanes x 4 parameters               */
+constexpr uint32_t kChunkElems = 4096;               /* the longest chunk: 4 rows                 */
+constexpr uint64_t kSmallLayerParams = 1ull << 26;   /* layers below this are cut into single rows (default) */
 
 /* Bits of TensorDesc::flags. */
 constexpr uint32_t kStateAligned = 1u; /* hi, res, m, v all 16-byte aligned          */
@@ -38,12 +37,30 @@ struct TensorDesc {
 };
 static_assert(sizeof(TensorDesc) == 64, "descriptor layout is read by the kernels");
 
-/* Chunk table entry: which tensor (index into the plan's layer-ordered
- * descriptor array) and which chunk of it. */
+/* Chunk table entry: which tensor (index into the layer-ordered descriptor array) and which part
+ * of it.  `where` holds the chunk's first parameter in units of kRowElems in its low 30 bits and
+ * log2 of the chunk's length in rows in its top 2 bits. */
 struct Chunk {
     uint32_t tensor;
-    uint32_t index;
+    uint32_t where;
 };
+constexpr uint32_t kChunkStartBits = 30;
+constexpr uint32_t kChunkStartMask = (1u << kChunkStartBits) - 1u;
+constexpr uint64_t kMaxTensorElems = (uint64_t)kRowElems << kChunkStartBits; /* 2^40 */
+
+inline uint32_t chunk_where(uint64_t first_elem, uint32_t rows_log2)
+{
+    return (uint32_t)(first_elem / kRowElems) | (rows_log2 << kChunkStartBits);
+}
+
+/* How one layer's tensors are cut (Section 3.1, "Fused" optimizer: one launch over many tensors).
+ * All chunks of a layer have the same length; in the table the layer's ragged chunks (the last,
+ * shorter chunk of a tensor) come first, so that they run beside full chunks instead of at the
+ * end of the launch, then the full chunks tensor by tensor. */
+inline uint32_t layer_rows_log2(uint64_t layer_params, uint64_t small_layer_params)
+{
+    return layer_params < small_layer_params ? 0u : 2u;
+}
 
 /* Scalars of one step, already rounded to fp32 on the host (Section 3.1:
  * the classic optimizers).  Adam uses all but LR/MU; SGD uses LR, MU, WD, IS. */
@@ -58,12 +75,16 @@ struct StepScalars {
     uint32_t seed_lo, seed_hi, step32;
 };
 
-/* Per-call gradient pointers for one layer (Section 3.2), passed by value. */
+/* Per-call gradient pointers for one layer (Section 3.2), passed by value to the kernels that are
+ * compiled for them; launches that use the plan's own pointers carry NoOverride instead. */
 struct GradOverride {
     const uint16_t *ptr[MPO_MAX_LAYER_GRADS];
     uint64_t misaligned; /* bit i set: ptr[i] is not 16-byte aligned            */
     uint32_t first;      /* descriptor index of the layer's first tensor        */
-    uint32_t enabled;
+    uint32_t pad;
+};
+struct NoOverride {
+    uint32_t unused;
 };
 
 enum Decay { kNoDecay = 0, kDecoupled = 1, kL2 = 2 };
@@ -103,11 +124,47 @@ struct StepLaunch {
     int momentum; /* SGD: momentum != 0 */
     int rmode;    /* ResMode         */
     StepScalars s;
+    bool use_ov;  /* gradients come from `ov` (mpo_step_layer with per-call pointers) */
     GradOverride ov;
     hipStream_t stream;
 };
 
+/* Where one tensor's chunks sit in the chunk table (see layer_rows_log2). */
+struct TensorLayout {
+    uint32_t rows_log2;   /* chunk length of the tensor's layer: 2^rows_log2 rows            */
+    uint32_t has_ragged;  /* the tensor ends in a shorter chunk                               */
+    uint64_t ragged_pos;  /* table index of that chunk                                        */
+    uint64_t full_pos;    /* table index of the tensor's first full chunk                     */
+    uint64_t num_full;    /* number of full chunks                                            */
+};
+
+/* Host-side pieces shared by the plan (mpo_host.cpp) and the entry point that allocates nothing
+ * (mpo_noalloc.hip).  None of them allocates. */
+struct Range {
+    uintptr_t lo, hi; /* [lo, hi) in bytes */
+    bool written;
+};
+bool has_conflict(Range *r, uint64_t count);                 /* sorts r in place */
+/* Validates one list entry and appends its ranges (at most 5) to r[*count...]. */
+mpo_status check_tensor(const mpo_tensor &t, uint32_t &res_slot, Range *r, uint64_t *count);
+TensorDesc make_desc(const mpo_tensor &t, uint32_t tensor_id);
+/* descs[0..nt) in layer order, layer[k] the layer id of descs[k]: fills lay[0..nt), returns the
+ * number of chunks, or UINT64_MAX if a tensor is too long for the table's encoding. */
+uint64_t layout_chunks(const TensorDesc *descs, const int32_t *layer, uint64_t nt, uint64_t small_layer_params,
+                       TensorLayout *lay);
+mpo_status adam_scalars(const mpo_adam_cfg *c, uint64_t step, StepLaunch &L);
+mpo_status sgd_scalars(const mpo_sgd_cfg *c, uint64_t step, StepLaunch &L);
+/* Residual storage of a list against the format and rounding mode of a step: fills L.rmode. */
+mpo_status check_res_mode(uint32_t res_slot, bool any_explicit_bits, uint32_t min_res_bits, uint32_t max_res_bits,
+                          StepLaunch &L);
+mpo_status hip_fail(hipError_t e);
+
 hipError_t launch_step(const StepLaunch &L);
+/* the four parts of launch_step, one object file each (mpo_step.hip) */
+hipError_t launch_step_adam(const StepLaunch &L);
+hipError_t launch_step_adam_ov(const StepLaunch &L);
+hipError_t launch_step_sgd(const StepLaunch &L);
+hipError_t launch_step_sgd_ov(const StepLaunch &L);
 hipError_t launch_split(const float *w32, uint16_t *hi, void *res, uint64_t n, int fmt, int res_bits, int packed,
                         int round, uint64_t seed, uint32_t tensor_id, hipStream_t stream);
 hipError_t launch_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n, int fmt, int res_bits, int packed,

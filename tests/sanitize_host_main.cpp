@@ -18,7 +18,10 @@ static void unreachable(const char *what)
     std::fprintf(stderr, "launcher reached: %s\n", what);
     std::abort();
 }
-hipError_t launch_step(const StepLaunch &) { unreachable("step"); return hipSuccess; }
+hipError_t launch_step_adam(const StepLaunch &) { unreachable("step"); return hipSuccess; }
+hipError_t launch_step_adam_ov(const StepLaunch &) { unreachable("step"); return hipSuccess; }
+hipError_t launch_step_sgd(const StepLaunch &) { unreachable("step"); return hipSuccess; }
+hipError_t launch_step_sgd_ov(const StepLaunch &) { unreachable("step"); return hipSuccess; }
 hipError_t launch_split(const float *, uint16_t *, void *, uint64_t, int, int, int, int, uint64_t, uint32_t, hipStream_t)
 {
     unreachable("split");
@@ -46,10 +49,14 @@ int main()
         std::vector<mpo_tensor> ts(nt);
         uintptr_t at = 0x100000;
         uint64_t total = 0, chunks = 0;
+        uint64_t per_layer[9] = {0};
         for (uint64_t i = 0; i < nt; ++i) {
             mpo_tensor &t = ts[i];
             t.n = (lcg(&seed) % 7 == 0) ? 0 : 1 + lcg(&seed) % 20000;
             t.layer = (int32_t)(lcg(&seed) % 9);
+            /* now and then one tensor long enough to give its layer the long chunks */
+            if (round % 4 == 1 && i == nt / 2) t.n = (1ull << 26) + lcg(&seed) % 10000;
+            per_layer[t.layer] += t.n;
             t.res_bits = bits;
             t.res_packed = packed;
             auto take = [&](uint64_t bytes) { void *p = (void *)at; at += (bytes + 255) / 256 * 256 + 256; return p; };
@@ -59,26 +66,34 @@ int main()
             t.m = (float *)take(t.n * 4);
             t.v = (i % 3) ? (float *)take(t.n * 4) : nullptr;
             total += t.n;
-            chunks += (t.n + 4095) / 4096;
+        }
+        for (uint64_t i = 0; i < nt; ++i) {
+            const uint64_t ce = per_layer[ts[i].layer] >= (1ull << 26) ? 4096 : 1024;
+            chunks += (ts[i].n + ce - 1) / ce;
         }
         mpo_plan *p = nullptr;
         CHECK(mpo_plan_create_host(ts.data(), nt, &p) == MPO_OK && p);
         CHECK(mpo_plan_num_params(p) == total && mpo_plan_num_chunks(p) == chunks);
-        uint64_t seen = 0;
+        uint64_t seen = 0, covered = 0;
         for (uint64_t c = 0; c < chunks; ++c) {
-            uint64_t tensor, index;
-            CHECK(mpo_plan_get_chunk(p, c, &tensor, &index) == MPO_OK && tensor < nt);
-            CHECK(index * 4096 < ts[tensor].n);
+            uint64_t tensor, first, count;
+            CHECK(mpo_plan_get_chunk(p, c, &tensor, &first, &count) == MPO_OK && tensor < nt);
+            CHECK(count >= 1 && first + count <= ts[tensor].n);
+            covered += count;
             ++seen;
         }
-        uint64_t tensor, index;
-        CHECK(mpo_plan_get_chunk(p, chunks, &tensor, &index) == MPO_ERR_INVALID_ARG);
+        uint64_t tensor, first, count;
+        CHECK(mpo_plan_get_chunk(p, chunks, &tensor, &first, &count) == MPO_ERR_INVALID_ARG);
         uint64_t by_layer = 0;
         for (int32_t l = 0; l < 9; ++l) {
-            uint64_t fc, nc, ntl, np;
-            if (mpo_plan_layer_info(p, l, &fc, &nc, &ntl, &np) == MPO_OK) { CHECK(fc + nc <= chunks); by_layer += np; }
+            uint64_t fc, nc, ntl, np, ce;
+            if (mpo_plan_layer_info(p, l, &fc, &nc, &ntl, &np, &ce) == MPO_OK) {
+                CHECK(fc + nc <= chunks);
+                CHECK(ce == (per_layer[l] >= (1ull << 26) ? 4096u : 1024u));
+                by_layer += np;
+            }
         }
-        CHECK(by_layer == total && seen == chunks);
+        CHECK(by_layer == total && seen == chunks && covered == total);
         /* a host plan cannot be stepped */
         mpo_adam_cfg a = {1e-3, 0.9, 0.999, 1e-8, 0.0, 1, 1.0, MPO_BF16, MPO_BF16, MPO_ROUND_TRUNC, 0, 0.0};
         CHECK(mpo_adam_step(p, &a, 1, nullptr) == MPO_ERR_INVALID_ARG);

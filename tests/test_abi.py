@@ -158,34 +158,44 @@ def test_plan_alias_detection():
 
 def test_plan_layout_covers_every_element_once_in_layer_order():
     ce0 = _host_plan([]).chunk_elems
-    sizes = [1, ce0 - 1, ce0, ce0 + 1, 3 * ce0 + 5, 0, 100000, 64]
-    layers = [3, 0, 2, 0, 1, 1, 2, 0]
+    small = 1024                                    # chunk length in layers below 2^26 parameters
+    big = (1 << 26) + 5                             # one layer large enough for the long chunks
+    sizes = [1, ce0 - 1, ce0, ce0 + 1, 3 * ce0 + 5, 0, 100000, 64, big, 4096 * 3 + 1]
+    layers = [3, 0, 2, 0, 1, 1, 2, 0, 5, 5]
     ts = [T(i, n=n, layer=l) for i, (n, l) in enumerate(zip(sizes, layers))]
+    far = 0x100000000000                            # the large tensor needs room: arrays 1 GiB apart
+    ts[8] = T(8, n=big, layer=5, hi=far, res=far + (1 << 30), grad=far + (2 << 30), m=far + (3 << 30), v=far + (4 << 30))
     p = _host_plan(ts)
-    ce = p.chunk_elems
-    assert ce == ce0 and ce % 1024 == 0
+    assert p.chunk_elems == ce0 == 4096
     assert p.num_params == sum(sizes)
-    assert p.num_chunks == sum((n + ce - 1) // ce for n in sizes)
-    seen = {}
+    clen = {l: (ce0 if sum(n for n, l2 in zip(sizes, layers) if l2 == l) >= (1 << 26) else small) for l in set(layers)}
+    assert p.num_chunks == sum((n + clen[l] - 1) // clen[l] for n, l in zip(sizes, layers))
+    covered = {t: [] for t in range(len(sizes))}
     order = []
     for i in range(p.num_chunks):
-        t, k = p.chunk(i)
-        assert (t, k) not in seen
-        seen[(t, k)] = i
-        order.append(t)
-    for t, n in enumerate(sizes):
-        for k in range((n + ce - 1) // ce):
-            assert (t, k) in seen
-    # launch order: by layer, then by position in the caller's list, chunks ascending
-    keys = [(layers[t], t) for t in order]
-    assert keys == sorted(keys)
+        t, first, count = p.chunk(i)
+        ce = clen[layers[t]]
+        assert first % ce == 0 and 1 <= count <= ce and first + count <= sizes[t]
+        assert count == ce or first + count == sizes[t]          # only a tensor's last chunk is shorter
+        covered[t].append((first, count))
+        order.append((layers[t], count != ce, t, first))
+    for t, n in enumerate(sizes):                                 # every element exactly once
+        at = 0
+        for first, count in sorted(covered[t]):
+            assert first == at
+            at += count
+        assert at == n
+    # launch order: by layer; in a layer the ragged chunks first, then full chunks by tensor, ascending
+    assert order == sorted(order, key=lambda k: (k[0], not k[1], k[2], k[3]))
     for layer in set(layers):
         info = p.layer_info(layer)
         members = [t for t in range(len(sizes)) if layers[t] == layer]
         assert info["num_tensors"] == len(members)
         assert info["num_params"] == sum(sizes[t] for t in members)
-        rng = order[info["first_chunk"]: info["first_chunk"] + info["num_chunks"]]
-        assert set(rng) <= set(members) and info["num_chunks"] == sum((sizes[t] + ce - 1) // ce for t in members)
+        assert info["chunk_elems"] == clen[layer]
+        rng = [k[2] for k in order[info["first_chunk"]: info["first_chunk"] + info["num_chunks"]]]
+        assert set(rng) <= set(members)
+        assert info["num_chunks"] == sum((sizes[t] + clen[layer] - 1) // clen[layer] for t in members)
     assert _status(p.layer_info, 7) == mpo.MPO_ERR_INVALID_ARG
     assert _status(p.chunk, p.num_chunks) == mpo.MPO_ERR_INVALID_ARG
     p.destroy()

@@ -18,8 +18,22 @@ from gpu_util import (DEV, FMT, ROUND, DevTensor, HostTensor, assert_state_equal
 
 pytestmark = pytest.mark.gpu
 
-CHUNK = int(mpo.lib.mpo_plan_chunk_elems(None))      # parameters per workgroup
-SIZES = [1, 7, 8, 9, 2047, 2048, CHUNK - 1, CHUNK, CHUNK + 1, 3 * CHUNK + 5, (1 << 20) + 3]
+CHUNK = int(mpo.lib.mpo_plan_chunk_elems(None))      # parameters per workgroup (the long chunks)
+SHORT = 1024                                         # chunk length in small layers
+SIZES = [1, 7, 8, 9, SHORT - 1, SHORT, SHORT + 1, 2047, 2048, CHUNK - 1, CHUNK, CHUNK + 1, 3 * CHUNK + 5, (1 << 20) + 3]
+
+
+@pytest.fixture(params=["short-chunks", "long-chunks"])
+def chunking(request):
+    """Tests that step a plan run twice: with the chunk length a small layer gets by default (1024
+    parameters per workgroup, row by row) and with the long chunks of the large layers (4096, all
+    rows in flight), which a list of test size would otherwise never reach."""
+    from paper_2309_12381_amd import binding
+    old = binding.default_small_layer_params
+    binding.default_small_layer_params = 1 if request.param == "long-chunks" else 0
+    yield request.param
+    binding.default_small_layer_params = old
+
 
 
 def interesting_f32(rng, n):
@@ -158,7 +172,7 @@ def _edge_grads(fmt, n, rng, std, scale):
 
 
 @pytest.mark.parametrize("fmt", ["bf16", "fp16"])
-def test_adam_single_tensor_config0(fmt):
+def test_adam_single_tensor_config0(fmt, chunking):
     """Configuration 0: one tensor of 2^20 parameters, 10 Adam steps with fresh gradients."""
     gfmt, rfmt = FMT[fmt]
     scale = 1.0 if fmt == "bf16" else 1024.0
@@ -183,7 +197,7 @@ def test_adam_single_tensor_config0(fmt):
 
 @pytest.mark.parametrize("fmt", ["bf16", "fp16"])
 @pytest.mark.parametrize("momentum,wd", [(0.9, 0.0), (0.9, 2e-4), (0.0, 0.0), (0.0, 1e-3)])
-def test_sgd_single_tensor_config0(fmt, momentum, wd):
+def test_sgd_single_tensor_config0(fmt, momentum, wd, chunking):
     gfmt, rfmt = FMT[fmt]
     rng = np.random.default_rng(101)
     n = 1 << 20
@@ -221,7 +235,7 @@ def _same_or_both_nan(got: np.ndarray, want: np.ndarray, what: str):
                                      ("sgd", dict(lr=0.1, momentum=0.9, weight_decay=1e-3)),
                                      ("sgd", dict(lr=1e30, momentum=0.5))],
                          ids=["adamw", "adam-l2-tiny-eps", "adam-scaled-clip", "sgd", "sgd-huge-lr"])
-def test_steps_on_arbitrary_bit_patterns(fmt, kind, kw):
+def test_steps_on_arbitrary_bit_patterns(fmt, kind, kw, chunking):
     """State and gradients drawn as raw bit patterns over ALL exponents (denormals, huge values,
     infinite and NaN gradients, v = 0): every division, square root, product and sum of the step,
     with overflow and gradual underflow, has to round as IEEE binary32 on both sides."""
@@ -326,7 +340,7 @@ def test_all_fp16_gradient_patterns_convert_exactly():
 def _small_list(rng, count=41, total=1_500_000):
     s = np.exp(rng.uniform(np.log(3.0), np.log(200000.0), size=count))
     sizes = np.maximum(1, np.rint(s * total / s.sum())).astype(np.int64)
-    sizes[:6] = [1, 7, 8, CHUNK, CHUNK + 1, 2 * CHUNK - 1]
+    sizes[:9] = [1, 7, 8, CHUNK, CHUNK + 1, 2 * CHUNK - 1, SHORT, SHORT + 1, 2 * SHORT - 1]
     return [int(x) for x in sizes]
 
 
@@ -344,7 +358,7 @@ LIST_CASES = [
 
 @pytest.mark.parametrize("kind,fmt,kw", LIST_CASES, ids=["%s-%s-%d" % (c[0], c[1], i) for i, c in enumerate(LIST_CASES)])
 @pytest.mark.parametrize("misalign", [0, 1])
-def test_multi_tensor_list_matches_oracle(kind, fmt, kw, misalign):
+def test_multi_tensor_list_matches_oracle(kind, fmt, kw, misalign, chunking):
     """One launch over a ragged list (several chunks per tensor, tails of every residue) equals
     the oracle tensor by tensor; with misalign=1 every array starts 2 or 4 bytes off 16-byte
     alignment and takes the element-wise path."""
@@ -414,7 +428,7 @@ def _layered_model(rng, fmt, layers=6):
 
 
 @pytest.mark.parametrize("kind,fmt", [("adam", "bf16"), ("adam", "fp16"), ("sgd", "bf16")])
-def test_step_layer_in_backward_order_equals_full_step_and_oracle(kind, fmt):
+def test_step_layer_in_backward_order_equals_full_step_and_oracle(kind, fmt, chunking):
     """Section 3.2: stepping layer by layer, last layer first, with ONE gradient buffer reused by
     every layer, gives the same bits as one launch over the whole list and as the oracle."""
     gfmt, rfmt = FMT[fmt]
@@ -476,6 +490,77 @@ def test_step_layer_in_backward_order_equals_full_step_and_oracle(kind, fmt):
             assert_state_equal(C[i], H[i], "per layer (plan grads in reused buffer), tensor %d step %d" % (i, t))
     for p in (planA, planB, planC):
         p.destroy()
+
+
+# per-call gradient pointers that are NOT 16-byte aligned while the state is: the chunk then takes the
+# element-wise path (16-bit and byte slots) or the groups-of-8 path (packed planes)
+OFFSET_GRAD_CASES = [(kind, store, mode) for kind in ("adam", "sgd") for store in ("slots", "bytes", "planes")
+                     for mode in ("trunc", "nearest", "stochastic")]
+
+
+@pytest.mark.parametrize("kind,store,mode", OFFSET_GRAD_CASES, ids=["%s-%s-%s" % c for c in OFFSET_GRAD_CASES])
+def test_step_layer_with_misaligned_per_call_gradients(kind, store, mode, chunking):
+    """Section 3.2: the gradients of a layer are handed over per call, wherever backward left them.
+    Here each gradient starts 1 or 3 elements (2 or 6 bytes) past a 16-byte boundary, with one
+    aligned gradient per layer in between, while hi, res, m and v stay aligned."""
+    fmt = "bf16" if kind == "adam" else "fp16"
+    gfmt, rfmt = FMT[fmt]
+    full = 16 if fmt == "bf16" else 13
+    packed = store == "planes"
+    if store == "slots":
+        bits = 0
+    elif store == "bytes":
+        bits = 7 if mode == "stochastic" else 8            # the flag needs the eighth bit
+    else:
+        bits = 13 if fmt == "bf16" else 11                  # odd: the 1-bit plane is in play (8+4+1, 8+2+1)
+    assert not packed or bits - (mode == "stochastic") <= full
+    scale = 1.0 if fmt == "bf16" else 256.0
+    kw = dict(lr=1e-3, weight_decay=1e-2, decoupled_wd=True, loss_scale=scale) if kind == "adam" \
+        else dict(lr=1e-2, momentum=0.9, weight_decay=1e-4, loss_scale=scale)
+    lib_cfg, ref_cfg = cfg_pair(kind, fmt, res_bits=bits, packed=packed, round=mode, seed=77, **kw)
+    shapes = []
+    for ly in range(3):
+        shapes += [(ly, 3 * CHUNK + 17), (ly, 2 * CHUNK), (ly, SHORT + 9), (ly, 257), (ly, 8), (ly, 5)]
+    offsets = [1, 3, 0, 3, 1, 3]                            # elements past a 16-byte boundary, per tensor of a layer
+    say("misaligned per-call gradients kind=%s store=%s mode=%s" % (kind, store, mode))
+    devs, hosts = [], []
+    for i, (ly, n) in enumerate(shapes):
+        w0 = synth.gen_weights(n, synth.seed_for(61, i), "cpu", 0.02).numpy()
+        devs.append(DevTensor(w0, gfmt, with_v=(kind == "adam"), layer=ly, grad=torch.zeros(1, dtype=torch.int16, device=DEV),
+                              res_bits=bits, packed=packed, round=mode, seed=77, tensor_id=i))
+        hosts.append(HostTensor(w0, rfmt, with_v=(kind == "adam"), res_bits=bits, packed=packed, round=mode, seed=77,
+                                tensor_id=i))
+        for a in (devs[-1].hi, devs[-1].res, devs[-1].m):
+            assert a.data_ptr() % 16 == 0
+    plan = mpo.Plan([mpo.Tensor(d.hi, d.res, None, d.m, d.v, d.n, d.layer, bits, packed) for d in devs])
+    # one gradient buffer reused by every layer; slot k of a layer starts offsets[k] elements past a 16-byte boundary
+    slot_of, fill = [], 0
+    for k, (ly, n) in enumerate(shapes[:6]):
+        slot_of.append(fill + offsets[k])
+        fill += (n + offsets[k] + 7) // 8 * 8 + 8
+    gbuf = torch.zeros(fill, dtype=torch.int16, device=DEV)
+    assert gbuf.data_ptr() % 16 == 0
+    for t in range(1, 4):
+        for ly in (2, 1, 0):
+            members = [i for i, (l2, _) in enumerate(shapes) if l2 == ly]
+            ptrs = []
+            for k, i in enumerate(members):
+                n = shapes[i][1]
+                g = synth.bits16(synth.gen_grads(n, synth.seed_for(67, i, t), "cpu", 1e-3, fmt, scale))
+                view = gbuf[slot_of[k]:slot_of[k] + n]
+                assert view.data_ptr() % 16 == 2 * offsets[k]
+                view.copy_(dev_u16(g))
+                ptrs.append(view)
+                h = hosts[i]
+                if kind == "adam":
+                    ref.adam_step(h.hi, h.res, g, h.m, h.v, ref_cfg, t, tensor_id=i)
+                else:
+                    ref.sgd_step(h.hi, h.res, g, h.m, ref_cfg, t, tensor_id=i)
+            mpo.mpo_step_layer(plan, ly, lib_cfg, t, grads=ptrs)
+            torch.cuda.synchronize()                        # the buffer is rewritten for the next layer
+        for i, (d, h) in enumerate(zip(devs, hosts)):
+            assert_state_equal(d, h, "tensor %d (n=%d, gradient %d elements off) step %d" % (i, d.n, offsets[i % 6], t))
+    plan.destroy()
 
 
 def test_step_layer_argument_checks_on_device():
@@ -630,7 +715,7 @@ PARTIAL_CASES = [
 @pytest.mark.parametrize("kind,fmt,bits,kw", PARTIAL_CASES,
                          ids=["%s-%s-%s" % (c[0], c[1], "_".join(map(str, c[2]))) for c in PARTIAL_CASES])
 @pytest.mark.parametrize("misalign", [0, 1])
-def test_multi_tensor_list_partial_bits(kind, fmt, bits, kw, misalign):
+def test_multi_tensor_list_partial_bits(kind, fmt, bits, kw, misalign, chunking):
     """Lists whose tensors keep only E extra bits (bytes for E <= 8), several E in one list."""
     gfmt, rfmt = FMT[fmt]
     rng = np.random.default_rng(17 + misalign)
@@ -721,7 +806,7 @@ ROUND_CASES = [
 @pytest.mark.parametrize("kind,fmt,mode,bits,kw", ROUND_CASES,
                          ids=["%s-%s-%s-%s" % (c[0], c[1], c[2], "_".join(map(str, c[3]))) for c in ROUND_CASES])
 @pytest.mark.parametrize("misalign", [0, 1])
-def test_multi_tensor_list_rounding_modes(kind, fmt, mode, bits, kw, misalign):
+def test_multi_tensor_list_rounding_modes(kind, fmt, mode, bits, kw, misalign, chunking):
     """Steps with nearest / stochastic rounding of hi: every stored bit (hi, residual, flag, m, v)
     equals the oracle's; the random stream is selected by seed, step, tensor index and element,
     so stepping the whole list and stepping layer by layer give the same bits."""
@@ -797,7 +882,7 @@ def test_stochastic_argument_checks_on_device():
     plan.destroy()
 
 
-def test_step_can_be_captured_in_a_hip_graph_and_replayed():
+def test_step_can_be_captured_in_a_hip_graph_and_replayed(chunking):
     """A step is nothing but kernel launches on the caller's stream: it can be captured and
     replayed.  The step number is part of the captured arguments, so every replay applies the
     same step's scalars; each replay is checked against the oracle, with eager work and
@@ -892,7 +977,7 @@ PACKED_CASES = [
 @pytest.mark.parametrize("kind,fmt,bits,mode,kw", PACKED_CASES,
                          ids=["%s-%s-%s-%s" % (c[0], c[1], "_".join(map(str, c[2])), c[3]) for c in PACKED_CASES])
 @pytest.mark.parametrize("misalign", [0, 1])
-def test_multi_tensor_list_packed(kind, fmt, bits, mode, kw, misalign):
+def test_multi_tensor_list_packed(kind, fmt, bits, mode, kw, misalign, chunking):
     gfmt, rfmt = FMT[fmt]
     rng = np.random.default_rng(27 + misalign)
     sizes = _small_list(rng, count=21, total=600_000)
@@ -1011,7 +1096,7 @@ def _random_case(rng):
 
 
 @pytest.mark.parametrize("case", range(48))
-def test_random_configurations(case):
+def test_random_configurations(case, chunking):
     rng = np.random.default_rng(9000 + case)
     kind, fmt, gfmt, mode, packed, bits, kw = _random_case(rng)
     misalign = int(rng.integers(0, 4)) if rng.random() < 0.4 else 0

@@ -237,8 +237,8 @@ def test_one_tensor_longer_than_2_to_32():
 
 def test_stochastic_split_beyond_2_to_34_elements():
     """The random stream is indexed by (element / 4) as a 64-bit counter: with more than 2^34 elements
-    its high word is in use.  Sampled elements are rebuilt from the oracle's own pieces: the truncated
-    pair of the value, and the Philox block of the element's counter."""
+    its high word is in use.  Sampled runs of elements are split by the oracle itself, told where in
+    the tensor each run starts."""
     torch.cuda.empty_cache()
     free, total = torch.cuda.mem_get_info()
     if free < 230e9:
@@ -255,23 +255,21 @@ def test_stochastic_split_beyond_2_to_34_elements():
     mpo.mpo_split(w, hi, res, n, fmt=mpo.MPO_BF16, round=mpo.MPO_ROUND_STOCHASTIC, seed=seed, tensor_id=tid)
     torch.cuda.synchronize()
     rng = np.random.default_rng(14)
-    idx = np.concatenate([np.arange(0, 8), np.arange((1 << 34) - 8, (1 << 34) + 8), np.arange(n - 8, n),
-                          rng.integers(1 << 34, n, size=200), rng.integers(0, n, size=200)]).astype(np.int64)
-    ti = torch.from_numpy(idx).to(DEV)
-    x = w[ti].cpu().numpy()
-    got_hi, got_res = synth.bits16(hi[ti]), synth.bits16(res[ti])
-    t_hi, t_res = ref.split(np.ascontiguousarray(x), ref.BF16)              # truncation: hi and all 16 dropped bits
-    ups = 0
-    for k, i in enumerate(idx):
-        block = int(i) // 4
-        u = ref.philox([block & 0xFFFFFFFF, block >> 32, 0, tid], [seed & 0xFFFFFFFF, seed >> 32])[int(i) % 4] >> 16
-        up = int((int(t_hi[k]) & 0x7FFF) < 0x7F7F and u < int(t_res[k]))
-        ups += up
-        assert int(got_hi[k]) == (int(t_hi[k]) + up) & 0xFFFF, "element %d: hi" % i
-        assert int(got_res[k]) == (int(t_res[k]) >> 1) | (up << 15), "element %d: 15 kept bits and the flag" % i
-    assert 0.3 * idx.size < ups < 0.7 * idx.size                            # about half of them round up
+    # runs of 1 to 37 elements at the start, around 2^34 (where the counter's high word changes), at the
+    # end, and at random places on both sides of 2^34; starts of every residue modulo 4
+    starts = [0, 1, 2, 3, (1 << 34) - 19, (1 << 34) - 2, 1 << 34, (1 << 34) + 1, n - 37, n - 3, n - 1]
+    starts += [int(x) for x in rng.integers(1 << 34, n - 40, size=60)] + [int(x) for x in rng.integers(0, n - 40, size=60)]
+    ups = total_checked = 0
+    for k, lo in enumerate(starts):
+        cnt = min(n - lo, 1 + (k * 7) % 37)
+        x = np.ascontiguousarray(w[lo:lo + cnt].cpu().numpy())
+        want_hi, want_res = ref.split(x, ref.BF16, 0, ref.STOCHASTIC, seed, tid, first_index=lo)
+        assert np.array_equal(synth.bits16(hi[lo:lo + cnt]), want_hi), "hi of elements [%d, %d)" % (lo, lo + cnt)
+        assert np.array_equal(synth.bits16(res[lo:lo + cnt]), want_res), "15 kept bits and the flag of [%d, %d)" % (lo, lo + cnt)
+        ups += int((want_res >> 15).sum())
+        total_checked += cnt
+    assert 0.3 * total_checked < ups < 0.7 * total_checked                  # about half of them round up
     out = torch.empty(n, dtype=torch.float32, device=DEV)
-    del ti
     mpo.mpo_merge(hi, res, out, n, fmt=mpo.MPO_BF16, round=mpo.MPO_ROUND_STOCHASTIC)
     # merge undoes the rounding: the value cut to 16 + 15 bits
     w.view(torch.int32).bitwise_and_(-2)                                   # in place: no third 69 GB array

@@ -59,20 +59,21 @@ def test_host_plan_over_a_workload(key):
             at += (t.n * width + 255) // 256 * 256
         specs.append(mpo.Tensor(ptrs[0], ptrs[1], ptrs[2], ptrs[3], ptrs[4], t.n, t.layer))
     plan = mpo.Plan(specs, host_only=True)
-    chunk = plan.chunk_elems
     assert plan.num_params == wl.num_params
-    assert plan.num_chunks == sum((t.n + chunk - 1) // chunk for t in wl.tensors)
     total = 0
     for layer in wl.layers_backward:
         info = plan.layer_info(layer)
         mine = [t.n for t in wl.tensors if t.layer == layer]
         assert info["num_tensors"] == len(mine) and info["num_params"] == sum(mine)
+        # long chunks for the big layers (the transformer blocks of c3 and c4), short ones elsewhere
+        chunk = info["chunk_elems"]
+        assert chunk == (4096 if sum(mine) >= (1 << 26) else 1024)
         assert info["num_chunks"] == sum((n + chunk - 1) // chunk for n in mine)
         total += info["num_chunks"]
     assert total == plan.num_chunks
-    # the table lists every tensor's chunks in order, layer by layer
+    # the table goes layer by layer
     first = plan.chunk(0)
-    assert first[1] == 0 and wl.tensors[first[0]].layer == min(t.layer for t in wl.tensors)
+    assert wl.tensors[first[0]].layer == min(t.layer for t in wl.tensors)
     last = plan.chunk(plan.num_chunks - 1)
     assert wl.tensors[last[0]].layer == max(t.layer for t in wl.tensors)
     plan.destroy()
