@@ -43,7 +43,8 @@ typedef enum {
     MPO_ERR_UNSUPPORTED = 2, /* a combination that is not built (mixed residual widths, ...)  */
     MPO_ERR_ALIAS = 3,       /* buffers that are written overlap each other or an input      */
     MPO_ERR_HIP = 4,         /* a HIP runtime call failed (see mpo_last_hip_error)           */
-    MPO_ERR_NOMEM = 5        /* host or device allocation for a plan failed                  */
+    MPO_ERR_NOMEM = 5,       /* host or device allocation for a plan failed                  */
+    MPO_ERR_TOO_LARGE = 6    /* more tensors or chunks than mpo_adam_step_noalloc has room for */
 } mpo_status;
 
 /* Format of a 16-bit float array (Table 1): bf16 = 1+8+7 bits, 16 extra bits;
@@ -259,6 +260,26 @@ mpo_status mpo_sgd_step(mpo_plan *plan, const mpo_sgd_cfg *cfg, uint64_t step, v
 #define MPO_MAX_LAYER_GRADS 64
 mpo_status mpo_step_layer(mpo_plan *plan, int32_t layer, const void *const *grads, uint64_t ngrads,
                           mpo_opt opt, const void *cfg, uint64_t step, void *hip_stream);
+
+/* For callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  The same step as mpo_adam_step (one
+ * launch over the whole list, same results bit for bit) without a plan: the list is given
+ * on every call, and the chunk table and descriptors that a plan would hold in allocated
+ * memory are rebuilt, by a small kernel on `hip_stream`, in a fixed array inside the
+ * library's device image (16 MiB + 64 KiB per GPU, held until the process ends).  Nothing
+ * is allocated, freed or copied, on the host or on the device; the call only enqueues
+ * kernels (1 + ceil(nt / 32) of them).
+ * Every tensor needs grad, m and v.  Limits: at most MPO_NOALLOC_MAX_TENSORS tensors and
+ * MPO_NOALLOC_MAX_CHUNKS chunks (chunk lengths as described above: about 8.6e9 parameters
+ * in layers of 2^26 or more), else MPO_ERR_TOO_LARGE and nothing is enqueued.
+ * All calls on one GPU share that GPU's array: calls whose kernels may overlap in time
+ * (different streams or threads) race on it and must be ordered by the caller.  The first
+ * call on a device looks the array's address up and must not run under stream capture;
+ * later calls may be captured. */
+#define MPO_NOALLOC_MAX_TENSORS 1024
+#define MPO_NOALLOC_MAX_CHUNKS (1u << 21)
+mpo_status mpo_adam_step_noalloc(const mpo_tensor *tensors, uint64_t nt, const mpo_adam_cfg *cfg, uint64_t step,
+                                 void *hip_stream);
 
 const char *mpo_status_string(mpo_status s);
 /* hipError_t (as int) of the most recent failing HIP call on this thread, 0 if none. */

@@ -23,6 +23,7 @@ MPO_ERR_UNSUPPORTED = 2
 MPO_ERR_ALIAS = 3
 MPO_ERR_HIP = 4
 MPO_ERR_NOMEM = 5
+MPO_ERR_TOO_LARGE = 6
 
 MPO_BF16 = 0
 MPO_FP16 = 1
@@ -35,6 +36,8 @@ MPO_OPT_ADAM = 0
 MPO_OPT_SGD = 1
 
 MPO_MAX_LAYER_GRADS = 64
+MPO_NOALLOC_MAX_TENSORS = 1024
+MPO_NOALLOC_MAX_CHUNKS = 1 << 21
 
 
 class mpo_tensor(ctypes.Structure):
@@ -84,6 +87,8 @@ EXPORTS = {
     "mpo_sgd_step": ([ctypes.c_void_p, ctypes.POINTER(mpo_sgd_cfg), ctypes.c_uint64, ctypes.c_void_p], ctypes.c_int),
     "mpo_step_layer": ([ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint64,
                         ctypes.c_int, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p], ctypes.c_int),
+    "mpo_adam_step_noalloc": ([ctypes.POINTER(mpo_tensor), ctypes.c_uint64, ctypes.POINTER(mpo_adam_cfg), ctypes.c_uint64,
+                               ctypes.c_void_p], ctypes.c_int),
     "mpo_status_string": ([ctypes.c_int], ctypes.c_char_p),
     "mpo_last_hip_error": ([], ctypes.c_int),
 }
@@ -273,6 +278,19 @@ class Plan:
 def mpo_adam_step(plan: Plan, cfg: AdamCfg, step: int, stream=None):
     c = cfg.c()
     _check(lib.mpo_adam_step(plan._h, ctypes.byref(c), step, _stream(stream)), "mpo_adam_step")
+
+
+def mpo_adam_step_noalloc(tensors, cfg: AdamCfg, step: int, stream=None):
+    """mpo_adam_step without a plan, for callers that cannot allocate device memory.  `tensors` is a
+    sequence of Tensor, or an array made by tensor_array() (marshalled once, reused on every call)."""
+    arr, n = tensors if isinstance(tensors, tuple) else (_tensor_array(tensors), len(tensors))
+    c = cfg.c()
+    _check(lib.mpo_adam_step_noalloc(arr, n, ctypes.byref(c), step, _stream(stream)), "mpo_adam_step_noalloc")
+
+
+def tensor_array(tensors: Sequence[Tensor]):
+    """A C array of mpo_tensor for mpo_adam_step_noalloc, with its length."""
+    return _tensor_array(tensors), len(tensors)
 
 
 def mpo_sgd_step(plan: Plan, cfg: SgdCfg, step: int, stream=None):

@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmpo.so")
 # (source, extra flags): the step kernels are one source compiled in four parts (Adam / SGD, gradient
 # pointers from the plan / per call) so that the parts build side by side
-PARTS = [("mpo_host.cpp", ()), ("mpo_split_merge.hip", ()),
+PARTS = [("mpo_host.cpp", ()), ("mpo_split_merge.hip", ()), ("mpo_noalloc.hip", ()),
          ("mpo_step.hip", ("-DMPO_PART_OPT=0", "-DMPO_PART_OV=0")), ("mpo_step.hip", ("-DMPO_PART_OPT=0", "-DMPO_PART_OV=1")),
          ("mpo_step.hip", ("-DMPO_PART_OPT=1", "-DMPO_PART_OV=0")), ("mpo_step.hip", ("-DMPO_PART_OPT=1", "-DMPO_PART_OV=1"))]
 SOURCES = sorted({os.path.join(CSRC, src) for src, _ in PARTS})

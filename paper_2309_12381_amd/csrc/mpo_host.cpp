@@ -573,6 +573,7 @@ const char *mpo_status_string(mpo_status s)
     case MPO_ERR_ALIAS: return "buffers overlap";
     case MPO_ERR_HIP: return "HIP runtime error";
     case MPO_ERR_NOMEM: return "out of memory";
+    case MPO_ERR_TOO_LARGE: return "list too large for the entry point that allocates nothing";
     }
     return "unknown status";
 }

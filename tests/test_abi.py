@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported():
 
 def test_status_strings():
     seen = set()
-    for s in range(6):
+    for s in range(7):
         msg = mpo.lib.mpo_status_string(s).decode()
         assert msg and msg not in seen
         seen.add(msg)
