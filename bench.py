@@ -25,46 +25,77 @@ SGD_BYTES_PER_PARAM = 18          # read hi, res, grad, momentum buffer; write h
 ADAM_BYTES_PER_PARAM = 26         # read hi, res, grad (2 B each), m, v (4 B each); write hi, res, m, v
 # HBM-side bytes per parameter of the Adam step kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # each scaled by what the same counter reads for a plain kernel of known size (FETCH_SIZE x 2.000, WRITE_SIZE
-# x 1.000 on this GPU): 14.03 read + 12.00 written.  Source: profiles/step_kernel_adam_bf16_c3_pmc_traffic.txt.
-# It cannot be collected inside a timed run, so the figure is carried here.
-MEASURED_TRAFFIC_BYTES_PER_PARAM = {"c3": 26.03}
+# x 1.000 on this GPU): 14.12 read + 12.00 written.  Source: profiles/step_kernel_adam_bf16_c3_pmc_traffic.txt.
+# Counters cannot be collected inside a timed run, so the figure is carried here from that file and the JSON
+# line says so (roofline.traffic_source).
+MEASURED_TRAFFIC_BYTES_PER_PARAM = {"c3": 26.12}
+TRAFFIC_SOURCE = "carried from profiles/step_kernel_adam_bf16_c3_pmc_traffic.txt (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE), not measured in this run"
 
 
-def cpu_baseline(wl, sample_params: int, steps: int):
-    """The oracle as it stands, on host cores, on a slice of the same workload: elementwise work,
-    so a slice of one tensor is a fair sample.  Threads split the slice; each calls the C routine."""
+def host_threads():
+    """Host threads the oracle's timing may use: what the machine grants this job (OMP_NUM_THREADS where the
+    job's CPU share is announced that way, else the CPUs this process may run on)."""
+    env = os.environ.get("OMP_NUM_THREADS", "")
+    if env.isdigit() and int(env) > 0:
+        return int(env), "OMP_NUM_THREADS"
+    try:
+        return len(os.sched_getaffinity(0)), "sched_getaffinity"
+    except AttributeError:
+        return os.cpu_count() or 1, "cpu_count"
+
+
+def _oracle_rate(wl, n: int, steps: int, threads: int):
+    """params/s of the oracle's Adam step on n parameters of this workload's value distributions, the
+    array sliced over `threads` host threads (elementwise work: a slice per thread, each calling the C routine)."""
     import numpy as np
     from concurrent.futures import ThreadPoolExecutor
     from oracle import ref
     from paper_2309_12381_amd import synth
     rfmt = ref.BF16 if wl.fmt == "bf16" else ref.FP16
-    n = sample_params
     w = synth.gen_weights(n, 99, "cpu", wl.weight_std).numpy()
     g = synth.bits16(synth.gen_grads(n, 98, "cpu", wl.grad_std, wl.fmt, wl.loss_scale))
     cfg = ref.AdamCfg(lr=1e-3, weight_decay=wl.weight_decay, decoupled_wd=(wl.optimizer == "adamw"),
                       loss_scale=wl.loss_scale, weight_fmt=rfmt, grad_fmt=rfmt)
-    cores = max(1, min(16, os.cpu_count() or 1))
-    out = {}
-    for label, k in (("1", 1), ("all", cores)):
-        hi, res = ref.split(w, rfmt)
-        m = np.zeros(n, np.float32)
-        v = np.zeros(n, np.float32)
-        bounds = np.linspace(0, n, k + 1).astype(np.int64)
+    hi, res = ref.split(w, rfmt)
+    del w
+    m = np.zeros(n, np.float32)
+    v = np.zeros(n, np.float32)
+    bounds = np.linspace(0, n, threads + 1).astype(np.int64)
 
-        def run(i, t):
-            lo, up = int(bounds[i]), int(bounds[i + 1])
-            ref.adam_step(hi[lo:up], res[lo:up], g[lo:up], m[lo:up], v[lo:up], cfg, t)
-        with ThreadPoolExecutor(k) as ex:
-            list(ex.map(lambda i: run(i, 1), range(k)))          # warm the pages
-            t0 = time.perf_counter()
-            for t in range(2, 2 + steps):
-                list(ex.map(lambda i: run(i, t), range(k)))
-            dt = time.perf_counter() - t0
-        out[label] = n * steps / dt
-    return {"value": out["all"], "unit": "params/s", "cores": cores, "kind": "oracle",
-            "value_1core": out["1"], "host_GBps": out["all"] * ADAM_BYTES_PER_PARAM / 1e9,
-            "sample": "%d params of the same value distributions, %d Adam steps, oracle/mpo_ref.c as built for "
-                      "the tests, slice-parallel over %d host threads" % (n, steps, cores)}
+    def run(i, t):
+        lo, up = int(bounds[i]), int(bounds[i + 1])
+        ref.adam_step(hi[lo:up], res[lo:up], g[lo:up], m[lo:up], v[lo:up], cfg, t)
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(lambda i: run(i, 1), range(threads)))          # warm the pages
+        t0 = time.perf_counter()
+        for t in range(2, 2 + steps):
+            list(ex.map(lambda i: run(i, t), range(threads)))
+        dt = time.perf_counter() - t0
+    return n * steps / dt
+
+
+def cpu_baseline(wl, sample_params: int, steps: int, others: bool):
+    """The oracle as it stands, on host cores, on a slice of the same workload (elementwise work, so a
+    slice of one tensor is a fair sample), once on one thread and once on every thread the job is granted.
+    `others`: also the small configurations c0, c1 and c2 in full (their whole parameter count, same value
+    distributions), so that every configuration the oracle can hold has a CPU figure."""
+    from paper_2309_12381_amd import synth
+    cores, source = host_threads()
+    one = _oracle_rate(wl, sample_params, steps, 1)
+    many = _oracle_rate(wl, sample_params, steps, cores)
+    out = {"value": many, "unit": "params/s", "cores": cores, "cores_from": source, "kind": "oracle",
+           "value_1core": one, "host_GBps": many * ADAM_BYTES_PER_PARAM / 1e9,
+           "sample": "%d params of the same value distributions, %d Adam steps, oracle/mpo_ref.c as built for "
+                     "the tests, slice-parallel over %d host threads" % (sample_params, steps, cores)}
+    if others:
+        full = {}
+        for key, k in (("c0", 10), ("c1", 5), ("c2", 2)):
+            w2 = synth.workload(key)
+            full[key] = {"params": w2.num_params, "steps": k,
+                         "params_per_s_1core": _oracle_rate(w2, w2.num_params, k, 1),
+                         "params_per_s_all_cores": _oracle_rate(w2, w2.num_params, k, cores)}
+        out["full_configs"] = full
+    return out
 
 
 def layer_breakdown(st, cfg, stream, step_no, bpp):
@@ -91,6 +122,35 @@ def layer_breakdown(st, cfg, stream, step_no, bpp):
     if small:
         out["small_launches"] = [{"layer": s[3], "params": s[2], "us": s[1] * 1e3} for s in small]
     return out
+
+
+def graph_run(st, cfg, stream, step_no, steps, P, bpp):
+    """The same `steps` optimizer steps captured once in a HIP graph (each with its own step number) and
+    replayed: what is left when the host's launch latency is taken out.  Small lists only."""
+    import torch
+    from paper_2309_12381_amd import binding as mpo
+    side = torch.cuda.Stream()
+    side.wait_stream(stream)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for k in range(steps):
+            if isinstance(cfg, mpo.SgdCfg):
+                mpo.mpo_sgd_step(st.plan, cfg, step_no + 1 + k, stream=torch.cuda.current_stream())
+            else:
+                mpo.mpo_adam_step(st.plan, cfg, step_no + 1 + k, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    reps = 20
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        graph.replay()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / (reps * steps)
+    return {"ms_per_step": dt * 1e3, "params_per_s": P / dt, "GBps": bpp * P / dt / 1e9,
+            "frac_of_peak": bpp * P / dt / 1e9 / PEAK_HBM_GBPS,
+            "what": "%d steps captured in one HIP graph, %d replays (the step numbers are fixed in the graph: a "
+                    "measurement of launch cost, not a way to train)" % (steps, reps)}
 
 
 def traffic_probe(st, stream, with_v, bpp, steps):
@@ -200,6 +260,114 @@ def fused_backward_run(a):
     }), flush=True)
 
 
+def probe_streams_run(a):
+    """What the memory system gives the step's kind of traffic, and why the step kernel has the shape it
+    has: plain read-only / write-only / in-place streams and the arithmetic-free copy of the Adam step's
+    traffic (csrc/stream_probe.hip), with the arrays placed on purpose in one, two or three thirds of the
+    device memory, then every variant of the launch shape on the two-thirds placement.  Must be the first
+    thing a fresh process does on the GPU: ONE allocation of (almost) the whole memory is taken, which in
+    a fresh process is laid out in order, and arrays are carved out of its thirds.  Prints one JSON line."""
+    import torch
+    from paper_2309_12381_amd import probe
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(0)
+    GiB = 1 << 30
+    props = torch.cuda.get_device_properties(0)
+    free, total_mem = torch.cuda.mem_get_info()
+    third = 96 * GiB
+    whole = None
+    for gib in (272, 200):
+        if free > (gib + 4) * GiB:
+            whole = torch.empty(gib * GiB, dtype=torch.uint8, device=dev)
+            break
+    if whole is None:
+        print("bench.py --probe-streams: needs 204 GiB of free device memory in a fresh process", file=sys.stderr)
+        sys.exit(1)
+    thirds = whole.numel() // third + (1 if whole.numel() % third >= 24 * GiB else 0)
+    SLOT = 10 * GiB
+
+    def at(region, slot, nbytes):
+        """nbytes at slot `slot` (10 GiB apart, from 4 GiB on) of third `region` of the allocation."""
+        off = region * third + 4 * GiB + slot * SLOT
+        assert nbytes <= SLOT and off + nbytes <= whole.numel()
+        return whole[off:off + nbytes]
+
+    stream = torch.cuda.current_stream()
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    for r in range(min(thirds, 3)):
+        for sl in range(5 if r < 2 else 2):
+            at(r, sl, 8 * GiB).fill_(0x11)
+    torch.cuda.synchronize()
+
+    default_reps = a.steps or 10
+
+    def timed(fn, nbytes, reps=None):
+        reps = reps or default_reps
+        fn(); fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        e1.synchronize()
+        return nbytes * reps / e0.elapsed_time(e1) / 1e6          # GB/s
+
+    out = {"metric": "achieved HBM GB/s of plain streams and of the Adam step's traffic without arithmetic, by placement "
+                     "and by launch shape", "unit": "GB/s", "n_gpus": 1, "data": "synthetic",
+           "device": "%s (%d CUs)" % (props.name, props.multi_processor_count),
+           "allocation_GiB": whole.numel() // GiB, "thirds_GiB": 96, "rows": []}
+
+    def row(kind, what, gbps):
+        out["rows"].append({"kind": kind, "what": what, "GBps": round(gbps, 1), "frac_of_8TBps": round(gbps / PEAK_HBM_GBPS, 4)})
+        print("%-10s %-100s %8.1f GB/s" % (kind, what, gbps), file=sys.stderr, flush=True)
+
+    # ---- plain streams: k arrays of 2 GiB in lock step -------------------------------------------------
+    nb = 2 * GiB
+    modes = (("read", probe.PLAIN_READ, 1), ("write", probe.PLAIN_WRITE, 1), ("in-place", probe.PLAIN_INPLACE, 2))
+    layouts = [("1 array in one third", [(0, 0)]), ("2 arrays in one third", [(0, 0), (0, 1)]),
+               ("4 arrays in one third", [(0, 0), (0, 1), (0, 2), (0, 3)]),
+               ("2 arrays, one in each of two thirds", [(0, 0), (1, 0)]),
+               ("4 arrays, two in each of two thirds", [(0, 0), (0, 1), (1, 0), (1, 1)])]
+    if thirds >= 3:
+        layouts.append(("3 arrays, one in each of three thirds", [(0, 0), (1, 0), (2, 0)]))
+    # a nearly idle memory system for comparison (for counter runs: what one read costs without queueing)
+    row("read", "light load: 64 workgroups, 1 MiB", timed(lambda: probe.plain_streams(probe.PLAIN_READ, [at(0, 0, nb)], 1 << 20, sink, stream), 1 << 20))
+    for name, mode, passes in modes:
+        for what, where in layouts:
+            arrs = [at(r, sl, nb) for r, sl in where]
+            row(name, what, timed(lambda: probe.plain_streams(mode, arrs, nb, sink, stream), passes * nb * len(arrs)))
+
+    # ---- the Adam step's traffic (26 B per parameter, in place), by placement --------------------------
+    n = 1 << 28
+    placements = [("all five arrays in one third", dict(hi=0, res=0, grad=0, m=0, v=0)),
+                  ("hi, m | res, v, grad", dict(hi=0, res=1, grad=1, m=0, v=1)),
+                  ("hi, m, grad | res, v", dict(hi=0, res=1, grad=0, m=0, v=1)),
+                  ("hi, res, grad | m, v", dict(hi=0, res=0, grad=0, m=1, v=1)),
+                  ("hi, res, m | v, grad", dict(hi=0, res=0, grad=1, m=0, v=1))]
+    if thirds >= 3:
+        placements.append(("hi, m | res, v | grad", dict(hi=0, res=1, grad=2, m=0, v=1)))
+
+    def arrays(pl):
+        slot = dict(hi=0, res=1, grad=2, m=3, v=4)
+        if pl["grad"] == 2:
+            slot["grad"] = 0
+        return [at(pl[k], slot[k], n * (2 if k in ("hi", "res", "grad") else 4)) for k in ("hi", "res", "grad", "m", "v")]
+    for what, pl in placements:
+        hi, res, grad, m, v = arrays(pl)
+        row("adam-copy", what, timed(lambda: probe.stream_probe(hi, res, grad, m, v, n, stream), 26 * n))
+    hi, res, grad, m, v = arrays(placements[1][1])
+    n_long = 1 << 31
+    hi_l, res_l, grad_l, m_l, v_l = [at(r, sl, n_long * w) for r, sl, w in ((0, 0, 2), (1, 1, 2), (1, 2, 2), (0, 3, 4), (1, 4, 4))]
+    row("adam-copy", "hi, m | res, v, grad; one launch over 2^31 parameters (55.8 GB)",
+        timed(lambda: probe.stream_probe(hi_l, res_l, grad_l, m_l, v_l, n_long, stream), 26 * n_long, reps=min(3, default_reps)))
+    # ---- variants of the launch shape, on the two-thirds placement -------------------------------------
+    cus = props.multi_processor_count
+    for i, what in enumerate(probe.variants()):
+        row("variant", what, timed(lambda: probe.stream_variant(i, hi, res, grad, m, v, n, cus, stream), 26 * n))
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -218,16 +386,29 @@ def main():
                     help="rounding of the 16-bit value: trunc is the method's base mode and the headline")
     ap.add_argument("--fresh-grads", action="store_true",
                     help="regenerate each layer's gradients inside the loop (adds generator kernels to the timing)")
+    ap.add_argument("--chunk", default="auto", choices=["auto", "short", "long"],
+                    help="chunk length per workgroup: auto = 4096 parameters in layers of 2^26 parameters or more and 1024 "
+                         "in smaller ones (the library's default); short / long = 1024 / 4096 everywhere")
     ap.add_argument("--no-place", action="store_true",
                     help="allocate the state arrays one after the other instead of dividing them between two "
                          "HBM regions (paper_2309_12381_amd/placement.py)")
     ap.add_argument("--fused-backward", action="store_true",
                     help="instead of the optimizer-only benchmark: a real PyTorch backward with the step fused into "
                          "it (Section 3.2) against the classical schedule; see --width, --depth, --tokens")
+    ap.add_argument("--probe-streams", action="store_true",
+                    help="instead of the benchmark: plain and step-shaped streams by placement in the device memory and by "
+                         "launch shape (csrc/stream_probe.hip); takes (almost) all device memory, run it in a fresh process")
     ap.add_argument("--width", type=int, default=4096)
     ap.add_argument("--depth", type=int, default=16)
     ap.add_argument("--tokens", type=int, default=1024)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cpu-full-configs", action="store_true",
+                    help="CPU baseline on the sample only, not on c0, c1 and c2 in full as well")
+    ap.add_argument("--no-end-to-end", action="store_true",
+                    help="skip the extra steps that regenerate every gradient inside the loop")
+    ap.add_argument("--graph", action="store_true",
+                    help="single-launch workloads (c0, c1, c2): also capture the timed steps in ONE HIP graph and time "
+                         "its replays (launch latency taken out)")
     ap.add_argument("--no-breakdown", action="store_true", help="skip the per-layer breakdown step")
     ap.add_argument("--no-probe", action="store_true", help="skip the arithmetic-free traffic probe")
     ap.add_argument("--cpu-sample", type=int, default=202_383_360,
@@ -246,6 +427,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if a.probe_streams:
+        probe_streams_run(a)
+        return
     if a.fused_backward:
         fused_backward_run(a)
         return
@@ -258,7 +442,8 @@ def main():
     props = torch.cuda.get_device_properties(0)
     t_setup = time.perf_counter()
     st = harness.ModelState(wl, dev, res_bits=a.res_bits, res_packed=a.res_packed,
-                            round={"trunc": 0, "nearest": 1, "stochastic": 2}[a.round], place=not a.no_place)
+                            round={"trunc": 0, "nearest": 1, "stochastic": 2}[a.round], place=not a.no_place,
+                            small_layer_params={"auto": None, "short": (1 << 64) - 1, "long": 1}[a.chunk])
     if wl.per_layer:
         # the reused buffer holds one (largest) layer's worth of gradient values, read by every layer
         st.grad.normal_(0.0, wl.grad_std * wl.loss_scale, generator=synth.generator(7, dev))
@@ -311,7 +496,7 @@ def main():
                               % (wl.fmt, a.res_bits or (13 if wl.fmt == "fp16" else 15 if a.round == "stochastic" else 16),
                                  8 * st.res_bytes)),
                    "optimizer": wl.optimizer if a.optimizer == "adam" else "sgd-momentum", "round": a.round, "loss_scale": wl.loss_scale,
-                   "launches_per_step": launches // steps, "per_layer": wl.per_layer,
+                   "launches_per_step": launches // steps, "per_layer": wl.per_layer, "chunk": a.chunk,
                    "fresh_grads_in_loop": bool(a.fresh_grads), "resident_GB": st.resident_bytes / 1e9,
                    "placement": st.placement,
                    "device": "%s (%d CUs) %s" % (props.name, props.multi_processor_count,
@@ -320,13 +505,36 @@ def main():
                      "frac": achieved / PEAK_HBM_GBPS,
                      "traffic": (MEASURED_TRAFFIC_BYTES_PER_PARAM[wl.key] * P * steps / launches
                                  if wl.key in MEASURED_TRAFFIC_BYTES_PER_PARAM and a.optimizer == "adam" and st.res_bytes == 2
-                                 and not a.res_packed else None),
+                                 and not a.res_packed and a.chunk == "auto" else None),
+                     "traffic_source": TRAFFIC_SOURCE,
                      "kernel": "step_kernel<%s,%s>" % (a.optimizer, wl.fmt), "bytes_per_param": bpp,
                      "bytes_per_launch": bytes_per_launch, "avg_launch_ms": ev_ms / launches,
                      "event_ms": ev_ms, "launches": launches,
                      "step_ms_median": step_ms[len(step_ms) // 2], "step_ms_min": step_ms[0]},
         "setup_s": setup_s,
     }
+    if res["roofline"]["traffic"] is None:
+        res["roofline"]["traffic_source"] = None
+    if not a.fresh_grads and not a.no_end_to_end:
+        # the same steps with backward's stand-in inside the loop: every layer's gradient is regenerated (seeded
+        # normal draws cast to the gradient format, torch kernels) just before that layer's step
+        k = 3 if wl.per_layer else min(steps, 10)
+        step_no += 1
+        st.step(step_no, cfg, stream, fresh_grads=True)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(k):
+            step_no += 1
+            st.step(step_no, cfg, stream, fresh_grads=True)
+        torch.cuda.synchronize()
+        e2e = (time.perf_counter() - t1) / k
+        res["end_to_end_with_gradient_generation"] = {
+            "ms_per_step": e2e * 1e3, "params_per_s": P / e2e, "steps": k,
+            "what": "optimizer steps with each layer's gradient regenerated inside the loop by torch's generator and "
+                    "cast kernels (the stand-in for backward); the headline times the library's launches alone"}
+    if a.graph and not wl.per_layer:
+        res["hip_graph"] = graph_run(st, cfg, stream, step_no, steps, P, bpp)
+        step_no += steps
     if wl.per_layer and not a.no_breakdown:
         res["breakdown"] = layer_breakdown(st, cfg, stream, step_no + 1, bpp)
     if st.res_bytes == 2 and not a.res_packed and not a.no_probe:
@@ -342,7 +550,7 @@ def main():
         torch.cuda.synchronize()
         res["calibration"] = "3 x torch.add(src, 1.0, out=dst) on 2^28 fp32: 1 GiB read + 1 GiB written each"
     if not a.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(wl, a.cpu_sample, 5)
+        res["cpu_baseline"] = cpu_baseline(wl, a.cpu_sample, 5, others=not a.no_cpu_full_configs)
     print(json.dumps(res), flush=True)
 
 

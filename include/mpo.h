@@ -214,8 +214,9 @@ mpo_status mpo_plan_create_host(const mpo_tensor *tensors, uint64_t nt, mpo_plan
 
 /* mpo_plan_create with options; opts == NULL or a zero field means the default.
  *   small_layer_params  layers with fewer parameters than this are cut into chunks of 1024
- *                       parameters instead of 4096 (default 2^26; 1 = long chunks everywhere,
- *                       UINT64_MAX = short chunks everywhere).  A tuning knob: results do not
+ *                       parameters instead of 4096 (default UINT64_MAX = short chunks
+ *                       everywhere, the faster cut on MI355X; 1 = long chunks everywhere, a
+ *                       chunk table a quarter the size).  A tuning knob: results do not
  *                       depend on it.
  *   host_only           != 0: as mpo_plan_create_host. */
 typedef struct {
@@ -225,9 +226,9 @@ typedef struct {
 mpo_status mpo_plan_create_opts(const mpo_tensor *tensors, uint64_t nt, const mpo_plan_opts *opts, mpo_plan **out);
 
 /* Layout queries (host side, no HIP call).  One workgroup handles one chunk.  All
- * chunks of a layer have the same length: 4096 parameters (what mpo_plan_chunk_elems
- * returns, the longest), or 1024 in layers of fewer than 2^26 parameters, which fill
- * the GPU better with more, shorter chunks.  Chunks are numbered in launch order:
+ * chunks of a layer have the same length: 1024 parameters by default, or 4096 (what
+ * mpo_plan_chunk_elems returns, the longest) in layers of at least
+ * mpo_plan_opts.small_layer_params parameters.  Chunks are numbered in launch order:
  * layer by layer; within a layer first every tensor's last, shorter chunk (if its
  * length is not a multiple of the chunk length), then the full chunks tensor by
  * tensor.  Chunk i covers `count` elements from element `first` of tensor `tensor`
@@ -270,8 +271,9 @@ mpo_status mpo_step_layer(mpo_plan *plan, int32_t layer, const void *const *grad
  * is allocated, freed or copied, on the host or on the device; the call only enqueues
  * kernels (1 + ceil(nt / 32) of them).
  * Every tensor needs grad, m and v.  Limits: at most MPO_NOALLOC_MAX_TENSORS tensors and
- * MPO_NOALLOC_MAX_CHUNKS chunks (chunk lengths as described above: about 8.6e9 parameters
- * in layers of 2^26 or more), else MPO_ERR_TOO_LARGE and nothing is enqueued.
+ * MPO_NOALLOC_MAX_CHUNKS chunks (here layers of 2^26 parameters or more get the long
+ * chunks: about 8.6e9 parameters in such layers), else MPO_ERR_TOO_LARGE and nothing is
+ * enqueued.
  * All calls on one GPU share that GPU's array: calls whose kernels may overlap in time
  * (different streams or threads) race on it and must be ordered by the caller.  The first
  * call on a device looks the array's address up and must not run under stream capture;

@@ -44,6 +44,10 @@ def needs_build() -> bool:
     return _stale(LIB, SOURCES + HEADERS)
 
 
+def probe_needs_build() -> bool:
+    return _stale(PROBE_LIB, PROBE_SOURCES)
+
+
 def _compile(sources, out, extra=()):
     tmp = out + ".tmp.%d" % os.getpid()
     subprocess.check_call([HIPCC, *FLAGS, "-shared", *extra, "-x", "hip", *sources, "-o", tmp])

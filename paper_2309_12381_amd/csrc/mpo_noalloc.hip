@@ -132,7 +132,7 @@ extern "C" mpo_status mpo_adam_step_noalloc(const mpo_tensor *tensors, uint64_t 
         descs[k] = make_desc(tensors[i], i);
         layer[k] = tensors[i].layer;
     }
-    const uint64_t total = layout_chunks(descs, layer, nt, kSmallLayerParams, lay);
+    const uint64_t total = layout_chunks(descs, layer, nt, kNoallocSmallLayerParams, lay);
     if (total == UINT64_MAX) return MPO_ERR_INVALID_ARG;
     if (total > MPO_NOALLOC_MAX_CHUNKS) return MPO_ERR_TOO_LARGE;
     if (total == 0) return MPO_OK;

@@ -42,7 +42,7 @@ class ModelState:
 
     def __init__(self, wl: synth.Workload, device="cuda:0", seed: int = 2309, keep_w32_samples=None,
                  res_bits: int = 0, round: int = mpo.MPO_ROUND_TRUNC, rng_seed: int = 0x2309_12381,
-                 res_packed: bool = False, place: bool = True):
+                 res_packed: bool = False, place: bool = True, small_layer_params=None):
         self.wl = wl
         self.res_packed = res_packed        # extra bits stored in packed planes (Section 3.1, Figure 1)
         self.round = round                  # how hi is rounded (Section 3.1, last paragraph)
@@ -96,7 +96,7 @@ class ModelState:
         self.plan = mpo.Plan([mpo.Tensor(self.hi[tv.off:], self.res[self.res_off[i]:], self.grad[tv.goff:],
                                          self.m[tv.off:], self.v[tv.off:], tv.spec.n, tv.spec.layer, res_bits,
                                          res_packed)
-                              for i, tv in enumerate(self.views)])
+                              for i, tv in enumerate(self.views)], small_layer_params=small_layer_params)
         self.layers_backward = wl.layers_backward
         self.by_layer: Dict[int, List[int]] = {}
         for i, tv in enumerate(self.views):

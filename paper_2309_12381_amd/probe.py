@@ -16,12 +16,21 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
-            from . import build as _build          # nothing built yet: build once (needs hipcc)
-            _build.build_probe()
+        from . import build as _build
+        if not os.path.exists(LIB_PATH) or (_build.probe_needs_build() and os.path.exists(_build.HIPCC)):
+            _build.build_probe()                   # nothing built yet, or older than its source: build (needs hipcc)
         _lib = ctypes.CDLL(LIB_PATH)
         _lib.mpo_probe_stream.restype = ctypes.c_int
         _lib.mpo_probe_stream.argtypes = [ctypes.c_void_p] * 5 + [ctypes.c_longlong, ctypes.c_void_p]
+        _lib.mpo_probe_num_variants.restype = ctypes.c_int
+        _lib.mpo_probe_variant_name.restype = ctypes.c_char_p
+        _lib.mpo_probe_variant_name.argtypes = [ctypes.c_int]
+        _lib.mpo_probe_variant.restype = ctypes.c_int
+        _lib.mpo_probe_variant.argtypes = [ctypes.c_int] + [ctypes.c_void_p] * 5 + [ctypes.c_longlong, ctypes.c_int,
+                                                                                   ctypes.c_void_p]
+        _lib.mpo_probe_plain.restype = ctypes.c_int
+        _lib.mpo_probe_plain.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_ulonglong,
+                                         ctypes.c_void_p, ctypes.c_void_p]
     return _lib
 
 
@@ -33,3 +42,30 @@ def stream_probe(hi, res, grad, m, v, n: int, stream=None) -> None:
                                   stream.cuda_stream if stream is not None else None)
     if rc != 0:
         raise RuntimeError("mpo_probe_stream failed (%d)" % rc)
+
+
+def variants():
+    """Descriptions of the launch-shape variants mpo_probe_variant knows, in order (0 = the step kernel's shape)."""
+    lib = _load()
+    return [lib.mpo_probe_variant_name(i).decode() for i in range(lib.mpo_probe_num_variants())]
+
+
+def stream_variant(variant: int, hi, res, grad, m, v, n: int, compute_units: int, stream=None) -> None:
+    """The Adam-shaped traffic over the first n - n % 131072 elements in variant `variant` of the launch shape."""
+    rc = _load().mpo_probe_variant(variant, hi.data_ptr(), res.data_ptr(), grad.data_ptr(), m.data_ptr(), v.data_ptr(), n,
+                                   compute_units, stream.cuda_stream if stream is not None else None)
+    if rc != 0:
+        raise RuntimeError("mpo_probe_variant failed (%d)" % rc)
+
+
+PLAIN_READ, PLAIN_WRITE, PLAIN_INPLACE = 0, 1, 2
+
+
+def plain_streams(mode: int, arrays, nbytes: int, sink, stream=None) -> None:
+    """k (1 to 8) device arrays of nbytes bytes each walked in lock step: read, written, or read and written back.
+    `sink`: a 4-byte device tensor."""
+    ptrs = (ctypes.c_void_p * len(arrays))(*[a.data_ptr() for a in arrays])
+    rc = _load().mpo_probe_plain(mode, ptrs, len(arrays), nbytes, sink.data_ptr(),
+                                 stream.cuda_stream if stream is not None else None)
+    if rc != 0:
+        raise RuntimeError("mpo_probe_plain failed (%d)" % rc)

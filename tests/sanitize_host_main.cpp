@@ -72,7 +72,8 @@ int main()
             chunks += (ts[i].n + ce - 1) / ce;
         }
         mpo_plan *p = nullptr;
-        CHECK(mpo_plan_create_host(ts.data(), nt, &p) == MPO_OK && p);
+        const mpo_plan_opts mixed = {1ull << 26, 1};        /* host only; long chunks from 2^26 parameters on */
+        CHECK(mpo_plan_create_opts(ts.data(), nt, &mixed, &p) == MPO_OK && p);
         CHECK(mpo_plan_num_params(p) == total && mpo_plan_num_chunks(p) == chunks);
         uint64_t seen = 0, covered = 0;
         for (uint64_t c = 0; c < chunks; ++c) {

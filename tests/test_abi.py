@@ -165,7 +165,7 @@ def test_plan_layout_covers_every_element_once_in_layer_order():
     ts = [T(i, n=n, layer=l) for i, (n, l) in enumerate(zip(sizes, layers))]
     far = 0x100000000000                            # the large tensor needs room: arrays 1 GiB apart
     ts[8] = T(8, n=big, layer=5, hi=far, res=far + (1 << 30), grad=far + (2 << 30), m=far + (3 << 30), v=far + (4 << 30))
-    p = _host_plan(ts)
+    p = mpo.Plan(ts, host_only=True, small_layer_params=1 << 26)     # mixed: long chunks from 2^26 parameters on
     assert p.chunk_elems == ce0 == 4096
     assert p.num_params == sum(sizes)
     clen = {l: (ce0 if sum(n for n, l2 in zip(sizes, layers) if l2 == l) >= (1 << 26) else small) for l in set(layers)}
@@ -200,6 +200,12 @@ def test_plan_layout_covers_every_element_once_in_layer_order():
     assert _status(p.chunk, p.num_chunks) == mpo.MPO_ERR_INVALID_ARG
     p.destroy()
     p.destroy()   # idempotent
+    # default: every layer in short chunks; 1: every layer in long ones
+    for small, ce in ((None, 1024), (1, 4096)):
+        q = mpo.Plan(ts, host_only=True, small_layer_params=small)
+        assert q.num_chunks == sum((n + ce - 1) // ce for n in sizes)
+        assert all(q.layer_info(l)["chunk_elems"] == ce for l in set(layers))
+        q.destroy()
 
 
 def test_step_calls_validate_before_touching_the_gpu():

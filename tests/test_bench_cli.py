@@ -30,7 +30,8 @@ def test_without_a_gpu_it_fails_loudly():
 @pytest.mark.gpu
 def test_json_line_on_the_small_workload():
     """One JSON line with the fields the contract names, the roofline object and the CPU baseline."""
-    out = _run("--workload", "c0", "--steps", "3", "--warmup", "1", "--cpu-sample", str(1 << 20))
+    out = _run("--workload", "c0", "--steps", "3", "--warmup", "1", "--cpu-sample", str(1 << 20), "--no-cpu-full-configs",
+               "--graph")
     assert out.returncode == 0, out.stderr
     lines = [l for l in out.stdout.split("\n") if l.strip()]
     assert len(lines) == 1
@@ -47,3 +48,8 @@ def test_json_line_on_the_small_workload():
     assert abs(d["value"] - d["config"]["params"] / (d["ms_per_step"] * 1e-3)) < 1e-6 * d["value"]
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["unit"] == "params/s" and c["cores"] >= 1 and c["value"] > 0
+    assert r["traffic"] is None and r["traffic_source"] is None          # no counter reading is carried for c0
+    e = d["end_to_end_with_gradient_generation"]
+    assert e["ms_per_step"] >= 0.5 * d["ms_per_step"] and e["steps"] >= 1
+    g = d["hip_graph"]
+    assert g["ms_per_step"] > 0 and g["params_per_s"] > 0

@@ -65,9 +65,8 @@ def test_host_plan_over_a_workload(key):
         info = plan.layer_info(layer)
         mine = [t.n for t in wl.tensors if t.layer == layer]
         assert info["num_tensors"] == len(mine) and info["num_params"] == sum(mine)
-        # long chunks for the big layers (the transformer blocks of c3 and c4), short ones elsewhere
         chunk = info["chunk_elems"]
-        assert chunk == (4096 if sum(mine) >= (1 << 26) else 1024)
+        assert chunk == 1024                                  # the default cut: one row per workgroup
         assert info["num_chunks"] == sum((n + chunk - 1) // chunk for n in mine)
         total += info["num_chunks"]
     assert total == plan.num_chunks

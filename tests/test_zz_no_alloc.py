@@ -75,6 +75,44 @@ def test_noalloc_matches_the_plan_path_on_two_calls_in_a_row(fmt, kw):
         plan.destroy()
 
 
+def test_noalloc_large_layer_takes_the_long_chunks():
+    """A layer of 2^26 parameters or more is cut into chunks of 4096 in the fixed table (so that its 2^21
+    entries go further): same bits as the plan path (which cuts into 1024), ends checked against the oracle."""
+    n = (1 << 26) + 1029
+    say("noalloc, one tensor of %d parameters" % n)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(21)
+    w = torch.empty(n, dtype=torch.float32, device=DEV).normal_(0.0, 0.02, generator=g)
+    grad = torch.empty(n, dtype=torch.bfloat16, device=DEV).normal_(0.0, 1e-3, generator=g)
+    sets = []
+    for _ in range(2):
+        hi = torch.empty(n, dtype=torch.int16, device=DEV)
+        res = torch.empty(n, dtype=torch.int16, device=DEV)
+        mpo.mpo_split(w, hi, res, n)
+        sets.append((hi, res, torch.zeros(n, dtype=torch.float32, device=DEV), torch.zeros(n, dtype=torch.float32, device=DEV)))
+    spans = [(0, 8192), (n - 8192, n), ((1 << 25) - 100, (1 << 25) + 4096)]
+    host = []
+    for lo, up in spans:
+        h, r = ref.split(np.ascontiguousarray(w[lo:up].cpu().numpy()), ref.BF16)
+        host.append([h, r, np.zeros(up - lo, np.float32), np.zeros(up - lo, np.float32)])
+    del w
+    plan = mpo.Plan([mpo.Tensor(*sets[0][:2], grad, *sets[0][2:], n, 0)])
+    arr = mpo.tensor_array([mpo.Tensor(*sets[1][:2], grad, *sets[1][2:], n, 0)])
+    cfg, rcfg = mpo.AdamCfg(lr=1e-3, weight_decay=0.01), ref.AdamCfg(lr=1e-3, weight_decay=0.01)
+    for t in (1, 2):
+        mpo.mpo_adam_step(plan, cfg, t)
+        mpo.mpo_adam_step_noalloc(arr, cfg, t)
+        torch.cuda.synchronize()
+        for a, b, what in zip(sets[0], sets[1], ("hi", "res", "m", "v")):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16)), "%s differs at step %d" % (what, t)
+        for (lo, up), h in zip(spans, host):
+            ref.adam_step(h[0], h[1], synth.bits16(grad[lo:up]), h[2], h[3], rcfg, t)
+            assert np.array_equal(host_u16(sets[1][0][lo:up]), h[0]) and np.array_equal(host_u16(sets[1][1][lo:up]), h[1])
+            assert np.array_equal(host_f32(sets[1][2][lo:up]).view(np.uint32), h[2].view(np.uint32))
+            assert np.array_equal(host_f32(sets[1][3][lo:up]).view(np.uint32), h[3].view(np.uint32))
+    plan.destroy()
+
+
 def test_noalloc_limits_and_argument_checks():
     n = 100
     d = DevTensor(np.zeros(n, np.float32), mpo.MPO_BF16)
