@@ -368,6 +368,66 @@ def probe_streams_run(a):
     print(json.dumps(out), flush=True)
 
 
+def split_merge_run(a):
+    """mpo_split and mpo_merge (Section 3.1, Table 1: used when a model is brought in or exported) on 2^30
+    parameters, 8 bytes per parameter, with the three arrays placed on purpose in thirds of the device memory
+    (one allocation first thing in a fresh process, as --probe-streams).  Prints one JSON line."""
+    import torch
+    from paper_2309_12381_amd import binding as mpo
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(0)
+    GiB = 1 << 30
+    free, _ = torch.cuda.mem_get_info()
+    if free < 276 * GiB:
+        print("bench.py --split-merge: needs 276 GiB of free device memory in a fresh process", file=sys.stderr)
+        sys.exit(1)
+    whole = torch.empty(272 * GiB, dtype=torch.uint8, device=dev)
+    n = 1 << 30
+
+    def at(region, slot, nbytes):
+        off = region * 96 * GiB + 4 * GiB + slot * 10 * GiB
+        return whole[off:off + nbytes]
+    stream = torch.cuda.current_stream()
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(5)
+    for r in range(3):
+        at(r, 0, 4 * GiB).view(torch.float32).normal_(0.0, 0.02, generator=gen)
+    reps = a.steps or 10
+    rows = []
+    out = {"metric": "achieved HBM GB/s of mpo_split / mpo_merge on 2^30 parameters by placement", "unit": "GB/s", "n_gpus": 1,
+           "data": "synthetic", "rows": rows}
+
+    def timed(fn):
+        fn(); fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        e1.synchronize()
+        return 8.0 * n * reps / e0.elapsed_time(e1) / 1e6
+
+    placements = [("fp32, hi, res in one third", (0, 0, 0)), ("fp32, hi | res", (0, 0, 1)), ("fp32 | hi, res", (0, 1, 1)),
+                  ("fp32 | hi | res", (0, 1, 2))]
+    for fmt_name, fmt in (("bf16", mpo.MPO_BF16), ("fp16", mpo.MPO_FP16)):
+        for rname, rnd in (("trunc", mpo.MPO_ROUND_TRUNC), ("stochastic", mpo.MPO_ROUND_STOCHASTIC)):
+            if fmt_name == "fp16" and rname == "stochastic" and not a.all_variants:
+                continue
+            for what, (rw, rh, rr) in placements:
+                w = at(rw, 0, 4 * n).view(torch.float32)
+                hi = at(rh, 1, 2 * n).view(torch.int16)
+                res = at(rr, 2, 2 * n).view(torch.int16)
+                sp = timed(lambda: mpo.mpo_split(w, hi, res, n, fmt=fmt, round=rnd, seed=3, stream=stream))
+                back = at(rw, 3, 4 * n).view(torch.float32)
+                mg = timed(lambda: mpo.mpo_merge(hi, res, back, n, fmt=fmt, round=rnd, stream=stream))
+                rows.append({"format": fmt_name, "round": rname, "placement": what, "split_GBps": round(sp, 1),
+                             "merge_GBps": round(mg, 1)})
+                print("%-5s %-10s %-28s split %7.1f GB/s   merge %7.1f GB/s" % (fmt_name, rname, what, sp, mg),
+                      file=sys.stderr, flush=True)
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -387,8 +447,8 @@ def main():
     ap.add_argument("--fresh-grads", action="store_true",
                     help="regenerate each layer's gradients inside the loop (adds generator kernels to the timing)")
     ap.add_argument("--chunk", default="auto", choices=["auto", "short", "long"],
-                    help="chunk length per workgroup: auto = 4096 parameters in layers of 2^26 parameters or more and 1024 "
-                         "in smaller ones (the library's default); short / long = 1024 / 4096 everywhere")
+                    help="chunk length per workgroup: auto = the library's default (1024 parameters; with packed planes 4096 in "
+                         "layers of 2^26 parameters or more); short / long = 1024 / 4096 everywhere")
     ap.add_argument("--no-place", action="store_true",
                     help="allocate the state arrays one after the other instead of dividing them between two "
                          "HBM regions (paper_2309_12381_amd/placement.py)")
@@ -398,6 +458,9 @@ def main():
     ap.add_argument("--probe-streams", action="store_true",
                     help="instead of the benchmark: plain and step-shaped streams by placement in the device memory and by "
                          "launch shape (csrc/stream_probe.hip); takes (almost) all device memory, run it in a fresh process")
+    ap.add_argument("--split-merge", action="store_true",
+                    help="instead of the benchmark: mpo_split / mpo_merge on 2^30 parameters by placement (fresh process)")
+    ap.add_argument("--all-variants", action="store_true", help="--split-merge: also fp16 with stochastic rounding")
     ap.add_argument("--width", type=int, default=4096)
     ap.add_argument("--depth", type=int, default=16)
     ap.add_argument("--tokens", type=int, default=1024)
@@ -430,6 +493,9 @@ def main():
     if a.probe_streams:
         probe_streams_run(a)
         return
+    if a.split_merge:
+        split_merge_run(a)
+        return
     if a.fused_backward:
         fused_backward_run(a)
         return
@@ -443,7 +509,7 @@ def main():
     t_setup = time.perf_counter()
     st = harness.ModelState(wl, dev, res_bits=a.res_bits, res_packed=a.res_packed,
                             round={"trunc": 0, "nearest": 1, "stochastic": 2}[a.round], place=not a.no_place,
-                            small_layer_params={"auto": None, "short": (1 << 64) - 1, "long": 1}[a.chunk])
+                            small_layer_params={"auto": 0, "short": (1 << 64) - 1, "long": 1}[a.chunk])
     if wl.per_layer:
         # the reused buffer holds one (largest) layer's worth of gradient values, read by every layer
         st.grad.normal_(0.0, wl.grad_std * wl.loss_scale, generator=synth.generator(7, dev))

@@ -214,10 +214,11 @@ mpo_status mpo_plan_create_host(const mpo_tensor *tensors, uint64_t nt, mpo_plan
 
 /* mpo_plan_create with options; opts == NULL or a zero field means the default.
  *   small_layer_params  layers with fewer parameters than this are cut into chunks of 1024
- *                       parameters instead of 4096 (default UINT64_MAX = short chunks
- *                       everywhere, the faster cut on MI355X; 1 = long chunks everywhere, a
- *                       chunk table a quarter the size).  A tuning knob: results do not
- *                       depend on it.
+ *                       parameters instead of 4096.  0 = the default: short chunks everywhere
+ *                       for 16-bit and byte residuals, 2^26 for packed planes (what measured
+ *                       fastest on MI355X); 1 = long chunks everywhere (a chunk table a
+ *                       quarter the size); UINT64_MAX = short chunks everywhere.  A tuning
+ *                       knob: results do not depend on it.
  *   host_only           != 0: as mpo_plan_create_host. */
 typedef struct {
     uint64_t small_layer_params;
@@ -226,9 +227,10 @@ typedef struct {
 mpo_status mpo_plan_create_opts(const mpo_tensor *tensors, uint64_t nt, const mpo_plan_opts *opts, mpo_plan **out);
 
 /* Layout queries (host side, no HIP call).  One workgroup handles one chunk.  All
- * chunks of a layer have the same length: 1024 parameters by default, or 4096 (what
+ * chunks of a layer have the same length: 1024 parameters, or 4096 (what
  * mpo_plan_chunk_elems returns, the longest) in layers of at least
- * mpo_plan_opts.small_layer_params parameters.  Chunks are numbered in launch order:
+ * mpo_plan_opts.small_layer_params parameters (by default: never, except with packed
+ * planes from 2^26 parameters on).  Chunks are numbered in launch order:
  * layer by layer; within a layer first every tensor's last, shorter chunk (if its
  * length is not a multiple of the chunk length), then the full chunks tensor by
  * tensor.  Chunk i covers `count` elements from element `first` of tensor `tensor`

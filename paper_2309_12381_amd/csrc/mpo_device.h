@@ -11,22 +11,24 @@
  * there is no MFMA; the work is bounded by HBM bandwidth (replacing the
  * arithmetic by a copy does not change the measured time).
  *
- * Mapping: one workgroup of 256 lanes (4 wavefronts of 64) per chunk of 4096
- * (in small layers 1024) consecutive parameters of one tensor; the chunk table
- * lets one launch cover every tensor of a list (Section 3.1, "Fused" optimizer).
+ * Mapping: one workgroup of 256 lanes (4 wavefronts of 64) per chunk of 1024
+ * (optionally 4096) consecutive parameters of one tensor; the chunk table lets one
+ * launch cover every tensor of a list (Section 3.1, "Fused" optimizer).
  *   - A lane owns 4 consecutive parameters per row: 64-bit accesses to the
  *     16-bit arrays and 128-bit accesses to the fp32 arrays, so EVERY load and
  *     store instruction of a wavefront covers one dense span (512 B or 1 KiB)
  *     and no cache line is touched by two instructions.  (8 parameters per lane,
  *     i.e. 128-bit accesses to the 16-bit arrays and two 32-byte-strided
- *     accesses to the fp32 arrays, measured 7 % slower on MI355X, and 25 %
- *     slower once stores are non-temporal, because two instructions then write
- *     halves of each line.)
- *   - Each wavefront owns a contiguous quarter of the chunk and walks it in 4
- *     rows (+5 % over rows interleaved across the wavefronts).
- *   - All 4 rows are loaded before any arithmetic: 20 requests per lane in flight.
+ *     accesses to the fp32 arrays, measured 10 % slower on MI355X.)
+ *   - In a long chunk each wavefront owns a contiguous quarter and walks it row
+ *     by row.
+ *   - One row is in flight per wavefront (5 requests per lane): 44 to 70 vector
+ *     registers in every variant, so 7 or 8 wavefronts per SIMD hide the latency.
+ *     Requesting all 4 rows of a long chunk first measured the same or slower
+ *     (the memory system's queues are full either way) and cost the heavier
+ *     variants half their occupancy.
  *   - All accesses carry the non-temporal hint: every byte is used once per step,
- *     and streaming past the caches measured 6-8 % faster than the default policy.
+ *     and streaming past the caches measured 3-5 % faster than the default policy.
  *
  * Built with -ffp-contract=off and correctly rounded division / square root:
  * every line of arithmetic below is one IEEE binary32 operation.
@@ -41,7 +43,7 @@ namespace mpo {
 namespace {
 
 constexpr int EPL = 4;                                /* parameters per lane per row   */
-constexpr int ROWS = kChunkElems / (kBlock * EPL);    /* rows of the longest chunk, all in flight */
+constexpr int ROWS = kChunkElems / (kBlock * EPL);    /* rows of the longest chunk */
 static_assert(ROWS * kBlock * EPL == kChunkElems, "a chunk is a whole number of rows");
 static_assert(kBlock * EPL == kRowElems, "a row is one access of every lane of the workgroup");
 
@@ -164,7 +166,9 @@ template <> __device__ __forceinline__ void split32<MPO_FP16>(float w, uint32_t 
 }
 template <> __device__ __forceinline__ float cvt16<MPO_FP16>(uint32_t x)
 {
-    return merge16<MPO_FP16>(x, 0u);
+    /* every fp16 value is an fp32 value: the hardware conversion is exact (subnormals included;
+     * a NaN comes out quiet with its payload, as merge16 builds it) */
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)x);
 }
 
 /* ---- the update of one parameter (Section 3.1) ---------------------------
@@ -372,8 +376,10 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
             k0 += 0x9E3779B9u;
             k1 += 0xBB67AE85u;
         }
-        const uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
-        const uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
+        /* one 32 x 32 -> 64 bit product per multiplier: both halves from one instruction */
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t h0 = (uint32_t)(p0 >> 32), l0 = (uint32_t)p0;
+        const uint32_t h1 = (uint32_t)(p1 >> 32), l1 = (uint32_t)p1;
         const uint32_t n0 = h1 ^ c1 ^ k0, n2 = h0 ^ c3 ^ k1;
         c0 = n0; c1 = l1; c2 = n2; c3 = l0;
     }
@@ -646,19 +652,11 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
     gf32p v = Uses<OPT, MOM>::v ? (gf32p)(d.v + off) : (gf32p) nullptr;
     const uint32_t t = threadIdx.x;
 
-    if (aligned && len == kChunkElems) {
-        /* whole 4-row chunk: no bounds checks; every row is requested before the first is used */
-        Row x[ROWS];
-#pragma unroll
-        for (int r = 0; r < ROWS; ++r) load_row<OPT, MOM, RMODE>(x[r], hi, R, grad, m, v, row_elem(r, t));
-#pragma unroll
-        for (int r = 0; r < ROWS; ++r) {
-            if (RND) compute_row_rounded<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x[r], s, kept, sh, rng, off + row_elem(r, t));
-            else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x[r], s, sh);
-            store_row<OPT, MOM, RMODE>(x[r], hi, R, m, v, row_elem(r, t));
-        }
-    } else if (aligned && len == celems) {
-        /* whole shorter chunk (small layers): row by row, every lane active, no bounds checks */
+    if (aligned && len == celems) {
+        /* whole chunk: row by row, every lane active, no bounds checks.  One row in flight per
+         * wavefront keeps the register count low enough for 8 wavefronts per SIMD in every
+         * variant of the kernel, and they hide the latency: measured the same as, or faster
+         * than, requesting all rows of a long chunk before the first is used. */
 #pragma unroll 1
         for (uint32_t r = 0; r < rows; ++r) {
             const uint32_t e = row_elem(r, t, span);

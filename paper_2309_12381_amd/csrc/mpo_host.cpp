@@ -313,6 +313,8 @@ mpo_status build_plan(const mpo_tensor *tensors, uint64_t nt, uint64_t small_lay
             }
             p->num_params += t.n;
         }
+        /* default cut: by the kind of residual storage (see kSmallLayerParams) */
+        if (small_layer_params == 0) small_layer_params = p->res_slot == 3 ? kPlanesSmallLayerParams : kSmallLayerParams;
         std::vector<TensorLayout> lay(nt);
         const uint64_t total = layout_chunks(p->descs.data(), layer.data(), nt, small_layer_params, lay.data());
         if (total == UINT64_MAX) { delete p; return MPO_ERR_INVALID_ARG; }
@@ -426,7 +428,7 @@ mpo_status mpo_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n
 
 mpo_status mpo_plan_create_host(const mpo_tensor *tensors, uint64_t nt, mpo_plan **out)
 {
-    return build_plan(tensors, nt, kSmallLayerParams, out);
+    return build_plan(tensors, nt, 0, out);
 }
 
 mpo_status mpo_plan_create(const mpo_tensor *tensors, uint64_t nt, mpo_plan **out)
@@ -437,7 +439,7 @@ mpo_status mpo_plan_create(const mpo_tensor *tensors, uint64_t nt, mpo_plan **ou
 mpo_status mpo_plan_create_opts(const mpo_tensor *tensors, uint64_t nt, const mpo_plan_opts *opts, mpo_plan **out)
 {
     mpo_plan *p = nullptr;
-    const uint64_t small = (opts && opts->small_layer_params) ? opts->small_layer_params : kSmallLayerParams;
+    const uint64_t small = opts ? opts->small_layer_params : 0;   /* 0: the default for the storage kind */
     const mpo_status s = build_plan(tensors, nt, small, &p);
     if (s != MPO_OK) return s;
     if (opts && opts->host_only) {

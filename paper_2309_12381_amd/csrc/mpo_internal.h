@@ -12,14 +12,20 @@ namespace mpo {
 
 /* One workgroup (256 lanes = 4 wavefronts of 64) owns one chunk.  A chunk is 1, 2 or 4 "rows" of
  * 1024 consecutive parameters (4 per lane).  Measured on MI355X, one row per workgroup is the
- * faster cut everywhere: +5 % on a list of 25.6 M parameters (four times as many workgroups to
- * fill 256 compute units) and +0.5 % on layers of 2 * 10^8 parameters (27.17 against 27.32 ms per
- * step of the 7B-shaped set), at the price of a chunk table of 8 bytes per 1024 parameters
- * instead of per 4096.  The length is chosen per layer by a threshold the caller may set. */
+ * faster cut for 16-bit and byte residuals: +5 % on a list of 25.6 M parameters (four times as
+ * many workgroups to fill 256 compute units), and on layers of 2 * 10^8 parameters it measures the
+ * same as 4 rows walked one after the other by one workgroup (27.20 against 27.25 ms per step of
+ * the 7B-shaped set), at the price of a chunk table of 8 bytes per 1024 parameters instead of per
+ * 4096.  The length is chosen per layer by a threshold the caller may set.  A row is requested,
+ * updated and stored before the next is touched: with one row in flight per wavefront every
+ * variant of the kernel fits 7 or 8 wavefronts per SIMD, which hide the latency. */
 constexpr uint32_t kBlock = 256;
 constexpr uint32_t kRowElems = 1024;                 /* kBlock lanes x 4 parameters               */
 constexpr uint32_t kChunkElems = 4096;               /* the longest chunk: 4 rows                 */
 constexpr uint64_t kSmallLayerParams = UINT64_MAX;   /* plans: layers below this are cut into single rows (default: all) */
+constexpr uint64_t kPlanesSmallLayerParams = 1ull << 26; /* packed planes: the per-workgroup set-up (four plane addresses) and the
+                                                           * sub-dword accesses weigh more, and long chunks measured 3 % (fp16, 13
+                                                           * bits) faster on large layers, at -1.7 % for bf16 with 12 bits */
 constexpr uint64_t kNoallocSmallLayerParams = 1ull << 26; /* the fixed table of mpo_adam_step_noalloc: long chunks
                                                             * for large layers, so that 2^21 entries go further */
 
