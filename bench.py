@@ -190,37 +190,49 @@ def traffic_probe(st, stream, with_v, bpp, steps):
 
 
 def fused_backward_run(a):
-    """Section 3.2 on a real PyTorch backward: a stack of residual MLP blocks (bf16, synthetic data)
-    trained with the split-precision Adam step, once with the step fused into backward (each
-    parameter stepped in its post-accumulate-grad hook, gradient freed there), once more with those
-    steps on a stream of their own so that they overlap the rest of backward, and once with the
-    classical schedule (all gradients kept, stepped after backward).  Prints one JSON line with
-    the time per iteration and the peak device memory of both."""
+    """Section 3.2 on a real PyTorch backward: a stack of pre-norm transformer blocks (causal self-attention
+    through torch's scaled_dot_product_attention, then a GELU MLP; bf16, synthetic data) trained with the
+    split-precision Adam step, once with the step fused into backward (each parameter stepped in its
+    post-accumulate-grad hook, gradient freed there), once more without the placement of the optimizer state,
+    once with the hook's steps on a stream of their own, and once with the classical schedule (all gradients
+    kept, stepped after backward).  Each variant runs in this one process, one after the other.  Prints one JSON
+    line with the time per iteration, the peak device memory and the rate of the step launches on their own."""
     import torch
     import paper_2309_12381_amd as mpo
     from paper_2309_12381_amd.fused_backward import FusedBackwardOptimizer
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    d, depth, tokens = a.width, a.depth, a.tokens
+    d, depth, tokens, seq = a.width, a.depth, a.tokens, a.seq
+    heads = max(1, d // 128)
+    if tokens % seq:
+        print("bench.py: --tokens must be a multiple of --seq", file=sys.stderr)
+        sys.exit(2)
 
     class Block(torch.nn.Module):
         def __init__(self):
             super().__init__()
-            self.norm = torch.nn.LayerNorm(d)
+            self.norm1 = torch.nn.LayerNorm(d)
+            self.qkv = torch.nn.Linear(d, 3 * d, bias=False)
+            self.proj = torch.nn.Linear(d, d, bias=False)
+            self.norm2 = torch.nn.LayerNorm(d)
             self.up = torch.nn.Linear(d, 4 * d, bias=False)
             self.down = torch.nn.Linear(4 * d, d, bias=False)
 
-        def forward(self, x):
-            return x + self.down(torch.nn.functional.gelu(self.up(self.norm(x))))
+        def forward(self, x):                                   # x: (batch, seq, d)
+            b, s_, _ = x.shape
+            q, k, v = self.qkv(self.norm1(x)).view(b, s_, 3, heads, d // heads).permute(2, 0, 3, 1, 4)
+            att = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True)
+            x = x + self.proj(att.transpose(1, 2).reshape(b, s_, d))
+            return x + self.down(torch.nn.functional.gelu(self.up(self.norm2(x))))
 
-    def run(fused, overlap=False):
+    def run(fused, overlap=False, place=True):
         torch.manual_seed(0)
         model = torch.nn.Sequential(*[Block() for _ in range(depth)]).to(dev).to(torch.bfloat16)
         params = sum(p.numel() for p in model.parameters())
         opt = FusedBackwardOptimizer(model.parameters(), mpo.AdamCfg(lr=1e-4, weight_decay=0.01), fused=fused,
-                                     overlap=overlap)
-        x = torch.randn(tokens, d, device=dev, dtype=torch.bfloat16)
-        y = torch.randn(tokens, d, device=dev, dtype=torch.bfloat16)
+                                     overlap=overlap, place=place)
+        x = torch.randn(tokens // seq, seq, d, device=dev, dtype=torch.bfloat16)
+        y = torch.randn(tokens // seq, seq, d, device=dev, dtype=torch.bfloat16)
 
         def iteration():
             opt.start_step()
@@ -241,20 +253,44 @@ def fused_backward_run(a):
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / steps
         peak = torch.cuda.max_memory_allocated()
-        opt.close()
-        del model, opt, x, y
-        torch.cuda.empty_cache()
-        return {"ms_per_iteration": dt * 1e3, "peak_GB": peak / 1e9, "resident_GB": resident / 1e9}, params
+        out = {"ms_per_iteration": dt * 1e3, "peak_GB": peak / 1e9, "resident_GB": resident / 1e9,
+               "peak_above_resident_GB": (peak - resident) / 1e9, "placement": opt.placement}
+        # the step launches of one iteration on their own: every parameter stepped from one reused gradient buffer,
+        # as the hooks do it (one mpo_step_layer with a per-call gradient pointer per parameter)
+        big = max(p.numel() for p in opt.params)
+        gbuf = torch.randn(big, device=dev, dtype=torch.bfloat16) * 1e-4
+        stream = torch.cuda.current_stream()
 
-    fused, params = run(True)
+        def all_steps(t):
+            for i, p in enumerate(opt.params):
+                mpo.mpo_step_layer(opt.plan, i, opt.cfg, t, grads=[gbuf[:p.numel()]], stream=stream)
+        all_steps(opt.step_no + 1)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for k in range(3):
+            all_steps(opt.step_no + 2 + k)
+        e1.record(stream)
+        e1.synchronize()
+        ms = e0.elapsed_time(e1) / 3
+        out["step_launches"] = {"ms": ms, "GBps": ADAM_BYTES_PER_PARAM * params / ms / 1e6,
+                                "frac_of_peak": ADAM_BYTES_PER_PARAM * params / ms / 1e6 / PEAK_HBM_GBPS,
+                                "launches": len(opt.params)}
+        opt.close()
+        del model, opt, x, y, gbuf
+        torch.cuda.empty_cache()
+        return out, params
+
+    fused, params = run(True)                       # first: a fresh process's allocation order
+    unplaced, _ = run(True, place=False)
     overlapped, _ = run(True, overlap=True)
     classical, _ = run(False)
     print(json.dumps({
         "metric": "training iteration with the split-precision Adam step fused into backward vs stepped after it",
         "n_gpus": 1, "data": "synthetic", "dtype": "bf16 forward/backward, f32 update",
-        "config": {"workload": "%d residual MLP blocks of width %d (%.2f B parameters), %d tokens per iteration"
-                               % (depth, d, params / 1e9, tokens), "optimizer": "adamw"},
-        "fused": fused, "fused_overlapped": overlapped, "classical": classical,
+        "config": {"workload": "%d transformer blocks of width %d, %d heads (%.2f B parameters), %d tokens per iteration in "
+                               "sequences of %d" % (depth, d, heads, params / 1e9, tokens, seq), "optimizer": "adamw"},
+        "fused": fused, "fused_without_placement": unplaced, "fused_overlapped": overlapped, "classical": classical,
         "gradient_bytes_GB": params * 2 / 1e9,
         "peak_saved_GB": classical["peak_GB"] - fused["peak_GB"],
     }), flush=True)
@@ -462,8 +498,9 @@ def main():
                     help="instead of the benchmark: mpo_split / mpo_merge on 2^30 parameters by placement (fresh process)")
     ap.add_argument("--all-variants", action="store_true", help="--split-merge: also fp16 with stochastic rounding")
     ap.add_argument("--width", type=int, default=4096)
-    ap.add_argument("--depth", type=int, default=16)
+    ap.add_argument("--depth", type=int, default=12)
     ap.add_argument("--tokens", type=int, default=1024)
+    ap.add_argument("--seq", type=int, default=1024, help="--fused-backward: sequence length (tokens / seq sequences per iteration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cpu-full-configs", action="store_true",
                     help="CPU baseline on the sample only, not on c0, c1 and c2 in full as well")

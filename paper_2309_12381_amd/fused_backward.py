@@ -13,6 +13,7 @@ from typing import Callable, Iterable, Optional, Sequence
 import torch
 
 from . import binding as mpo
+from . import placement
 
 _FMT = {torch.bfloat16: mpo.MPO_BF16, torch.float16: mpo.MPO_FP16}
 
@@ -40,6 +41,13 @@ class FusedBackwardOptimizer:
                 2 B parameters: no gain, 22.8 against 23.0 ms per iteration; both the step and the
                 matrix products of backward fill every compute unit, so they take turns anyway.)
 
+    place       divide the optimizer state between two regions of the device memory (placement.py): `m` is
+                allocated first, next to the model's weights, and `res`, `v` where the bandwidth probe sees
+                the gain of a second region relative to the largest parameter and `m`.  Only models with a
+                parameter of at least 2^26 elements and 2.4e8 parameters in all are placed; the report is in
+                `self.placement`.  The search holds up to `max_transient_bytes` (default: half of the free
+                memory) beyond the state while it runs, so construct the optimizer before activations exist.
+
     Call `start_step()` before every backward: all parameters stepped during one backward share
     the step count.  With `overlap`, call `synchronize()` before reading parameters or state from
     another stream than the one `start_step()` is called on.
@@ -47,7 +55,8 @@ class FusedBackwardOptimizer:
 
     def __init__(self, params: Iterable[torch.nn.Parameter], cfg, res_bits: int = 0,
                  init_fp32: Optional[Sequence[torch.Tensor]] = None, fused: bool = True,
-                 observer: Optional[Callable] = None, res_packed: bool = False, overlap: bool = False):
+                 observer: Optional[Callable] = None, res_packed: bool = False, overlap: bool = False,
+                 place: bool = True, max_transient_bytes: Optional[int] = None):
         self.params = [p for p in params if p.requires_grad]
         if not self.params:
             raise ValueError("no parameters")
@@ -77,12 +86,30 @@ class FusedBackwardOptimizer:
             for p in self.params:
                 self.res_offs.append(fill)
                 fill += mpo.mpo_res_bytes(p.numel(), res_bits, True)
-            self.res = torch.zeros(fill, dtype=torch.uint8, device=dev)
+            res_spec = (fill, torch.uint8)
         else:
             self.res_offs = offs
-            self.res = torch.zeros(total, dtype=torch.uint8 if 1 <= res_bits <= 8 else torch.int16, device=dev)
-        self.m = torch.zeros(total, dtype=torch.float32, device=dev)
-        self.v = torch.zeros(total, dtype=torch.float32, device=dev) if self.is_adam else None
+            res_spec = (total, torch.uint8 if 1 <= res_bits <= 8 else torch.int16)
+        # m first: right behind the model's weights in a fresh process, i.e. in their region
+        self.m = torch.empty(total, dtype=torch.float32, device=dev)
+
+        def second():
+            out = {"res": torch.empty(res_spec[0], dtype=res_spec[1], device=dev)}
+            if self.is_adam:
+                out["v"] = torch.empty(total, dtype=torch.float32, device=dev)
+            return out
+        biggest = max(self.params, key=lambda p: p.numel())
+        res_bytes = res_spec[0] * (1 if res_spec[1] == torch.uint8 else 2)
+        if place and self.is_adam and biggest.numel() >= (1 << 26) and res_bytes >= (1 << 27):
+            chosen, self.placement = placement.place_second(biggest.data.view(-1), self.m, second, res_bytes + 4 * total,
+                                                            max_transient_bytes=max_transient_bytes, keep_hi=True)
+        else:
+            chosen = second()
+            self.placement = {"split": False, "why": "placement switched off" if not place else
+                              "not placed: needs Adam, a parameter of 2^26 elements and 16-bit weights of 2^27 bytes"}
+        self.res = chosen["res"].zero_()
+        self.m.zero_()
+        self.v = chosen["v"].zero_() if self.is_adam else None
         self.offs = offs
         specs = []
         for i, (p, off) in enumerate(zip(self.params, offs)):

@@ -15,12 +15,41 @@ from gpu_util import DEV, FMT, host_f32, host_res, say
 pytestmark = pytest.mark.gpu
 
 
-def _model(dtype, width=384, depth=3, seed=0):
+class _Attention(torch.nn.Module):
+    """Pre-norm causal self-attention with a residual connection (torch's scaled_dot_product_attention)."""
+
+    def __init__(self, width, heads=4):
+        super().__init__()
+        self.heads = heads
+        self.norm = torch.nn.LayerNorm(width)
+        self.qkv = torch.nn.Linear(width, 3 * width)
+        self.proj = torch.nn.Linear(width, width, bias=False)
+
+    def forward(self, x):                                   # (batch, seq, width)
+        b, s, w = x.shape
+        q, k, v = self.qkv(self.norm(x)).view(b, s, 3, self.heads, w // self.heads).permute(2, 0, 3, 1, 4)
+        att = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True)
+        return x + self.proj(att.transpose(1, 2).reshape(b, s, w))
+
+
+class _Mlp(torch.nn.Module):
+    def __init__(self, width):
+        super().__init__()
+        self.norm = torch.nn.LayerNorm(width)
+        self.up = torch.nn.Linear(width, 2 * width)
+        self.down = torch.nn.Linear(2 * width, width)
+
+    def forward(self, x):
+        return x + self.down(torch.nn.functional.gelu(self.up(self.norm(x))))
+
+
+def _model(dtype, width=256, depth=2, seed=0):
+    """A small transformer: input projection, `depth` blocks of attention + MLP, output head."""
     torch.manual_seed(seed)
-    layers = [torch.nn.Linear(128, width), torch.nn.GELU()]
+    layers = [torch.nn.Linear(128, width)]
     for _ in range(depth):
-        layers += [torch.nn.Linear(width, width), torch.nn.GELU(), torch.nn.LayerNorm(width)]
-    layers += [torch.nn.Linear(width, 10)]
+        layers += [_Attention(width), _Mlp(width)]
+    layers += [torch.nn.LayerNorm(width), torch.nn.Linear(width, 10)]
     return torch.nn.Sequential(*layers).to(DEV).to(dtype)
 
 
@@ -52,8 +81,8 @@ def test_hooks_step_every_parameter_and_match_the_oracle(dtype, kind, kw, res_bi
     steps = 3
     per_step = []
     for t in range(steps):
-        x = torch.randn(64, 128, device=DEV, dtype=dtype, generator=g)
-        y = torch.randn(64, 10, device=DEV, dtype=dtype, generator=g)
+        x = torch.randn(4, 16, 128, device=DEV, dtype=dtype, generator=g)        # 4 sequences of 16 tokens
+        y = torch.randn(4, 16, 10, device=DEV, dtype=dtype, generator=g)
         opt.start_step()
         seen.clear()
         loss = torch.nn.functional.mse_loss(model(x).float(), y.float()) * scale
@@ -92,10 +121,47 @@ def test_hooks_step_every_parameter_and_match_the_oracle(dtype, kind, kw, res_bi
     opt.close()
 
 
+def _train(overlap, steps=4, width=512, depth=3):
+    """A few iterations with no observer (nothing in the hooks touches the host); returns the final state."""
+    model = _model(torch.bfloat16, width=width, depth=depth, seed=3)
+    opt = FusedBackwardOptimizer(model.parameters(), mpo.AdamCfg(lr=1e-3, weight_decay=1e-2), overlap=overlap)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(9)
+    for _ in range(steps):
+        x = torch.randn(8, 64, 128, device=DEV, dtype=torch.bfloat16, generator=g)
+        y = torch.randn(8, 64, 10, device=DEV, dtype=torch.bfloat16, generator=g)
+        opt.start_step()
+        torch.nn.functional.mse_loss(model(x).float(), y.float()).backward()
+    opt.synchronize()
+    torch.cuda.synchronize()
+    out = []
+    for i, p in enumerate(opt.params):
+        res, m, v = opt.state_of(i)
+        out.append((p.detach().clone().view(torch.int16).reshape(-1), res.clone(), m.clone(), v.clone()))
+    opt.close()
+    return out
+
+
+def test_overlapped_steps_without_any_host_synchronisation_give_the_same_state():
+    """With `overlap` the steps run on a stream of their own while backward goes on; nothing in the hooks
+    waits for the device here (no observer), so a missing dependency between the kernel that writes a
+    gradient, the step that reads it and the next forward would show as different bits.  Needs a backward
+    that is reproducible from run to run, which is checked first."""
+    say("overlapped fused backward without observer")
+    a = _train(False)
+    b = _train(False)
+    if not all(torch.equal(x, y) for ta, tb in zip(a, b) for x, y in zip(ta, tb)):
+        pytest.skip("this backward is not bit-reproducible from run to run: nothing to compare an overlapped run with")
+    c = _train(True)
+    for i, (ta, tc) in enumerate(zip(a, c)):
+        for x, y, what in zip(ta, tc, ("hi", "res", "m", "v")):
+            assert torch.equal(x, y), "parameter %d: %s differs between the overlapped and the in-order run" % (i, what)
+
+
 def test_start_step_is_required():
     model = _model(torch.bfloat16, width=64, depth=1)
     opt = FusedBackwardOptimizer(model.parameters(), mpo.AdamCfg())
-    x = torch.randn(4, 128, device=DEV, dtype=torch.bfloat16)
+    x = torch.randn(2, 4, 128, device=DEV, dtype=torch.bfloat16)
     with pytest.raises(RuntimeError):
         model(x).float().sum().backward()
     opt.close()

@@ -87,6 +87,33 @@ def test_placed_state_is_clean_and_disjoint(res_dtype, zero_res):
     torch.cuda.empty_cache()
 
 
+def test_search_holds_no_more_than_it_is_allowed():
+    """The search reaches another region only by holding the memory before it; what it holds beyond the
+    arrays it returns is bounded by max_transient_bytes (here: room for one more candidate)."""
+    n = 1 << 28
+    need = 2 * n + 4 * n + 2 * (1 << 26)                      # res + v + grad of one candidate
+    say("allocate_state n=2^28 with a bound on transient memory")
+    torch.cuda.empty_cache()
+    torch.cuda.synchronize()
+    base = torch.cuda.memory_allocated()
+    torch.cuda.reset_peak_memory_stats()
+    bound = 17 << 30                                          # one stride: a filler and a second candidate
+    arrays, report = placement.allocate_state(n, (n, torch.int16), (1 << 26, torch.bfloat16), DEV, max_transient_bytes=bound)
+    print(report)
+    final = sum(t.numel() * t.element_size() for t in arrays.values())
+    peak = torch.cuda.max_memory_allocated() - base
+    assert report["peak_transient_bytes"] <= bound and report["candidates"] <= 2
+    assert peak <= final + bound + (1 << 30), (peak, final, bound)        # 1 GiB: the probe's own event and window slack
+    assert _disjoint(arrays) and not arrays["m"].any() and not arrays["v"].any()
+    del arrays
+    torch.cuda.empty_cache()
+    # and with no room at all it still allocates, plainly
+    arrays, report = placement.allocate_state(n, (n, torch.int16), (1 << 26, torch.bfloat16), DEV, max_transient_bytes=0)
+    assert report["candidates"] == 1 and report["peak_transient_bytes"] == 0 and _disjoint(arrays)
+    del arrays
+    torch.cuda.empty_cache()
+
+
 def test_placement_can_be_switched_off():
     n = 1 << 28
     arrays, report = placement.allocate_state(n, (n, torch.int16), (4096, torch.float16), DEV, place=False)
