@@ -171,7 +171,7 @@ struct Variant {
     (BLK) * (EPL) * (ROWS), (PIPE), (BLK), ((PERSIST) ? 8 : 0), variant_kernel<BLK, EPL, ROWS, FLY, NTL, NTS, NTHI, WAVEC, PERSIST, PIPE, XCD>
 
 const Variant kVariants[] = {
-    {"256 lanes, 4 parameters per lane, chunk of 4096 parameters with its 4 rows in flight, wavefront-contiguous, non-temporal (the step kernel's long chunks)",
+    {"256 lanes, 4 parameters per lane, chunk of 4096 parameters with its 4 rows in flight, wavefront-contiguous, non-temporal",
      V(256, 4, 4, 4, true, true, true, true, false, 1, false)},
     {"8 parameters per lane (128-bit 16-bit accesses, two 128-bit fp32 accesses 32 bytes apart)",
      V(256, 8, 2, 2, true, true, true, true, false, 1, false)},
@@ -179,7 +179,7 @@ const Variant kVariants[] = {
     {"default cache policy for stores only", V(256, 4, 4, 4, true, false, false, true, false, 1, false)},
     {"default cache policy for loads only", V(256, 4, 4, 4, false, true, true, true, false, 1, false)},
     {"default cache policy for the stores of hi only", V(256, 4, 4, 4, true, true, false, true, false, 1, false)},
-    {"one row in flight", V(256, 4, 4, 1, true, true, true, true, false, 1, false)},
+    {"chunk of 4096 parameters, one row in flight (the step kernel's long chunks)", V(256, 4, 4, 1, true, true, true, true, false, 1, false)},
     {"two rows in flight", V(256, 4, 4, 2, true, true, true, true, false, 1, false)},
     {"chunk of 1024 parameters, one row (the step kernel's default)", V(256, 4, 1, 1, true, true, true, true, false, 1, false)},
     {"chunk of 2048 parameters", V(256, 4, 2, 2, true, true, true, true, false, 1, false)},
