@@ -225,12 +225,12 @@ def fused_backward_run(a):
             x = x + self.proj(att.transpose(1, 2).reshape(b, s_, d))
             return x + self.down(torch.nn.functional.gelu(self.up(self.norm2(x))))
 
-    def run(fused, overlap=False, place=True):
+    def run(fused, overlap=False, place=True, bucket=0):
         torch.manual_seed(0)
         model = torch.nn.Sequential(*[Block() for _ in range(depth)]).to(dev).to(torch.bfloat16)
         params = sum(p.numel() for p in model.parameters())
         opt = FusedBackwardOptimizer(model.parameters(), mpo.AdamCfg(lr=1e-4, weight_decay=0.01), fused=fused,
-                                     overlap=overlap, place=place)
+                                     overlap=overlap, place=place, bucket_params=bucket)
         x = torch.randn(tokens // seq, seq, d, device=dev, dtype=torch.bfloat16)
         y = torch.randn(tokens // seq, seq, d, device=dev, dtype=torch.bfloat16)
 
@@ -262,8 +262,15 @@ def fused_backward_run(a):
         stream = torch.cuda.current_stream()
 
         def all_steps(t):
+            if opt.buckets is not None:                          # one launch per bucket, as the hooks issue them
+                for b, members in enumerate(opt.buckets):
+                    mpo.mpo_step_layer(opt.bucket_plan, b, opt.cfg, t, grads=[gbufs[k][:opt.params[i].numel()]
+                                                                               for k, i in enumerate(members)], stream=stream)
+                return
             for i, p in enumerate(opt.params):
                 mpo.mpo_step_layer(opt.plan, i, opt.cfg, t, grads=[gbuf[:p.numel()]], stream=stream)
+        if opt.buckets is not None:
+            gbufs = [torch.randn(big, device=dev, dtype=torch.bfloat16) * 1e-4 for _ in range(max(len(b) for b in opt.buckets))]
         all_steps(opt.step_no + 1)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -275,24 +282,44 @@ def fused_backward_run(a):
         ms = e0.elapsed_time(e1) / 3
         out["step_launches"] = {"ms": ms, "GBps": ADAM_BYTES_PER_PARAM * params / ms / 1e6,
                                 "frac_of_peak": ADAM_BYTES_PER_PARAM * params / ms / 1e6 / PEAK_HBM_GBPS,
-                                "launches": len(opt.params)}
+                                "launches": len(opt.buckets) if opt.buckets is not None else len(opt.params)}
         opt.close()
         del model, opt, x, y, gbuf
+        gbufs = None
         torch.cuda.empty_cache()
         return out, params
 
-    fused, params = run(True)                       # first: a fresh process's allocation order
-    unplaced, _ = run(True, place=False)
-    overlapped, _ = run(True, overlap=True)
-    classical, _ = run(False)
+    variants = {"fused": dict(fused=True), "fused_one_launch_per_block": dict(fused=True, bucket=12 * d * d),
+                "fused_without_placement": dict(fused=True, place=False), "fused_overlapped": dict(fused=True, overlap=True),
+                "classical": dict(fused=False)}
+    if a.fb_variant:
+        out, params = run(**variants[a.fb_variant])
+        out["params"] = params
+        print(json.dumps(out), flush=True)
+        return
+    # every variant in a process of its own: where its arrays land depends on what the process allocated before
+    import subprocess
+    res = {}
+    for name in variants:
+        cmd = [sys.executable, os.path.abspath(__file__), "--fused-backward", "--fb-variant", name, "--width", str(d),
+               "--depth", str(depth), "--tokens", str(tokens), "--seq", str(seq), "--warmup", str(a.warmup)]
+        if a.steps:
+            cmd += ["--steps", str(a.steps)]
+        r = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
+        if r.returncode != 0:
+            print("bench.py --fused-backward: variant %s failed:\n%s" % (name, r.stderr[-2000:]), file=sys.stderr)
+            sys.exit(1)
+        res[name] = json.loads([l for l in r.stdout.split("\n") if l.startswith("{")][-1])
+    params = res["fused"]["params"]
     print(json.dumps({
         "metric": "training iteration with the split-precision Adam step fused into backward vs stepped after it",
         "n_gpus": 1, "data": "synthetic", "dtype": "bf16 forward/backward, f32 update",
         "config": {"workload": "%d transformer blocks of width %d, %d heads (%.2f B parameters), %d tokens per iteration in "
-                               "sequences of %d" % (depth, d, heads, params / 1e9, tokens, seq), "optimizer": "adamw"},
-        "fused": fused, "fused_without_placement": unplaced, "fused_overlapped": overlapped, "classical": classical,
+                               "sequences of %d; every variant in a process of its own" % (depth, d, heads, params / 1e9, tokens, seq),
+                   "optimizer": "adamw"},
+        **res,
         "gradient_bytes_GB": params * 2 / 1e9,
-        "peak_saved_GB": classical["peak_GB"] - fused["peak_GB"],
+        "peak_saved_GB": res["classical"]["peak_GB"] - res["fused"]["peak_GB"],
     }), flush=True)
 
 
@@ -485,6 +512,8 @@ def main():
     ap.add_argument("--chunk", default="auto", choices=["auto", "short", "long"],
                     help="chunk length per workgroup: auto = the library's default (1024 parameters; with packed planes 4096 in "
                          "layers of 2^26 parameters or more); short / long = 1024 / 4096 everywhere")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="per-layer workloads: also time the steps with the layers' launches going round this many streams")
     ap.add_argument("--no-place", action="store_true",
                     help="allocate the state arrays one after the other instead of dividing them between two "
                          "HBM regions (paper_2309_12381_amd/placement.py)")
@@ -497,6 +526,7 @@ def main():
     ap.add_argument("--split-merge", action="store_true",
                     help="instead of the benchmark: mpo_split / mpo_merge on 2^30 parameters by placement (fresh process)")
     ap.add_argument("--all-variants", action="store_true", help="--split-merge: also fp16 with stochastic rounding")
+    ap.add_argument("--fb-variant", default=None, help=argparse.SUPPRESS)      # --fused-backward: one variant, in this process
     ap.add_argument("--width", type=int, default=4096)
     ap.add_argument("--depth", type=int, default=12)
     ap.add_argument("--tokens", type=int, default=1024)
@@ -635,6 +665,29 @@ def main():
             "ms_per_step": e2e * 1e3, "params_per_s": P / e2e, "steps": k,
             "what": "optimizer steps with each layer's gradient regenerated inside the loop by torch's generator and "
                     "cast kernels (the stand-in for backward); the headline times the library's launches alone"}
+    if a.streams > 1 and wl.per_layer:
+        # the same steps with the per-layer launches going round several streams: consecutive launches overlap where
+        # one drains and the next fills the GPU
+        side = [torch.cuda.Stream() for _ in range(a.streams)]
+        for sd in side:
+            sd.wait_stream(stream)
+        for _ in range(2):
+            step_no += 1
+            st.step(step_no, cfg, streams=side)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(steps):
+            step_no += 1
+            st.step(step_no, cfg, streams=side)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t1) / steps
+        for sd in side:
+            stream.wait_stream(sd)
+        res["launches_over_several_streams"] = {
+            "streams": a.streams, "ms_per_step": dt * 1e3, "params_per_s": P / dt, "GBps": bpp * P / dt / 1e9,
+            "frac_of_peak": bpp * P / dt / 1e9 / PEAK_HBM_GBPS,
+            "what": "the timed steps again with the per-layer launches going round %d streams (wall clock); the headline "
+                    "uses one stream" % a.streams}
     if a.graph and not wl.per_layer:
         res["hip_graph"] = graph_run(st, cfg, stream, step_no, steps, P, bpp)
         step_no += steps

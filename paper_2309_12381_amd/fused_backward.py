@@ -41,10 +41,17 @@ class FusedBackwardOptimizer:
                 2 B parameters: no gain, 22.8 against 23.0 ms per iteration; both the step and the
                 matrix products of backward fill every compute unit, so they take turns anyway.)
 
+    bucket_params  0 (default): one launch per parameter, as the paper steps.  > 0: consecutive parameters are
+                grouped into buckets of at least this many elements (at most 64 parameters each); a bucket is stepped
+                in ONE launch when the last of its gradients has arrived, and its gradients are released then.  Fewer,
+                larger launches run closer to the memory system's rate (a launch over one matrix spends 5-10 % of its
+                time filling and draining the GPU); the price is that one bucket's gradients, not one parameter's, are
+                alive at a time.  A bucket whose gradients do not all arrive in a backward is stepped for those that
+                did by `start_step()` / `synchronize_buckets()`, parameter by parameter.
     place       divide the optimizer state between two regions of the device memory (placement.py): `m` is
                 allocated first, next to the model's weights, and `res`, `v` where the bandwidth probe sees
                 the gain of a second region relative to the largest parameter and `m`.  Only models with a
-                parameter of at least 2^26 elements and 2.4e8 parameters in all are placed; the report is in
+                parameter of at least 2^26 elements and 2e8 parameters in all are placed; the report is in
                 `self.placement`.  The search holds up to `max_transient_bytes` (default: half of the free
                 memory) beyond the state while it runs, so construct the optimizer before activations exist.
 
@@ -56,7 +63,7 @@ class FusedBackwardOptimizer:
     def __init__(self, params: Iterable[torch.nn.Parameter], cfg, res_bits: int = 0,
                  init_fp32: Optional[Sequence[torch.Tensor]] = None, fused: bool = True,
                  observer: Optional[Callable] = None, res_packed: bool = False, overlap: bool = False,
-                 place: bool = True, max_transient_bytes: Optional[int] = None):
+                 place: bool = True, max_transient_bytes: Optional[int] = None, bucket_params: int = 0):
         self.params = [p for p in params if p.requires_grad]
         if not self.params:
             raise ValueError("no parameters")
@@ -123,6 +130,20 @@ class FusedBackwardOptimizer:
                                     self.v[off:] if self.is_adam else None, n, i, res_bits, res_packed))
         torch.cuda.synchronize(dev)
         self.plan = mpo.Plan(specs)          # one layer id per parameter: the paper steps per parameter
+        # optional buckets: a second plan over the same tensors whose layers are runs of consecutive parameters
+        self.bucket_of, self.buckets, self.bucket_plan = None, None, None
+        if bucket_params > 0 and fused:
+            self.bucket_of, self.buckets, fill = [], [], 0
+            for i, p in enumerate(self.params):
+                if not self.buckets or fill >= bucket_params or len(self.buckets[-1]) == mpo.MPO_MAX_LAYER_GRADS:
+                    self.buckets.append([])
+                    fill = 0
+                self.buckets[-1].append(i)
+                self.bucket_of.append(len(self.buckets) - 1)
+                fill += p.numel()
+            self.bucket_plan = mpo.Plan([mpo.Tensor(t.hi, t.res, None, t.m, t.v, t.n, self.bucket_of[i], res_bits, res_packed)
+                                         for i, t in enumerate(specs)])
+            self._pending = [dict() for _ in self.buckets]      # bucket -> {parameter index: gradient}
         self._index = {id(p): i for i, p in enumerate(self.params)}
         self._handles = []
         if fused:
@@ -130,13 +151,35 @@ class FusedBackwardOptimizer:
                 self._handles.append(p.register_post_accumulate_grad_hook(self._on_grad))
 
     def start_step(self):
+        self.synchronize_buckets()
         self.synchronize()
         self.step_no += 1
+
+    def synchronize_buckets(self):
+        """Step, parameter by parameter, whatever gradients are still waiting in incomplete buckets (parameters
+        that took no part in the last backward leave their bucket incomplete)."""
+        if self.buckets is None:
+            return
+        for pending in self._pending:
+            for i, g in sorted(pending.items()):
+                self._launch(self.plan, i, [g])
+            pending.clear()
 
     def synchronize(self):
         """Make the current stream wait for the steps enqueued so far (a no-op without `overlap`)."""
         if self.side is not None:
             torch.cuda.current_stream(self.params[0].device).wait_stream(self.side)
+
+    def _launch(self, plan, layer: int, grads):
+        stream = torch.cuda.current_stream(self.params[0].device)
+        if self.side is not None:
+            # after everything backward has enqueued so far (the kernels that read these weights and
+            # wrote these gradients among it), and keep the gradients' memory until the step has run
+            self.side.wait_stream(stream)
+            for g in grads:
+                g.record_stream(self.side)
+            stream = self.side
+        mpo.mpo_step_layer(plan, layer, self.cfg, self.step_no, grads=grads, stream=stream)
 
     def _step_param(self, i: int, p: torch.nn.Parameter):
         g = p.grad
@@ -146,14 +189,15 @@ class FusedBackwardOptimizer:
             g = g.contiguous()
         if self.observer is not None:
             self.observer(i, g)
-        stream = torch.cuda.current_stream(p.device)
-        if self.side is not None:
-            # after everything backward has enqueued so far (the kernels that read this weight and
-            # wrote this gradient among it), and keep the gradient's memory until the step has run
-            self.side.wait_stream(stream)
-            g.record_stream(self.side)
-            stream = self.side
-        mpo.mpo_step_layer(self.plan, i, self.cfg, self.step_no, grads=[g], stream=stream)
+        if self.buckets is not None:
+            b = self.bucket_of[i]
+            pending = self._pending[b]
+            pending[i] = g
+            if len(pending) == len(self.buckets[b]):        # the bucket's last gradient: one launch for all of them
+                self._launch(self.bucket_plan, b, [pending[k] for k in self.buckets[b]])
+                pending.clear()
+            return
+        self._launch(self.plan, i, [g])
 
     def _on_grad(self, p: torch.nn.Parameter):
         if self.step_no == 0:
@@ -172,6 +216,7 @@ class FusedBackwardOptimizer:
 
     def master_fp32(self, i: int) -> torch.Tensor:
         """The fp32 value of parameter i held by (hi, res)."""
+        self.synchronize_buckets()
         self.synchronize()
         p = self.params[i]
         out = torch.empty(p.numel(), dtype=torch.float32, device=p.device)
@@ -180,14 +225,18 @@ class FusedBackwardOptimizer:
         return out.view_as(p)
 
     def state_of(self, i: int):
+        self.synchronize_buckets()
         self.synchronize()
         n, off, roff = self.params[i].numel(), self.offs[i], self.res_offs[i]
         rlen = mpo.mpo_res_bytes(n, self.res_bits, True) if self.res_packed else n
         return self.res[roff:roff + rlen], self.m[off:off + n], (self.v[off:off + n] if self.is_adam else None)
 
     def close(self):
+        self.synchronize_buckets()
         self.synchronize()
         for h in self._handles:
             h.remove()
         self._handles = []
         self.plan.destroy()
+        if self.bucket_plan is not None:
+            self.bucket_plan.destroy()

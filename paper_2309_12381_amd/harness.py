@@ -125,10 +125,11 @@ class ModelState:
             synth.gen_grads(tv.spec.n, synth.seed_for(self.seed, 2, i, step), self.device, wl.grad_std, wl.fmt,
                             wl.loss_scale, out=self.grad[tv.goff:])
 
-    def step(self, step: int, cfg=None, stream=None, fresh_grads: bool = False, before_layer=None) -> int:
+    def step(self, step: int, cfg=None, stream=None, fresh_grads: bool = False, before_layer=None, streams=None) -> int:
         """One optimizer step over the whole model.  Per-layer workloads: one mpo_step_layer per
         layer in backward order; otherwise one mpo_adam_step.  Returns the number of launches.
         `before_layer(layer, tensor_ids)` runs after that layer's gradients are in the buffer."""
+        assert not (streams and fresh_grads), "gradients are generated on one stream"
         cfg = cfg or self.adam_cfg()
         if not self.wl.per_layer:
             if fresh_grads:
@@ -140,13 +141,15 @@ class ModelState:
             else:
                 mpo.mpo_adam_step(self.plan, cfg, step, stream=stream)
             return 1
-        for layer in self.layers_backward:
+        for k, layer in enumerate(self.layers_backward):
             ids = self.by_layer[layer]
             if fresh_grads:
                 self.fill_grads(ids, step)
             if before_layer:
                 before_layer(layer, ids)
-            mpo.mpo_step_layer(self.plan, layer, cfg, step, stream=stream)
+            # `streams`: the layers' steps go round a set of streams (layers are independent of each other), so that
+            # one launch fills the GPU while the one before it drains; the caller orders the streams around the step
+            mpo.mpo_step_layer(self.plan, layer, cfg, step, stream=streams[k % len(streams)] if streams else stream)
         return len(self.layers_backward)
 
     def close(self):

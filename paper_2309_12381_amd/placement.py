@@ -20,7 +20,8 @@ until the choice is made (memory that is freed comes back in any order, so the o
 reach another region is to hold what lies before it).  Each candidate is timed with the
 bandwidth probe (csrc/stream_probe.hip) on windows at several matching positions of the
 arrays, the way the step walks them; the search stops at the first candidate that shows the
-gain of a second region (8 % on average over the positions, at least 4 % at each); the fastest
+gain of a second region (7 % on average over the positions, at least 4 % at each: a candidate that
+straddles two regions shows the gain at one end only; one in the same region measures within 4 % of the reference); the fastest
 candidate seen is kept and the others are freed.  What the search may hold on top of the
 arrays it returns is bounded by `max_transient_bytes`.  Nothing here knows physical addresses:
 every decision is a measurement, and the outcome is reported to the caller.
@@ -66,14 +67,14 @@ def _nbytes(t: torch.Tensor) -> int:
 
 
 def place_second(hi: torch.Tensor, m: torch.Tensor, make_second: Callable[[], Dict[str, torch.Tensor]], need: int,
-                 gain: float = 1.08, floor: float = 1.04, max_tries: int = 8,
+                 gain: float = 1.07, floor: float = 1.04, max_tries: int = 8,
                  positions: Sequence[float] = (0.0, 1.0 / 3, 2.0 / 3, 1.0), max_transient_bytes: Optional[int] = None,
                  keep_hi: bool = False) -> Tuple[Dict[str, torch.Tensor], dict]:
     """Choose where res, v (and grad) go, given hi and m.
 
     hi            16-bit weights (any dtype of 2 bytes), at least 2^26 elements; the probe overwrites the
                   windows it uses unless `keep_hi` (then they are saved and restored: a model's weights).
-    m             fp32, at least 7 * 2^25 elements (the one-region reference takes all five windows from it);
+    m             fp32, at least 6 * 2^25 elements (the one-region reference takes four of its five windows from it);
                   overwritten (clear it afterwards).
     make_second   allocates and returns {"res": ..., "v": ..., and optionally "grad": ...}; res at least 2^27 bytes
                   (a 16-bit window), v fp32 of at least 2^26 elements.  Called once per candidate.
@@ -83,7 +84,7 @@ def place_second(hi: torch.Tensor, m: torch.Tensor, make_second: Callable[[], Di
     region (`gain` on average over the tested positions, `floor` at each of them) for the candidate kept;
     report["peak_transient_bytes"] what the search held at most beyond the candidate it returns."""
     dev = m.device
-    if _nbytes(hi) < _N2 or _nbytes(m) < 7 * _N2:
+    if _nbytes(hi) < _N2 or _nbytes(m) < 6 * _N2:
         return make_second(), {"split": False, "why": "arrays too small to probe", "peak_transient_bytes": 0}
     stream = torch.cuda.current_stream(dev)
     free0, _ = torch.cuda.mem_get_info(dev)
@@ -99,20 +100,26 @@ def place_second(hi: torch.Tensor, m: torch.Tensor, make_second: Callable[[], Di
         return w
 
     try:
-        # reference: all five windows inside m, i.e. certainly close together
+        # reference: the same hi windows the candidates are measured with, everything else inside m, i.e.
+        # certainly close together (hi and m are taken to lie in one region: m is allocated right after hi)
         one_region = []
         for q in positions:
-            w = _window(m, q, 7 * _N2)
-            one_region.append(_rate(w[:_N2], w[_N2 + _N4:2 * _N2 + _N4], w[2 * _N2 + _N4:3 * _N2 + _N4],
-                                    w[_N2:_N2 + _N4], w[3 * _N2 + _N4:], stream))
+            w = _window(m, q, 6 * _N2)
+            one_region.append(_rate(hi_window(q), w[:_N2], w[_N2:2 * _N2], w[2 * _N2:2 * _N2 + _N4], w[2 * _N2 + _N4:], stream))
 
         def measure(c):
             out = []
             for q in positions:
-                res_w = _window(c["res"], q, _N2)
                 g = c.get("grad")
-                grad_w = _window(g, 0.0, _N2) if g is not None and _nbytes(g) >= _N2 else res_w   # read-only: may alias
-                out.append(_rate(hi_window(q), res_w, grad_w, _window(m, q, _N4), _window(c["v"], q, _N4), stream))
+                if g is not None and _nbytes(g) >= _N2:
+                    grad_w = _window(g, 0.0, _N2)
+                else:
+                    # no gradient array to read from: a part of m away from the m window (where read-only data
+                    # lie does not matter; reading the res window twice would save a sixth of the reads and
+                    # make every candidate look better than it is)
+                    grad_w = _window(m, q + 0.5 if q <= 0.5 else q - 0.5, _N2)
+                out.append(_rate(hi_window(q), _window(c["res"], q, _N2), grad_w, _window(m, q, _N4), _window(c["v"], q, _N4),
+                                 stream))
             return out
 
         def good(r):
@@ -157,7 +164,7 @@ def place_second(hi: torch.Tensor, m: torch.Tensor, make_second: Callable[[], Di
 
 
 def allocate_state(n: int, res_spec: Tuple[int, torch.dtype], grad_spec: Tuple[int, torch.dtype], device="cuda:0",
-                   zero_res: bool = False, place: bool = True, gain: float = 1.08, floor: float = 1.04, max_tries: int = 8,
+                   zero_res: bool = False, place: bool = True, gain: float = 1.07, floor: float = 1.04, max_tries: int = 8,
                    positions: Sequence[float] = (0.0, 1.0 / 3, 2.0 / 3, 1.0),
                    max_transient_bytes: Optional[int] = None) -> Tuple[Dict[str, torch.Tensor], dict]:
     """Allocate hi (int16) and m, v (fp32, cleared) of n elements, res and grad as specified

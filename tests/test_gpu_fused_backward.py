@@ -59,10 +59,12 @@ def _model(dtype, width=256, depth=2, seed=0):
     (torch.float16, "adam", dict(lr=1e-3, loss_scale=256.0, grad_clip=0.01)),
     (torch.bfloat16, "sgd", dict(lr=1e-2, momentum=0.9, weight_decay=2e-4)),
 ], ids=["bf16-adamw", "bf16-adam-clip-stochastic", "fp16-adam-scaled-clip", "bf16-sgd"])
-@pytest.mark.parametrize("res_bits,packed,overlap", [(0, False, False), (7, False, False), (13, True, False),
-                                                     (6, True, False), (0, False, True), (13, True, True)],
-                         ids=["all", "7", "13-packed", "6-packed", "all-overlapped", "13-packed-overlapped"])
-def test_hooks_step_every_parameter_and_match_the_oracle(dtype, kind, kw, res_bits, packed, overlap):
+@pytest.mark.parametrize("res_bits,packed,overlap,bucket", [(0, False, False, 0), (7, False, False, 0), (13, True, False, 0),
+                                                            (6, True, False, 0), (0, False, True, 0), (13, True, True, 0),
+                                                            (0, False, False, 300_000), (13, True, True, 150_000)],
+                         ids=["all", "7", "13-packed", "6-packed", "all-overlapped", "13-packed-overlapped",
+                              "all-bucketed", "13-packed-overlapped-bucketed"])
+def test_hooks_step_every_parameter_and_match_the_oracle(dtype, kind, kw, res_bits, packed, overlap, bucket):
     fmt = "bf16" if dtype == torch.bfloat16 else "fp16"
     say("fused backward dtype=%s kind=%s kw=%s res_bits=%d packed=%s" % (fmt, kind, kw, res_bits, packed))
     model = _model(dtype)
@@ -74,7 +76,10 @@ def test_hooks_step_every_parameter_and_match_the_oracle(dtype, kind, kw, res_bi
 
     def observer(i, g):
         seen.append((i, synth.bits16(g.reshape(-1))))
-    opt = FusedBackwardOptimizer(params, cfg, res_bits=res_bits, observer=observer, res_packed=packed, overlap=overlap)
+    opt = FusedBackwardOptimizer(params, cfg, res_bits=res_bits, observer=observer, res_packed=packed, overlap=overlap,
+                                 bucket_params=bucket)
+    if bucket:
+        assert 2 <= len(opt.buckets) < len(params) and sum(len(b) for b in opt.buckets) == len(params)
     scale = kw.get("loss_scale", 1.0)
     g = torch.Generator(device=DEV)
     g.manual_seed(5)
