@@ -75,6 +75,51 @@ def test_noalloc_matches_the_plan_path_on_two_calls_in_a_row(fmt, kw):
         plan.destroy()
 
 
+def test_noalloc_captured_in_a_hip_graph_replays_like_eager_calls():
+    """The callers the entry point is for: its launches are recorded into a HIP graph (nothing in it allocates,
+    copies or clears, so nothing but kernels is recorded) and the graph is replayed several times, with new
+    gradients, eager work and synchronisations between the replays; after every replay the state equals that of
+    the plan path called eagerly with the same step numbers, bit for bit."""
+    rng = np.random.default_rng(17)
+    sizes = [4096 * 3 + 9, 1023, 0, 70_001] + [int(x) for x in rng.integers(1, 20_000, 36)]
+    layers = [i % 3 for i in range(len(sizes))]
+    kw = dict(res_bits=8)
+    A, B, _ = _make(sizes, layers, "bf16", 300, **kw)
+    lib_cfg, _ = cfg_pair("adam", "bf16", lr=1e-3, weight_decay=1e-2, decoupled_wd=True, res_bits=8)
+    plan = mpo.Plan([d.spec() for d in A])
+    arr = mpo.tensor_array([d.spec() for d in B])
+    say("noalloc under graph capture, %d tensors" % len(sizes))
+
+    def new_grads(r):
+        for i, (a, b) in enumerate(zip(A, B)):
+            if a.n:
+                g = dev_u16(synth.bits16(synth.gen_grads(a.n, synth.seed_for(9, r, i), "cpu", 1e-3, "bf16", 1.0)))
+                a.grad.copy_(g)
+                b.grad.copy_(g)
+    new_grads(0)
+    # the first call on a device looks the fixed array's address up: made before the capture
+    mpo.mpo_adam_step(plan, lib_cfg, 1)
+    mpo.mpo_adam_step_noalloc(arr, lib_cfg, 1)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for t in (2, 3):
+            mpo.mpo_adam_step_noalloc(arr, lib_cfg, t, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for r in range(1, 4):
+        new_grads(r)
+        torch.cuda.synchronize()
+        graph.replay()
+        for t in (2, 3):
+            mpo.mpo_adam_step(plan, lib_cfg, t)
+        for i, (a, b) in enumerate(zip(A, B)):
+            if a.n:
+                _same(a, b, "replay %d tensor %d (n=%d)" % (r, i, a.n))
+    plan.destroy()
+
+
 def test_noalloc_large_layer_takes_the_long_chunks():
     """A layer of 2^26 parameters or more is cut into chunks of 4096 in the fixed table (so that its 2^21
     entries go further): same bits as the plan path (which cuts into 1024), ends checked against the oracle."""
