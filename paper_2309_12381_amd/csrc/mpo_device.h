@@ -137,6 +137,9 @@ template <> __device__ __forceinline__ float merge16<MPO_FP16>(uint32_t hi, uint
 {
     const uint32_t sign = (hi & 0x8000u) << 16;
     const uint32_t P = ((hi & 0x7FFFu) << 13) | (res & 0x1FFFu);
+    /* The usual case, decided for the whole wavefront: every active lane holds a normal number
+     * (exponent field 1..30), and the payload only needs its exponent re-biased. */
+    if (__all(((hi & 0x7FFFu) - 0x0400u) < 0x7800u)) return __uint_as_float(sign | (P + 0x38000000u));
     const uint32_t E = (hi >> 10) & 31u;
     const uint32_t k = hi & 0x3FFu;
     const uint32_t normal = P + 0x38000000u;                  /* exponent + 112 */
@@ -152,6 +155,13 @@ template <> __device__ __forceinline__ void split32<MPO_FP16>(float w, uint32_t 
     const uint32_t b = __float_as_uint(w);
     const uint32_t sign = (b >> 16) & 0x8000u;
     const uint32_t a = b & 0x7FFFFFFFu;
+    /* The usual case, decided for the whole wavefront: 2^-14 <= |w| < 65536 in every active lane */
+    if (__all((a - 0x38800000u) < 0x0F000000u)) {
+        const uint32_t Pn = a - 0x38000000u;
+        hi = sign | (Pn >> 13);
+        res = Pn & 0x1FFFu;
+        return;
+    }
     const uint32_t E = a >> 23;
     /* below 2^-14: shift the 24-bit significand down to the 2^-37 grid, toward zero */
     const uint32_t sh = 113u - E;
@@ -174,17 +184,20 @@ template <> __device__ __forceinline__ float cvt16<MPO_FP16>(uint32_t x)
 /* ---- the update of one parameter (Section 3.1) ---------------------------
  * One IEEE operation per line; the order is part of the definition. */
 
-template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM>
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, bool CLAMP = true>
 __device__ __forceinline__ void step_one(uint32_t &hi, uint32_t &res, uint32_t g16, float &m, float &v,
                                          const StepScalars &s)
 {
     float w = merge16<WFMT>(hi, res);
     float g = cvt16<GFMT>(g16);
     g = g * s.IS;
-    /* Section 4.1: element-wise clipping inside the step; the bound is +infinity when off,
-     * and a NaN gradient stays NaN */
-    g = g > s.CLIP ? s.CLIP : g;
-    g = g < -s.CLIP ? -s.CLIP : g;
+    /* Section 4.1: element-wise clipping inside the step; the bound is +infinity when off (the
+     * two lines then change nothing, and CLAMP = false leaves them out), and a NaN gradient
+     * stays NaN */
+    if (CLAMP) {
+        g = g > s.CLIP ? s.CLIP : g;
+        g = g < -s.CLIP ? -s.CLIP : g;
+    }
     if (OPT == MPO_OPT_ADAM) {
         if (DECAY == kDecoupled) {
             w = w * s.DEC;
@@ -282,19 +295,23 @@ __device__ __forceinline__ ResRef res_ref(void *base, uint64_t n, uint64_t off, 
     return R;
 }
 
-/* 1, 2 or 4 bytes of a plane: everything a lane owns of one plane fits a dword */
+/* 1, 2 or 4 bytes of a plane: everything a lane owns of one plane fits a dword.  Where a
+ * wavefront covers whole 128-byte lines (2 and 4 bytes per lane) the accesses are streaming
+ * like those of the other arrays; single bytes (a wavefront then writes a part of a line, the
+ * rest comes from its neighbours) go through the cache with the default policy: measured
+ * 2-3 % faster than streaming them. */
 template <int NBYTES> __device__ __forceinline__ uint32_t ld_bytes(const MPO_GLOBAL uint8_t *p)
 {
     static_assert(NBYTES == 1 || NBYTES == 2 || NBYTES == 4, "a lane owns 4, 2 or 1 bytes of a plane");
     if (NBYTES == 1) return *p;
-    if (NBYTES == 2) return *reinterpret_cast<const MPO_GLOBAL uint16_t *>(p);
-    return *reinterpret_cast<const MPO_GLOBAL uint32_t *>(p);
+    if (NBYTES == 2) return ld_stream(reinterpret_cast<const MPO_GLOBAL uint16_t *>(p));
+    return ld_stream(reinterpret_cast<const MPO_GLOBAL uint32_t *>(p));
 }
 template <int NBYTES> __device__ __forceinline__ void st_bytes(MPO_GLOBAL uint8_t *p, uint32_t x)
 {
     if (NBYTES == 1) *p = (uint8_t)x;
-    else if (NBYTES == 2) *reinterpret_cast<MPO_GLOBAL uint16_t *>(p) = (uint16_t)x;
-    else *reinterpret_cast<MPO_GLOBAL uint32_t *>(p) = x;
+    else if (NBYTES == 2) st_stream(reinterpret_cast<MPO_GLOBAL uint16_t *>(p), (uint16_t)x);
+    else st_stream(reinterpret_cast<MPO_GLOBAL uint32_t *>(p), x);
 }
 
 /* The EPL values that start at chunk-local parameter e (a multiple of EPL): the 8-, 4- and
@@ -304,15 +321,17 @@ __device__ __forceinline__ void planes_unpack(const ResRef &R, uint32_t e, uint3
     const uint32_t b8 = (R.S & 8u) ? ld_bytes<EPL>(R.p8 + e) : 0u;
     const uint32_t b4 = (R.S & 4u) ? ld_bytes<EPL / 2>(R.p4 + e / 2) : 0u;
     const uint32_t b2 = (R.S & 2u) ? ld_bytes<EPL / 4>(R.p2 + e / 4) : 0u;
+    /* width of each piece, 0 when S does not contain it (its bits above are then 0 as well): the
+     * pieces are joined by shifts by these uniform widths, with no selection per value */
+    const uint32_t w4 = R.S & 4u, w2 = R.S & 2u, w1 = R.S & 1u;
 #pragma unroll
     for (int j = 0; j < EPL / 2; ++j) r[j] = 0u;
 #pragma unroll
     for (int k = 0; k < EPL; ++k) {
-        uint32_t x = 0u;
-        if (R.S & 8u) x = (b8 >> (8 * k)) & 0xFFu;
-        if (R.S & 4u) x = (x << 4) | ((b4 >> (4 * k)) & 0xFu);
-        if (R.S & 2u) x = (x << 2) | ((b2 >> (2 * k)) & 0x3u);
-        if (R.S & 1u) x = (x << 1) | ((ones >> k) & 1u);
+        uint32_t x = (b8 >> (8 * k)) & 0xFFu;
+        x = (x << w4) | ((b4 >> (4 * k)) & 0xFu);
+        x = (x << w2) | ((b2 >> (2 * k)) & 0x3u);
+        x = (x << w1) | ((ones >> k) & 1u);
         r[k / 2] |= x << (16 * (k & 1));
     }
 }
@@ -321,15 +340,17 @@ __device__ __forceinline__ void planes_unpack(const ResRef &R, uint32_t e, uint3
  * bits of the 1-bit plane. */
 __device__ __forceinline__ uint32_t planes_pack(const ResRef &R, uint32_t e, const uint32_t (&r)[EPL / 2])
 {
+    /* width and position (from the low end of the S bits) of each piece; a bit field of width 0 is 0 */
+    const uint32_t w8 = R.S & 8u, w4 = R.S & 4u, w2 = R.S & 2u, w1 = R.S & 1u;
+    const uint32_t o8 = R.S - w8, o4 = o8 - w4, o2 = o4 - w2;
     uint32_t b8 = 0u, b4 = 0u, b2 = 0u, ones = 0u;
 #pragma unroll
     for (int k = 0; k < EPL; ++k) {
         const uint32_t x = (r[k / 2] >> (16 * (k & 1))) & 0xFFFFu;
-        uint32_t left = R.S;
-        if (R.S & 8u) { left -= 8u; b8 |= ((x >> left) & 0xFFu) << (8 * k); }
-        if (R.S & 4u) { left -= 4u; b4 |= ((x >> left) & 0xFu) << (4 * k); }
-        if (R.S & 2u) { left -= 2u; b2 |= ((x >> left) & 0x3u) << (2 * k); }
-        if (R.S & 1u) ones |= (x & 1u) << k;
+        b8 |= __builtin_amdgcn_ubfe(x, o8, w8) << (8 * k);
+        b4 |= __builtin_amdgcn_ubfe(x, o4, w4) << (4 * k);
+        b2 |= __builtin_amdgcn_ubfe(x, o2, w2) << (2 * k);
+        ones |= (x & w1) << k;
     }
     if (R.S & 8u) st_bytes<EPL>(R.p8 + e, b8);
     if (R.S & 4u) st_bytes<EPL / 2>(R.p4 + e / 2, b4);
@@ -343,7 +364,7 @@ static_assert(EPL == 4, "two lanes share a byte of the 1-bit plane");
  * the 1-bit plane is shared by lanes 2k and 2k+1. */
 __device__ __forceinline__ void planes_load(const ResRef &R, uint32_t e, uint32_t (&r)[EPL / 2])
 {
-    const uint32_t ones = (R.S & 1u) ? ((uint32_t)R.p1[e / 8] >> (e & 4u)) & 0xFu : 0u;
+    const uint32_t ones = (R.S & 1u) ? (ld_bytes<1>(R.p1 + e / 8) >> (e & 4u)) & 0xFu : 0u;
     planes_unpack(R, e, ones, r);
 }
 
@@ -352,7 +373,7 @@ __device__ __forceinline__ void planes_store(const ResRef &R, uint32_t e, const 
     const uint32_t ones = planes_pack(R, e, r);
     if (R.S & 1u) {
         const uint32_t other = (uint32_t)__shfl_xor((int)ones, 1);
-        if (!(e & 4u)) R.p1[e / 8] = (uint8_t)(ones | (other << 4));
+        if (!(e & 4u)) st_bytes<1>(R.p1 + e / 8, ones | (other << 4));
     }
 }
 
@@ -367,6 +388,12 @@ struct Rng {
     uint32_t seed_lo, seed_hi, step32, tensor_id;
 };
 
+/* a ^ b ^ c in one instruction (the three-input bit operation of gfx950, truth table 0x96) */
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c)
+{
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
                                               uint32_t k1, uint32_t (&out)[4])
 {
@@ -380,7 +407,7 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
         const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
         const uint32_t h0 = (uint32_t)(p0 >> 32), l0 = (uint32_t)p0;
         const uint32_t h1 = (uint32_t)(p1 >> 32), l1 = (uint32_t)p1;
-        const uint32_t n0 = h1 ^ c1 ^ k0, n2 = h0 ^ c3 ^ k1;
+        const uint32_t n0 = xor3(h1, c1, k0), n2 = xor3(h0, c3, k1);
         c0 = n0; c1 = l1; c2 = n2; c3 = l0;
     }
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
@@ -472,9 +499,9 @@ __device__ __forceinline__ void load_row(Row &x, gcu16p hi, const ResRef &R, gcu
 /* The same with the 16-bit value rounded to nearest or stochastically: un-round, update,
  * round again with this step's draws.  `first` is the tensor-relative index of the row's
  * first parameter (a multiple of 4). */
-template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE>
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE, bool CLAMP>
 __device__ __forceinline__ void compute_row_rounded(Row &x, const StepScalars &s, uint32_t kept, uint32_t sh,
-                                                    const Rng &g, uint64_t first)
+                                                    const Rng &g, uint64_t first, uint32_t round)
 {
     uint32_t rin[EPL / 2];
 #pragma unroll
@@ -482,17 +509,17 @@ __device__ __forceinline__ void compute_row_rounded(Row &x, const StepScalars &s
 #pragma unroll
     for (int q = 0; q < EPL / 4; ++q) {
         uint32_t u[4] = {0u, 0u, 0u, 0u};
-        if (s.round == MPO_ROUND_STOCHASTIC) draw4<FullBits<WFMT>::value>(g, first / 4 + q, u);
+        if (round == MPO_ROUND_STOCHASTIC) draw4<FullBits<WFMT>::value>(g, first / 4 + q, u);
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj) {
             const int j = 2 * q + jj;
             uint32_t h0 = x.h[j] & 0xFFFFu, h1 = x.h[j] >> 16, r0, r1;
-            unround<WFMT>(h0, slot_get<RMODE>(rin, 2 * j), r0, kept, sh, s.round);
-            unround<WFMT>(h1, slot_get<RMODE>(rin, 2 * j + 1), r1, kept, sh, s.round);
-            step_one<OPT, WFMT, GFMT, DECAY, MOM>(h0, r0, x.g[j] & 0xFFFFu, x.m[2 * j], x.v[2 * j], s);
-            step_one<OPT, WFMT, GFMT, DECAY, MOM>(h1, r1, x.g[j] >> 16, x.m[2 * j + 1], x.v[2 * j + 1], s);
-            const uint32_t s0 = reround<WFMT>(h0, r0, kept, sh, s.round, u[2 * jj]);
-            const uint32_t s1 = reround<WFMT>(h1, r1, kept, sh, s.round, u[2 * jj + 1]);
+            unround<WFMT>(h0, slot_get<RMODE>(rin, 2 * j), r0, kept, sh, round);
+            unround<WFMT>(h1, slot_get<RMODE>(rin, 2 * j + 1), r1, kept, sh, round);
+            step_one<OPT, WFMT, GFMT, DECAY, MOM, CLAMP>(h0, r0, x.g[j] & 0xFFFFu, x.m[2 * j], x.v[2 * j], s);
+            step_one<OPT, WFMT, GFMT, DECAY, MOM, CLAMP>(h1, r1, x.g[j] >> 16, x.m[2 * j + 1], x.v[2 * j + 1], s);
+            const uint32_t s0 = reround<WFMT>(h0, r0, kept, sh, round, u[2 * jj]);
+            const uint32_t s1 = reround<WFMT>(h1, r1, kept, sh, round, u[2 * jj + 1]);
             x.h[j] = h0 | (h1 << 16);
             slot_put<RMODE>(x.r, 2 * j, s0);
             slot_put<RMODE>(x.r, 2 * j + 1, s1);
@@ -500,7 +527,7 @@ __device__ __forceinline__ void compute_row_rounded(Row &x, const StepScalars &s
     }
 }
 
-template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE>
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE, bool CLAMP>
 __device__ __forceinline__ void compute_row(Row &x, const StepScalars &s, uint32_t sh)
 {
     uint32_t rin[EPL / 2];
@@ -510,8 +537,8 @@ __device__ __forceinline__ void compute_row(Row &x, const StepScalars &s, uint32
     for (int j = 0; j < EPL / 2; ++j) {
         uint32_t h0 = x.h[j] & 0xFFFFu, h1 = x.h[j] >> 16;
         uint32_t r0 = res_get<RMODE>(rin, 2 * j, sh), r1 = res_get<RMODE>(rin, 2 * j + 1, sh);
-        step_one<OPT, WFMT, GFMT, DECAY, MOM>(h0, r0, x.g[j] & 0xFFFFu, x.m[2 * j], x.v[2 * j], s);
-        step_one<OPT, WFMT, GFMT, DECAY, MOM>(h1, r1, x.g[j] >> 16, x.m[2 * j + 1], x.v[2 * j + 1], s);
+        step_one<OPT, WFMT, GFMT, DECAY, MOM, CLAMP>(h0, r0, x.g[j] & 0xFFFFu, x.m[2 * j], x.v[2 * j], s);
+        step_one<OPT, WFMT, GFMT, DECAY, MOM, CLAMP>(h1, r1, x.g[j] >> 16, x.m[2 * j + 1], x.v[2 * j + 1], s);
         x.h[j] = h0 | (h1 << 16);
         res_put<RMODE>(x.r, 2 * j, r0, sh);
         res_put<RMODE>(x.r, 2 * j + 1, r1, sh);
@@ -553,7 +580,7 @@ __device__ __forceinline__ void step_scalar(gu16p hi, MPO_GLOBAL void *res_, gcu
 template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, bool RND>
 __device__ __forceinline__ void step_group_planes(gu16p hi, const ResRef &R, gcu16p grad, gf32p m, gf32p v, uint32_t e,
                                                   uint32_t len, const StepScalars &s, uint32_t kept, uint32_t sh,
-                                                  const Rng &g, uint64_t off)
+                                                  const Rng &g, uint64_t off, uint32_t round)
 {
     uint32_t ones = (R.S & 1u) ? R.p1[e / 8] : 0u;
 #pragma unroll
@@ -563,18 +590,18 @@ __device__ __forceinline__ void step_group_planes(gu16p hi, const ResRef &R, gcu
             uint32_t r[EPL / 2];
             planes_unpack(R, eh, (ones >> (4 * half)) & 0xFu, r);
             uint32_t u[4] = {0u, 0u, 0u, 0u};
-            if (RND && s.round == MPO_ROUND_STOCHASTIC) draw4<FullBits<WFMT>::value>(g, (off + eh) / 4, u);
+            if (RND && round == MPO_ROUND_STOCHASTIC) draw4<FullBits<WFMT>::value>(g, (off + eh) / 4, u);
 #pragma unroll
             for (int k = 0; k < EPL; ++k) {
                 if (eh + k < len) {
                     uint32_t h = hi[eh + k], rr;
                     uint32_t slot = (r[k / 2] >> (16 * (k & 1))) & 0xFFFFu;
-                    if (RND) unround<WFMT>(h, slot, rr, kept, sh, s.round);
+                    if (RND) unround<WFMT>(h, slot, rr, kept, sh, round);
                     else rr = slot << sh;
                     float mm = Uses<OPT, MOM>::m ? m[eh + k] : 0.0f;
                     float vv = Uses<OPT, MOM>::v ? v[eh + k] : 0.0f;
                     step_one<OPT, WFMT, GFMT, DECAY, MOM>(h, rr, grad[eh + k], mm, vv, s);
-                    if (RND) slot = reround<WFMT>(h, rr, kept, sh, s.round, u[k]);
+                    if (RND) slot = reround<WFMT>(h, rr, kept, sh, round, u[k]);
                     else slot = rr >> sh;
                     hi[eh + k] = (uint16_t)h;
                     if (Uses<OPT, MOM>::m) m[eh + k] = mm;
@@ -592,17 +619,17 @@ __device__ __forceinline__ void step_group_planes(gu16p hi, const ResRef &R, gcu
 template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE>
 __device__ __forceinline__ void step_scalar_rounded(gu16p hi, MPO_GLOBAL void *res_, gcu16p grad, gf32p m, gf32p v,
                                                     uint32_t e, const StepScalars &s, uint32_t kept, uint32_t sh,
-                                                    const Rng &g, uint64_t index)
+                                                    const Rng &g, uint64_t index, uint32_t round)
 {
     MPO_GLOBAL typename ResElem<RMODE>::T *res = static_cast<MPO_GLOBAL typename ResElem<RMODE>::T *>(res_);
     uint32_t h = hi[e], r;
-    unround<WFMT>(h, (uint32_t)res[e], r, kept, sh, s.round);
+    unround<WFMT>(h, (uint32_t)res[e], r, kept, sh, round);
     float mm = Uses<OPT, MOM>::m ? m[e] : 0.0f;
     float vv = Uses<OPT, MOM>::v ? v[e] : 0.0f;
     step_one<OPT, WFMT, GFMT, DECAY, MOM>(h, r, grad[e], mm, vv, s);
     uint32_t u[4] = {0u, 0u, 0u, 0u};
-    if (s.round == MPO_ROUND_STOCHASTIC) draw4<FullBits<WFMT>::value>(g, index / 4, u);
-    const uint32_t slot = reround<WFMT>(h, r, kept, sh, s.round, u[index % 4]);
+    if (round == MPO_ROUND_STOCHASTIC) draw4<FullBits<WFMT>::value>(g, index / 4, u);
+    const uint32_t slot = reround<WFMT>(h, r, kept, sh, round, u[index % 4]);
     hi[e] = (uint16_t)h;
     res[e] = (typename ResElem<RMODE>::T)slot;
     if (Uses<OPT, MOM>::m) m[e] = mm;
@@ -614,11 +641,13 @@ __device__ __forceinline__ void step_scalar_rounded(gu16p hi, MPO_GLOBAL void *r
 template <bool OV> struct OvArg { typedef NoOverride T; };
 template <> struct OvArg<true> { typedef GradOverride T; };
 
-template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE, bool RND, bool OV>
-__global__ void __launch_bounds__(kBlock)
-step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chunks, uint64_t first_chunk,
-            StepScalars s, typename OvArg<OV>::T ov)
+/* One chunk per workgroup.  ROUND is the rounding mode as a constant (the kernel branches on
+ * the uniform s.round once, so the loops hold the code of one mode only). */
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE, bool RND, bool OV, uint32_t ROUND>
+__device__ __forceinline__ void step_chunk(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chunks,
+                                           uint64_t first_chunk, const StepScalars &s, const typename OvArg<OV>::T &ov)
 {
+    constexpr uint32_t round = ROUND;
     /* Uniform per workgroup: scalar loads. */
     const Chunk c = chunks[first_chunk + blockIdx.x];
     const TensorDesc d = descs[c.tensor];
@@ -637,10 +666,10 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
     const uint32_t len = left < celems ? (uint32_t)left : celems;
 
     /* cut bits of this tensor's residual (uniform); a full residual has none */
-    const uint32_t all = (RND && s.round == MPO_ROUND_STOCHASTIC && WFMT == MPO_BF16) ? 15u : FullBits<WFMT>::value;
+    const uint32_t all = (RND && round == MPO_ROUND_STOCHASTIC && WFMT == MPO_BF16) ? 15u : FullBits<WFMT>::value;
     const uint32_t stored = d.res_bits ? d.res_bits : all;
     /* in the planes the flag of stochastic rounding is the leading one of the stored bits */
-    const uint32_t kept = (RMODE == kResPlanes && RND && s.round == MPO_ROUND_STOCHASTIC) ? stored - 1u : stored;
+    const uint32_t kept = (RMODE == kResPlanes && RND && round == MPO_ROUND_STOCHASTIC) ? stored - 1u : stored;
     const uint32_t sh = (RMODE == kResFull && !RND) ? 0u : FullBits<WFMT>::value - kept;
     const Rng rng = {s.seed_lo, s.seed_hi, s.step32, d.tensor_id};
     gu16p hi = (gu16p)(d.hi + off);
@@ -651,6 +680,7 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
     gf32p m = Uses<OPT, MOM>::m ? (gf32p)(d.m + off) : (gf32p) nullptr;
     gf32p v = Uses<OPT, MOM>::v ? (gf32p)(d.v + off) : (gf32p) nullptr;
     const uint32_t t = threadIdx.x;
+    const bool clamp = s.CLIP < __builtin_inff();      /* uniform: clipping is switched on */
 
     if (aligned && len == celems) {
         /* whole chunk: row by row, every lane active, no bounds checks.  One row in flight per
@@ -662,14 +692,19 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
             const uint32_t e = row_elem(r, t, span);
             Row x;
             load_row<OPT, MOM, RMODE>(x, hi, R, grad, m, v, e);
-            if (RND) compute_row_rounded<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x, s, kept, sh, rng, off + e);
-            else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x, s, sh);
+            if (clamp) {
+                if (RND) compute_row_rounded<OPT, WFMT, GFMT, DECAY, MOM, RREG, true>(x, s, kept, sh, rng, off + e, round);
+                else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RREG, true>(x, s, sh);
+            } else {
+                if (RND) compute_row_rounded<OPT, WFMT, GFMT, DECAY, MOM, RREG, false>(x, s, kept, sh, rng, off + e, round);
+                else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RREG, false>(x, s, sh);
+            }
             store_row<OPT, MOM, RMODE>(x, hi, R, m, v, e);
         }
     } else if (RMODE == kResPlanes) {
         /* packed planes outside the fast path: every lane walks whole groups of 8 parameters */
         for (uint32_t e = t * 8u; e < len; e += kBlock * 8u)
-            step_group_planes<OPT, WFMT, GFMT, DECAY, MOM, RND>(hi, R, grad, m, v, e, len, s, kept, sh, rng, off);
+            step_group_planes<OPT, WFMT, GFMT, DECAY, MOM, RND>(hi, R, grad, m, v, e, len, s, kept, sh, rng, off, round);
     } else if (aligned) {
         /* last chunk of a tensor: full vectors, then one lane finishes the ragged end */
 #pragma unroll 1
@@ -678,22 +713,35 @@ step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chun
             if (e + EPL <= len) {
                 Row x;
                 load_row<OPT, MOM, RMODE>(x, hi, R, grad, m, v, e);
-                if (RND) compute_row_rounded<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x, s, kept, sh, rng, off + e);
-                else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x, s, sh);
+                if (RND) compute_row_rounded<OPT, WFMT, GFMT, DECAY, MOM, RREG, true>(x, s, kept, sh, rng, off + e, round);
+                else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RREG, true>(x, s, sh);
                 store_row<OPT, MOM, RMODE>(x, hi, R, m, v, e);
             } else if (e < len) {
                 for (uint32_t i = e; i < len; ++i) {
-                    if (RND) step_scalar_rounded<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(hi, res, grad, m, v, i, s, kept, sh, rng, off + i);
+                    if (RND) step_scalar_rounded<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(hi, res, grad, m, v, i, s, kept, sh, rng, off + i, round);
                     else step_scalar<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(hi, res, grad, m, v, i, s, sh);
                 }
             }
         }
     } else {
         for (uint32_t i = t; i < len; i += kBlock) {
-            if (RND) step_scalar_rounded<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(hi, res, grad, m, v, i, s, kept, sh, rng, off + i);
+            if (RND) step_scalar_rounded<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(hi, res, grad, m, v, i, s, kept, sh, rng, off + i, round);
             else step_scalar<OPT, WFMT, GFMT, DECAY, MOM, RMODE>(hi, res, grad, m, v, i, s, sh);
         }
     }
+}
+
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE, bool RND, bool OV>
+__global__ void __launch_bounds__(kBlock)
+step_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chunks, uint64_t first_chunk,
+            StepScalars s, typename OvArg<OV>::T ov)
+{
+    if (!RND)
+        step_chunk<OPT, WFMT, GFMT, DECAY, MOM, RMODE, RND, OV, MPO_ROUND_TRUNC>(descs, chunks, first_chunk, s, ov);
+    else if (s.round == MPO_ROUND_STOCHASTIC)
+        step_chunk<OPT, WFMT, GFMT, DECAY, MOM, RMODE, RND, OV, MPO_ROUND_STOCHASTIC>(descs, chunks, first_chunk, s, ov);
+    else
+        step_chunk<OPT, WFMT, GFMT, DECAY, MOM, RMODE, RND, OV, MPO_ROUND_NEAREST>(descs, chunks, first_chunk, s, ov);
 }
 
 /* Grids are limited to 2^31-1 workgroups: longer lists go out in slices. */
