@@ -137,9 +137,6 @@ template <> __device__ __forceinline__ float merge16<MPO_FP16>(uint32_t hi, uint
 {
     const uint32_t sign = (hi & 0x8000u) << 16;
     const uint32_t P = ((hi & 0x7FFFu) << 13) | (res & 0x1FFFu);
-    /* The usual case, decided for the whole wavefront: every active lane holds a normal number
-     * (exponent field 1..30), and the payload only needs its exponent re-biased. */
-    if (__all(((hi & 0x7FFFu) - 0x0400u) < 0x7800u)) return __uint_as_float(sign | (P + 0x38000000u));
     const uint32_t E = (hi >> 10) & 31u;
     const uint32_t k = hi & 0x3FFu;
     const uint32_t normal = P + 0x38000000u;                  /* exponent + 112 */
@@ -155,13 +152,6 @@ template <> __device__ __forceinline__ void split32<MPO_FP16>(float w, uint32_t 
     const uint32_t b = __float_as_uint(w);
     const uint32_t sign = (b >> 16) & 0x8000u;
     const uint32_t a = b & 0x7FFFFFFFu;
-    /* The usual case, decided for the whole wavefront: 2^-14 <= |w| < 65536 in every active lane */
-    if (__all((a - 0x38800000u) < 0x0F000000u)) {
-        const uint32_t Pn = a - 0x38000000u;
-        hi = sign | (Pn >> 13);
-        res = Pn & 0x1FFFu;
-        return;
-    }
     const uint32_t E = a >> 23;
     /* below 2^-14: shift the 24-bit significand down to the 2^-37 grid, toward zero */
     const uint32_t sh = 113u - E;
@@ -184,20 +174,17 @@ template <> __device__ __forceinline__ float cvt16<MPO_FP16>(uint32_t x)
 /* ---- the update of one parameter (Section 3.1) ---------------------------
  * One IEEE operation per line; the order is part of the definition. */
 
-template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, bool CLAMP = true>
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM>
 __device__ __forceinline__ void step_one(uint32_t &hi, uint32_t &res, uint32_t g16, float &m, float &v,
                                          const StepScalars &s)
 {
     float w = merge16<WFMT>(hi, res);
     float g = cvt16<GFMT>(g16);
     g = g * s.IS;
-    /* Section 4.1: element-wise clipping inside the step; the bound is +infinity when off (the
-     * two lines then change nothing, and CLAMP = false leaves them out), and a NaN gradient
-     * stays NaN */
-    if (CLAMP) {
-        g = g > s.CLIP ? s.CLIP : g;
-        g = g < -s.CLIP ? -s.CLIP : g;
-    }
+    /* Section 4.1: element-wise clipping inside the step; the bound is +infinity when off,
+     * and a NaN gradient stays NaN */
+    g = g > s.CLIP ? s.CLIP : g;
+    g = g < -s.CLIP ? -s.CLIP : g;
     if (OPT == MPO_OPT_ADAM) {
         if (DECAY == kDecoupled) {
             w = w * s.DEC;
@@ -499,7 +486,7 @@ __device__ __forceinline__ void load_row(Row &x, gcu16p hi, const ResRef &R, gcu
 /* The same with the 16-bit value rounded to nearest or stochastically: un-round, update,
  * round again with this step's draws.  `first` is the tensor-relative index of the row's
  * first parameter (a multiple of 4). */
-template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE, bool CLAMP>
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE>
 __device__ __forceinline__ void compute_row_rounded(Row &x, const StepScalars &s, uint32_t kept, uint32_t sh,
                                                     const Rng &g, uint64_t first, uint32_t round)
 {
@@ -516,8 +503,8 @@ __device__ __forceinline__ void compute_row_rounded(Row &x, const StepScalars &s
             uint32_t h0 = x.h[j] & 0xFFFFu, h1 = x.h[j] >> 16, r0, r1;
             unround<WFMT>(h0, slot_get<RMODE>(rin, 2 * j), r0, kept, sh, round);
             unround<WFMT>(h1, slot_get<RMODE>(rin, 2 * j + 1), r1, kept, sh, round);
-            step_one<OPT, WFMT, GFMT, DECAY, MOM, CLAMP>(h0, r0, x.g[j] & 0xFFFFu, x.m[2 * j], x.v[2 * j], s);
-            step_one<OPT, WFMT, GFMT, DECAY, MOM, CLAMP>(h1, r1, x.g[j] >> 16, x.m[2 * j + 1], x.v[2 * j + 1], s);
+            step_one<OPT, WFMT, GFMT, DECAY, MOM>(h0, r0, x.g[j] & 0xFFFFu, x.m[2 * j], x.v[2 * j], s);
+            step_one<OPT, WFMT, GFMT, DECAY, MOM>(h1, r1, x.g[j] >> 16, x.m[2 * j + 1], x.v[2 * j + 1], s);
             const uint32_t s0 = reround<WFMT>(h0, r0, kept, sh, round, u[2 * jj]);
             const uint32_t s1 = reround<WFMT>(h1, r1, kept, sh, round, u[2 * jj + 1]);
             x.h[j] = h0 | (h1 << 16);
@@ -527,7 +514,7 @@ __device__ __forceinline__ void compute_row_rounded(Row &x, const StepScalars &s
     }
 }
 
-template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE, bool CLAMP>
+template <int OPT, int WFMT, int GFMT, int DECAY, bool MOM, int RMODE>
 __device__ __forceinline__ void compute_row(Row &x, const StepScalars &s, uint32_t sh)
 {
     uint32_t rin[EPL / 2];
@@ -537,8 +524,8 @@ __device__ __forceinline__ void compute_row(Row &x, const StepScalars &s, uint32
     for (int j = 0; j < EPL / 2; ++j) {
         uint32_t h0 = x.h[j] & 0xFFFFu, h1 = x.h[j] >> 16;
         uint32_t r0 = res_get<RMODE>(rin, 2 * j, sh), r1 = res_get<RMODE>(rin, 2 * j + 1, sh);
-        step_one<OPT, WFMT, GFMT, DECAY, MOM, CLAMP>(h0, r0, x.g[j] & 0xFFFFu, x.m[2 * j], x.v[2 * j], s);
-        step_one<OPT, WFMT, GFMT, DECAY, MOM, CLAMP>(h1, r1, x.g[j] >> 16, x.m[2 * j + 1], x.v[2 * j + 1], s);
+        step_one<OPT, WFMT, GFMT, DECAY, MOM>(h0, r0, x.g[j] & 0xFFFFu, x.m[2 * j], x.v[2 * j], s);
+        step_one<OPT, WFMT, GFMT, DECAY, MOM>(h1, r1, x.g[j] >> 16, x.m[2 * j + 1], x.v[2 * j + 1], s);
         x.h[j] = h0 | (h1 << 16);
         res_put<RMODE>(x.r, 2 * j, r0, sh);
         res_put<RMODE>(x.r, 2 * j + 1, r1, sh);
@@ -680,7 +667,6 @@ __device__ __forceinline__ void step_chunk(const TensorDesc *__restrict__ descs,
     gf32p m = Uses<OPT, MOM>::m ? (gf32p)(d.m + off) : (gf32p) nullptr;
     gf32p v = Uses<OPT, MOM>::v ? (gf32p)(d.v + off) : (gf32p) nullptr;
     const uint32_t t = threadIdx.x;
-    const bool clamp = s.CLIP < __builtin_inff();      /* uniform: clipping is switched on */
 
     if (aligned && len == celems) {
         /* whole chunk: row by row, every lane active, no bounds checks.  One row in flight per
@@ -692,13 +678,8 @@ __device__ __forceinline__ void step_chunk(const TensorDesc *__restrict__ descs,
             const uint32_t e = row_elem(r, t, span);
             Row x;
             load_row<OPT, MOM, RMODE>(x, hi, R, grad, m, v, e);
-            if (clamp) {
-                if (RND) compute_row_rounded<OPT, WFMT, GFMT, DECAY, MOM, RREG, true>(x, s, kept, sh, rng, off + e, round);
-                else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RREG, true>(x, s, sh);
-            } else {
-                if (RND) compute_row_rounded<OPT, WFMT, GFMT, DECAY, MOM, RREG, false>(x, s, kept, sh, rng, off + e, round);
-                else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RREG, false>(x, s, sh);
-            }
+            if (RND) compute_row_rounded<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x, s, kept, sh, rng, off + e, round);
+            else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x, s, sh);
             store_row<OPT, MOM, RMODE>(x, hi, R, m, v, e);
         }
     } else if (RMODE == kResPlanes) {
@@ -713,8 +694,8 @@ __device__ __forceinline__ void step_chunk(const TensorDesc *__restrict__ descs,
             if (e + EPL <= len) {
                 Row x;
                 load_row<OPT, MOM, RMODE>(x, hi, R, grad, m, v, e);
-                if (RND) compute_row_rounded<OPT, WFMT, GFMT, DECAY, MOM, RREG, true>(x, s, kept, sh, rng, off + e, round);
-                else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RREG, true>(x, s, sh);
+                if (RND) compute_row_rounded<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x, s, kept, sh, rng, off + e, round);
+                else compute_row<OPT, WFMT, GFMT, DECAY, MOM, RREG>(x, s, sh);
                 store_row<OPT, MOM, RMODE>(x, hi, R, m, v, e);
             } else if (e < len) {
                 for (uint32_t i = e; i < len; ++i) {
