@@ -431,6 +431,41 @@ def probe_streams_run(a):
     print(json.dumps(out), flush=True)
 
 
+def compare_libs_run(a, st, cfg, stream):
+    """Two builds of libmpo.so stepping the same state in turn (4 rounds of `--steps`, default 10, steps each
+    after 2 untimed ones; HIP events).  Where the arrays lie is then the same for both, which it is not between
+    two processes.  The plan made by the in-tree build is used by both: the other build must come from the
+    same host sources.  Prints one JSON line."""
+    import torch
+    from paper_2309_12381_amd import binding as mpo
+    builds = {"in_tree": mpo.lib, "other": mpo.load_library(a.compare_lib)}
+    steps = a.steps or 10
+    rows = {k: [] for k in builds}
+    step_no = 0
+    try:
+        for _ in range(4):
+            for name, lib in builds.items():
+                mpo.lib = lib
+                for _ in range(2):
+                    step_no += 1
+                    st.step(step_no, cfg, stream)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(steps):
+                    step_no += 1
+                    st.step(step_no, cfg, stream)
+                e1.record(stream)
+                e1.synchronize()
+                rows[name].append(e0.elapsed_time(e1) / steps)
+    finally:
+        mpo.lib = builds["in_tree"]
+    print(json.dumps({"metric": "ms per step of two builds of libmpo.so in one process, in turn", "unit": "ms", "n_gpus": 1,
+                      "data": "synthetic", "steps_per_round": steps, "config": {"workload": st.wl.key, "other": a.compare_lib,
+                                                                              "placement": st.placement},
+                      "ms_per_step": rows,
+                      "other_over_in_tree": sum(rows["other"]) / sum(rows["in_tree"])}))
+
+
 def split_merge_run(a):
     """mpo_split and mpo_merge (Section 3.1, Table 1: used when a model is brought in or exported) on 2^30
     parameters, 8 bytes per parameter, with the three arrays placed on purpose in thirds of the device memory
@@ -543,6 +578,11 @@ def main():
     ap.add_argument("--no-probe", action="store_true", help="skip the arithmetic-free traffic probe")
     ap.add_argument("--cpu-sample", type=int, default=202_383_360,
                     help="parameters of the CPU baseline's sample (default: one transformer layer of the 7B-shaped set)")
+    ap.add_argument("--compare-lib", default=None, metavar="PATH",
+                    help="time the workload with the in-tree libmpo.so and with another build of it (same host sources, "
+                         "e.g. paper_2309_12381_amd.build.build(force=True, out=PATH, csrc=<a modified copy of csrc/>)) in "
+                         "turn, in this process and on the same arrays: differences between processes (1-2 %%) are "
+                         "larger than those between builds of the kernel")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise kernel that reads 1 GiB and writes 1 GiB (known traffic, "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -587,6 +627,9 @@ def main():
 
     stream = torch.cuda.current_stream()
     cfg = st.adam_cfg() if a.optimizer == "adam" else st.sgd_cfg()
+    if a.compare_lib:
+        compare_libs_run(a, st, cfg, stream)
+        return
     bpp = ADAM_BYTES_PER_PARAM if a.optimizer == "adam" else SGD_BYTES_PER_PARAM
     if a.res_packed:
         bpp += 2 * (a.res_bits / 8.0 - 2.0)  # packed planes: res_bits/8 bytes read and written instead of 2

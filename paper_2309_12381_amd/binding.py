@@ -94,18 +94,23 @@ EXPORTS = {
 }
 
 
-def _load():
-    path = _build.LIB
-    if not os.path.exists(path) or (_build.needs_build() and os.path.exists(_build.HIPCC)):
-        # nothing built yet, or the sources are newer than the library (and there is a compiler):
-        # build (a no-op when fresh); never fall back to another implementation
-        path = _build.build()
+def load_library(path: str):
+    """A build of libmpo.so with the argument types of every export set."""
     lib = ctypes.CDLL(path)
     for name, (argtypes, restype) in EXPORTS.items():
         fn = getattr(lib, name)
         fn.argtypes = argtypes
         fn.restype = restype
     return lib
+
+
+def _load():
+    path = _build.LIB
+    if not os.path.exists(path) or (_build.needs_build() and os.path.exists(_build.HIPCC)):
+        # nothing built yet, or the sources are newer than the library (and there is a compiler):
+        # build (a no-op when fresh); never fall back to another implementation
+        path = _build.build()
+    return load_library(path)
 
 
 lib = _load()

@@ -55,18 +55,20 @@ def _compile(sources, out, extra=()):
     return out
 
 
-def build(force: bool = False, extra=(), out: str = LIB) -> str:
+def build(force: bool = False, extra=(), out: str = LIB, csrc: str = CSRC) -> str:
     """Compile the library: every part to an object file (in parallel), then one link.
-    `extra` adds compiler flags for experiments."""
+    `extra` adds compiler flags, `out` and `csrc` name another output and another copy of the sources:
+    for experiments (bench.py --compare-lib times two builds against each other in one process)."""
     if not force and out == LIB and not needs_build():
         return out
     import tempfile
     from concurrent.futures import ThreadPoolExecutor
+    flags = FLAGS[:-1] + [csrc]         # the last flag is the include path of the sources' own headers
     with tempfile.TemporaryDirectory(prefix="mpo_build_") as tmpdir:
         def one(i):
             src, defs = PARTS[i]
             obj = os.path.join(tmpdir, "part%d.o" % i)
-            subprocess.check_call([HIPCC, *FLAGS, *extra, *defs, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj])
+            subprocess.check_call([HIPCC, *flags, *extra, *defs, "-x", "hip", "-c", os.path.join(csrc, src), "-o", obj])
             return obj
         with ThreadPoolExecutor(min(len(PARTS), os.cpu_count() or 1)) as ex:
             objs = list(ex.map(one, range(len(PARTS))))

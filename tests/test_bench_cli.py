@@ -53,3 +53,19 @@ def test_json_line_on_the_small_workload():
     assert e["ms_per_step"] >= 0.5 * d["ms_per_step"] and e["steps"] >= 1
     g = d["hip_graph"]
     assert g["ms_per_step"] > 0 and g["params_per_s"] > 0
+
+
+@pytest.mark.gpu
+def test_two_builds_compared_in_one_process():
+    """--compare-lib steps the same state with two builds of the library in turn (here: the in-tree build
+    against itself) and prints the per-round times of both."""
+    from paper_2309_12381_amd import build
+    out = _run("--workload", "c1", "--steps", "3", "--compare-lib", build.LIB)
+    assert out.returncode == 0, out.stderr
+    lines = [l for l in out.stdout.split("\n") if l.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    assert d["unit"] == "ms" and d["steps_per_round"] == 3 and d["config"]["workload"] == "c1"
+    assert len(d["ms_per_step"]["in_tree"]) == 4 and len(d["ms_per_step"]["other"]) == 4
+    assert all(x > 0 for k in ("in_tree", "other") for x in d["ms_per_step"][k])
+    assert 0.5 < d["other_over_in_tree"] < 2.0
