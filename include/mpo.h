@@ -146,8 +146,9 @@ mpo_status mpo_merge(const uint16_t *hi, const void *res, float *w32, uint64_t n
  * region runs about 14 % slower than one whose written arrays are divided
  * between two (measured; arrays allocated one after the other in a fresh
  * process all land in the first region).  The library takes the pointers it
- * is given; the Python package's placement.allocate_state shows one way to
- * arrange it.
+ * is given; mpo_place_second (mpo_probe.h, libmpo_probe.so) finds a block in
+ * another region by measurement, and the Python package's
+ * placement.allocate_state does the same on torch tensors.
  */
 typedef struct {
     uint16_t *hi;

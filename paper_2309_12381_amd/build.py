@@ -1,5 +1,5 @@
 """Build libmpo.so (hand-written HIP for gfx950 + the C entry points) in-tree with hipcc, and
-libmpo_probe.so, the bandwidth probe bench.py measures the step kernel against."""
+libmpo_probe.so, the bandwidth probe bench.py measures the step kernel against (and the native placement search)."""
 import os
 import subprocess
 import sys
@@ -16,7 +16,8 @@ PARTS = [("mpo_host.cpp", ()), ("mpo_split_merge.hip", ()), ("mpo_noalloc.hip", 
 SOURCES = sorted({os.path.join(CSRC, src) for src, _ in PARTS})
 HEADERS = [os.path.join(CSRC, "mpo_internal.h"), os.path.join(CSRC, "mpo_device.h"), os.path.join(ROOT, "include", "mpo.h")]
 PROBE_LIB = os.path.join(HERE, "libmpo_probe.so")
-PROBE_SOURCES = [os.path.join(CSRC, "stream_probe.hip")]
+PROBE_SOURCES = [os.path.join(CSRC, "stream_probe.hip"), os.path.join(CSRC, "place_second.cpp")]
+PROBE_HEADERS = [os.path.join(ROOT, "include", "mpo_probe.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
@@ -45,7 +46,7 @@ def needs_build() -> bool:
 
 
 def probe_needs_build() -> bool:
-    return _stale(PROBE_LIB, PROBE_SOURCES)
+    return _stale(PROBE_LIB, PROBE_SOURCES + PROBE_HEADERS)
 
 
 def _compile(sources, out, extra=()):
@@ -80,7 +81,7 @@ def build(force: bool = False, extra=(), out: str = LIB, csrc: str = CSRC) -> st
 
 def build_probe(force: bool = False) -> str:
     """Compile the bandwidth probe (a measuring aid; the library does not depend on it)."""
-    if force or _stale(PROBE_LIB, PROBE_SOURCES):
+    if force or probe_needs_build():
         _compile(PROBE_SOURCES, PROBE_LIB)
     return PROBE_LIB
 

@@ -26,6 +26,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "mpo_probe.h"
+
 namespace {
 
 #define PROBE_GLOBAL __attribute__((address_space(1)))

@@ -13,6 +13,13 @@ LIB_PATH = os.path.join(_HERE, "libmpo_probe.so")
 _lib = None
 
 
+class mpo_place_report(ctypes.Structure):
+    _fields_ = [("split", ctypes.c_int32), ("candidates", ctypes.c_int32), ("chosen", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("one_region_GBps", ctypes.c_double * 4), ("chosen_GBps", ctypes.c_double * 4),
+                ("peak_transient_bytes", ctypes.c_uint64), ("max_transient_bytes", ctypes.c_uint64),
+                ("block_bytes", ctypes.c_uint64), ("v_offset", ctypes.c_uint64), ("grad_offset", ctypes.c_uint64)]
+
+
 def _load():
     global _lib
     if _lib is None:
@@ -31,6 +38,13 @@ def _load():
         _lib.mpo_probe_plain.restype = ctypes.c_int
         _lib.mpo_probe_plain.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_ulonglong,
                                          ctypes.c_void_p, ctypes.c_void_p]
+        _lib.mpo_place_second.restype = ctypes.c_int
+        _lib.mpo_place_second.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint64,
+                                          ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int,
+                                          ctypes.POINTER(ctypes.c_void_p),
+                                          ctypes.POINTER(mpo_place_report), ctypes.c_void_p]
+        _lib.mpo_place_free.restype = ctypes.c_int
+        _lib.mpo_place_free.argtypes = [ctypes.c_void_p]
     return _lib
 
 
@@ -69,3 +83,27 @@ def plain_streams(mode: int, arrays, nbytes: int, sink, stream=None) -> None:
                                  stream.cuda_stream if stream is not None else None)
     if rc != 0:
         raise RuntimeError("mpo_probe_plain failed (%d)" % rc)
+
+
+def place_second_native(hi, m, res_bytes: int, v_bytes: int, grad_bytes: int, max_transient_bytes: int = 0,
+                        keep_hi: bool = True, stream=None):
+    """mpo_place_second, the C interface's placement search (placement.py is the same search on torch tensors):
+    returns (device address of a block allocated with hipMalloc that holds res, v and grad, report as a dict with
+    the offsets of v and grad).  Free the block with place_free.  `m` is overwritten."""
+    block = ctypes.c_void_p()
+    rep = mpo_place_report()
+    rc = _load().mpo_place_second(hi.data_ptr(), hi.numel() * hi.element_size(), m.data_ptr(), m.numel() * m.element_size(),
+                                  res_bytes, v_bytes, grad_bytes, max_transient_bytes, 1 if keep_hi else 0, ctypes.byref(block),
+                                  ctypes.byref(rep), stream.cuda_stream if stream is not None else None)
+    if rc != 0:
+        raise RuntimeError("mpo_place_second failed (%d)" % rc)
+    return block.value, {"split": bool(rep.split), "candidates": rep.candidates, "chosen": rep.chosen,
+                         "one_region_GBps": list(rep.one_region_GBps), "chosen_GBps": list(rep.chosen_GBps),
+                         "peak_transient_bytes": rep.peak_transient_bytes, "max_transient_bytes": rep.max_transient_bytes,
+                         "block_bytes": rep.block_bytes, "v_offset": rep.v_offset, "grad_offset": rep.grad_offset}
+
+
+def place_free(block: int) -> None:
+    rc = _load().mpo_place_free(block)
+    if rc != 0:
+        raise RuntimeError("mpo_place_free failed (%d)" % rc)

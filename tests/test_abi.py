@@ -29,6 +29,21 @@ def test_every_declared_symbol_is_exported():
         assert n in binding.EXPORTS, "binding does not cover " + n
 
 
+def test_probe_library_exports_what_its_header_declares():
+    text = open(os.path.join(ROOT, "include", "mpo_probe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = sorted(set(re.findall(r"\b(mpo_[a-z_0-9]+)\s*\(", text)))
+    assert "mpo_probe_stream" in names and "mpo_place_second" in names and len(names) == 7
+    from paper_2309_12381_amd import probe
+    lib = probe._load()
+    for n in names:
+        assert hasattr(lib, n), n
+    # argument checks that need no GPU
+    assert lib.mpo_probe_stream(None, None, None, None, None, 4096, None) == -1
+    assert lib.mpo_place_second(None, 0, None, 0, 0, 0, 0, 0, 0, None, None, None) == -1
+    assert lib.mpo_place_free(None) == 0
+
+
 def test_status_strings():
     seen = set()
     for s in range(7):

@@ -121,3 +121,39 @@ def test_placement_can_be_switched_off():
     assert not arrays["m"].any() and not arrays["v"].any()
     del arrays
     torch.cuda.empty_cache()
+
+
+def test_native_search_returns_a_block_restores_the_weights_and_keeps_its_bound():
+    """mpo_place_second (the same search behind the C interface, on hipMalloc'ed blocks): whatever it finds, it
+    returns one block of the size asked for, frees the rest, leaves hi as it was, and holds no more than allowed."""
+    n = 1 << 28
+    need = 2 * n + 4 * n + 2 * (1 << 26)
+    say("mpo_place_second n=2^28")
+    g = torch.Generator(device=DEV)
+    g.manual_seed(11)
+    hi = torch.randint(-30000, 30000, (n,), dtype=torch.int16, device=DEV, generator=g)
+    m = torch.empty(n, dtype=torch.float32, device=DEV)
+    before = hi.clone()
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    bound = 17 << 30
+    block, report = probe.place_second_native(hi, m, 2 * n, 4 * n, 2 * (1 << 26), max_transient_bytes=bound, keep_hi=True)
+    print(report)
+    torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
+    assert block and block % 256 == 0
+    assert report["v_offset"] == 2 * n and report["grad_offset"] == 6 * n and report["block_bytes"] == need
+    assert 1 <= report["candidates"] <= 2 and 0 <= report["chosen"] < report["candidates"]
+    assert report["peak_transient_bytes"] <= bound and report["max_transient_bytes"] == bound
+    assert all(3000.0 < r < 8000.0 for r in report["one_region_GBps"] + report["chosen_GBps"])
+    assert torch.equal(hi, before)
+    assert need - (64 << 20) <= free0 - free1 < need + (1 << 30)            # only the returned block is still held
+    probe.place_free(block)
+    free2, _ = torch.cuda.mem_get_info()
+    assert free0 - free2 < (1 << 30)
+    # arrays too small to probe: a plain allocation
+    block, report = probe.place_second_native(hi[:4096], m, 2 * n, 4 * n, 1000)
+    assert block and report["split"] is False and report["candidates"] == 1 and report["peak_transient_bytes"] == 0
+    probe.place_free(block)
+    with pytest.raises(RuntimeError):
+        probe.place_second_native(hi, m, 0, 4 * n, 0)
