@@ -431,6 +431,24 @@ def probe_streams_run(a):
     print(json.dumps(out), flush=True)
 
 
+def c_caller_run(a):
+    """The stand-alone C program as a child process (this process never touches the GPU); its JSON line is passed on."""
+    import subprocess
+    from paper_2309_12381_amd import build
+    exe = build.C_CALLER
+    if not os.path.exists(exe):
+        print("bench.py --c-caller: %s is not built (python -c 'import __graft_entry__ as g; g.build()')" % exe, file=sys.stderr)
+        sys.exit(1)
+    shape = a.shape or {"c3": (4096, 11008, 32, 32000), "c4": (5120, 13824, 40, 32000)}.get(a.workload)
+    if shape is None:
+        print("bench.py --c-caller: --workload c3 or c4, or --shape", file=sys.stderr)
+        sys.exit(2)
+    out = subprocess.run([exe, *[str(x) for x in shape], str(a.steps or 20), "0" if a.no_place else "1"], capture_output=True, text=True)
+    sys.stderr.write(out.stderr)
+    sys.stdout.write(out.stdout)
+    sys.exit(out.returncode)
+
+
 def compare_libs_run(a, st, cfg, stream):
     """Two builds of libmpo.so stepping the same state in turn (4 rounds of `--steps`, default 10, steps each
     after 2 untimed ones; HIP events).  Where the arrays lie is then the same for both, which it is not between
@@ -583,6 +601,13 @@ def main():
                          "e.g. paper_2309_12381_amd.build.build(force=True, out=PATH, csrc=<a modified copy of csrc/>)) in "
                          "turn, in this process and on the same arrays: differences between processes (1-2 %%) are "
                          "larger than those between builds of the kernel")
+    ap.add_argument("--c-caller", action="store_true",
+                    help="run paper_2309_12381_amd/mpo_c_caller (csrc/c_caller.cpp): the per-layer Adam steps of a "
+                         "Llama-shaped list driven through the C interface alone (hipMalloc, mpo_place_second, "
+                         "mpo_plan_create, mpo_step_layer), in a process of its own without Python or PyTorch; "
+                         "--workload c3 (default) or c4 gives the shape (bf16 either way), --no-place skips the search")
+    ap.add_argument("--shape", type=int, nargs=4, default=None, metavar=("HIDDEN", "INTER", "LAYERS", "VOCAB"),
+                    help="--c-caller: another Llama shape")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise kernel that reads 1 GiB and writes 1 GiB (known traffic, "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -592,6 +617,9 @@ def main():
               % a.gpus, file=sys.stderr)
         sys.exit(2)
 
+    if a.c_caller:
+        c_caller_run(a)
+        return
     import torch
     from paper_2309_12381_amd import harness, synth
     if not torch.cuda.is_available():

@@ -86,6 +86,23 @@ def build_probe(force: bool = False) -> str:
     return PROBE_LIB
 
 
+C_CALLER = os.path.join(HERE, "mpo_c_caller")
+C_CALLER_SOURCES = [os.path.join(CSRC, "c_caller.cpp")]
+
+
+def build_c_caller(force: bool = False) -> str:
+    """Compile the stand-alone program that uses the C interface alone (bench.py --c-caller runs it); it finds
+    libmpo.so and libmpo_probe.so beside itself."""
+    if force or _stale(C_CALLER, C_CALLER_SOURCES + HEADERS + PROBE_HEADERS + [LIB, PROBE_LIB]):
+        tmp = C_CALLER + ".tmp.%d" % os.getpid()
+        subprocess.check_call([HIPCC, "-O2", "-std=c++17", "-Wall", "-Wextra", "-I", os.path.join(ROOT, "include"),
+                               "-x", "hip", "--offload-arch=gfx950", *C_CALLER_SOURCES, "-x", "none", LIB, PROBE_LIB,
+                               "-Wl,-rpath,$ORIGIN", "-o", tmp])
+        os.replace(tmp, C_CALLER)
+    return C_CALLER
+
+
 if __name__ == "__main__":
     print(build(force=True, extra=sys.argv[1:]))
     print(build_probe(force=True))
+    print(build_c_caller(force=True))

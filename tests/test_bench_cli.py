@@ -69,3 +69,16 @@ def test_two_builds_compared_in_one_process():
     assert len(d["ms_per_step"]["in_tree"]) == 4 and len(d["ms_per_step"]["other"]) == 4
     assert all(x > 0 for k in ("in_tree", "other") for x in d["ms_per_step"][k])
     assert 0.5 < d["other_over_in_tree"] < 2.0
+
+
+@pytest.mark.gpu
+def test_c_interface_alone_steps_a_small_llama_shape():
+    """--c-caller: a program that uses only include/mpo.h and include/mpo_probe.h (no Python, no PyTorch in its
+    process) allocates, places, plans and steps a Llama-shaped list and reports a plausible rate."""
+    out = _run("--c-caller", "--shape", "2048", "5504", "6", "32000", "--steps", "5")
+    assert out.returncode == 0, out.stderr
+    d = json.loads(out.stdout.strip())
+    params = 2 * 32000 * 2048 + 6 * (2 * 2048 + 4 * 2048 * 2048 + 3 * 2048 * 5504) + 2048
+    assert d["params"] == params and d["tensors"] == 1 + 9 * 6 + 2 and d["launches_per_step"] == 9 and d["steps"] == 5
+    assert 2000.0 < d["GBps"] < 8000.0 and abs(d["frac_of_peak"] - d["GBps"] / 8000.0) < 1e-3
+    assert d["placement"]["searched"] is True and d["placement"]["candidates"] >= 1
