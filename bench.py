@@ -579,7 +579,10 @@ def main():
     ap.add_argument("--split-merge", action="store_true",
                     help="instead of the benchmark: mpo_split / mpo_merge on 2^30 parameters by placement (fresh process)")
     ap.add_argument("--all-variants", action="store_true", help="--split-merge: also fp16 with stochastic rounding")
-    ap.add_argument("--fb-variant", default=None, help=argparse.SUPPRESS)      # --fused-backward: one variant, in this process
+    ap.add_argument("--fb-variant", default=None,
+                    choices=["fused", "fused_one_launch_per_block", "fused_without_placement", "fused_overlapped", "classical"],
+                    help="--fused-backward: this one variant only, in this process (what the full run starts five times; "
+                         "also the form to run under a profiler, which must not see child processes)")
     ap.add_argument("--width", type=int, default=4096)
     ap.add_argument("--depth", type=int, default=12)
     ap.add_argument("--tokens", type=int, default=1024)
