@@ -10,6 +10,10 @@ timed region; the timed region contains nothing but the library's launches.
 Prints ONE JSON line: parameters updated per second, with a `roofline` object
 (algorithmic bytes = 26 B per parameter for Adam, against 8 TB/s) and a
 `cpu_baseline` object (the CPU oracle timed on this host on a bounded sample).
+
+Other legs, each printing one JSON line of its own: --fused-backward (the step inside a real PyTorch backward),
+--probe-streams and --split-merge (what the memory system gives, by placement and launch shape), --compare-lib
+(two builds of the library in one process), --c-caller (the same steps from a C program, no Python in its process).
 """
 import argparse
 import json
