@@ -229,7 +229,7 @@ def fused_backward_run(a):
             x = x + self.proj(att.transpose(1, 2).reshape(b, s_, d))
             return x + self.down(torch.nn.functional.gelu(self.up(self.norm2(x))))
 
-    def run(fused, overlap=False, place=True, bucket=0):
+    def run(fused, overlap=False, place=True, bucket=None):
         torch.manual_seed(0)
         model = torch.nn.Sequential(*[Block() for _ in range(depth)]).to(dev).to(torch.bfloat16)
         params = sum(p.numel() for p in model.parameters())
@@ -293,7 +293,8 @@ def fused_backward_run(a):
         torch.cuda.empty_cache()
         return out, params
 
-    variants = {"fused": dict(fused=True), "fused_one_launch_per_block": dict(fused=True, bucket=12 * d * d),
+    variants = {"fused": dict(fused=True), "fused_one_launch_per_parameter": dict(fused=True, bucket=0),
+                "fused_one_launch_per_block": dict(fused=True, bucket=12 * d * d),
                 "fused_without_placement": dict(fused=True, place=False), "fused_overlapped": dict(fused=True, overlap=True),
                 "classical": dict(fused=False)}
     if a.fb_variant:
@@ -584,8 +585,9 @@ def main():
                     help="instead of the benchmark: mpo_split / mpo_merge on 2^30 parameters by placement (fresh process)")
     ap.add_argument("--all-variants", action="store_true", help="--split-merge: also fp16 with stochastic rounding")
     ap.add_argument("--fb-variant", default=None,
-                    choices=["fused", "fused_one_launch_per_block", "fused_without_placement", "fused_overlapped", "classical"],
-                    help="--fused-backward: this one variant only, in this process (what the full run starts five times; "
+                    choices=["fused", "fused_one_launch_per_parameter", "fused_one_launch_per_block", "fused_without_placement",
+                             "fused_overlapped", "classical"],
+                    help="--fused-backward: this one variant only, in this process (what the full run starts six times; "
                          "also the form to run under a profiler, which must not see child processes)")
     ap.add_argument("--width", type=int, default=4096)
     ap.add_argument("--depth", type=int, default=12)

@@ -41,13 +41,16 @@ class FusedBackwardOptimizer:
                 2 B parameters: no gain, 22.8 against 23.0 ms per iteration; both the step and the
                 matrix products of backward fill every compute unit, so they take turns anyway.)
 
-    bucket_params  0 (default): one launch per parameter, as the paper steps.  > 0: consecutive parameters are
-                grouped into buckets of at least this many elements (at most 64 parameters each); a bucket is stepped
-                in ONE launch when the last of its gradients has arrived, and its gradients are released then.  Fewer,
-                larger launches run closer to the memory system's rate (a launch over one matrix spends 5-10 % of its
-                time filling and draining the GPU); the price is that one bucket's gradients, not one parameter's, are
-                alive at a time.  A bucket whose gradients do not all arrive in a backward is stepped for those that
-                did by `start_step()` / `synchronize_buckets()`, parameter by parameter.
+    bucket_params  consecutive parameters are grouped into buckets of at least this many elements (at most 64 parameters
+                each); a bucket is stepped in ONE launch when the last of its gradients has arrived, and its gradients
+                are released then.  None (default): 2^16, which only makes a small parameter (a norm weight, a bias)
+                wait for the next large one: a launch over a few thousand elements is all latency, and half of a
+                transformer's launches are of that kind.  0: strictly one launch per parameter, as the paper steps.
+                Larger values (say the size of a block) give fewer, larger launches, which run closer to the memory
+                system's rate (a launch over one matrix spends 2-3 % of its time filling and draining the GPU); the
+                price is that one bucket's gradients, not one parameter's, are alive at a time.  A bucket whose gradients
+                do not all arrive in a backward is stepped for those that did by `start_step()` /
+                `synchronize_buckets()`, parameter by parameter.
     place       divide the optimizer state between two regions of the device memory (placement.py): `m` is
                 allocated first, next to the model's weights, and `res`, `v` where the bandwidth probe sees
                 the gain of a second region relative to the largest parameter and `m`.  Only models with a
@@ -63,7 +66,7 @@ class FusedBackwardOptimizer:
     def __init__(self, params: Iterable[torch.nn.Parameter], cfg, res_bits: int = 0,
                  init_fp32: Optional[Sequence[torch.Tensor]] = None, fused: bool = True,
                  observer: Optional[Callable] = None, res_packed: bool = False, overlap: bool = False,
-                 place: bool = True, max_transient_bytes: Optional[int] = None, bucket_params: int = 0):
+                 place: bool = True, max_transient_bytes: Optional[int] = None, bucket_params: Optional[int] = None):
         self.params = [p for p in params if p.requires_grad]
         if not self.params:
             raise ValueError("no parameters")
@@ -132,6 +135,8 @@ class FusedBackwardOptimizer:
         self.plan = mpo.Plan(specs)          # one layer id per parameter: the paper steps per parameter
         # optional buckets: a second plan over the same tensors whose layers are runs of consecutive parameters
         self.bucket_of, self.buckets, self.bucket_plan = None, None, None
+        if bucket_params is None:
+            bucket_params = 1 << 16
         if bucket_params > 0 and fused:
             self.bucket_of, self.buckets, fill = [], [], 0
             for i, p in enumerate(self.params):

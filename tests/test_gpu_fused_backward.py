@@ -61,9 +61,10 @@ def _model(dtype, width=256, depth=2, seed=0):
 ], ids=["bf16-adamw", "bf16-adam-clip-stochastic", "fp16-adam-scaled-clip", "bf16-sgd"])
 @pytest.mark.parametrize("res_bits,packed,overlap,bucket", [(0, False, False, 0), (7, False, False, 0), (13, True, False, 0),
                                                             (6, True, False, 0), (0, False, True, 0), (13, True, True, 0),
-                                                            (0, False, False, 300_000), (13, True, True, 150_000)],
+                                                            (0, False, False, 300_000), (13, True, True, 150_000),
+                                                            (0, False, False, None), (7, False, True, None)],
                          ids=["all", "7", "13-packed", "6-packed", "all-overlapped", "13-packed-overlapped",
-                              "all-bucketed", "13-packed-overlapped-bucketed"])
+                              "all-bucketed", "13-packed-overlapped-bucketed", "all-default-buckets", "7-overlapped-default-buckets"])
 def test_hooks_step_every_parameter_and_match_the_oracle(dtype, kind, kw, res_bits, packed, overlap, bucket):
     fmt = "bf16" if dtype == torch.bfloat16 else "fp16"
     say("fused backward dtype=%s kind=%s kw=%s res_bits=%d packed=%s" % (fmt, kind, kw, res_bits, packed))
@@ -78,8 +79,14 @@ def test_hooks_step_every_parameter_and_match_the_oracle(dtype, kind, kw, res_bi
         seen.append((i, synth.bits16(g.reshape(-1))))
     opt = FusedBackwardOptimizer(params, cfg, res_bits=res_bits, observer=observer, res_packed=packed, overlap=overlap,
                                  bucket_params=bucket)
-    if bucket:
+    if bucket is None:
+        # the default: small parameters wait for the next large one (2^16 elements and more close a bucket)
+        assert opt.buckets is not None and sum(len(b) for b in opt.buckets) == len(params)
+        assert all(sum(params[i].numel() for i in b[:-1]) < (1 << 16) for b in opt.buckets)
+    elif bucket:
         assert 2 <= len(opt.buckets) < len(params) and sum(len(b) for b in opt.buckets) == len(params)
+    else:
+        assert opt.buckets is None
     scale = kw.get("loss_scale", 1.0)
     g = torch.Generator(device=DEV)
     g.manual_seed(5)
