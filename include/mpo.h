@@ -280,7 +280,8 @@ mpo_status mpo_step_layer(mpo_plan *plan, int32_t layer, const void *const *grad
  * All calls on one GPU share that GPU's array: calls whose kernels may overlap in time
  * (different streams or threads) race on it and must be ordered by the caller.  The first
  * call on a device looks the array's address up and must not run under stream capture;
- * later calls may be captured. */
+ * later calls may be captured.  The validation works in fixed-size arrays on the calling
+ * thread's stack, about 256 KiB of it. */
 #define MPO_NOALLOC_MAX_TENSORS 1024
 #define MPO_NOALLOC_MAX_CHUNKS (1u << 21)
 mpo_status mpo_adam_step_noalloc(const mpo_tensor *tensors, uint64_t nt, const mpo_adam_cfg *cfg, uint64_t step,
