@@ -38,8 +38,8 @@ class FusedBackwardOptimizer:
                 backward had enqueued when its gradient arrived, and `start_step()` makes the
                 next forward wait for the last steps.  Results are the same; a gradient lives
                 until its step has run instead of until it is enqueued.  (Measured on MI355X with
-                2 B parameters: no gain, 22.8 against 23.0 ms per iteration; both the step and the
-                matrix products of backward fill every compute unit, so they take turns anyway.)
+                2.4 B parameters: 29.4 against 29.5 ms per iteration; both the step and the matrix
+                products of backward fill every compute unit, so they take turns anyway.)
 
     bucket_params  consecutive parameters are grouped into buckets of at least this many elements (at most 64 parameters
                 each); a bucket is stepped in ONE launch when the last of its gradients has arrived, and its gradients
