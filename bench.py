@@ -12,7 +12,8 @@ Prints ONE JSON line: parameters updated per second, with a `roofline` object
 `cpu_baseline` object (the CPU oracle timed on this host on a bounded sample).
 
 Other legs, each printing one JSON line of its own: --fused-backward (the step inside a real PyTorch backward),
---probe-streams and --split-merge (what the memory system gives, by placement and launch shape), --compare-lib
+--probe-streams and --split-merge (what the memory system gives, by placement and launch shape), --measure-traffic
+(HBM-side bytes per parameter from hardware counters), --compare-lib
 (two builds of the library in one process), --c-caller (the same steps from a C program, no Python in its process).
 """
 import argparse
@@ -31,9 +32,10 @@ ADAM_BYTES_PER_PARAM = 26         # read hi, res, grad (2 B each), m, v (4 B eac
 # each scaled by what the same counter reads for a plain kernel of known size (FETCH_SIZE x 2.000, WRITE_SIZE
 # x 1.000 on this GPU): 14.12 read + 12.00 written.  Source: profiles/step_kernel_adam_bf16_c3_pmc_traffic.txt.
 # Counters cannot be collected inside a timed run, so the figure is carried here from that file and the JSON
-# line says so (roofline.traffic_source).
+# line says so (roofline.traffic_source); `python bench.py --measure-traffic` takes the measurement again.
 MEASURED_TRAFFIC_BYTES_PER_PARAM = {"c3": 26.12}
-TRAFFIC_SOURCE = "carried from profiles/step_kernel_adam_bf16_c3_pmc_traffic.txt (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE), not measured in this run"
+TRAFFIC_SOURCE = ("carried from profiles/step_kernel_adam_bf16_c3_pmc_traffic.txt (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE), not measured "
+                  "in this run; python bench.py --measure-traffic measures it")
 
 
 def host_threads():
@@ -436,6 +438,74 @@ def probe_streams_run(a):
     print(json.dumps(out), flush=True)
 
 
+def measure_traffic_run(a):
+    """HBM-side bytes per parameter of the step kernel, measured: two child runs of this script (the workload of the
+    command line, 2 steps, with --calibrate-copy) under `rocprofv3 --pmc`, one with FETCH_SIZE and one with
+    WRITE_SIZE (KiB per dispatch), each reading scaled by what the same counter shows for a plain kernel that reads
+    1 GiB and writes 1 GiB.  This process never touches the GPU.  Prints one JSON line."""
+    import csv
+    import glob
+    import shutil
+    import subprocess
+    if shutil.which("rocprofv3") is None:
+        print("bench.py --measure-traffic: rocprofv3 is not on PATH", file=sys.stderr)
+        sys.exit(1)
+    out_root = os.path.join(ROOT, "gpurun_out", "traffic")
+    passthrough = ["--workload", a.workload, "--optimizer", a.optimizer, "--res-bits", str(a.res_bits), "--round", a.round,
+                   "--chunk", a.chunk] + (["--res-packed"] if a.res_packed else []) + (["--no-place"] if a.no_place else [])
+    env = dict(os.environ, TMPDIR="/tmp")
+    got = {}
+    for counter in ("FETCH_SIZE", "WRITE_SIZE"):
+        d = os.path.join(out_root, counter)
+        shutil.rmtree(d, ignore_errors=True)
+        os.makedirs(d)
+        cmd = ["rocprofv3", "--pmc", counter, "-d", d, "-o", "t", "--output-format", "csv", "--", "python3",
+               os.path.join(ROOT, "bench.py"), *passthrough, "--steps", "2", "--warmup", "1", "--no-cpu-baseline",
+               "--no-end-to-end", "--no-breakdown", "--calibrate-copy"]
+        r = subprocess.run(cmd, cwd=ROOT, env=env, capture_output=True, text=True, timeout=900)
+        files = glob.glob(os.path.join(d, "**", "t_counter_collection.csv"), recursive=True)
+        if r.returncode != 0 or not files:
+            print("bench.py --measure-traffic: the %s run failed:\n%s" % (counter, (r.stderr or r.stdout)[-2000:]), file=sys.stderr)
+            sys.exit(1)
+        step, copy = {}, []
+        for row in csv.DictReader(open(files[0])):
+            if row["Counter_Name"] != counter:
+                continue
+            name, grid, val = row["Kernel_Name"], int(row["Grid_Size"]), float(row["Counter_Value"])
+            if "step_kernel" in name:
+                step.setdefault(grid, []).append(val)
+            elif "elementwise" in name and "add" in name.lower() and grid >= (1 << 26):
+                copy.append(val)
+        if not step or not copy:
+            print("bench.py --measure-traffic: no step_kernel or calibration dispatches in %s" % files[0], file=sys.stderr)
+            sys.exit(1)
+        big = max(step)
+        got[counter] = {"lanes": big, "dispatches": len(step[big]), "KiB_per_dispatch": sum(step[big]) / len(step[big]),
+                        "calibration_KiB_per_GiB": sum(copy) / len(copy), "scale": 1048576.0 / (sum(copy) / len(copy))}
+        line = [l for l in r.stdout.split("\n") if l.startswith("{")]
+        if line:
+            got["config"] = json.loads(line[-1])["config"]
+    # parameters of the largest launch: one workgroup of 256 lanes per chunk; the chunk length from the plan's default
+    lanes = got["FETCH_SIZE"]["lanes"]
+    if got["WRITE_SIZE"]["lanes"] != lanes:
+        print("bench.py --measure-traffic: the two runs saw different launches", file=sys.stderr)
+        sys.exit(1)
+    from paper_2309_12381_amd import synth
+    wl = synth.workload(a.workload)
+    by_layer = {}
+    for t in wl.tensors:
+        by_layer[t.layer] = by_layer.get(t.layer, 0) + t.n
+    params = max(by_layer.values()) if wl.per_layer else wl.num_params
+    rd = got["FETCH_SIZE"]["KiB_per_dispatch"] * 1024.0 * got["FETCH_SIZE"]["scale"]
+    wr = got["WRITE_SIZE"]["KiB_per_dispatch"] * 1024.0 * got["WRITE_SIZE"]["scale"]
+    print(json.dumps({"metric": "HBM-side traffic of the step kernel's largest launch (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE)",
+                      "unit": "bytes per parameter", "n_gpus": 1, "data": "synthetic",
+                      "config": got.get("config", {"workload": a.workload}), "params_per_launch": params,
+                      "read_bytes_per_param": rd / params, "written_bytes_per_param": wr / params,
+                      "value": (rd + wr) / params, "traffic_bytes_per_launch": rd + wr,
+                      "counters": {k: got[k] for k in ("FETCH_SIZE", "WRITE_SIZE")}}))
+
+
 def c_caller_run(a):
     """The stand-alone C program as a child process (this process never touches the GPU); its JSON line is passed on."""
     import subprocess
@@ -610,6 +680,11 @@ def main():
                          "e.g. paper_2309_12381_amd.build.build(force=True, out=PATH, csrc=<a modified copy of csrc/>)) in "
                          "turn, in this process and on the same arrays: differences between processes (1-2 %%) are "
                          "larger than those between builds of the kernel")
+    ap.add_argument("--measure-traffic", action="store_true",
+                    help="measure the HBM-side bytes per parameter of the step kernel: runs this script twice as a child "
+                         "under rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE; 2 steps with --calibrate-copy) and scales "
+                         "the readings by those of a plain kernel of known size; the figure the default run carries "
+                         "as roofline.traffic comes from this")
     ap.add_argument("--c-caller", action="store_true",
                     help="run paper_2309_12381_amd/mpo_c_caller (csrc/c_caller.cpp): the per-layer Adam steps of a "
                          "Llama-shaped list driven through the C interface alone (hipMalloc, mpo_place_second, "
@@ -628,6 +703,9 @@ def main():
 
     if a.c_caller:
         c_caller_run(a)
+        return
+    if a.measure_traffic:
+        measure_traffic_run(a)
         return
     import torch
     from paper_2309_12381_amd import harness, synth
